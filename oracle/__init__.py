@@ -1,0 +1,216 @@
+"""ctypes face of the CPU oracle (oracle/relibra_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the CPU-baseline
+leg of the benchmark.  The product package never imports this module and this module
+never imports the product package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "relibra_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over rows; no BLAS, no intrinsics)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-std=c99", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.oracle_replicate_node.restype = C.c_longlong
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _u16(a):
+    """bf16 torch tensor or uint16 array -> contiguous uint16 numpy array (bit patterns)."""
+    if hasattr(a, "view") and hasattr(a, "dtype") and str(a.dtype) == "torch.bfloat16":
+        import torch
+        return a.contiguous().view(torch.int16).numpy().view(np.uint16)
+    return np.ascontiguousarray(a, dtype=np.uint16)
+
+
+# ------------------------------------------------------------------ integer path
+def route_hist(ids, E):
+    """ids[n_mb,T,k] -> (counts[n_mb,E] int32, total[E] int64)."""
+    ids = _i32(ids)
+    n_mb, T, k = ids.shape
+    counts = np.empty((n_mb, E), np.int32)
+    total = np.empty(E, np.int64)
+    rc = lib().oracle_route_hist(_p(ids), n_mb, T, k, E, _p(counts), _p(total))
+    if rc:
+        raise ValueError(f"oracle_route_hist: status {rc}")
+    return counts, total
+
+
+def lpt(l, EP):
+    l = _i64(l)
+    out = np.empty(l.shape[0], np.int32)
+    lib().oracle_lpt(_p(l), l.shape[0], EP, _p(out))
+    return out
+
+
+def swap_descent(l, EP, rank_of):
+    l = _i64(l)
+    out = _i32(rank_of).copy()
+    lib().oracle_swap_descent(_p(l), l.shape[0], EP, _p(out))
+    return out
+
+
+def reorder(l, EP):
+    l = _i64(l)
+    out = np.empty(l.shape[0], np.int32)
+    lib().oracle_reorder(_p(l), l.shape[0], EP, _p(out))
+    return out
+
+
+def balance_split(z, a):
+    """Balance the split a[ne,n] (warm start) under placement z[ne,n]; returns the new split."""
+    z = np.ascontiguousarray(z, dtype=np.uint8)
+    a = _i64(a).copy()
+    ne, n = z.shape
+    lib().oracle_balance_split(_p(z), ne, n, _p(a))
+    return a
+
+
+def replicate_node(cnt, home, n, r):
+    cnt = _i64(cnt)
+    home = _i32(home)
+    ne = cnt.shape[0]
+    z = np.empty((ne, n), np.uint8)
+    a = np.empty((ne, n), np.int64)
+    mx = lib().oracle_replicate_node(_p(cnt), _p(home), ne, n, r, _p(z), _p(a))
+    return z, a, int(mx)
+
+
+def plan(counts, EP, rpn, r):
+    """counts[n_mb,E] -> dict of plan tables (see oracle_plan in the C file)."""
+    counts = _i32(counts)
+    n_mb, E = counts.shape
+    M = E // EP if EP > 0 else 0
+    G = EP * (M + r)
+    cap = E + EP * r
+    out = dict(
+        expert_to_slot=np.empty(E, np.int32),
+        replica_expert=np.empty((n_mb, EP, r), np.int32),
+        inst_ptr=np.empty((n_mb, E + 1), np.int32),
+        inst_rank=np.empty((n_mb, cap), np.int32),
+        inst_rows=np.empty((n_mb, cap), np.int32),
+        inst_group=np.empty((n_mb, cap), np.int32),
+        group_expert=np.empty((n_mb, G), np.int32),
+        group_offset=np.empty((n_mb, G + 1), np.int32),
+        max_before=np.empty(n_mb, np.int64),
+        max_after=np.empty(n_mb, np.int64),
+    )
+    rc = lib().oracle_plan(_p(counts), n_mb, E, EP, rpn, r,
+                           _p(out["expert_to_slot"]), _p(out["replica_expert"]),
+                           _p(out["inst_ptr"]), _p(out["inst_rank"]), _p(out["inst_rows"]),
+                           _p(out["inst_group"]), _p(out["group_expert"]), _p(out["group_offset"]),
+                           _p(out["max_before"]), _p(out["max_after"]))
+    if rc:
+        raise ValueError(f"oracle_plan: status {rc}")
+    return out
+
+
+def permute(ids, E, inst_ptr, inst_rows, inst_group, group_offset):
+    """ids[T,k] + one micro-batch's plan tables -> (row_of[N], src_of[N])."""
+    ids = _i32(ids)
+    T, k = ids.shape
+    row_of = np.full(T * k, -1, np.int32)
+    src_of = np.full(T * k, -1, np.int32)
+    rc = lib().oracle_permute(_p(ids), T, k, E, _p(_i32(inst_ptr)), _p(_i32(inst_rows)),
+                              _p(_i32(inst_group)), _p(_i32(group_offset)), _p(row_of), _p(src_of))
+    if rc:
+        raise ValueError(f"oracle_permute: status {rc}")
+    return row_of, src_of
+
+
+# ------------------------------------------------------------------ floating point
+def gather_rows(X, src_of, k):
+    X = _u16(X)
+    src_of = _i32(src_of)
+    N, h = src_of.shape[0], X.shape[1]
+    out = np.empty((N, h), np.uint16)
+    lib().oracle_gather_rows(_p(X), _p(src_of), N, k, h, _p(out))
+    return out
+
+
+def ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None):
+    """-> Gt, U, A [N,h'] and Y [N,h], float64 (rows outside the group range are NaN)."""
+    Xrows, Wg, Wu, Wd = _u16(Xrows), _u16(Wg), _u16(Wu), _u16(Wd)
+    go, ge = _i32(group_offset), _i32(group_expert)
+    if g_end is None:
+        g_end = ge.shape[0]
+    N, h = Xrows.shape
+    hff = Wg.shape[1]
+    assert Wg.shape[2] == h and Wd.shape[1] == h and Wd.shape[2] == hff
+    Gt = np.full((N, hff), np.nan)
+    U = np.full((N, hff), np.nan)
+    A = np.full((N, hff), np.nan)
+    Y = np.full((N, h), np.nan)
+    lib().oracle_ffn_fwd(_p(Xrows), _p(go), _p(ge), g_begin, g_end, _p(Wg), _p(Wu), _p(Wd),
+                         h, hff, _p(Gt), _p(U), _p(A), _p(Y))
+    return Gt, U, A, Y
+
+
+def ffn_bwd(Xrows, dYrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None):
+    """-> dXrows [N,h], dWg, dWu [E,h',h], dWd [E,h,h'], float64."""
+    Xrows, dYrows, Wg, Wu, Wd = _u16(Xrows), _u16(dYrows), _u16(Wg), _u16(Wu), _u16(Wd)
+    go, ge = _i32(group_offset), _i32(group_expert)
+    if g_end is None:
+        g_end = ge.shape[0]
+    N, h = Xrows.shape
+    E, hff = Wg.shape[0], Wg.shape[1]
+    dX = np.full((N, h), np.nan)
+    dWg = np.empty((E, hff, h))
+    dWu = np.empty((E, hff, h))
+    dWd = np.empty((E, h, hff))
+    lib().oracle_ffn_bwd(_p(Xrows), _p(dYrows), _p(go), _p(ge), g_begin, g_end, E,
+                         _p(Wg), _p(Wu), _p(Wd), h, hff, _p(dX), _p(dWg), _p(dWu), _p(dWd))
+    return dX, dWg, dWu, dWd
+
+
+def combine_fwd(Yrows, gates, row_of, T, k):
+    Yrows = np.ascontiguousarray(Yrows, dtype=np.float64)
+    g = None if gates is None else np.ascontiguousarray(gates, dtype=np.float32)
+    h = Yrows.shape[1]
+    out = np.empty((T, h))
+    lib().oracle_combine_fwd(_p(Yrows), _p(g), _p(_i32(row_of)), T, k, h, _p(out))
+    return out
+
+
+def combine_bwd(dOut, Yrows, gates, row_of, T, k):
+    dOut = np.ascontiguousarray(dOut, dtype=np.float64)
+    Yrows = np.ascontiguousarray(Yrows, dtype=np.float64)
+    g = np.ascontiguousarray(gates, dtype=np.float32)
+    h = Yrows.shape[1]
+    dY = np.empty_like(Yrows)
+    dgate = np.empty((T, k))
+    lib().oracle_combine_bwd(_p(dOut), _p(Yrows), _p(g), _p(_i32(row_of)), T, k, h, _p(dY), _p(dgate))
+    return dY, dgate

@@ -1,0 +1,634 @@
+/*
+ * CPU oracle for the replay-guided MoE expert-layer path.  TEST INFRASTRUCTURE ONLY:
+ * it is called by the tests, by the smoke check and by the benchmark's CPU-baseline
+ * leg, never by the product path, and it shares no code with the HIP library.
+ *
+ * Plain loops, integers for everything that is counted, double precision for
+ * everything that is floating point (inputs are bf16 bit patterns, widened exactly).
+ * Each function names the passage of the paper it follows.
+ *
+ * Parity pins live in tests/test_oracle_*.py.  Unpinned: nothing in this file (the
+ * randomized annealing of Algorithm 1 is not implemented here at all).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+typedef long long i64;
+typedef unsigned __int128 u128;
+
+/* ------------------------------------------------------------------------- */
+/* Per-expert load (Eq. 1: l_e = number of routed tokens of expert e).        */
+/* counts[mb][e]; total[e] = sum over micro-batches (Section 4.1: the         */
+/* inter-batch problem balances the load accumulated over the whole batch).   */
+/* returns 0, or -2 if an id is outside [0,E).                                */
+int oracle_route_hist(const int32_t *ids, int n_mb, int T, int k, int E,
+                      int32_t *counts, i64 *total)
+{
+    for (int i = 0; i < n_mb * E; ++i) counts[i] = 0;
+    for (int e = 0; e < E; ++e) total[e] = 0;
+    for (int mb = 0; mb < n_mb; ++mb)
+        for (int t = 0; t < T; ++t)
+            for (int s = 0; s < k; ++s) {
+                int e = ids[((size_t)mb * T + t) * k + s];
+                if (e < 0 || e >= E) return -2;
+                counts[mb * E + e] += 1;
+                total[e] += 1;
+            }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Stage 1: inter-batch expert reordering (Section 4, Algorithm 1 made        */
+/* deterministic: steepest swap descent over the same swap neighbourhood).    */
+
+/* Greedy LPT with a per-rank capacity of M experts (Section 4.2): experts in  */
+/* descending load (ties: lower id first), each onto the rank that still has   */
+/* room and has the smallest load so far (ties: lower rank).                   */
+void oracle_lpt(const i64 *l, int E, int EP, int32_t *rank_of)
+{
+    int M = E / EP;
+    int *order = (int *)malloc(sizeof(int) * E);
+    for (int e = 0; e < E; ++e) order[e] = e;
+    /* insertion sort: descending load, ascending id */
+    for (int i = 1; i < E; ++i) {
+        int x = order[i], j = i - 1;
+        while (j >= 0 && (l[order[j]] < l[x] || (l[order[j]] == l[x] && order[j] > x))) {
+            order[j + 1] = order[j];
+            --j;
+        }
+        order[j + 1] = x;
+    }
+    i64 *load = (i64 *)calloc(EP, sizeof(i64));
+    int *held = (int *)calloc(EP, sizeof(int));
+    for (int i = 0; i < E; ++i) {
+        int e = order[i], best = -1;
+        for (int g = 0; g < EP; ++g) {
+            if (held[g] >= M) continue;
+            if (best < 0 || load[g] < load[best]) best = g;
+        }
+        rank_of[e] = best;
+        load[best] += l[e];
+        held[best] += 1;
+    }
+    free(order); free(load); free(held);
+}
+
+/* State cost: (max_g L_g, sum_g L_g^2), compared lexicographically.  The second  */
+/* component does the job of the paper's log-sum-exp smoothing (Section 4.2,      */
+/* "objective smoothing"): it still moves when the maximum sits on a plateau.     */
+static void phi_of(const i64 *load, int EP, i64 *mx, u128 *sq)
+{
+    i64 m = 0; u128 s = 0;
+    for (int g = 0; g < EP; ++g) {
+        if (load[g] > m) m = load[g];
+        s += (u128)load[g] * (u128)load[g];
+    }
+    *mx = m; *sq = s;
+}
+static int phi_less(i64 m1, u128 s1, i64 m2, u128 s2)
+{
+    return m1 < m2 || (m1 == m2 && s1 < s2);
+}
+
+/* Steepest swap descent from the placement in rank_of (updated in place).       */
+/* Every pair of experts on different ranks is tried; the swap with the smallest  */
+/* resulting cost wins (ties: smallest (e_a, e_b)); it is applied only if it      */
+/* strictly lowers the cost.                                                      */
+void oracle_swap_descent(const i64 *l, int E, int EP, int32_t *rank_of)
+{
+    i64 *load = (i64 *)calloc(EP, sizeof(i64));
+    for (int e = 0; e < E; ++e) load[rank_of[e]] += l[e];
+    i64 cur_m; u128 cur_s;
+    phi_of(load, EP, &cur_m, &cur_s);
+    for (;;) {
+        int ba = -1, bb = -1; i64 bm = 0; u128 bs = 0;
+        for (int a = 0; a < E; ++a)
+            for (int b = a + 1; b < E; ++b) {
+                int ga = rank_of[a], gb = rank_of[b];
+                if (ga == gb) continue;
+                /* only the two ranks involved change (Section 4.2, incremental update) */
+                load[ga] += l[b] - l[a];
+                load[gb] += l[a] - l[b];
+                i64 m; u128 s;
+                phi_of(load, EP, &m, &s);
+                load[ga] -= l[b] - l[a];
+                load[gb] -= l[a] - l[b];
+                if (ba < 0 || phi_less(m, s, bm, bs)) { ba = a; bb = b; bm = m; bs = s; }
+            }
+        if (ba < 0 || !phi_less(bm, bs, cur_m, cur_s)) break;
+        int ga = rank_of[ba], gb = rank_of[bb];
+        load[ga] += l[bb] - l[ba];
+        load[gb] += l[ba] - l[bb];
+        rank_of[ba] = gb; rank_of[bb] = ga;
+        cur_m = bm; cur_s = bs;
+    }
+    free(load);
+}
+
+/* Reordering without the batch-level guard: descent from the unplanned layout    */
+/* (expert e on rank e / M) and from LPT; the better final cost wins, ties keep    */
+/* the unplanned start.                                                            */
+void oracle_reorder(const i64 *l, int E, int EP, int32_t *rank_of)
+{
+    int M = E / EP;
+    int32_t *p_id = (int32_t *)malloc(sizeof(int32_t) * E);
+    int32_t *p_lpt = (int32_t *)malloc(sizeof(int32_t) * E);
+    for (int e = 0; e < E; ++e) p_id[e] = e / M;
+    oracle_lpt(l, E, EP, p_lpt);
+    oracle_swap_descent(l, E, EP, p_id);
+    oracle_swap_descent(l, E, EP, p_lpt);
+    i64 *load = (i64 *)malloc(sizeof(i64) * EP);
+    i64 m1, m2; u128 s1, s2;
+    for (int g = 0; g < EP; ++g) load[g] = 0;
+    for (int e = 0; e < E; ++e) load[p_id[e]] += l[e];
+    phi_of(load, EP, &m1, &s1);
+    for (int g = 0; g < EP; ++g) load[g] = 0;
+    for (int e = 0; e < E; ++e) load[p_lpt[e]] += l[e];
+    phi_of(load, EP, &m2, &s2);
+    free(load);
+    int lpt_better = phi_less(m2, s2, m1, s1);
+    memcpy(rank_of, lpt_better ? p_lpt : p_id, sizeof(int32_t) * E);
+    free(p_id); free(p_lpt);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Stage 2: intra-batch replication for one node (Section 5.2, Algorithm 2,   */
+/* computation-only objective: the time of a rank is its load in tokens).     */
+/*                                                                            */
+/* A node has n ranks (local ids 0..n-1) and ne experts (local ids 0..ne-1,    */
+/* listed in ascending global expert id).  home[e] is the local rank of e.     */
+/* z[e*n+g] = 1 iff tokens of e may be served on g (Eq. 8-11); a[e*n+g] is the  */
+/* integer number of tokens of e served on g (the split y scaled by x).        */
+
+/* Token split for a given placement z (Section 5.2, SolveTokenSplitLP, restricted   */
+/* to the computation term).  Among the splits that minimise the largest rank load   */
+/* the linear program leaves the choice open; the one taken here also minimises the   */
+/* sum of squared rank loads, reached by repeatedly moving tokens along a chain of    */
+/* ranks from a heavier rank u to a lighter rank v whenever load(v) <= load(u) - 2:    */
+/*   - ranks are tried as u in descending load (ties: lower id);                       */
+/*   - breadth-first search from u over ranks: u' -> v' if some expert with tokens on  */
+/*     u' may also be served on v' (v' scanned ascending; the lowest such expert is    */
+/*     the one that moves along that edge);                                            */
+/*   - v = the reached rank of smallest load (ties: lower id); if load(v) <= load(u)-2  */
+/*     move d = min(floor((load(u)-load(v))/2), tokens available on each edge of the    */
+/*     path) and start over; if no u has such a v the split is final.                  */
+/* When no such chain is left the split is optimal for every convex cost of the loads  */
+/* at once, the maximum included.  The split continues from the one in a (warm start).  */
+void oracle_balance_split(const uint8_t *z, int ne, int n, i64 *a)
+{
+    i64 *load = (i64 *)malloc(sizeof(i64) * n);
+    int *par = (int *)malloc(sizeof(int) * n);
+    int *par_e = (int *)malloc(sizeof(int) * n);
+    int *queue = (int *)malloc(sizeof(int) * n);
+    int *order = (int *)malloc(sizeof(int) * n);
+    for (;;) {
+        for (int g = 0; g < n; ++g) {
+            load[g] = 0;
+            for (int e = 0; e < ne; ++e) load[g] += a[e * n + g];
+            order[g] = g;
+        }
+        for (int i = 1; i < n; ++i) {            /* descending load, ascending id */
+            int x = order[i], j = i - 1;
+            while (j >= 0 && load[order[j]] < load[x]) { order[j + 1] = order[j]; --j; }
+            order[j + 1] = x;
+        }
+        int moved = 0;
+        for (int oi = 0; oi < n && !moved; ++oi) {
+            int u = order[oi];
+            for (int g = 0; g < n; ++g) par[g] = -2;
+            par[u] = -1;
+            int qh = 0, qt = 0;
+            queue[qt++] = u;
+            while (qh < qt) {
+                int w = queue[qh++];
+                for (int v = 0; v < n; ++v) {
+                    if (par[v] != -2) continue;
+                    int via = -1;
+                    for (int e = 0; e < ne; ++e)
+                        if (a[e * n + w] > 0 && z[e * n + v]) { via = e; break; }
+                    if (via < 0) continue;
+                    par[v] = w; par_e[v] = via;
+                    queue[qt++] = v;
+                }
+            }
+            int v = -1;
+            for (int g = 0; g < n; ++g)
+                if (g != u && par[g] != -2 && (v < 0 || load[g] < load[v])) v = g;
+            if (v < 0 || load[v] > load[u] - 2) continue;
+            i64 d = (load[u] - load[v]) / 2;
+            for (int x = v; par[x] >= 0; x = par[x])
+                if (a[par_e[x] * n + par[x]] < d) d = a[par_e[x] * n + par[x]];
+            for (int x = v; par[x] >= 0; x = par[x]) {
+                a[par_e[x] * n + par[x]] -= d;
+                a[par_e[x] * n + x] += d;
+            }
+            moved = 1;
+        }
+        if (!moved) break;
+    }
+    free(load); free(par); free(par_e); free(queue); free(order);
+}
+
+/* Algorithm 2 on one node.  Outputs z and a (ne*n each); returns the node's max   */
+/* rank load after replication.                                                    */
+i64 oracle_replicate_node(const i64 *cnt, const int32_t *home, int ne, int n, int r,
+                          uint8_t *z, i64 *a)
+{
+    int *used = (int *)calloc(n, sizeof(int));
+    i64 *load = (i64 *)calloc(n, sizeof(i64));
+    i64 total = 0;
+    for (int i = 0; i < ne * n; ++i) { z[i] = 0; a[i] = 0; }
+    for (int e = 0; e < ne; ++e) {           /* no replica: everything at home */
+        z[e * n + home[e]] = 1;
+        a[e * n + home[e]] = cnt[e];
+        total += cnt[e];
+    }
+    i64 floor_cap = (total + n - 1) / n;     /* no split can beat the node average */
+    for (;;) {
+        for (int g = 0; g < n; ++g) {
+            load[g] = 0;
+            for (int e = 0; e < ne; ++e) load[g] += a[e * n + g];
+        }
+        int gb = 0;                          /* bottleneck rank */
+        for (int g = 1; g < n; ++g) if (load[g] > load[gb]) gb = g;
+        if (load[gb] <= floor_cap) break;
+        /* experts served on gb with a positive share, heaviest share first; the first  */
+        /* one that some rank can still take a replica of is replicated                  */
+        int picked_e = -1, picked_g = -1;
+        uint8_t *tried = (uint8_t *)calloc(ne, 1);
+        for (;;) {
+            int e_star = -1;
+            for (int e = 0; e < ne; ++e) {
+                if (tried[e] || a[e * n + gb] <= 0) continue;
+                if (e_star < 0 || a[e * n + gb] > a[e_star * n + gb]) e_star = e;
+            }
+            if (e_star < 0) break;
+            tried[e_star] = 1;
+            int gt = -1;                     /* least-loaded rank that can take a replica */
+            for (int g = 0; g < n; ++g) {
+                if (z[e_star * n + g] || used[g] >= r) continue;
+                if (gt < 0 || load[g] < load[gt]) gt = g;
+            }
+            if (gt >= 0) { picked_e = e_star; picked_g = gt; break; }
+        }
+        free(tried);
+        if (picked_e < 0) break;
+        z[picked_e * n + picked_g] = 1;
+        used[picked_g] += 1;
+        oracle_balance_split(z, ne, n, a);
+    }
+    /* a replica that ended up with no tokens is not materialised */
+    for (int e = 0; e < ne; ++e)
+        for (int g = 0; g < n; ++g)
+            if (g != home[e] && z[e * n + g] && a[e * n + g] == 0) z[e * n + g] = 0;
+    i64 mx = 0;
+    for (int g = 0; g < n; ++g) {
+        i64 s = 0;
+        for (int e = 0; e < ne; ++e) s += a[e * n + g];
+        if (s > mx) mx = s;
+    }
+    free(used); free(load);
+    return mx;
+}
+
+/* Replication of one micro-batch over all nodes under placement rank_of.          */
+/* zz, aa: [E][EP] (global ids).  Returns the micro-batch's max rank load.          */
+static i64 replicate_mb(const int32_t *cnt_mb, const int32_t *rank_of, int E, int EP, int rpn,
+                        int r, uint8_t *zz, i64 *aa)
+{
+    int nodes = EP / rpn;
+    i64 worst = 0;
+    memset(zz, 0, (size_t)E * EP);
+    memset(aa, 0, sizeof(i64) * (size_t)E * EP);
+    int *ex = (int *)malloc(sizeof(int) * E);
+    for (int nd = 0; nd < nodes; ++nd) {
+        int ne = 0;
+        for (int e = 0; e < E; ++e)
+            if (rank_of[e] / rpn == nd) ex[ne++] = e;
+        i64 *cnt = (i64 *)malloc(sizeof(i64) * (ne ? ne : 1));
+        int32_t *home = (int32_t *)malloc(sizeof(int32_t) * (ne ? ne : 1));
+        uint8_t *z = (uint8_t *)malloc((size_t)(ne ? ne : 1) * rpn);
+        i64 *a = (i64 *)malloc(sizeof(i64) * (size_t)(ne ? ne : 1) * rpn);
+        for (int i = 0; i < ne; ++i) { cnt[i] = cnt_mb[ex[i]]; home[i] = rank_of[ex[i]] - nd * rpn; }
+        i64 mx = oracle_replicate_node(cnt, home, ne, rpn, r, z, a);
+        if (mx > worst) worst = mx;
+        for (int i = 0; i < ne; ++i)
+            for (int g = 0; g < rpn; ++g) {
+                zz[(size_t)ex[i] * EP + nd * rpn + g] = z[i * rpn + g];
+                aa[(size_t)ex[i] * EP + nd * rpn + g] = a[i * rpn + g];
+            }
+        free(cnt); free(home); free(z); free(a);
+    }
+    free(ex);
+    return worst;
+}
+
+/* Whole plan (Sections 4 and 5): reorder once per batch, replicate per micro-batch, */
+/* and keep the reordering only if it lowers J = sum over micro-batches of the max    */
+/* rank load after replication (ties keep the unplanned layout, which moves no        */
+/* expert).  Output tables:                                                           */
+/*   expert_to_slot[E]           rank*M + local slot (local slots by ascending id)     */
+/*   replica_expert[n_mb][EP][r] expert in each replica slot (ascending id), -1 empty  */
+/*   inst_ptr[n_mb][E+1], inst_rank/rows/group[n_mb][E+EP*r]                           */
+/*                               instances of each expert, ascending rank; the home    */
+/*                               instance is always listed                             */
+/*   group_expert[n_mb][G], group_offset[n_mb][G+1], G = EP*(M+r), rank-major:         */
+/*                               M home slots then r replica slots per rank            */
+/*   max_before[n_mb]            max rank load, unplanned layout, no replicas          */
+/*   max_after[n_mb]             max rank load under the plan                          */
+int oracle_plan(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r,
+                int32_t *expert_to_slot, int32_t *replica_expert,
+                int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                int32_t *group_expert, int32_t *group_offset,
+                i64 *max_before, i64 *max_after)
+{
+    if (E <= 0 || EP <= 0 || E % EP || rpn <= 0 || EP % rpn || r < 0 || n_mb <= 0) return -1;
+    int M = E / EP, G = EP * (M + r), cap_inst = E + EP * r;
+    i64 *l = (i64 *)calloc(E, sizeof(i64));
+    for (int mb = 0; mb < n_mb; ++mb)
+        for (int e = 0; e < E; ++e) {
+            if (counts[mb * E + e] < 0) { free(l); return -1; }
+            l[e] += counts[mb * E + e];
+        }
+    int32_t *p_id = (int32_t *)malloc(sizeof(int32_t) * E);
+    int32_t *p_new = (int32_t *)malloc(sizeof(int32_t) * E);
+    for (int e = 0; e < E; ++e) p_id[e] = e / M;
+    oracle_reorder(l, E, EP, p_new);
+
+    size_t zsz = (size_t)E * EP;
+    uint8_t *z_id = (uint8_t *)malloc(zsz * n_mb), *z_new = (uint8_t *)malloc(zsz * n_mb);
+    i64 *a_id = (i64 *)malloc(sizeof(i64) * zsz * n_mb), *a_new = (i64 *)malloc(sizeof(i64) * zsz * n_mb);
+    i64 *mx_id = (i64 *)malloc(sizeof(i64) * n_mb), *mx_new = (i64 *)malloc(sizeof(i64) * n_mb);
+    i64 J_id = 0, J_new = 0;
+    for (int mb = 0; mb < n_mb; ++mb) {
+        mx_id[mb] = replicate_mb(counts + (size_t)mb * E, p_id, E, EP, rpn, r, z_id + zsz * mb, a_id + zsz * mb);
+        mx_new[mb] = replicate_mb(counts + (size_t)mb * E, p_new, E, EP, rpn, r, z_new + zsz * mb, a_new + zsz * mb);
+        J_id += mx_id[mb]; J_new += mx_new[mb];
+    }
+    int use_new = J_new < J_id;
+    const int32_t *rank_of = use_new ? p_new : p_id;
+    const uint8_t *zz = use_new ? z_new : z_id;
+    const i64 *aa = use_new ? a_new : a_id;
+    const i64 *mx = use_new ? mx_new : mx_id;
+
+    /* local slots: ascending expert id within a rank */
+    int *next_local = (int *)calloc(EP, sizeof(int));
+    for (int e = 0; e < E; ++e) expert_to_slot[e] = rank_of[e] * M + next_local[rank_of[e]]++;
+    free(next_local);
+
+    for (int mb = 0; mb < n_mb; ++mb) {
+        const uint8_t *z = zz + zsz * mb;
+        const i64 *a = aa + zsz * mb;
+        int32_t *rep = replica_expert + (size_t)mb * EP * r;
+        int32_t *gexp = group_expert + (size_t)mb * G;
+        int32_t *goff = group_offset + (size_t)mb * (G + 1);
+        i64 *grow = (i64 *)calloc(G, sizeof(i64));
+        for (int g = 0; g < G; ++g) gexp[g] = -1;
+        for (int i = 0; i < EP * r; ++i) rep[i] = -1;
+        for (int e = 0; e < E; ++e) {
+            int slot = expert_to_slot[e];
+            int grp = (slot / M) * (M + r) + slot % M;
+            gexp[grp] = e;
+            grow[grp] = a[(size_t)e * EP + rank_of[e]];
+        }
+        for (int g = 0; g < EP; ++g) {
+            int j = 0;
+            for (int e = 0; e < E; ++e)          /* ascending id fills slots in order */
+                if (rank_of[e] != g && z[(size_t)e * EP + g]) {
+                    rep[g * r + j] = e;
+                    gexp[g * (M + r) + M + j] = e;
+                    grow[g * (M + r) + M + j] = a[(size_t)e * EP + g];
+                    ++j;
+                }
+        }
+        goff[0] = 0;
+        for (int g = 0; g < G; ++g) goff[g + 1] = goff[g] + (int32_t)grow[g];
+        /* instances of each expert, ascending rank */
+        int32_t *ip = inst_ptr + (size_t)mb * (E + 1);
+        int32_t *ir = inst_rank + (size_t)mb * cap_inst;
+        int32_t *iw = inst_rows + (size_t)mb * cap_inst;
+        int32_t *ig = inst_group + (size_t)mb * cap_inst;
+        for (int i = 0; i < cap_inst; ++i) { ir[i] = -1; iw[i] = 0; ig[i] = -1; }
+        int p = 0;
+        for (int e = 0; e < E; ++e) {
+            ip[e] = p;
+            for (int g = 0; g < EP; ++g) {
+                if (!z[(size_t)e * EP + g]) continue;
+                int grp = -1;
+                if (g == rank_of[e]) grp = g * (M + r) + expert_to_slot[e] % M;
+                else for (int j = 0; j < r; ++j) if (rep[g * r + j] == e) grp = g * (M + r) + M + j;
+                ir[p] = g; iw[p] = (int32_t)a[(size_t)e * EP + g]; ig[p] = grp;
+                ++p;
+            }
+        }
+        ip[E] = p;
+        free(grow);
+        /* unplanned: expert e on rank e / M, no replicas */
+        i64 worst = 0;
+        for (int g = 0; g < EP; ++g) {
+            i64 s = 0;
+            for (int e = g * M; e < (g + 1) * M; ++e) s += counts[(size_t)mb * E + e];
+            if (s > worst) worst = s;
+        }
+        max_before[mb] = worst;
+        max_after[mb] = mx[mb];
+    }
+    free(l); free(p_id); free(p_new); free(z_id); free(z_new); free(a_id); free(a_new);
+    free(mx_id); free(mx_new);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Permutation (Section 5.2, token splitting): assignment a = t*k + s of       */
+/* expert e has ordinal q among the assignments of e (in ascending a); the      */
+/* instances of e, in ascending rank, take consecutive runs of ordinals of the   */
+/* lengths the plan gave them.  row_of[a] is the row in the group-ordered        */
+/* buffer; src_of is its inverse.                                                */
+int oracle_permute(const int32_t *ids, int T, int k, int E,
+                   const int32_t *inst_ptr, const int32_t *inst_rows, const int32_t *inst_group,
+                   const int32_t *group_offset, int32_t *row_of, int32_t *src_of)
+{
+    int N = T * k;
+    int32_t *seen = (int32_t *)calloc(E, sizeof(int32_t));
+    for (int a = 0; a < N; ++a) {
+        int e = ids[a];
+        if (e < 0 || e >= E) { free(seen); return -2; }
+        int q = seen[e]++;
+        int i = inst_ptr[e], before = 0;
+        while (i < inst_ptr[e + 1] && q >= before + inst_rows[i]) { before += inst_rows[i]; ++i; }
+        if (i >= inst_ptr[e + 1]) { free(seen); return -3; }   /* plan does not cover this token */
+        int row = group_offset[inst_group[i]] + (q - before);
+        row_of[a] = row;
+        src_of[row] = a;
+    }
+    free(seen);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Floating point.  bf16 bit patterns widen exactly to double.                */
+static inline double bf(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16; float f; memcpy(&f, &u, 4); return (double)f;
+}
+static inline double sigmoid(double x) { return 1.0 / (1.0 + exp(-x)); }
+
+/* Gather of token rows into group order: Xrows[row] = X[src_of[row] / k] (bit copy). */
+void oracle_gather_rows(const uint16_t *X, const int32_t *src_of, int N, int k, int h, uint16_t *Xrows)
+{
+    for (int row = 0; row < N; ++row)
+        memcpy(Xrows + (size_t)row * h, X + (size_t)(src_of[row] / k) * h, sizeof(uint16_t) * h);
+}
+
+/* Expert FFN forward over groups [g_begin, g_end) (Section 4.1: three GEMMs of   */
+/* 2hh' flops per token).  For a row x of a group whose expert is e:              */
+/*   Gt = Wg_e x, U = Wu_e x, A = silu(Gt) * U, y = Wd_e A.                        */
+/* Wg, Wu: [E][h'][h]; Wd: [E][h][h'].  Outputs are double, no rounding between.   */
+void oracle_ffn_fwd(const uint16_t *Xrows, const int32_t *group_offset, const int32_t *group_expert,
+                    int g_begin, int g_end, const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd,
+                    int h, int hff, double *Gt, double *U, double *A, double *Y)
+{
+    for (int g = g_begin; g < g_end; ++g) {
+        int e = group_expert[g];
+        if (e < 0) continue;
+        const uint16_t *wg = Wg + (size_t)e * hff * h, *wu = Wu + (size_t)e * hff * h;
+        const uint16_t *wd = Wd + (size_t)e * h * hff;
+        #pragma omp parallel for schedule(static)
+        for (int row = group_offset[g]; row < group_offset[g + 1]; ++row) {
+            const uint16_t *x = Xrows + (size_t)row * h;
+            for (int j = 0; j < hff; ++j) {
+                double sg = 0.0, su = 0.0;
+                for (int i = 0; i < h; ++i) {
+                    double xi = bf(x[i]);
+                    sg += xi * bf(wg[(size_t)j * h + i]);
+                    su += xi * bf(wu[(size_t)j * h + i]);
+                }
+                Gt[(size_t)row * hff + j] = sg;
+                U[(size_t)row * hff + j] = su;
+                A[(size_t)row * hff + j] = sg * sigmoid(sg) * su;
+            }
+            for (int i = 0; i < h; ++i) {
+                double s = 0.0;
+                for (int j = 0; j < hff; ++j) s += A[(size_t)row * hff + j] * bf(wd[(size_t)i * hff + j]);
+                Y[(size_t)row * h + i] = s;
+            }
+        }
+    }
+}
+
+/* Expert FFN backward over groups [g_begin, g_end).  With dy the upstream         */
+/* gradient of a row:                                                              */
+/*   dA = Wd_e^T dy;  dGt = dA * U * silu'(Gt);  dU = dA * silu(Gt);                */
+/*   dx = Wg_e^T dGt + Wu_e^T dU;                                                   */
+/*   dWd_e += dy A^T;  dWg_e += dGt x^T;  dWu_e += dU x^T                            */
+/* summed over every group (home or replica) of expert e in the range (Section 5.1:  */
+/* replica gradients are pushed back and accumulated on the home copy).              */
+/* dWg, dWu: [E][h'][h]; dWd: [E][h][h']; all zeroed here first.                     */
+void oracle_ffn_bwd(const uint16_t *Xrows, const uint16_t *dYrows,
+                    const int32_t *group_offset, const int32_t *group_expert,
+                    int g_begin, int g_end, int E,
+                    const uint16_t *Wg, const uint16_t *Wu, const uint16_t *Wd, int h, int hff,
+                    double *dXrows, double *dWg, double *dWu, double *dWd)
+{
+    size_t wsz = (size_t)E * h * hff;
+    memset(dWg, 0, sizeof(double) * wsz);
+    memset(dWu, 0, sizeof(double) * wsz);
+    memset(dWd, 0, sizeof(double) * wsz);
+    for (int g = g_begin; g < g_end; ++g) {
+        int e = group_expert[g];
+        if (e < 0) continue;
+        int r0 = group_offset[g], n = group_offset[g + 1] - r0;
+        if (n <= 0) continue;
+        const uint16_t *wg = Wg + (size_t)e * hff * h, *wu = Wu + (size_t)e * hff * h;
+        const uint16_t *wd = Wd + (size_t)e * h * hff;
+        double *Gt = (double *)malloc(sizeof(double) * (size_t)n * hff);
+        double *U = (double *)malloc(sizeof(double) * (size_t)n * hff);
+        double *Aa = (double *)malloc(sizeof(double) * (size_t)n * hff);
+        double *dGt = (double *)malloc(sizeof(double) * (size_t)n * hff);
+        double *dU = (double *)malloc(sizeof(double) * (size_t)n * hff);
+        #pragma omp parallel for schedule(static)
+        for (int q = 0; q < n; ++q) {
+            const uint16_t *x = Xrows + (size_t)(r0 + q) * h;
+            const uint16_t *dy = dYrows + (size_t)(r0 + q) * h;
+            for (int j = 0; j < hff; ++j) {
+                double sg = 0.0, su = 0.0, da = 0.0;
+                for (int i = 0; i < h; ++i) {
+                    double xi = bf(x[i]);
+                    sg += xi * bf(wg[(size_t)j * h + i]);
+                    su += xi * bf(wu[(size_t)j * h + i]);
+                    da += bf(dy[i]) * bf(wd[(size_t)i * hff + j]);
+                }
+                double sig = sigmoid(sg);
+                size_t o = (size_t)q * hff + j;
+                Gt[o] = sg; U[o] = su; Aa[o] = sg * sig * su;
+                dGt[o] = da * su * (sig * (1.0 + sg * (1.0 - sig)));
+                dU[o] = da * (sg * sig);
+            }
+            for (int i = 0; i < h; ++i) {
+                double s = 0.0;
+                for (int j = 0; j < hff; ++j)
+                    s += dGt[(size_t)q * hff + j] * bf(wg[(size_t)j * h + i])
+                       + dU[(size_t)q * hff + j] * bf(wu[(size_t)j * h + i]);
+                dXrows[(size_t)(r0 + q) * h + i] = s;
+            }
+        }
+        double *gg = dWg + (size_t)e * hff * h, *gu = dWu + (size_t)e * hff * h;
+        double *gd = dWd + (size_t)e * h * hff;
+        #pragma omp parallel for schedule(static)
+        for (int j = 0; j < hff; ++j)
+            for (int i = 0; i < h; ++i) {
+                double s1 = 0.0, s2 = 0.0;
+                for (int q = 0; q < n; ++q) {
+                    double xi = bf(Xrows[(size_t)(r0 + q) * h + i]);
+                    s1 += dGt[(size_t)q * hff + j] * xi;
+                    s2 += dU[(size_t)q * hff + j] * xi;
+                }
+                gg[(size_t)j * h + i] += s1;
+                gu[(size_t)j * h + i] += s2;
+            }
+        #pragma omp parallel for schedule(static)
+        for (int i = 0; i < h; ++i)
+            for (int j = 0; j < hff; ++j) {
+                double s = 0.0;
+                for (int q = 0; q < n; ++q)
+                    s += bf(dYrows[(size_t)(r0 + q) * h + i]) * Aa[(size_t)q * hff + j];
+                gd[(size_t)i * hff + j] += s;
+            }
+        free(Gt); free(U); free(Aa); free(dGt); free(dU);
+    }
+}
+
+/* Unpermute + gate-weighted combine (Section 2.1: the outputs of a token's selected */
+/* experts are combined): Out[t] = sum_s gate[t][s] * Yrows[row_of[t*k+s]].           */
+/* gates == NULL means every gate is 1 (the backward of the row gather).              */
+void oracle_combine_fwd(const double *Yrows, const float *gates, const int32_t *row_of,
+                        int T, int k, int h, double *Out)
+{
+    for (int t = 0; t < T; ++t)
+        for (int i = 0; i < h; ++i) {
+            double s = 0.0;
+            for (int j = 0; j < k; ++j) {
+                double gt = gates ? (double)gates[t * k + j] : 1.0;
+                s += gt * Yrows[(size_t)row_of[t * k + j] * h + i];
+            }
+            Out[(size_t)t * h + i] = s;
+        }
+}
+
+/* Backward of the combine: dYrows[row] = gate * dOut[t]; dgate[t][s] = <dOut[t], Yrows[row]>. */
+void oracle_combine_bwd(const double *dOut, const double *Yrows, const float *gates,
+                        const int32_t *row_of, int T, int k, int h, double *dYrows, double *dgate)
+{
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < k; ++j) {
+            size_t row = (size_t)row_of[t * k + j];
+            double gt = (double)gates[t * k + j], dot = 0.0;
+            for (int i = 0; i < h; ++i) {
+                dYrows[row * h + i] = gt * dOut[(size_t)t * h + i];
+                dot += dOut[(size_t)t * h + i] * Yrows[row * h + i];
+            }
+            dgate[t * k + j] = dot;
+        }
+}
