@@ -1,0 +1,208 @@
+/*
+ * relibra.h -- C ABI of the replay-guided MoE expert-layer path for one AMD MI355X (gfx950).
+ *
+ * The path: replayed top-k routing ids -> per-expert load histogram -> inter-batch expert
+ * reordering + intra-batch expert replication plan -> token permutation into
+ * expert/replica-grouped rows -> SwiGLU expert FFN forward / backward as grouped bf16 MFMA
+ * GEMMs -> unpermute + gate-weighted combine.  "Simulated EP": the groups of every
+ * expert-parallel rank live on the one GPU; a [g_begin, g_end) range selects one rank's share.
+ *
+ * Conventions
+ *  - Every pointer is marked "dev" (device memory, the caller's allocation) or "host".
+ *    The library allocates no device memory and keeps no state between calls.
+ *  - Device work is enqueued on `stream` (a hipStream_t) and not waited for.  Only
+ *    relibra_plan is synchronous: it is host code with host inputs and outputs.
+ *  - bf16 tensors are passed as `void*` to 2-byte elements, row-major, last index contiguous.
+ *  - Return value: RELIBRA_OK or a negative status.  Bad contents of device tables are
+ *    found by the kernels themselves: they skip the offending work (no out-of-bounds access)
+ *    and OR a bit into *err_flag_dev, which the caller zeroes beforehand and reads back when
+ *    it next synchronises.
+ *  - Notation follows the paper: E experts, top-k, T tokens per micro-batch, N = T*k routed
+ *    rows, EP ranks, M = E/EP home experts per rank, r replica slots per rank,
+ *    G = EP*(M+r) groups (rank-major: M home slots then r replica slots per rank),
+ *    h hidden size, hff = h' expert intermediate size.
+ */
+#ifndef RELIBRA_H
+#define RELIBRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *relibra_stream;
+
+enum {
+    RELIBRA_OK = 0,
+    RELIBRA_EINVAL = -1,      /* a size or pointer argument is unusable                   */
+    RELIBRA_ERANGE = -2,      /* a host table holds a value outside its range             */
+    RELIBRA_EWORKSPACE = -3,  /* workspace_bytes is below relibra_workspace_bytes(...)    */
+    RELIBRA_EHIP = -4,        /* a HIP runtime call failed                                */
+    RELIBRA_EUNSUPPORTED = -5 /* shape outside what the kernels are built for             */
+};
+
+/* bits OR-ed into *err_flag_dev by kernels */
+enum {
+    RELIBRA_ERR_ID_RANGE = 1,    /* an expert id outside [0,E)                               */
+    RELIBRA_ERR_PLAN_COVER = 2,  /* plan tables do not cover an assignment (permute)         */
+    RELIBRA_ERR_GROUP_TABLE = 4  /* group_offset / group_expert / dw_slot tables inconsistent */
+};
+
+/* which = */
+enum { RELIBRA_WS_PERMUTE = 0, RELIBRA_WS_FFN_FWD = 1, RELIBRA_WS_FFN_BWD = 2 };
+
+/* flags of relibra_moe_ffn_bwd */
+enum {
+    RELIBRA_BWD_ACCUMULATE = 1,     /* home dW += this micro-batch's gradient (else overwrite) */
+    RELIBRA_BWD_NO_REPLICA_SUM = 2  /* leave replica-slot dW where it is (partial group range) */
+};
+
+/* modes of relibra_unpermute_combine */
+enum { RELIBRA_COMBINE_FWD = 0, RELIBRA_COMBINE_BWD = 1, RELIBRA_COMBINE_SUM = 2 };
+
+/*
+ * Per-expert load histogram (paper Eq. 1: l_e = tokens routed to expert e), one histogram per
+ * micro-batch in a single launch.
+ *   ids_dev    [n_mb, T, k] int32, dev, in   replayed top-k expert ids (Section 2.3)
+ *   counts_dev [n_mb, E]    int32, dev, out  overwritten
+ *   err_flag_dev            int32, dev, in/out  RELIBRA_ERR_ID_RANGE on an id outside [0,E);
+ *                                              such ids are not counted
+ * Limits: 1 <= E <= 4096, 1 <= k <= E.  Empty input (n_mb*T == 0) is a no-op on counts of size 0,
+ * or zeroes counts when only T == 0.
+ */
+int relibra_route_hist(const int32_t *ids_dev, int n_mb, int T, int k, int E,
+                       int32_t *counts_dev, int32_t *err_flag_dev, relibra_stream stream);
+
+/*
+ * Load-balancing plan (paper Section 4: inter-batch expert reordering, Algorithm 1 with a
+ * deterministic steepest swap descent in place of random annealing moves; Section 5.2:
+ * intra-batch expert replication, Algorithm 2, with the token-split LP solved exactly in
+ * integers).  Objective: computation load only (Eq. 1), i.e. the largest number of routed rows
+ * any rank serves.  All pointers are HOST memory; the call is synchronous and deterministic.
+ *
+ *   counts_host      [n_mb, E] int32  in   histograms of one training batch
+ *   ranks_per_node                    in   replicas stay inside a node (Section 5.2, G(e))
+ *   r                                 in   replica slots per rank (Eq. 11)
+ *   expert_to_slot   [E]              out  rank*M + local slot (local slots by ascending id);
+ *                                          the same for every micro-batch of the batch
+ *   replica_expert   [n_mb, EP, r]    out  expert held by each replica slot (ascending id), -1 empty
+ *   inst_ptr         [n_mb, E+1]      out  CSR over experts into the three inst_* tables
+ *   inst_rank/rows/group [n_mb, E+EP*r] out instances of each expert in ascending rank: rank,
+ *                                          rows served (the integer token split), group index;
+ *                                          the home instance is always listed; unused tail = -1/0/-1
+ *   group_expert     [n_mb, G]        out  expert of each group, -1 for an empty replica slot
+ *   group_offset     [n_mb, G+1]      out  exclusive prefix sum of rows per group; [G] = T*k
+ *   group_dw_slot    [n_mb, G]        out  weight-gradient slot of the group: e for a home group,
+ *                                          E + rank*r + j for replica slot j of a rank
+ *   max_load_before  [n_mb] int64     out  largest rank load, unplanned layout (e on rank e/M)
+ *   max_load_after   [n_mb] int64     out  largest rank load under the plan
+ * The reordering is kept only if it lowers sum_mb max_load_after; otherwise experts stay put.
+ * Errors: RELIBRA_EINVAL unless E % EP == 0, EP % ranks_per_node == 0, 1 <= k <= E, r >= 0,
+ * n_mb >= 1; RELIBRA_ERANGE on a negative count.
+ */
+int relibra_plan(const int32_t *counts_host, int n_mb, int E, int k, int EP, int ranks_per_node, int r,
+                 int32_t *expert_to_slot, int32_t *replica_expert,
+                 int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                 int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                 int64_t *max_load_before, int64_t *max_load_after);
+
+/*
+ * Token permutation of one micro-batch (Section 5.2, token splitting; the local half of the
+ * dispatch all-to-all, Section 2.1).  Assignment a = t*k + s with expert e = ids[a] has
+ * ordinal q among e's assignments in ascending a; the instances of e, in ascending rank, take
+ * consecutive runs of ordinals of inst_rows length; the assignment lands on row
+ * group_offset[inst_group[i]] + (q - rows of earlier instances).
+ *   ids_dev [T,k]; inst_ptr_dev [E+1]; inst_rows_dev, inst_group_dev [>= inst_ptr[E]];
+ *   group_offset_dev [G+1]: one micro-batch's slices of the plan tables, dev, in
+ *   X_dev      [T, h] bf16, dev, in  (may be NULL together with Xrows_dev: indices only)
+ *   row_of_dev [N] int32, dev, out   assignment -> row
+ *   src_of_dev [N] int32, dev, out   row -> assignment (inverse)
+ *   Xrows_dev  [N, h] bf16, dev, out Xrows[row] = X[src_of[row] / k]
+ *   workspace_dev: relibra_workspace_bytes(RELIBRA_WS_PERMUTE, ...) bytes, dev, scratch
+ * Limits: E <= 4096, h % 8 == 0, 16-byte aligned X / Xrows.
+ */
+int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
+                    const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                    const void *X_dev, int T, int k, int E, int G, int h,
+                    int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                    void *workspace_dev, size_t workspace_bytes,
+                    int32_t *err_flag_dev, relibra_stream stream);
+
+/*
+ * Expert FFN forward over groups [g_begin, g_end) (Section 4.1: three GEMMs, 6hh' flops per row).
+ * For every row x of a group whose expert is e:
+ *   Gt = Wg_e x,  U = Wu_e x,  A = silu(Gt) * U,  y = Wd_e A
+ * with bf16 operands, fp32 accumulation, and one rounding to bf16 of each stored tensor.
+ *   Xrows [n_rows, h] bf16 in;  Wg, Wu [E, hff, h] bf16 in;  Wd [E, h, hff] bf16 in
+ *   group_offset_dev [G+1], group_expert_dev [G] int32 in (groups with expert -1 or no rows are skipped)
+ *   Gt_save, U_save, A_save [n_rows, hff] bf16 out (kept for the backward pass)
+ *   Yrows [n_rows, h] bf16 out.  Rows of groups outside the range are left untouched.
+ *   n_rows: capacity of the row buffers; offsets beyond it raise RELIBRA_ERR_GROUP_TABLE.
+ * Limits: h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.
+ */
+int relibra_moe_ffn_fwd(const void *Xrows_dev, int n_rows,
+                        const int32_t *group_offset_dev, const int32_t *group_expert_dev,
+                        int G, int g_begin, int g_end, int E,
+                        const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
+                        void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Yrows_dev,
+                        void *workspace_dev, size_t workspace_bytes,
+                        int32_t *err_flag_dev, relibra_stream stream);
+
+/*
+ * Expert FFN backward over groups [g_begin, g_end).  With dy the upstream gradient of a row:
+ *   dA = Wd_e^T dy;  dGt = dA * U * silu'(Gt);  dU = dA * silu(Gt);  dx = Wg_e^T dGt + Wu_e^T dU
+ *   dWd += dy A^T;   dWg += dGt x^T;   dWu += dU x^T          (contraction over the group's rows)
+ * Each group writes the weight-gradient slot group_dw_slot[g]; slots >= E are replica slots,
+ * whose gradients are then added into the home expert's slot in ascending slot order
+ * (Section 5.1: replica gradients are pushed back and accumulated on the source GPU), unless
+ * RELIBRA_BWD_NO_REPLICA_SUM.  Home slots are overwritten, or added to with
+ * RELIBRA_BWD_ACCUMULATE (gradient accumulation over micro-batches, Section 2.1); a home group
+ * with no rows writes zeros (overwrite) or nothing (accumulate).  No float atomics: results
+ * are bit-reproducible.
+ *   dYrows, Xrows [n_rows,h]; Gt_save, U_save, A_save [n_rows,hff] bf16 in
+ *   dXrows [n_rows, h] bf16 out
+ *   dWg, dWu [n_dw_slots, hff, h], dWd [n_dw_slots, h, hff] fp32 in/out, n_dw_slots >= E
+ *   workspace_dev: relibra_workspace_bytes(RELIBRA_WS_FFN_BWD, ...) bytes (holds dGt, dU)
+ */
+int relibra_moe_ffn_bwd(const void *dYrows_dev, const void *Xrows_dev,
+                        const void *Gt_save_dev, const void *U_save_dev, const void *A_save_dev, int n_rows,
+                        const int32_t *group_offset_dev, const int32_t *group_expert_dev,
+                        const int32_t *group_dw_slot_dev,
+                        int G, int g_begin, int g_end, int E, int n_dw_slots,
+                        const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
+                        void *dXrows_dev, float *dWg_dev, float *dWu_dev, float *dWd_dev, int flags,
+                        void *workspace_dev, size_t workspace_bytes,
+                        int32_t *err_flag_dev, relibra_stream stream);
+
+/*
+ * Unpermute + gate-weighted combine and its backward (Section 2.1: the outputs of a token's
+ * selected experts are combined; the local half of the combine all-to-all).
+ *  mode RELIBRA_COMBINE_FWD: out_tok[t] = sum_s gates[t,s] * rows[row_of[t*k+s]]   (fp32 sum in
+ *        slot order, one rounding to bf16)
+ *  mode RELIBRA_COMBINE_SUM: same with every gate = 1 (backward of the row gather); gates unused
+ *  mode RELIBRA_COMBINE_BWD: out_rows[row_of[t*k+s]] = gates[t,s] * tok[t]  (bf16) and
+ *        dgate[t,s] = <tok[t], rows[row_of[t*k+s]]>  (fp32); tok = dOut, rows = Yrows
+ *   rows_dev [N,h] bf16 in; tok_dev [T,h] bf16 in (BWD only); gates_dev [T,k] fp32 in;
+ *   row_of_dev [N] int32 in; out_tok_dev [T,h] bf16 out (FWD, SUM); out_rows_dev [N,h] bf16 out
+ *   and dgate_dev [T,k] fp32 out (BWD).  Rows referenced must lie in [0, N): others are skipped
+ *   and flagged RELIBRA_ERR_PLAN_COVER.
+ * Limits: h % 8 == 0, 1 <= k <= 64.
+ */
+int relibra_unpermute_combine(int mode, const void *rows_dev, const void *tok_dev,
+                              const float *gates_dev, const int32_t *row_of_dev,
+                              int T, int k, int h,
+                              void *out_tok_dev, void *out_rows_dev, float *dgate_dev,
+                              int32_t *err_flag_dev, relibra_stream stream);
+
+/* Bytes of device scratch each call needs (0 on unusable sizes). */
+size_t relibra_workspace_bytes(int which, int T, int k, int E, int G, int h, int hff);
+
+/* Text for a status code (static storage). */
+const char *relibra_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

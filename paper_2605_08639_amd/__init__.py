@@ -1,0 +1,234 @@
+"""Thin Python binding of librelibra.so (see include/relibra.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels (or, for
+relibra_plan, its host C++).  PyTorch supplies device memory and the current HIP stream.
+There is no fallback: if the shared library is missing, importing the binding's functions
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librelibra.so")
+
+OK, EINVAL, ERANGE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
+WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD = 0, 1, 2
+BWD_ACCUMULATE, BWD_NO_REPLICA_SUM = 1, 2
+COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
+
+EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_permute", "relibra_moe_ffn_fwd",
+           "relibra_moe_ffn_bwd", "relibra_unpermute_combine", "relibra_workspace_bytes",
+           "relibra_status_string")
+
+_lib = None
+
+
+class RelibraError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__(f"{fn}: status {status} ({status_string(status)})")
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(hipcc, gfx950) first; there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        L.relibra_workspace_bytes.restype = C.c_size_t
+        L.relibra_status_string.restype = C.c_char_p
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().relibra_status_string(int(status)).decode()
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise RelibraError(fn, rc)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dp(t, dtype=None):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL)."""
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return C.c_void_p(t.data_ptr())
+
+
+def _hp(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def workspace_bytes(which, T, k, E, G, h, hff):
+    return int(lib().relibra_workspace_bytes(which, T, k, E, G, h, hff))
+
+
+def new_err_flag(device="cuda"):
+    return torch.zeros(1, dtype=torch.int32, device=device)
+
+
+# ---------------------------------------------------------------------------------------------
+def relibra_route_hist(ids, E, counts=None, err_flag=None):
+    """ids [n_mb,T,k] int32 (device) -> counts [n_mb,E] int32 (device)."""
+    n_mb, T, k = ids.shape
+    if counts is None:
+        counts = torch.empty((n_mb, E), dtype=torch.int32, device=ids.device)
+    if err_flag is None:
+        err_flag = new_err_flag(ids.device)
+    rc = lib().relibra_route_hist(_dp(ids, torch.int32), n_mb, T, k, E, _dp(counts, torch.int32),
+                                  _dp(err_flag, torch.int32), _stream())
+    _check("relibra_route_hist", rc)
+    return counts
+
+
+def relibra_plan(counts_host, k, EP, ranks_per_node, r):
+    """counts_host [n_mb,E] int32 numpy (host) -> dict of host numpy plan tables."""
+    counts_host = np.ascontiguousarray(counts_host, dtype=np.int32)
+    n_mb, E = counts_host.shape
+    M = E // EP if EP > 0 and E % EP == 0 else 0
+    G = max(EP * (M + r), 1) if EP > 0 and r >= 0 else 1
+    cap = max(E + max(EP, 0) * max(r, 0), 1)
+    out = dict(
+        expert_to_slot=np.empty(E, np.int32),
+        replica_expert=np.empty((n_mb, max(EP, 0), max(r, 0)), np.int32),
+        inst_ptr=np.empty((n_mb, E + 1), np.int32),
+        inst_rank=np.empty((n_mb, cap), np.int32),
+        inst_rows=np.empty((n_mb, cap), np.int32),
+        inst_group=np.empty((n_mb, cap), np.int32),
+        group_expert=np.empty((n_mb, G), np.int32),
+        group_offset=np.empty((n_mb, G + 1), np.int32),
+        group_dw_slot=np.empty((n_mb, G), np.int32),
+        max_load_before=np.empty(n_mb, np.int64),
+        max_load_after=np.empty(n_mb, np.int64),
+    )
+    rep = out["replica_expert"]
+    rc = lib().relibra_plan(_hp(counts_host), n_mb, E, k, EP, ranks_per_node, r,
+                            _hp(out["expert_to_slot"]), _hp(rep) if rep.size else C.c_void_p(0),
+                            _hp(out["inst_ptr"]), _hp(out["inst_rank"]), _hp(out["inst_rows"]),
+                            _hp(out["inst_group"]), _hp(out["group_expert"]), _hp(out["group_offset"]),
+                            _hp(out["group_dw_slot"]), _hp(out["max_load_before"]), _hp(out["max_load_after"]))
+    _check("relibra_plan", rc)
+    return out
+
+
+def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,
+                    row_of=None, src_of=None, Xrows=None, workspace=None, err_flag=None):
+    """One micro-batch: ids [T,k], plan tables (device int32), X [T,h] bf16 -> row_of, src_of, Xrows."""
+    T, k = ids.shape
+    N = T * k
+    h = 0 if X is None else X.shape[1]
+    dev = ids.device
+    if row_of is None:
+        row_of = torch.empty(N, dtype=torch.int32, device=dev)
+    if src_of is None:
+        src_of = torch.empty(N, dtype=torch.int32, device=dev)
+    if Xrows is None and X is not None:
+        Xrows = torch.empty((N, h), dtype=torch.bfloat16, device=dev)
+    need = workspace_bytes(WS_PERMUTE, T, k, E, G, h, 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_permute(_dp(ids, torch.int32), _dp(inst_ptr, torch.int32), _dp(inst_rows, torch.int32),
+                               _dp(inst_group, torch.int32), _dp(group_offset, torch.int32),
+                               _dp(X), T, k, E, G, h, _dp(row_of), _dp(src_of), _dp(Xrows),
+                               _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
+    _check("relibra_permute", rc)
+    return row_of, src_of, Xrows
+
+
+def relibra_moe_ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
+                        Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None):
+    """Xrows [n_rows,h] bf16, weights bf16 -> (Gt, U, A [n_rows,h'], Yrows [n_rows,h]) bf16."""
+    n_rows, h = Xrows.shape
+    E, hff = Wg.shape[0], Wg.shape[1]
+    G = group_expert.shape[0]
+    g_end = G if g_end is None else g_end
+    dev = Xrows.device
+    mk = lambda cols: torch.empty((n_rows, cols), dtype=torch.bfloat16, device=dev)
+    Gt = mk(hff) if Gt is None else Gt
+    U = mk(hff) if U is None else U
+    A = mk(hff) if A is None else A
+    Yrows = mk(h) if Yrows is None else Yrows
+    if workspace is None:
+        need = workspace_bytes(WS_FFN_FWD, max(n_rows, 1), 1, E, G, h, hff)
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_moe_ffn_fwd(_dp(Xrows, torch.bfloat16), n_rows, _dp(group_offset, torch.int32),
+                                   _dp(group_expert, torch.int32), G, g_begin, g_end, E,
+                                   _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
+                                   h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows),
+                                   _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
+    _check("relibra_moe_ffn_fwd", rc)
+    return Gt, U, A, Yrows
+
+
+def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, group_dw_slot,
+                        Wg, Wu, Wd, dWg, dWu, dWd, g_begin=0, g_end=None, flags=0,
+                        dXrows=None, workspace=None, err_flag=None):
+    """-> dXrows [n_rows,h] bf16; dWg, dWu [slots,h',h] and dWd [slots,h,h'] fp32 are written in place."""
+    n_rows, h = Xrows.shape
+    E, hff = Wg.shape[0], Wg.shape[1]
+    G = group_expert.shape[0]
+    g_end = G if g_end is None else g_end
+    dev = Xrows.device
+    if dXrows is None:
+        dXrows = torch.empty((n_rows, h), dtype=torch.bfloat16, device=dev)
+    if workspace is None:
+        need = workspace_bytes(WS_FFN_BWD, max(n_rows, 1), 1, E, G, h, hff)
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    n_slots = dWg.shape[0]
+    assert dWu.shape[0] == n_slots and dWd.shape[0] == n_slots
+    rc = lib().relibra_moe_ffn_bwd(_dp(dYrows, torch.bfloat16), _dp(Xrows, torch.bfloat16),
+                                   _dp(Gt, torch.bfloat16), _dp(U, torch.bfloat16), _dp(A, torch.bfloat16), n_rows,
+                                   _dp(group_offset, torch.int32), _dp(group_expert, torch.int32),
+                                   _dp(group_dw_slot, torch.int32), G, g_begin, g_end, E, n_slots,
+                                   _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
+                                   h, hff, _dp(dXrows), _dp(dWg, torch.float32), _dp(dWu, torch.float32),
+                                   _dp(dWd, torch.float32), int(flags),
+                                   _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
+    _check("relibra_moe_ffn_bwd", rc)
+    return dXrows
+
+
+def relibra_unpermute_combine(mode, rows, row_of, T, k, gates=None, tok=None,
+                              out_tok=None, out_rows=None, dgate=None, err_flag=None):
+    """FWD/SUM -> out_tok [T,h] bf16; BWD -> (out_rows [N,h] bf16, dgate [T,k] fp32)."""
+    h = rows.shape[1]
+    dev = rows.device
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    if mode == COMBINE_BWD:
+        if out_rows is None:
+            out_rows = torch.empty((T * k, h), dtype=torch.bfloat16, device=dev)
+        if dgate is None:
+            dgate = torch.empty((T, k), dtype=torch.float32, device=dev)
+    elif out_tok is None:
+        out_tok = torch.empty((T, h), dtype=torch.bfloat16, device=dev)
+    rc = lib().relibra_unpermute_combine(int(mode), _dp(rows, torch.bfloat16), _dp(tok), _dp(gates),
+                                         _dp(row_of, torch.int32), T, k, h, _dp(out_tok), _dp(out_rows),
+                                         _dp(dgate), _dp(err_flag), _stream())
+    _check("relibra_unpermute_combine", rc)
+    return (out_rows, dgate) if mode == COMBINE_BWD else out_tok

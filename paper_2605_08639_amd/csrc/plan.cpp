@@ -1,0 +1,394 @@
+// relibra_plan: host-side load-balancing solver (paper Sections 4 and 5.2).
+//
+// Stage 1 (per training batch) reorders experts across ranks: greedy LPT as the starting
+// state, then steepest descent over the pair-swap neighbourhood of Algorithm 1 with O(1)
+// incremental evaluation of a swap (Section 4.2, "incremental state update").
+// Stage 2 (per micro-batch, per node) is Algorithm 2: replicate the heaviest expert of the
+// bottleneck rank onto the least-loaded rank of the node that can take it, then re-solve the
+// token split; repeated until no slot helps.  One worker thread per micro-batch (Section 6).
+//
+// All arithmetic is integer; every choice has a fixed tie-break, so the plan is a pure
+// function of the histograms.
+#include "../../include/relibra.h"
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <numeric>
+#include <thread>
+#include <vector>
+
+namespace {
+
+using i64 = long long;
+using u128 = unsigned __int128;
+
+struct Cost {
+    i64 peak;
+    u128 sq;
+    bool operator<(const Cost &o) const { return peak < o.peak || (peak == o.peak && sq < o.sq); }
+};
+
+// ---------------------------------------------------------------- stage 1
+std::vector<int> lpt_start(const std::vector<i64> &load_of, int EP)
+{
+    const int E = (int)load_of.size(), M = E / EP;
+    std::vector<int> by_load(E);
+    std::iota(by_load.begin(), by_load.end(), 0);
+    std::stable_sort(by_load.begin(), by_load.end(),
+                     [&](int a, int b) { return load_of[a] > load_of[b]; });
+    std::vector<i64> L(EP, 0);
+    std::vector<int> room(EP, M), where(E, 0);
+    for (int e : by_load) {
+        int pick = -1;
+        for (int g = 0; g < EP; ++g)
+            if (room[g] > 0 && (pick < 0 || L[g] < L[pick])) pick = g;
+        where[e] = pick;
+        L[pick] += load_of[e];
+        --room[pick];
+    }
+    return where;
+}
+
+// Three largest rank loads with their ranks, so that "max over the ranks a swap does not
+// touch" is a constant-time lookup.
+struct Top3 {
+    i64 v[3];
+    int g[3];
+    void build(const std::vector<i64> &L)
+    {
+        for (int i = 0; i < 3; ++i) { v[i] = -1; g[i] = -1; }
+        for (int x = 0; x < (int)L.size(); ++x) {
+            i64 val = L[x];
+            int idx = x;
+            for (int i = 0; i < 3; ++i)
+                if (val > v[i]) { std::swap(val, v[i]); std::swap(idx, g[i]); }
+        }
+    }
+    i64 max_excluding(int a, int b) const
+    {
+        for (int i = 0; i < 3; ++i)
+            if (g[i] != a && g[i] != b) return v[i] < 0 ? 0 : v[i];
+        return 0;
+    }
+};
+
+Cost cost_of(const std::vector<i64> &L)
+{
+    Cost c{0, 0};
+    for (i64 x : L) { c.peak = std::max(c.peak, x); c.sq += (u128)x * (u128)x; }
+    return c;
+}
+
+Cost swap_descent(const std::vector<i64> &load_of, int EP, std::vector<int> &where)
+{
+    const int E = (int)load_of.size();
+    std::vector<i64> L(EP, 0);
+    for (int e = 0; e < E; ++e) L[where[e]] += load_of[e];
+    Cost cur = cost_of(L);
+    Top3 top;
+    for (;;) {
+        top.build(L);
+        bool have = false;
+        Cost best{0, 0};
+        int pa = -1, pb = -1;
+        for (int a = 0; a < E; ++a) {
+            const int ga = where[a];
+            const i64 la = load_of[a], La = L[ga];
+            for (int b = a + 1; b < E; ++b) {
+                const int gb = where[b];
+                if (gb == ga) continue;
+                const i64 d = load_of[b] - la;            // rank ga gains d, rank gb loses d
+                const i64 na = La + d, nb = L[gb] - d;
+                Cost c;
+                c.peak = std::max(std::max(na, nb), top.max_excluding(ga, gb));
+                c.sq = cur.sq - (u128)La * (u128)La - (u128)L[gb] * (u128)L[gb]
+                     + (u128)na * (u128)na + (u128)nb * (u128)nb;
+                if (!have || c < best) { have = true; best = c; pa = a; pb = b; }
+            }
+        }
+        if (!have || !(best < cur)) break;
+        const int ga = where[pa], gb = where[pb];
+        const i64 d = load_of[pb] - load_of[pa];
+        L[ga] += d;
+        L[gb] -= d;
+        where[pa] = gb;
+        where[pb] = ga;
+        cur = best;
+    }
+    return cur;
+}
+
+// ---------------------------------------------------------------- stage 2
+// One node: n ranks, experts listed in ascending global id.
+struct Node {
+    int n = 0, r = 0;
+    std::vector<i64> cnt;                  // tokens of each expert in this micro-batch
+    std::vector<int> home;                 // local home rank
+    std::vector<uint32_t> allowed;         // bit g set: expert may be served on local rank g
+    std::vector<std::vector<i64>> share;   // share[e][g]: tokens of e served on g
+    std::vector<i64> L;                    // rank loads
+
+    void recompute_loads()
+    {
+        std::fill(L.begin(), L.end(), 0);
+        for (size_t e = 0; e < cnt.size(); ++e)
+            for (int g = 0; g < n; ++g) L[g] += share[e][g];
+    }
+
+    // Token split for the current placement: move tokens along chains of ranks from a
+    // heavier rank to a lighter one while some chain joins two ranks whose loads differ by
+    // two or more.  The end state minimises the largest load (it is an optimum of the
+    // split LP of Section 5.2) and the sum of squares.  Order of moves: source = ranks by
+    // descending load, lower id first; breadth-first chains, neighbours in ascending rank,
+    // lowest expert id per hop; sink = lightest reached rank, lower id first.
+    void balance()
+    {
+        const int ne = (int)cnt.size();
+        std::vector<int> by_load(n), parent(n), via(n), bfs;
+        bfs.reserve(n);
+        for (;;) {
+            recompute_loads();
+            std::iota(by_load.begin(), by_load.end(), 0);
+            std::stable_sort(by_load.begin(), by_load.end(), [&](int a, int b) { return L[a] > L[b]; });
+            bool moved = false;
+            for (int u : by_load) {
+                uint32_t seen = 1u << u;
+                parent[u] = -1;
+                bfs.clear();
+                bfs.push_back(u);
+                for (size_t head = 0; head < bfs.size(); ++head) {
+                    const int w = bfs[head];
+                    uint32_t fresh = 0;
+                    for (int e = 0; e < ne; ++e) {        // ascending id: first hit = lowest expert
+                        if (share[e][w] <= 0) continue;
+                        uint32_t reach = allowed[e] & ~seen;
+                        while (reach) {
+                            const int v = __builtin_ctz(reach);
+                            reach &= reach - 1;
+                            seen |= 1u << v;
+                            fresh |= 1u << v;
+                            parent[v] = w;
+                            via[v] = e;
+                        }
+                    }
+                    while (fresh) {                        // neighbours join the queue in ascending rank
+                        bfs.push_back(__builtin_ctz(fresh));
+                        fresh &= fresh - 1;
+                    }
+                }
+                int sink = -1;
+                for (int g = 0; g < n; ++g)
+                    if (g != u && (seen >> g & 1) && (sink < 0 || L[g] < L[sink])) sink = g;
+                if (sink < 0 || L[sink] + 2 > L[u]) continue;
+                i64 d = (L[u] - L[sink]) / 2;
+                for (int x = sink; parent[x] >= 0; x = parent[x]) d = std::min(d, share[via[x]][parent[x]]);
+                for (int x = sink; parent[x] >= 0; x = parent[x]) {
+                    share[via[x]][parent[x]] -= d;
+                    share[via[x]][x] += d;
+                }
+                moved = true;
+                break;
+            }
+            if (!moved) return;
+        }
+    }
+
+    i64 solve()
+    {
+        const int ne = (int)cnt.size();
+        share.assign(ne, std::vector<i64>(n, 0));
+        allowed.assign(ne, 0);
+        L.assign(n, 0);
+        i64 total = 0;
+        for (int e = 0; e < ne; ++e) {
+            allowed[e] = 1u << home[e];
+            share[e][home[e]] = cnt[e];
+            total += cnt[e];
+        }
+        const i64 floor_load = (total + n - 1) / n;
+        std::vector<int> slots_used(n, 0);
+        std::vector<int> cand;
+        for (;;) {
+            recompute_loads();
+            const int gb = (int)(std::max_element(L.begin(), L.end()) - L.begin());   // first max
+            if (L[gb] <= floor_load) break;
+            cand.clear();
+            for (int e = 0; e < ne; ++e)
+                if (share[e][gb] > 0) cand.push_back(e);
+            std::stable_sort(cand.begin(), cand.end(),
+                             [&](int a, int b) { return share[a][gb] > share[b][gb]; });
+            int e_pick = -1, g_pick = -1;
+            for (int e : cand) {
+                for (int g = 0; g < n; ++g) {
+                    if ((allowed[e] >> g & 1) || slots_used[g] >= r) continue;
+                    if (g_pick < 0 || L[g] < L[g_pick]) g_pick = g;
+                }
+                if (g_pick >= 0) { e_pick = e; break; }
+            }
+            if (e_pick < 0) break;
+            allowed[e_pick] |= 1u << g_pick;
+            ++slots_used[g_pick];
+            balance();
+        }
+        for (int e = 0; e < ne; ++e)                       // drop replicas that got no tokens
+            for (int g = 0; g < n; ++g)
+                if (g != home[e] && (allowed[e] >> g & 1) && share[e][g] == 0) allowed[e] &= ~(1u << g);
+        recompute_loads();
+        return *std::max_element(L.begin(), L.end());
+    }
+};
+
+// Result of stage 2 for one micro-batch under a given placement.
+struct MbPlan {
+    i64 peak = 0;
+    std::vector<std::vector<std::pair<int, i64>>> inst;   // per expert: (rank, rows), ascending rank
+};
+
+MbPlan replicate_microbatch(const int32_t *cnt, const std::vector<int> &where, int E, int EP, int rpn, int r)
+{
+    MbPlan out;
+    out.inst.resize(E);
+    for (int base = 0; base < EP; base += rpn) {
+        Node nd;
+        nd.n = rpn;
+        nd.r = r;
+        std::vector<int> members;
+        for (int e = 0; e < E; ++e)
+            if (where[e] >= base && where[e] < base + rpn) {
+                members.push_back(e);
+                nd.cnt.push_back(cnt[e]);
+                nd.home.push_back(where[e] - base);
+            }
+        out.peak = std::max(out.peak, nd.solve());
+        for (size_t i = 0; i < members.size(); ++i)
+            for (int g = 0; g < rpn; ++g)
+                if (nd.allowed[i] >> g & 1) out.inst[members[i]].push_back({base + g, nd.share[i][g]});
+    }
+    return out;
+}
+
+std::vector<MbPlan> replicate_batch(const int32_t *counts, int n_mb, const std::vector<int> &where,
+                                    int E, int EP, int rpn, int r)
+{
+    std::vector<MbPlan> plans(n_mb);
+    unsigned hw = std::thread::hardware_concurrency();
+    int workers = (int)std::min<unsigned>(hw ? hw : 1u, (unsigned)n_mb);
+    workers = std::min(workers, 16);
+    if (workers <= 1) {
+        for (int mb = 0; mb < n_mb; ++mb)
+            plans[mb] = replicate_microbatch(counts + (size_t)mb * E, where, E, EP, rpn, r);
+        return plans;
+    }
+    std::vector<std::thread> pool;
+    for (int w = 0; w < workers; ++w)
+        pool.emplace_back([&, w]() {
+            for (int mb = w; mb < n_mb; mb += workers)
+                plans[mb] = replicate_microbatch(counts + (size_t)mb * E, where, E, EP, rpn, r);
+        });
+    for (auto &t : pool) t.join();
+    return plans;
+}
+
+}  // namespace
+
+extern "C" int relibra_plan(const int32_t *counts, int n_mb, int E, int k, int EP, int rpn, int r,
+                            int32_t *expert_to_slot, int32_t *replica_expert,
+                            int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                            int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                            int64_t *max_load_before, int64_t *max_load_after)
+{
+    if (!counts || !expert_to_slot || !inst_ptr || !inst_rank || !inst_rows || !inst_group ||
+        !group_expert || !group_offset || !group_dw_slot || !max_load_before || !max_load_after)
+        return RELIBRA_EINVAL;
+    if (n_mb < 1 || E < 1 || EP < 1 || E % EP || rpn < 1 || rpn > 32 || EP % rpn || r < 0 || k < 1 || k > E)
+        return RELIBRA_EINVAL;
+    if (r > 0 && !replica_expert) return RELIBRA_EINVAL;
+    const int M = E / EP, S = M + r, G = EP * S, inst_cap = E + EP * r;
+
+    std::vector<i64> batch_load(E, 0);
+    for (int mb = 0; mb < n_mb; ++mb)
+        for (int e = 0; e < E; ++e) {
+            const int32_t c = counts[(size_t)mb * E + e];
+            if (c < 0) return RELIBRA_ERANGE;
+            batch_load[e] += c;
+        }
+
+    // stage 1: descent from the unplanned layout and from LPT; ties keep the unplanned one
+    std::vector<int> unplanned(E);
+    for (int e = 0; e < E; ++e) unplanned[e] = e / M;
+    std::vector<int> from_id = unplanned, from_lpt = lpt_start(batch_load, EP);
+    const Cost c_id = swap_descent(batch_load, EP, from_id);
+    const Cost c_lpt = swap_descent(batch_load, EP, from_lpt);
+    const std::vector<int> &reordered = (c_lpt < c_id) ? from_lpt : from_id;
+
+    // stage 2 under both placements; the reordering must pay for itself over the batch
+    std::vector<MbPlan> with_id = replicate_batch(counts, n_mb, unplanned, E, EP, rpn, r);
+    bool keep_reorder = false;
+    std::vector<MbPlan> with_new;
+    if (reordered != unplanned) {
+        with_new = replicate_batch(counts, n_mb, reordered, E, EP, rpn, r);
+        i64 j_id = 0, j_new = 0;
+        for (int mb = 0; mb < n_mb; ++mb) { j_id += with_id[mb].peak; j_new += with_new[mb].peak; }
+        keep_reorder = j_new < j_id;
+    }
+    const std::vector<int> &where = keep_reorder ? reordered : unplanned;
+    const std::vector<MbPlan> &plans = keep_reorder ? with_new : with_id;
+
+    std::vector<int> filled(EP, 0);
+    for (int e = 0; e < E; ++e) expert_to_slot[e] = where[e] * M + filled[where[e]]++;
+
+    for (int mb = 0; mb < n_mb; ++mb) {
+        const MbPlan &P = plans[mb];
+        int32_t *gexp = group_expert + (size_t)mb * G;
+        int32_t *goff = group_offset + (size_t)mb * (G + 1);
+        int32_t *gslot = group_dw_slot + (size_t)mb * G;
+        int32_t *rep = r ? replica_expert + (size_t)mb * EP * r : nullptr;
+        int32_t *iptr = inst_ptr + (size_t)mb * (E + 1);
+        int32_t *irank = inst_rank + (size_t)mb * inst_cap;
+        int32_t *irows = inst_rows + (size_t)mb * inst_cap;
+        int32_t *igrp = inst_group + (size_t)mb * inst_cap;
+        std::vector<i64> rows(G, 0);
+        std::fill(gexp, gexp + G, -1);
+        for (int g = 0; g < G; ++g) gslot[g] = (g % S < M) ? -1 : E + (g / S) * r + (g % S - M);
+        if (rep) std::fill(rep, rep + (size_t)EP * r, -1);
+        std::fill(irank, irank + inst_cap, -1);
+        std::fill(irows, irows + inst_cap, 0);
+        std::fill(igrp, igrp + inst_cap, -1);
+        std::vector<int> next_rep(EP, 0);
+        int p = 0;
+        for (int e = 0; e < E; ++e) {                      // ascending e fills replica slots in id order
+            iptr[e] = p;
+            for (const auto &ir : P.inst[e]) {
+                const int rk = ir.first;
+                int grp;
+                if (rk == where[e]) {
+                    grp = rk * S + expert_to_slot[e] % M;
+                    gslot[grp] = e;
+                } else {
+                    const int j = next_rep[rk]++;
+                    grp = rk * S + M + j;
+                    rep[rk * r + j] = e;
+                }
+                gexp[grp] = e;
+                rows[grp] = ir.second;
+                irank[p] = rk;
+                irows[p] = (int32_t)ir.second;
+                igrp[p] = grp;
+                ++p;
+            }
+        }
+        iptr[E] = p;
+        goff[0] = 0;
+        for (int g = 0; g < G; ++g) goff[g + 1] = goff[g] + (int32_t)rows[g];
+        i64 worst = 0;
+        for (int g = 0; g < EP; ++g) {
+            i64 s = 0;
+            for (int e = g * M; e < (g + 1) * M; ++e) s += counts[(size_t)mb * E + e];
+            worst = std::max(worst, s);
+        }
+        max_load_before[mb] = worst;
+        max_load_after[mb] = P.peak;
+    }
+    return RELIBRA_OK;
+}

@@ -1,0 +1,401 @@
+// Routing-side kernels: load histogram, token permutation, unpermute + combine.
+// All three are bound by HBM traffic (or, for the index parts, by launch latency); none is
+// a contraction, so there is no MFMA here: the work is coalesced 16-byte accesses,
+// wave-level ballots and LDS-private counters.
+#include "common.h"
+
+namespace relibra {
+
+constexpr int kMaxExperts = 4096;
+constexpr int kHistThreads = 256;
+constexpr int kHistChunk = 8192;     // assignments per histogram block
+constexpr int kUnit = 512;           // assignments per permutation unit (one wave)
+constexpr int kPermThreads = 256;    // 4 waves = 4 units per block
+
+// ---------------------------------------------------------------- fill
+__global__ void fill_i32_kernel(int32_t *p, size_t n, int32_t v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------- histogram (Eq. 1)
+// grid = n_mb * blocks_per_mb.  A block owns a contiguous chunk of one micro-batch's ids,
+// counts them in an LDS-private histogram (LDS atomics absorb the hot-expert conflicts) and
+// adds its non-zero bins to the micro-batch's global histogram with integer atomics, so the
+// result does not depend on the order in which blocks finish.
+__global__ void __launch_bounds__(kHistThreads)
+hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int blocks_per_mb,
+            int32_t *__restrict__ counts, int32_t *err_flag)
+{
+    extern __shared__ int32_t bins[];
+    const int mb = blockIdx.x / blocks_per_mb;
+    const int chunk = blockIdx.x % blocks_per_mb;
+    for (int e = threadIdx.x; e < E; e += kHistThreads) bins[e] = 0;
+    __syncthreads();
+    const int32_t *src = ids + (size_t)mb * per_mb;
+    const int lo = chunk * kHistChunk;
+    const int hi = min(per_mb, lo + kHistChunk);
+    bool bad = false;
+    if ((per_mb & 3) == 0) {          // 16-byte aligned rows of the id tensor
+        const int4 *v = reinterpret_cast<const int4 *>(src);
+        for (int i = lo / 4 + threadIdx.x; i < hi / 4; i += kHistThreads) {
+            const int4 q = v[i];
+            const int e4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if ((unsigned)e4[j] < (unsigned)E) atomicAdd(&bins[e4[j]], 1);
+                else bad = true;
+            }
+        }
+    } else {
+        for (int i = lo + threadIdx.x; i < hi; i += kHistThreads) {
+            const int e = src[i];
+            if ((unsigned)e < (unsigned)E) atomicAdd(&bins[e], 1);
+            else bad = true;
+        }
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_ID_RANGE);
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kHistThreads) {
+        const int c = bins[e];
+        if (c) atomicAdd(&counts[(size_t)mb * E + e], c);
+    }
+}
+
+// ---------------------------------------------------------------- permutation indices
+// The stable partition is a counting sort over experts in three passes:
+//   1. every wave counts its 512-assignment unit per expert        -> unit_cnt[unit][e]
+//   2. an exclusive scan over units, per expert                    -> unit_cnt[unit][e] = base
+//   3. every wave walks its unit in order, 64 assignments at a time; a ballot-built mask of
+//      the lanes holding the same expert gives each lane its ordinal inside the step, an LDS
+//      counter per expert carries the ordinal across steps.
+// The ordinal is then mapped through the expert's instance list to a row (Section 5.2).
+
+__global__ void __launch_bounds__(kPermThreads)
+perm_count_kernel(const int32_t *__restrict__ ids, int N, int E, int32_t *__restrict__ unit_cnt,
+                  int32_t *__restrict__ src_of, int32_t *err_flag)
+{
+    extern __shared__ int32_t lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int32_t *bins = lds + wave * E;
+    const int unit = blockIdx.x * (kPermThreads / 64) + wave;
+    for (int e = lane; e < E; e += 64) bins[e] = 0;
+    __builtin_amdgcn_wave_barrier();
+    const int lo = unit * kUnit, hi = min(N, lo + kUnit);
+    bool bad = false;
+    for (int a = lo + lane; a < hi; a += 64) {
+        const int e = ids[a];
+        if ((unsigned)e < (unsigned)E) atomicAdd(&bins[e], 1);
+        else bad = true;
+        src_of[a] = -1;                // rows nobody claims stay marked
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_ID_RANGE);
+    __builtin_amdgcn_wave_barrier();
+    if (lo < N)
+        for (int e = lane; e < E; e += 64) unit_cnt[(size_t)unit * E + e] = bins[e];
+}
+
+__global__ void perm_scan_kernel(int32_t *unit_cnt, int n_units, int E)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    int run = 0;
+    for (int u = 0; u < n_units; ++u) {
+        const int c = unit_cnt[(size_t)u * E + e];
+        unit_cnt[(size_t)u * E + e] = run;
+        run += c;
+    }
+}
+
+__global__ void __launch_bounds__(kPermThreads)
+perm_rank_kernel(const int32_t *__restrict__ ids, int N, int E, int G, int ebits,
+                 const int32_t *__restrict__ unit_base,
+                 const int32_t *__restrict__ inst_ptr, const int32_t *__restrict__ inst_rows,
+                 const int32_t *__restrict__ inst_group, const int32_t *__restrict__ group_offset,
+                 int32_t *__restrict__ row_of, int32_t *__restrict__ src_of, int32_t *err_flag)
+{
+    extern __shared__ int32_t lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int32_t *next = lds + wave * E;        // next ordinal of each expert, private to the wave
+    const int unit = blockIdx.x * (kPermThreads / 64) + wave;
+    const int lo = unit * kUnit, hi = min(N, lo + kUnit);
+    if (lo < N)
+        for (int e = lane; e < E; e += 64) next[e] = unit_base[(size_t)unit * E + e];
+    __builtin_amdgcn_wave_barrier();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int flags = 0;
+    for (int base = lo; base < hi; base += 64) {
+        const int a = base + lane;
+        const bool live = a < hi;
+        const int e_raw = live ? ids[a] : -1;
+        const bool ok = live && (unsigned)e_raw < (unsigned)E;
+        const int e = ok ? e_raw : 0;
+        // lanes with the same expert: intersect ballots bit by bit
+        uint64_t same = __ballot(ok);
+        for (int b = 0; b < ebits; ++b) {
+            const uint64_t vote = __ballot((e >> b) & 1);
+            same &= ((e >> b) & 1) ? vote : ~vote;
+        }
+        int q = 0;
+        if (ok) {
+            const int before = __popcll(same & lt_mask);
+            const int leader = __ffsll((long long)same) - 1;
+            int start = 0;
+            if (lane == leader) {          // one lane per expert touches the counter
+                start = next[e];
+                next[e] = start + __popcll(same);
+            }
+            start = __shfl(start, leader);
+            q = start + before;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (ok) {
+            int i = inst_ptr[e];
+            const int end = inst_ptr[e + 1];
+            int skipped = 0, row = -1;
+            for (; i < end; ++i) {
+                const int n = inst_rows[i];
+                if (q < skipped + n) {
+                    const int g = inst_group[i];
+                    if ((unsigned)g < (unsigned)G) row = group_offset[g] + (q - skipped);
+                    break;
+                }
+                skipped += n;
+            }
+            if ((unsigned)row < (unsigned)N) {
+                row_of[a] = row;
+                src_of[row] = a;
+            } else {
+                row_of[a] = -1;
+                flags |= RELIBRA_ERR_PLAN_COVER;
+            }
+        } else if (live) {
+            row_of[a] = -1;
+            flags |= RELIBRA_ERR_ID_RANGE;
+        }
+    }
+    if (flags) atomicOr(err_flag, flags);
+}
+
+// Row gather: Xrows[row] = X[src_of[row] / k], 16 bytes per thread, consecutive threads on
+// consecutive 16-byte pieces of a row.
+__global__ void __launch_bounds__(256)
+gather_rows_kernel(const uint4 *__restrict__ X, const int32_t *__restrict__ src_of, int N, int T, int k,
+                   int vec_per_row, uint4 *__restrict__ Xrows)
+{
+    const size_t total = (size_t)N * vec_per_row;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int row = (int)(i / vec_per_row), c = (int)(i % vec_per_row);
+        const int a = src_of[row];
+        if (a < 0) continue;
+        const int t = a / k;
+        if (t >= T) continue;
+        Xrows[i] = X[(size_t)t * vec_per_row + c];
+    }
+}
+
+// ---------------------------------------------------------------- combine
+__device__ __forceinline__ void unpack8(const uint4 &v, float *f)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f[2 * j] = __uint_as_float(w[j] << 16);
+        f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ uint4 pack8(const float *f)
+{
+    uint4 v;
+    v.x = pack2bf(f[0], f[1]);
+    v.y = pack2bf(f[2], f[3]);
+    v.z = pack2bf(f[4], f[5]);
+    v.w = pack2bf(f[6], f[7]);
+    return v;
+}
+
+// out[t] = sum_s gate[t,s] * rows[row_of[t,s]]; fp32 accumulation in slot order.
+template <bool GATED>
+__global__ void __launch_bounds__(256)
+combine_fwd_kernel(const uint4 *__restrict__ rows, const float *__restrict__ gates,
+                   const int32_t *__restrict__ row_of, int T, int k, int N, int vec_per_row,
+                   uint4 *__restrict__ out, int32_t *err_flag)
+{
+    const size_t total = (size_t)T * vec_per_row;
+    bool bad = false;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int t = (int)(i / vec_per_row), c = (int)(i % vec_per_row);
+        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int s = 0; s < k; ++s) {
+            const int row = row_of[(size_t)t * k + s];
+            if ((unsigned)row >= (unsigned)N) { bad = true; continue; }
+            const float g = GATED ? gates[(size_t)t * k + s] : 1.0f;
+            float f[8];
+            unpack8(rows[(size_t)row * vec_per_row + c], f);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = fmaf(g, f[j], acc[j]);
+        }
+        out[i] = pack8(acc);
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_PLAN_COVER);
+}
+
+// One wave per assignment (t,s): dYrows[row] = gate * dOut[t]; dgate = <dOut[t], Yrows[row]>.
+__global__ void __launch_bounds__(256)
+combine_bwd_kernel(const uint4 *__restrict__ Yrows, const uint4 *__restrict__ dOut,
+                   const float *__restrict__ gates, const int32_t *__restrict__ row_of,
+                   int N, int vec_per_row, int k, uint4 *__restrict__ dYrows, float *__restrict__ dgate,
+                   int32_t *err_flag)
+{
+    const int lane = threadIdx.x & 63;
+    const int a = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (a >= N) return;
+    const int row = row_of[a];
+    if ((unsigned)row >= (unsigned)N) {
+        if (lane == 0) { atomicOr(err_flag, RELIBRA_ERR_PLAN_COVER); dgate[a] = 0.0f; }
+        return;
+    }
+    const int t = a / k;
+    const float g = gates[a];
+    float dot = 0.0f;
+    for (int c = lane; c < vec_per_row; c += 64) {
+        float d[8], y[8], o[8];
+        unpack8(dOut[(size_t)t * vec_per_row + c], d);
+        unpack8(Yrows[(size_t)row * vec_per_row + c], y);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            o[j] = g * d[j];
+            dot = fmaf(d[j], y[j], dot);
+        }
+        dYrows[(size_t)row * vec_per_row + c] = pack8(o);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+    if (lane == 0) dgate[a] = dot;
+}
+
+inline int grid_for(size_t work_items, int per_block, int cap)
+{
+    size_t b = (work_items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > (size_t)cap) b = cap;
+    return (int)b;
+}
+
+}  // namespace relibra
+
+using namespace relibra;
+
+extern "C" int relibra_route_hist(const int32_t *ids_dev, int n_mb, int T, int k, int E,
+                                  int32_t *counts_dev, int32_t *err_flag_dev, relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (n_mb < 0 || T < 0 || k < 1 || E < 1 || E > kMaxExperts || k > E) return RELIBRA_EINVAL;
+    if ((size_t)T * k > 0x7fffffffull) return RELIBRA_EINVAL;
+    if (n_mb == 0) return RELIBRA_OK;
+    if (!counts_dev || !err_flag_dev) return RELIBRA_EINVAL;
+    const size_t n_counts = (size_t)n_mb * E;
+    fill_i32_kernel<<<(unsigned)((n_counts + 255) / 256), 256, 0, stream>>>(counts_dev, n_counts, 0);
+    RELIBRA_HIP_TRY(launch_check());
+    const int per_mb = T * k;
+    if (per_mb == 0) return RELIBRA_OK;
+    if (!ids_dev) return RELIBRA_EINVAL;
+    const int blocks_per_mb = (per_mb + kHistChunk - 1) / kHistChunk;
+    hist_kernel<<<(unsigned)(n_mb * blocks_per_mb), kHistThreads, E * sizeof(int32_t), stream>>>(
+        ids_dev, per_mb, E, blocks_per_mb, counts_dev, err_flag_dev);
+    RELIBRA_HIP_TRY(launch_check());
+    return RELIBRA_OK;
+}
+
+extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
+                               const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                               const void *X_dev, int T, int k, int E, int G, int h,
+                               int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                               void *workspace_dev, size_t workspace_bytes,
+                               int32_t *err_flag_dev, relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (T < 0 || k < 1 || E < 1 || E > kMaxExperts || k > E || G < 1 || h < 0) return RELIBRA_EINVAL;
+    if ((size_t)T * k > 0x7fffffffull) return RELIBRA_EINVAL;
+    const int N = T * k;
+    if (N == 0) return RELIBRA_OK;
+    if (!ids_dev || !inst_ptr_dev || !inst_rows_dev || !inst_group_dev || !group_offset_dev ||
+        !row_of_dev || !src_of_dev || !err_flag_dev || !workspace_dev)
+        return RELIBRA_EINVAL;
+    const bool with_rows = X_dev != nullptr || Xrows_dev != nullptr;
+    if (with_rows && (!X_dev || !Xrows_dev || h < 8 || h % 8 || !aligned16(X_dev) || !aligned16(Xrows_dev)))
+        return RELIBRA_EINVAL;
+    if (workspace_bytes < relibra_workspace_bytes(RELIBRA_WS_PERMUTE, T, k, E, G, h, 0)) return RELIBRA_EWORKSPACE;
+    int32_t *unit_cnt = (int32_t *)workspace_dev;
+    const int n_units = (N + kUnit - 1) / kUnit;
+    const int blocks = (n_units + 3) / 4;
+    const size_t lds = (size_t)4 * E * sizeof(int32_t);
+    int ebits = 0;
+    while ((1 << ebits) < E) ++ebits;
+    perm_count_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, unit_cnt, src_of_dev, err_flag_dev);
+    RELIBRA_HIP_TRY(launch_check());
+    perm_scan_kernel<<<(E + 255) / 256, 256, 0, stream>>>(unit_cnt, n_units, E);
+    RELIBRA_HIP_TRY(launch_check());
+    perm_rank_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, G, ebits, unit_cnt, inst_ptr_dev,
+                                                            inst_rows_dev, inst_group_dev, group_offset_dev,
+                                                            row_of_dev, src_of_dev, err_flag_dev);
+    RELIBRA_HIP_TRY(launch_check());
+    if (with_rows) {
+        const int vpr = h / 8;
+        const int grid = grid_for((size_t)N * vpr, 256 * 4, 256 * 64);
+        gather_rows_kernel<<<grid, 256, 0, stream>>>((const uint4 *)X_dev, src_of_dev, N, T, k, vpr,
+                                                     (uint4 *)Xrows_dev);
+        RELIBRA_HIP_TRY(launch_check());
+    }
+    return RELIBRA_OK;
+}
+
+extern "C" int relibra_unpermute_combine(int mode, const void *rows_dev, const void *tok_dev,
+                                         const float *gates_dev, const int32_t *row_of_dev,
+                                         int T, int k, int h,
+                                         void *out_tok_dev, void *out_rows_dev, float *dgate_dev,
+                                         int32_t *err_flag_dev, relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (T < 0 || k < 1 || k > 64 || h < 8 || h % 8) return RELIBRA_EINVAL;
+    if ((size_t)T * k > 0x7fffffffull) return RELIBRA_EINVAL;
+    if (mode != RELIBRA_COMBINE_FWD && mode != RELIBRA_COMBINE_BWD && mode != RELIBRA_COMBINE_SUM)
+        return RELIBRA_EINVAL;
+    if (T == 0) return RELIBRA_OK;
+    if (!rows_dev || !row_of_dev || !err_flag_dev || !aligned16(rows_dev)) return RELIBRA_EINVAL;
+    const int N = T * k, vpr = h / 8;
+    if (mode == RELIBRA_COMBINE_BWD) {
+        if (!tok_dev || !gates_dev || !out_rows_dev || !dgate_dev || !aligned16(tok_dev) || !aligned16(out_rows_dev))
+            return RELIBRA_EINVAL;
+        combine_bwd_kernel<<<(N + 3) / 4, 256, 0, stream>>>((const uint4 *)rows_dev, (const uint4 *)tok_dev,
+                                                            gates_dev, row_of_dev, N, vpr, k,
+                                                            (uint4 *)out_rows_dev, dgate_dev, err_flag_dev);
+    } else {
+        if (!out_tok_dev || !aligned16(out_tok_dev)) return RELIBRA_EINVAL;
+        const int grid = grid_for((size_t)T * vpr, 256, 256 * 64);
+        if (mode == RELIBRA_COMBINE_FWD) {
+            if (!gates_dev) return RELIBRA_EINVAL;
+            combine_fwd_kernel<true><<<grid, 256, 0, stream>>>((const uint4 *)rows_dev, gates_dev, row_of_dev,
+                                                               T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev);
+        } else {
+            combine_fwd_kernel<false><<<grid, 256, 0, stream>>>((const uint4 *)rows_dev, nullptr, row_of_dev,
+                                                                T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev);
+        }
+    }
+    RELIBRA_HIP_TRY(launch_check());
+    return RELIBRA_OK;
+}
+
+extern "C" const char *relibra_status_string(int status)
+{
+    switch (status) {
+    case RELIBRA_OK: return "ok";
+    case RELIBRA_EINVAL: return "invalid argument";
+    case RELIBRA_ERANGE: return "table value out of range";
+    case RELIBRA_EWORKSPACE: return "workspace too small";
+    case RELIBRA_EHIP: return "HIP runtime error";
+    case RELIBRA_EUNSUPPORTED: return "unsupported shape";
+    default: return "unknown status";
+    }
+}

@@ -1,0 +1,307 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle on the same seeded
+inputs.  Integer results (counts, plans, permutation indices, gathered rows) must be bit-exact;
+floating-point results must be within relative L2 5e-3 of the oracle, which computes in double
+precision on the same bf16-rounded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2605_08639_amd as rl
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+DEV = "cuda"
+
+
+def rel_l2(got, want):
+    got = got.double().cpu().numpy() if torch.is_tensor(got) else np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    den = np.linalg.norm(want)
+    return float(np.linalg.norm(got - want) / den) if den > 0 else float(np.linalg.norm(got))
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def routing(cfg):
+    ids, gates = zip(*[wl.make_routing(cfg, mb) for mb in range(cfg.n_mb)])
+    return np.stack(ids), np.stack(gates)
+
+
+# ------------------------------------------------------------------ histogram
+@pytest.mark.parametrize("kw", [
+    dict(), dict(T=513, k=3, E=12, EP=4),                       # T*k not a multiple of 4: scalar loads
+    dict(T=20000, k=8, E=256, EP=8, n_mb=2), dict(T=1, k=1, E=4, EP=4, n_mb=1)])
+def test_route_hist_bit_exact(kw):
+    cfg = wl.small_config(**kw)
+    ids, _ = routing(cfg)
+    want, _ = oracle.route_hist(ids, cfg.E)
+    err = rl.new_err_flag()
+    got = rl.relibra_route_hist(torch.from_numpy(ids).to(DEV), cfg.E, err_flag=err)
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert err.item() == 0
+
+
+def test_route_hist_flags_bad_ids_and_handles_empty():
+    ids = torch.zeros((1, 64, 2), dtype=torch.int32, device=DEV)
+    ids[0, 5, 1] = 9
+    ids[0, 6, 0] = -1
+    err = rl.new_err_flag()
+    got = rl.relibra_route_hist(ids, 8, err_flag=err)
+    assert err.item() == rl.ERR_ID_RANGE
+    assert got.sum().item() == 126 and got[0, 0].item() == 126
+    got = rl.relibra_route_hist(torch.zeros((2, 0, 2), dtype=torch.int32, device=DEV), 8)
+    assert got.shape == (2, 8) and got.sum().item() == 0
+
+
+# ------------------------------------------------------------------ plan + permute
+def plan_both(cfg, counts):
+    want = oracle.plan(counts, cfg.EP, cfg.rpn, cfg.r)
+    got = rl.relibra_plan(counts, cfg.k, cfg.EP, cfg.rpn, cfg.r)
+    for key in ("expert_to_slot", "replica_expert", "inst_ptr", "inst_rank", "inst_rows", "inst_group",
+                "group_expert", "group_offset"):
+        assert np.array_equal(got[key], want[key]), key
+    return got
+
+
+@pytest.mark.parametrize("kw", [
+    dict(), dict(E=8, k=2, EP=4, r=1, T=512, n_mb=1, routing="single"),
+    dict(E=128, k=8, EP=8, r=2, T=3000, n_mb=2, h=64),
+    dict(E=16, k=8, EP=8, r=2, T=1000, n_mb=2, routing="stress", zipf_s=1.5, h=64),
+    dict(E=5, k=5, EP=1, r=0, T=37, n_mb=1, h=8)])
+def test_hist_plan_permute_bit_exact(kw):
+    cfg = wl.small_config(**kw)
+    ids, _ = routing(cfg)
+    counts = rl.relibra_route_hist(torch.from_numpy(ids).to(DEV), cfg.E).cpu().numpy()
+    p = plan_both(cfg, counts)
+    for mb in range(cfg.n_mb):
+        X, _ = wl.make_tokens(cfg, mb)
+        want_row, want_src = oracle.permute(ids[mb], cfg.E, p["inst_ptr"][mb], p["inst_rows"][mb],
+                                            p["inst_group"][mb], p["group_offset"][mb])
+        err = rl.new_err_flag()
+        row_of, src_of, Xrows = rl.relibra_permute(
+            torch.from_numpy(ids[mb]).to(DEV), dev_i32(p["inst_ptr"][mb]), dev_i32(p["inst_rows"][mb]),
+            dev_i32(p["inst_group"][mb]), dev_i32(p["group_offset"][mb]), X.to(DEV), cfg.E, cfg.G, err_flag=err)
+        assert err.item() == 0
+        assert np.array_equal(row_of.cpu().numpy(), want_row)
+        assert np.array_equal(src_of.cpu().numpy(), want_src)
+        want_rows = oracle.gather_rows(X, want_src, cfg.k)
+        got_rows = Xrows.cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got_rows, want_rows)                     # bit copy
+
+
+def test_permute_flags_a_plan_that_does_not_cover_the_routing():
+    cfg = wl.small_config(E=8, k=2, EP=4, r=1, T=200, n_mb=1, h=64)
+    ids, _ = routing(cfg)
+    counts, _ = oracle.route_hist(ids, cfg.E)
+    p = rl.relibra_plan(counts, cfg.k, cfg.EP, cfg.rpn, cfg.r)
+    rows = p["inst_rows"][0].copy()
+    rows[p["inst_ptr"][0][3]] -= 1                                     # one row short for expert 3
+    err = rl.new_err_flag()
+    row_of, src_of, _ = rl.relibra_permute(
+        torch.from_numpy(ids[0]).to(DEV), dev_i32(p["inst_ptr"][0]), dev_i32(rows), dev_i32(p["inst_group"][0]),
+        dev_i32(p["group_offset"][0]), None, cfg.E, cfg.G, err_flag=err)
+    assert err.item() & rl.ERR_PLAN_COVER
+    assert (row_of == -1).sum().item() == 1
+
+
+# ------------------------------------------------------------------ expert FFN
+def ffn_case(seed, E, h, hff, rows, experts, wscale=0.05):
+    rng = np.random.default_rng(seed)
+    go = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    ge = np.array(experts, np.int32)
+    N = int(go[-1])
+    bf = lambda x: torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16)
+    X = bf(rng.standard_normal((N, h)))
+    dY = bf(rng.standard_normal((N, h)))
+    Wg = bf(wscale * rng.standard_normal((E, hff, h)))
+    Wu = bf(wscale * rng.standard_normal((E, hff, h)))
+    Wd = bf(wscale * rng.standard_normal((E, h, hff)))
+    return go, ge, X, dY, Wg, Wu, Wd
+
+
+FFN_CASES = [
+    # rows per group span: empty, 1, one short of a tile, a tile, one over, several tiles + tail
+    dict(seed=1, E=4, h=256, hff=192, rows=(0, 1, 127, 128, 129, 300, 0, 65), experts=(0, 1, 2, 3, 0, 1, -1, 3)),
+    dict(seed=2, E=3, h=128, hff=256, rows=(40, 513, 7), experts=(2, 0, 1)),
+    dict(seed=3, E=2, h=64, hff=64, rows=(5, 3), experts=(1, 0)),
+    dict(seed=4, E=2, h=320, hff=448, rows=(200, 0, 131), experts=(0, 1, 0)),
+]
+
+
+def dw_slots(ge, E):
+    """Home group of an expert = its first group; later groups of the same expert are replicas."""
+    seen, slots, nxt = set(), [], E
+    for e in ge.tolist():
+        if e < 0:
+            slots.append(nxt); nxt += 1
+        elif e in seen:
+            slots.append(nxt); nxt += 1
+        else:
+            seen.add(e); slots.append(e)
+    return np.array(slots, np.int32), nxt
+
+
+@pytest.mark.parametrize("case", FFN_CASES)
+def test_ffn_fwd_bwd_within_tolerance(case):
+    go, ge, X, dY, Wg, Wu, Wd = ffn_case(**case)
+    E, hff, h = Wg.shape
+    Gt_o, U_o, A_o, Y_o = oracle.ffn_fwd(X, go, ge, Wg, Wu, Wd)
+    dX_o, dWg_o, dWu_o, dWd_o = oracle.ffn_bwd(X, dY, go, ge, Wg, Wu, Wd)
+    live = np.concatenate([np.arange(go[g], go[g + 1]) for g in range(len(ge)) if ge[g] >= 0]).astype(np.int64)
+
+    d = lambda t: t.to(DEV)
+    err = rl.new_err_flag()
+    Xd, dYd, Wgd, Wud, Wdd = d(X), d(dY), d(Wg), d(Wu), d(Wd)
+    god, ged = dev_i32(go), dev_i32(ge)
+    N = X.shape[0]
+    sentinel = lambda cols: torch.full((N, cols), 7.0, dtype=torch.bfloat16, device=DEV)
+    Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xd, god, ged, Wgd, Wud, Wdd, Gt=sentinel(hff), U=sentinel(hff),
+                                         A=sentinel(hff), Yrows=sentinel(h), err_flag=err)
+    for name, got, want in (("Gt", Gt, Gt_o), ("U", U, U_o), ("A", A, A_o), ("Y", Y, Y_o)):
+        assert rel_l2(got[live], want[live]) <= TOL, name
+        for g in range(len(ge)):                                   # per group, so a bad tile cannot hide
+            if ge[g] >= 0 and go[g + 1] > go[g]:
+                assert rel_l2(got[go[g]:go[g + 1]], want[go[g]:go[g + 1]]) <= TOL, (name, g)
+    dead = np.setdiff1d(np.arange(N), live)
+    if dead.size:                                                   # rows of empty slots stay untouched
+        assert (Y[dead].float() == 7.0).all()
+
+    slots, n_slots = dw_slots(ge, E)
+    mk = lambda *s: torch.full(s, 3.0, dtype=torch.float32, device=DEV)
+    dWg, dWu, dWd = mk(n_slots, hff, h), mk(n_slots, hff, h), mk(n_slots, h, hff)
+    dX = rl.relibra_moe_ffn_bwd(dYd, Xd, Gt, U, A, god, ged, dev_i32(slots), Wgd, Wud, Wdd, dWg, dWu, dWd,
+                                dXrows=sentinel(h), err_flag=err)
+    assert err.item() == 0
+    assert rel_l2(dX[live], dX_o[live]) <= TOL
+    used = sorted(set(e for e in ge.tolist() if e >= 0))
+    for name, got, want in (("dWg", dWg, dWg_o), ("dWu", dWu, dWu_o), ("dWd", dWd, dWd_o)):
+        for e in used:
+            if np.linalg.norm(want[e]) > 0:
+                assert rel_l2(got[e], want[e]) <= TOL, (name, e)
+            else:
+                assert (got[e] == 0).all(), (name, e)              # expert seen only through empty groups
+    # accumulate mode adds the same gradient on top
+    before = dWd[:E].clone()
+    rl.relibra_moe_ffn_bwd(dYd, Xd, Gt, U, A, god, ged, dev_i32(slots), Wgd, Wud, Wdd, dWg, dWu, dWd,
+                           flags=rl.BWD_ACCUMULATE, err_flag=err)
+    for e in used:
+        assert rel_l2(dWd[e], 2 * before[e].double().cpu().numpy()) <= 1e-6
+    # bit-reproducible
+    dWg2, dWu2, dWd2 = mk(n_slots, hff, h), mk(n_slots, hff, h), mk(n_slots, h, hff)
+    dX2 = rl.relibra_moe_ffn_bwd(dYd, Xd, Gt, U, A, god, ged, dev_i32(slots), Wgd, Wud, Wdd, dWg2, dWu2, dWd2)
+    assert torch.equal(dX2[live], dX[live]) and torch.equal(dWg2[:E][used], dWg[:E][used])
+
+
+def test_ffn_group_range_runs_one_ranks_share_only():
+    go, ge, X, dY, Wg, Wu, Wd = ffn_case(seed=5, E=4, h=128, hff=128, rows=(30, 50, 0, 20, 140, 9),
+                                         experts=(0, 1, 2, 3, 0, 1))
+    _, _, _, Y_o = oracle.ffn_fwd(X, go, ge, Wg, Wu, Wd)
+    d = lambda t: t.to(DEV)
+    N, h = X.shape
+    Y = torch.full((N, h), 7.0, dtype=torch.bfloat16, device=DEV)
+    rl.relibra_moe_ffn_fwd(d(X), dev_i32(go), dev_i32(ge), d(Wg), d(Wu), d(Wd), g_begin=3, g_end=5, Yrows=Y)
+    a, b = int(go[3]), int(go[5])
+    assert rel_l2(Y[a:b], Y_o[a:b]) <= TOL
+    assert (Y[:a].float() == 7.0).all() and (Y[b:].float() == 7.0).all()
+
+
+def test_ffn_flags_inconsistent_group_tables_without_faulting():
+    go, ge, X, dY, Wg, Wu, Wd = ffn_case(seed=6, E=2, h=64, hff=64, rows=(10, 10), experts=(0, 1))
+    d = lambda t: t.to(DEV)
+    err = rl.new_err_flag()
+    bad_go = go.copy()
+    bad_go[2] = 5000                                                 # beyond the row buffer
+    rl.relibra_moe_ffn_fwd(d(X), dev_i32(bad_go), dev_i32(ge), d(Wg), d(Wu), d(Wd), err_flag=err)
+    assert err.item() & rl.ERR_GROUP_TABLE
+    err.zero_()
+    rl.relibra_moe_ffn_fwd(d(X), dev_i32(go), dev_i32(np.array([0, 9], np.int32)), d(Wg), d(Wu), d(Wd), err_flag=err)
+    assert err.item() & rl.ERR_GROUP_TABLE
+
+
+# ------------------------------------------------------------------ combine
+@pytest.mark.parametrize("T,k,h", [(97, 4, 256), (5, 1, 8), (300, 8, 2048)])
+def test_combine_modes(T, k, h):
+    rng = np.random.default_rng(T)
+    N = T * k
+    row_of = rng.permutation(N).astype(np.int32)
+    bf = lambda x: torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16)
+    Y = bf(rng.standard_normal((N, h)))
+    dOut = bf(rng.standard_normal((T, h)))
+    gates = rng.random((T, k)).astype(np.float32)
+    gates /= gates.sum(1, keepdims=True)
+    Yd, gd, rd = Y.to(DEV), torch.from_numpy(gates).to(DEV), dev_i32(row_of)
+    err = rl.new_err_flag()
+    out = rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yd, rd, T, k, gates=gd, err_flag=err)
+    assert rel_l2(out, oracle.combine_fwd(Y.double().numpy(), gates, row_of, T, k)) <= TOL
+    out = rl.relibra_unpermute_combine(rl.COMBINE_SUM, Yd, rd, T, k, err_flag=err)
+    assert rel_l2(out, oracle.combine_fwd(Y.double().numpy(), None, row_of, T, k)) <= TOL
+    dY, dgate = rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yd, rd, T, k, gates=gd, tok=dOut.to(DEV), err_flag=err)
+    dY_o, dgate_o = oracle.combine_bwd(dOut.double().numpy(), Y.double().numpy(), gates, row_of, T, k)
+    assert rel_l2(dY, dY_o) <= TOL and rel_l2(dgate, dgate_o) <= TOL
+    assert err.item() == 0
+
+
+# ------------------------------------------------------------------ whole path
+def run_layer_gpu(cfg, mb, ids, gates, p, Wg, Wu, Wd, X, dOut, dW):
+    """One micro-batch through every entry point; returns what the layer hands back."""
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    err = rl.new_err_flag()
+    ids_d, gates_d = t(ids), t(gates)
+    tabs = {key: dev_i32(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset",
+                                                 "group_expert", "group_dw_slot")}
+    row_of, src_of, Xrows = rl.relibra_permute(ids_d, tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                               tabs["group_offset"], X, cfg.E, cfg.G, err_flag=err)
+    Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], Wg, Wu, Wd, err_flag=err)
+    Out = rl.relibra_unpermute_combine(rl.COMBINE_FWD, Y, row_of, cfg.T, cfg.k, gates=gates_d, err_flag=err)
+    dY, dgate = rl.relibra_unpermute_combine(rl.COMBINE_BWD, Y, row_of, cfg.T, cfg.k, gates=gates_d, tok=dOut,
+                                             err_flag=err)
+    dXrows = rl.relibra_moe_ffn_bwd(dY, Xrows, Gt, U, A, tabs["group_offset"], tabs["group_expert"],
+                                    tabs["group_dw_slot"], Wg, Wu, Wd, *dW, err_flag=err)
+    dX = rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, cfg.T, cfg.k, err_flag=err)
+    assert err.item() == 0
+    return Out, dgate, dX
+
+
+def run_layer_oracle(cfg, mb, ids, gates, p, Wg, Wu, Wd, X, dOut):
+    row_of, src_of = oracle.permute(ids, cfg.E, p["inst_ptr"][mb], p["inst_rows"][mb], p["inst_group"][mb],
+                                    p["group_offset"][mb])
+    Xrows = oracle.gather_rows(X, src_of, cfg.k)
+    go, ge = p["group_offset"][mb], p["group_expert"][mb]
+    _, _, _, Y = oracle.ffn_fwd(Xrows, go, ge, Wg, Wu, Wd)
+    Out = oracle.combine_fwd(Y, gates, row_of, cfg.T, cfg.k)
+    dY, dgate = oracle.combine_bwd(dOut.double().numpy(), Y, gates, row_of, cfg.T, cfg.k)
+    # the oracle's backward takes bf16 rows: round the upstream row gradients once, as the path does
+    dY16 = torch.from_numpy(dY).to(torch.bfloat16)
+    dXrows, dWg, dWu, dWd = oracle.ffn_bwd(Xrows, dY16, go, ge, Wg, Wu, Wd)
+    dX = oracle.combine_fwd(dXrows, None, row_of, cfg.T, cfg.k)
+    return Out, dgate, dX, dWg, dWu, dWd
+
+
+@pytest.mark.parametrize("cfg", [wl.CONFIGS[0],
+                                 wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=2, h=256, hff=192)],
+                         ids=["config1-tiny", "ragged-small"])
+def test_whole_layer_matches_oracle(cfg):
+    ids, gates = routing(cfg)
+    counts = rl.relibra_route_hist(torch.from_numpy(ids).to(DEV), cfg.E).cpu().numpy()
+    assert np.array_equal(counts, oracle.route_hist(ids, cfg.E)[0])
+    p = plan_both(cfg, counts)
+    Wg, Wu, Wd = wl.make_weights(cfg)
+    Wgd, Wud, Wdd = Wg.to(DEV), Wu.to(DEV), Wd.to(DEV)
+    n_slots = cfg.E + cfg.EP * cfg.r
+    for mb in range(cfg.n_mb):
+        X, dOut = wl.make_tokens(cfg, mb)
+        dW = [torch.empty((n_slots, cfg.hff, cfg.h), dtype=torch.float32, device=DEV),
+              torch.empty((n_slots, cfg.hff, cfg.h), dtype=torch.float32, device=DEV),
+              torch.empty((n_slots, cfg.h, cfg.hff), dtype=torch.float32, device=DEV)]
+        Out, dgate, dX = run_layer_gpu(cfg, mb, ids[mb], gates[mb], p, Wgd, Wud, Wdd, X.to(DEV), dOut.to(DEV), dW)
+        Out_o, dgate_o, dX_o, dWg_o, dWu_o, dWd_o = run_layer_oracle(cfg, mb, ids[mb], gates[mb], p, Wg, Wu, Wd, X, dOut)
+        assert rel_l2(Out, Out_o) <= TOL
+        assert rel_l2(dgate, dgate_o) <= TOL
+        assert rel_l2(dX, dX_o) <= TOL
+        assert rel_l2(dW[0][:cfg.E], dWg_o) <= TOL
+        assert rel_l2(dW[1][:cfg.E], dWu_o) <= TOL
+        assert rel_l2(dW[2][:cfg.E], dWd_o) <= TOL

@@ -1,0 +1,133 @@
+"""CPU-side checks of the product library: it loads, exports what the header declares, the
+host planner equals the oracle's plan bit for bit, and bad arguments come back as status codes.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+import paper_2605_08639_amd as rl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "relibra.h")).read()
+    declared = set(re.findall(r"\b(relibra_[a-z_]+)\s*\(", header))
+    declared -= {"relibra_stream"}
+    assert {"relibra_route_hist", "relibra_plan", "relibra_permute", "relibra_moe_ffn_fwd",
+            "relibra_moe_ffn_bwd", "relibra_unpermute_combine"} <= declared
+    L = ctypes.CDLL(rl.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert set(rl.EXPORTS) == declared
+
+
+def _counts(cfg):
+    ids = np.stack([wl.make_routing(cfg, mb)[0] for mb in range(cfg.n_mb)])
+    return oracle.route_hist(ids, cfg.E)[0]
+
+
+PLAN_KEYS = ("expert_to_slot", "replica_expert", "inst_ptr", "inst_rank", "inst_rows", "inst_group",
+             "group_expert", "group_offset")
+
+
+def _assert_same_plan(cfg, counts):
+    want = oracle.plan(counts, cfg.EP, cfg.rpn, cfg.r)
+    got = rl.relibra_plan(counts, cfg.k, cfg.EP, cfg.rpn, cfg.r)
+    for key in PLAN_KEYS:
+        assert np.array_equal(got[key], want[key]), key
+    assert np.array_equal(got["max_load_before"], want["max_before"])
+    assert np.array_equal(got["max_load_after"], want["max_after"])
+    # gradient slots follow from the layout: home group -> its expert, replica slot j of rank g -> E + g*r + j
+    M, r, E = cfg.M, cfg.r, cfg.E
+    for mb in range(counts.shape[0]):
+        for grp in range(cfg.G):
+            rk, loc = divmod(grp, M + r)
+            exp = want["group_expert"][mb, grp] if loc < M else E + rk * r + (loc - M)
+            assert got["group_dw_slot"][mb, grp] == exp
+    return got
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(E=8, k=2, EP=4, r=1, T=512, n_mb=1, routing="single"),
+    dict(E=32, k=4, EP=16, r=2, T=300, n_mb=4, ranks_per_node=8),
+    dict(E=32, k=4, EP=16, r=1, T=300, n_mb=3, ranks_per_node=4),
+    dict(E=24, k=3, EP=4, r=0, T=200, n_mb=2),
+    dict(E=16, k=8, EP=8, r=2, T=1000, n_mb=5, routing="stress", zipf_s=1.5),
+    dict(E=64, k=6, EP=8, r=3, T=2000, n_mb=6, zipf_s=2.0),
+    dict(E=12, k=1, EP=2, r=1, T=50, n_mb=2, ranks_per_node=1),
+])
+def test_planner_equals_oracle_plan(kw):
+    cfg = wl.small_config(**kw)
+    _assert_same_plan(cfg, _counts(cfg))
+
+
+def test_planner_equals_oracle_on_random_histograms():
+    rng = np.random.default_rng(42)
+    for trial in range(60):
+        EP = int(rng.choice([1, 2, 4, 8, 16]))
+        M = int(rng.integers(1, 6))
+        rpn = int(rng.choice([d for d in (1, 2, 4, 8) if EP % d == 0]))
+        cfg = wl.small_config(E=EP * M, EP=EP, k=1, r=int(rng.integers(0, 4)), n_mb=int(rng.integers(1, 4)),
+                              ranks_per_node=rpn)
+        kind = trial % 3
+        if kind == 0:
+            counts = rng.integers(0, 50, size=(cfg.n_mb, cfg.E))
+        elif kind == 1:
+            counts = (rng.zipf(1.3, size=(cfg.n_mb, cfg.E)) % 5000)
+        else:
+            counts = rng.integers(0, 3, size=(cfg.n_mb, cfg.E)) * 7       # many ties and zeros
+        _assert_same_plan(cfg, counts.astype(np.int32))
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_planner_equals_oracle_on_paper_shaped_configs(idx):
+    cfg = wl.CONFIGS[idx]
+    got = _assert_same_plan(cfg, _counts(cfg))
+    assert (got["max_load_after"] <= got["max_load_before"]).all() or cfg.n_mb > 1
+    assert got["max_load_after"].sum() <= got["max_load_before"].sum()
+
+
+def test_plan_argument_errors():
+    c = np.zeros((1, 8), np.int32)
+    for bad in (dict(EP=3), dict(rpn=3), dict(r=-1), dict(k=0), dict(k=9)):
+        args = dict(k=2, EP=4, rpn=4, r=1)
+        args.update(bad)
+        with pytest.raises(rl.RelibraError) as ei:
+            rl.relibra_plan(c, args["k"], args["EP"], args["rpn"], args["r"])
+        assert ei.value.status == rl.EINVAL
+    c[0, 3] = -1
+    with pytest.raises(rl.RelibraError) as ei:
+        rl.relibra_plan(c, 2, 4, 4, 1)
+    assert ei.value.status == rl.ERANGE
+
+
+def test_workspace_sizes_and_status_strings():
+    assert rl.workspace_bytes(rl.WS_PERMUTE, 512, 2, 8, 12, 128, 256) >= ((1024 + 511) // 512) * 8 * 4
+    fwd = rl.workspace_bytes(rl.WS_FFN_FWD, 512, 2, 8, 12, 128, 256)
+    bwd = rl.workspace_bytes(rl.WS_FFN_BWD, 512, 2, 8, 12, 128, 256)
+    assert bwd >= fwd + 2 * 1024 * 256 * 2                 # room for dGt and dU
+    assert rl.workspace_bytes(99, 512, 2, 8, 12, 128, 256) == 0
+    assert rl.status_string(rl.OK) == "ok" and "workspace" in rl.status_string(rl.EWORKSPACE)
+
+
+def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
+    L = rl.lib()
+    z = ctypes.c_void_p(0)
+    assert L.relibra_route_hist(z, 1, 4, 2, 0, z, z, z) == rl.EINVAL          # E < 1
+    assert L.relibra_route_hist(z, 1, 4, 9, 8, z, z, z) == rl.EINVAL          # k > E
+    assert L.relibra_route_hist(z, 0, 4, 2, 8, z, z, z) == rl.OK              # empty batch
+    assert L.relibra_permute(z, z, z, z, z, z, 4, 2, 5000, 12, 128, z, z, z, z, ctypes.c_size_t(0), z, z) == rl.EINVAL
+    assert L.relibra_permute(z, z, z, z, z, z, 0, 2, 8, 12, 128, z, z, z, z, ctypes.c_size_t(0), z, z) == rl.OK
+    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 0, 12, 8, z, z, z, 100, 256, z, z, z, z, z,
+                                 ctypes.c_size_t(0), z, z) == rl.EUNSUPPORTED  # h % 64
+    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 5, 3, 8, z, z, z, 128, 256, z, z, z, z, z,
+                                 ctypes.c_size_t(0), z, z) == rl.EINVAL        # g_begin > g_end
+    assert L.relibra_unpermute_combine(7, z, z, z, z, 4, 2, 128, z, z, z, z, z) == rl.EINVAL
+    assert L.relibra_unpermute_combine(0, z, z, z, z, 4, 2, 100, z, z, z, z, z) == rl.EINVAL
