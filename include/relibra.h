@@ -196,6 +196,24 @@ int relibra_unpermute_combine(int mode, const void *rows_dev, const void *tok_de
                               void *out_tok_dev, void *out_rows_dev, float *dgate_dev,
                               int32_t *err_flag_dev, relibra_stream stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the method).  Between relibra_prof_start and
+ * relibra_prof_stop every kernel launch of the chosen level is bracketed by two HIP events on
+ * its launch stream: level 1 = the six grouped-GEMM kernels, level 2 = every kernel, 0 = off.
+ * At most max_records launches are recorded (events are created in relibra_prof_start, host
+ * side only).  relibra_prof_stop waits for the recorded events and returns, per kernel id
+ * (RELIBRA_K_*), the summed milliseconds and the launch count in two host arrays of
+ * RELIBRA_K_COUNT entries.  Process-global, not thread-safe.
+ */
+enum {
+    RELIBRA_K_FILL = 0, RELIBRA_K_HIST, RELIBRA_K_PERM_COUNT, RELIBRA_K_PERM_SCAN, RELIBRA_K_PERM_RANK,
+    RELIBRA_K_GATHER, RELIBRA_K_COMBINE_FWD, RELIBRA_K_COMBINE_BWD, RELIBRA_K_COMBINE_SUM, RELIBRA_K_SCHED,
+    RELIBRA_K_FWD_GATE_UP, RELIBRA_K_FWD_DOWN, RELIBRA_K_BWD_ACT, RELIBRA_K_BWD_DX,
+    RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_COUNT
+};
+int relibra_prof_start(int level, int max_records);
+int relibra_prof_stop(double *ms_by_kernel_host, int64_t *launches_by_kernel_host);
+
 /* Bytes of device scratch each call needs (0 on unusable sizes). */
 size_t relibra_workspace_bytes(int which, int T, int k, int E, int G, int h, int hff);
 

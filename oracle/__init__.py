@@ -214,3 +214,8 @@ def combine_bwd(dOut, Yrows, gates, row_of, T, k):
     dgate = np.empty((T, k))
     lib().oracle_combine_bwd(_p(dOut), _p(Yrows), _p(g), _p(_i32(row_of)), T, k, h, _p(dY), _p(dgate))
     return dY, dgate
+
+
+def num_threads():
+    """Threads the oracle's OpenMP loops use."""
+    return int(lib().oracle_num_threads())

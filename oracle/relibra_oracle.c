@@ -15,6 +15,10 @@
 #include <string.h>
 #include <math.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 typedef long long i64;
 typedef unsigned __int128 u128;
 
@@ -631,4 +635,14 @@ void oracle_combine_bwd(const double *dOut, const double *Yrows, const float *ga
             }
             dgate[t * k + j] = dot;
         }
+}
+
+/* Threads the row loops above run on (for reporting beside timings). */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

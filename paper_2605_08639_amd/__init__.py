@@ -24,7 +24,11 @@ COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_permute", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_unpermute_combine", "relibra_workspace_bytes",
-           "relibra_status_string")
+           "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
+
+KERNELS = ("fill", "hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
+           "combine_sum", "sched", "fwd_gate_up", "fwd_down", "bwd_act", "bwd_dx", "wgrad_down",
+           "wgrad_gate_up", "replica_sum")
 
 _lib = None
 
@@ -232,3 +236,16 @@ def relibra_unpermute_combine(mode, rows, row_of, T, k, gates=None, tok=None,
                                          _dp(dgate), _dp(err_flag), _stream())
     _check("relibra_unpermute_combine", rc)
     return (out_rows, dgate) if mode == COMBINE_BWD else out_tok
+
+
+def prof_start(level=1, max_records=4096):
+    """Bracket kernel launches with HIP events (level 1: grouped GEMMs, 2: every kernel)."""
+    _check("relibra_prof_start", lib().relibra_prof_start(int(level), int(max_records)))
+
+
+def prof_stop():
+    """-> {kernel name: (total ms, launches)} for the launches recorded since prof_start."""
+    ms = np.zeros(len(KERNELS), np.float64)
+    n = np.zeros(len(KERNELS), np.int64)
+    _check("relibra_prof_stop", lib().relibra_prof_stop(_hp(ms), _hp(n)))
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(KERNELS) if n[i]}

@@ -35,4 +35,16 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline hipError_t launch_check() { return hipGetLastError(); }
 
+// Event bracketing of a launch (prof.hip); both are no-ops while profiling is off.
+bool prof_before(int kernel_id, hipStream_t s);
+void prof_after(int kernel_id, hipStream_t s);
+
+// LAUNCH(kernel id, stream, kernel<<<...>>>(...)): launch, optionally timed.
+#define RELIBRA_LAUNCH(id, stream, ...)                         \
+    do {                                                        \
+        const bool prof_ = relibra::prof_before((id), (stream)); \
+        __VA_ARGS__;                                            \
+        if (prof_) relibra::prof_after((id), (stream));         \
+    } while (0)
+
 }  // namespace relibra

@@ -510,16 +510,16 @@ extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
         return RELIBRA_EINVAL;
     if (ws_bytes < ffn_ws_bytes(n_rows, Gr, hff, false)) return RELIBRA_EWORKSPACE;
     Sched s = carve(ws, n_rows, Gr, hff, false);
-    sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, nullptr, g_begin, Gr, n_rows, E, 0, s, err_flag);
+    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, nullptr, g_begin, Gr, n_rows, E, 0, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     const int R = max_row_tiles(n_rows, Gr);
     const int ct1 = (hff + BN - 1) / BN, ct2 = (h + BN - 1) / BN;
-    fwd_gate_up_kernel<<<(unsigned)(R * ct1), THREADS, 0, stream>>>(
+    RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<<<(unsigned)(R * ct1), THREADS, 0, stream>>>(
         s, (const bf16_t *)Xrows, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
-        (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save);
+        (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save));
     RELIBRA_HIP_TRY(launch_check());
-    fwd_down_kernel<<<(unsigned)(R * ct2), THREADS, 0, stream>>>(
-        s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows);
+    RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<<<(unsigned)(R * ct2), THREADS, 0, stream>>>(
+        s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }
@@ -547,34 +547,34 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
         return RELIBRA_EINVAL;
     if (ws_bytes < ffn_ws_bytes(n_rows, Gr, hff, true)) return RELIBRA_EWORKSPACE;
     Sched s = carve(ws, n_rows, Gr, hff, true);
-    sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, group_dw_slot, g_begin, Gr, n_rows, E,
-                                        n_dw_slots, s, err_flag);
+    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, group_dw_slot, g_begin, Gr, n_rows, E,
+                                        n_dw_slots, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     const int R = max_row_tiles(n_rows, Gr);
     const int ct_ff = (hff + BN - 1) / BN, ct_h = (h + BN - 1) / BN;
     const int accumulate = (flags & RELIBRA_BWD_ACCUMULATE) ? 1 : 0;
     if (n_rows > 0) {
-        bwd_act_kernel<<<(unsigned)(R * ct_ff), THREADS, 0, stream>>>(
+        RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<<<(unsigned)(R * ct_ff), THREADS, 0, stream>>>(
             s, (const bf16_t *)dYrows, (const bf16_t *)Wd, (const bf16_t *)Gt_save, (const bf16_t *)U_save,
-            h, hff, ct_ff);
+            h, hff, ct_ff));
         RELIBRA_HIP_TRY(launch_check());
-        bwd_dx_kernel<<<(unsigned)(R * ct_h), THREADS, 0, stream>>>(
-            s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, (bf16_t *)dXrows);
+        RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<<<(unsigned)(R * ct_h), THREADS, 0, stream>>>(
+            s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, (bf16_t *)dXrows));
         RELIBRA_HIP_TRY(launch_check());
     }
     const int tiles = ct_ff * ct_h;
-    wgrad_kernel<1><<<(unsigned)(Gr * tiles), THREADS, 0, stream>>>(
-        s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, dWd, nullptr);
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1><<<(unsigned)(Gr * tiles), THREADS, 0, stream>>>(
+        s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, dWd, nullptr));
     RELIBRA_HIP_TRY(launch_check());
-    wgrad_kernel<2><<<(unsigned)(Gr * tiles), THREADS, 0, stream>>>(
-        s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, dWg, dWu);
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_kernel<2><<<(unsigned)(Gr * tiles), THREADS, 0, stream>>>(
+        s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, dWg, dWu));
     RELIBRA_HIP_TRY(launch_check());
     if (!(flags & RELIBRA_BWD_NO_REPLICA_SUM) && n_dw_slots > E) {
         const size_t vec4 = (size_t)h * hff / 4;
         const int grid = (int)((vec4 + 255) / 256 < 4096 ? (vec4 + 255) / 256 : 4096);
-        replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWg);
-        replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWu);
-        replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWd);
+        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWg));
+        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWu));
+        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWd));
         RELIBRA_HIP_TRY(launch_check());
     }
     return RELIBRA_OK;

@@ -25,7 +25,7 @@ __global__ void fill_i32_kernel(int32_t *p, size_t n, int32_t v)
 // adds its non-zero bins to the micro-batch's global histogram with integer atomics, so the
 // result does not depend on the order in which blocks finish.
 __global__ void __launch_bounds__(kHistThreads)
-hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int blocks_per_mb,
+hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int blocks_per_mb, int vec_ok,
             int32_t *__restrict__ counts, int32_t *err_flag)
 {
     extern __shared__ int32_t bins[];
@@ -37,7 +37,7 @@ hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int blocks_per_m
     const int lo = chunk * kHistChunk;
     const int hi = min(per_mb, lo + kHistChunk);
     bool bad = false;
-    if ((per_mb & 3) == 0) {          // 16-byte aligned rows of the id tensor
+    if (vec_ok) {                      // 16-byte aligned rows of the id tensor
         const int4 *v = reinterpret_cast<const int4 *>(src);
         for (int i = lo / 4 + threadIdx.x; i < hi / 4; i += kHistThreads) {
             const int4 q = v[i];
@@ -296,14 +296,14 @@ extern "C" int relibra_route_hist(const int32_t *ids_dev, int n_mb, int T, int k
     if (n_mb == 0) return RELIBRA_OK;
     if (!counts_dev || !err_flag_dev) return RELIBRA_EINVAL;
     const size_t n_counts = (size_t)n_mb * E;
-    fill_i32_kernel<<<(unsigned)((n_counts + 255) / 256), 256, 0, stream>>>(counts_dev, n_counts, 0);
+    RELIBRA_LAUNCH(RELIBRA_K_FILL, stream, fill_i32_kernel<<<(unsigned)((n_counts + 255) / 256), 256, 0, stream>>>(counts_dev, n_counts, 0));
     RELIBRA_HIP_TRY(launch_check());
     const int per_mb = T * k;
     if (per_mb == 0) return RELIBRA_OK;
     if (!ids_dev) return RELIBRA_EINVAL;
     const int blocks_per_mb = (per_mb + kHistChunk - 1) / kHistChunk;
-    hist_kernel<<<(unsigned)(n_mb * blocks_per_mb), kHistThreads, E * sizeof(int32_t), stream>>>(
-        ids_dev, per_mb, E, blocks_per_mb, counts_dev, err_flag_dev);
+    RELIBRA_LAUNCH(RELIBRA_K_HIST, stream, hist_kernel<<<(unsigned)(n_mb * blocks_per_mb), kHistThreads, E * sizeof(int32_t), stream>>>(
+        ids_dev, per_mb, E, blocks_per_mb, ((per_mb & 3) == 0 && aligned16(ids_dev)) ? 1 : 0, counts_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }
@@ -333,19 +333,19 @@ extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_d
     const size_t lds = (size_t)4 * E * sizeof(int32_t);
     int ebits = 0;
     while ((1 << ebits) < E) ++ebits;
-    perm_count_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, unit_cnt, src_of_dev, err_flag_dev);
+    RELIBRA_LAUNCH(RELIBRA_K_PERM_COUNT, stream, perm_count_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, unit_cnt, src_of_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
-    perm_scan_kernel<<<(E + 255) / 256, 256, 0, stream>>>(unit_cnt, n_units, E);
+    RELIBRA_LAUNCH(RELIBRA_K_PERM_SCAN, stream, perm_scan_kernel<<<(E + 255) / 256, 256, 0, stream>>>(unit_cnt, n_units, E));
     RELIBRA_HIP_TRY(launch_check());
-    perm_rank_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, G, ebits, unit_cnt, inst_ptr_dev,
+    RELIBRA_LAUNCH(RELIBRA_K_PERM_RANK, stream, perm_rank_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, G, ebits, unit_cnt, inst_ptr_dev,
                                                             inst_rows_dev, inst_group_dev, group_offset_dev,
-                                                            row_of_dev, src_of_dev, err_flag_dev);
+                                                            row_of_dev, src_of_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
     if (with_rows) {
         const int vpr = h / 8;
         const int grid = grid_for((size_t)N * vpr, 256 * 4, 256 * 64);
-        gather_rows_kernel<<<grid, 256, 0, stream>>>((const uint4 *)X_dev, src_of_dev, N, T, k, vpr,
-                                                     (uint4 *)Xrows_dev);
+        RELIBRA_LAUNCH(RELIBRA_K_GATHER, stream, gather_rows_kernel<<<grid, 256, 0, stream>>>((const uint4 *)X_dev, src_of_dev, N, T, k, vpr,
+                                                     (uint4 *)Xrows_dev));
         RELIBRA_HIP_TRY(launch_check());
     }
     return RELIBRA_OK;
@@ -368,19 +368,19 @@ extern "C" int relibra_unpermute_combine(int mode, const void *rows_dev, const v
     if (mode == RELIBRA_COMBINE_BWD) {
         if (!tok_dev || !gates_dev || !out_rows_dev || !dgate_dev || !aligned16(tok_dev) || !aligned16(out_rows_dev))
             return RELIBRA_EINVAL;
-        combine_bwd_kernel<<<(N + 3) / 4, 256, 0, stream>>>((const uint4 *)rows_dev, (const uint4 *)tok_dev,
+        RELIBRA_LAUNCH(RELIBRA_K_COMBINE_BWD, stream, combine_bwd_kernel<<<(N + 3) / 4, 256, 0, stream>>>((const uint4 *)rows_dev, (const uint4 *)tok_dev,
                                                             gates_dev, row_of_dev, N, vpr, k,
-                                                            (uint4 *)out_rows_dev, dgate_dev, err_flag_dev);
+                                                            (uint4 *)out_rows_dev, dgate_dev, err_flag_dev));
     } else {
         if (!out_tok_dev || !aligned16(out_tok_dev)) return RELIBRA_EINVAL;
         const int grid = grid_for((size_t)T * vpr, 256, 256 * 64);
         if (mode == RELIBRA_COMBINE_FWD) {
             if (!gates_dev) return RELIBRA_EINVAL;
-            combine_fwd_kernel<true><<<grid, 256, 0, stream>>>((const uint4 *)rows_dev, gates_dev, row_of_dev,
-                                                               T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev);
+            RELIBRA_LAUNCH(RELIBRA_K_COMBINE_FWD, stream, combine_fwd_kernel<true><<<grid, 256, 0, stream>>>((const uint4 *)rows_dev, gates_dev, row_of_dev,
+                                                               T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev));
         } else {
-            combine_fwd_kernel<false><<<grid, 256, 0, stream>>>((const uint4 *)rows_dev, nullptr, row_of_dev,
-                                                                T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev);
+            RELIBRA_LAUNCH(RELIBRA_K_COMBINE_SUM, stream, combine_fwd_kernel<false><<<grid, 256, 0, stream>>>((const uint4 *)rows_dev, nullptr, row_of_dev,
+                                                                T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev));
         }
     }
     RELIBRA_HIP_TRY(launch_check());
