@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the replay-guided MoE expert-layer path on one MI355X.
+
+A step = one pass of the whole hot path over one training batch of the Qwen3-30B-A3B-shaped
+workload (16 micro-batches x 8192 tokens, E=128, top-8, h=2048, h'=768, simulated EP=8, r=2):
+histogram of every micro-batch -> plan (host) -> per micro-batch: permute, expert FFN forward,
+combine, combine backward, expert FFN backward (weight gradients accumulated over the batch),
+gather backward.  Inputs are seeded synthetic and resident in HBM before the timed region.
+
+Prints ONE JSON line: metric = expert-layer fwd+bwd TFLOP/s (18*h*h'*N flops per micro-batch
+over the whole step time), plus `roofline` for the dominant kernel (HIP events recorded by the
+library around each launch, live in the timed region) and `cpu_baseline` (the CPU oracle timed
+on a bounded sample on this machine's host cores).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+GEMM_FLOP_FACTOR = {"fwd_gate_up": 4, "fwd_down": 2, "bwd_act": 2, "bwd_dx": 4, "wgrad_down": 2,
+                    "wgrad_gate_up": 4}          # x h*h'*N per launch (2hh' per row per GEMM, Eq. 4)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (default: the metric's config)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target length of the oracle sample (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the straggler and bandwidth-kernel sections")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (each simulated EP rank's share executes on it); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2605_08639_amd as rl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    cfg = wl.CONFIGS[args.config]
+    E, k, h, hff, T, n_mb, EP, r, G, N = cfg.E, cfg.k, cfg.h, cfg.hff, cfg.T, cfg.n_mb, cfg.EP, cfg.r, cfg.G, cfg.N
+    n_slots = E + EP * r
+    log = lambda *a: print("[bench]", *a, file=sys.stderr, flush=True)
+
+    # ---------------- inputs, resident in HBM
+    t0 = time.time()
+    routed = [wl.make_routing(cfg, mb) for mb in range(n_mb)]
+    ids_h = np.stack([x[0] for x in routed])
+    gates_h = np.stack([x[1] for x in routed])
+    ids_all = torch.from_numpy(ids_h).to(dev)
+    gates_all = torch.from_numpy(gates_h).to(dev)
+    tok = [wl.make_tokens_device(cfg, mb, dev) for mb in range(n_mb)]
+    Wg, Wu, Wd = wl.make_weights(cfg, dev)
+    log(f"inputs for {cfg.name} drawn in {time.time() - t0:.1f}s")
+
+    # ---------------- buffers (allocated once; the library allocates nothing)
+    bf = lambda *s: torch.empty(s, dtype=torch.bfloat16, device=dev)
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=dev)
+    counts_d = i32(n_mb, E)
+    err = rl.new_err_flag(dev)
+    row_of, src_of = i32(N), i32(N)
+    Xrows, Yrows, dYrows, dXrows = bf(N, h), bf(N, h), bf(N, h), bf(N, h)
+    Gt, U, A = bf(N, hff), bf(N, hff), bf(N, hff)
+    Out, dX = bf(T, h), bf(T, h)
+    dgate = torch.empty((T, k), dtype=torch.float32, device=dev)
+    dWg = torch.empty((n_slots, hff, h), dtype=torch.float32, device=dev)
+    dWu = torch.empty_like(dWg)
+    dWd = torch.empty((n_slots, h, hff), dtype=torch.float32, device=dev)
+    ws_perm = torch.empty(rl.workspace_bytes(rl.WS_PERMUTE, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
+    ws_ffn = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
+    TABLES = ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert", "group_dw_slot")
+
+    def upload(plan):
+        return {key: torch.from_numpy(plan[key]).to(dev, non_blocking=True) for key in TABLES}
+
+    def layer(mb, tabs, first, g_range=None, flags_extra=0):
+        X, dOut = tok[mb]
+        rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
+                           tabs["group_offset"][mb], X, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
+                           Xrows=Xrows, workspace=ws_perm, err_flag=err)
+        rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
+                               Gt=Gt, U=U, A=A, Yrows=Yrows, workspace=ws_ffn, err_flag=err)
+        rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
+        rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
+                                     out_rows=dYrows, dgate=dgate, err_flag=err)
+        rl.relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, tabs["group_offset"][mb], tabs["group_expert"][mb],
+                               tabs["group_dw_slot"][mb], Wg, Wu, Wd, dWg, dWu, dWd,
+                               flags=0 if first else rl.BWD_ACCUMULATE, dXrows=dXrows, workspace=ws_ffn, err_flag=err)
+        rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, out_tok=dX, err_flag=err)
+
+    plan_ms = []
+
+    def step():
+        rl.relibra_route_hist(ids_all, E, counts=counts_d, err_flag=err)
+        counts_h = counts_d.cpu().numpy()                       # the path's one device->host crossing
+        tp = time.perf_counter()
+        plan = rl.relibra_plan(counts_h, k, EP, cfg.rpn, r)
+        plan_ms.append((time.perf_counter() - tp) * 1e3)
+        tabs = upload(plan)
+        for mb in range(n_mb):
+            layer(mb, tabs, first=(mb == 0))
+        return plan, tabs
+
+    # ---------------- warmup, then the timed region
+    for _ in range(max(args.warmup, 0)):
+        plan, tabs = step()
+    torch.cuda.synchronize()
+    assert err.item() == 0, f"device error flag {err.item()} during warmup"
+    plan_ms.clear()
+    rl.prof_start(level=1, max_records=args.steps * n_mb * 6 + 64)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        plan, tabs = step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    prof = rl.prof_stop()
+    assert err.item() == 0, f"device error flag {err.item()}"
+    ms_per_step = (t_end - t_begin) * 1e3 / args.steps
+    flops_step = cfg.flops_per_mb * n_mb
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        fl = GEMM_FLOP_FACTOR[name] * h * hff * N
+        kernels[name] = {"avg_ms": ms / n, "launches": n, "tflops": fl / (ms / n * 1e-3) / 1e12}
+    gemm_ms_step = sum(ms for ms, _ in prof.values()) / args.steps
+    dominant = max(prof, key=lambda nm: prof[nm][0])
+    roofline = {"bound": "mfma", "kernel": dominant, "achieved": kernels[dominant]["tflops"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dominant]["tflops"] / PEAK_BF16_TFLOPS,
+                "traffic": None, "avg_launch_ms": kernels[dominant]["avg_ms"],
+                "flops_per_launch": GEMM_FLOP_FACTOR[dominant] * h * hff * N}
+    gemm_tflops = flops_step / (gemm_ms_step * 1e-3) / 1e12
+    log(f"step {ms_per_step:.2f} ms  value {value:.1f} TFLOP/s  grouped GEMMs alone {gemm_tflops:.1f} TFLOP/s")
+
+    extras = {}
+    if not args.no_extras:
+        # ---- every kernel once more, untimed, for the bandwidth-bound kernels' GB/s
+        rl.prof_start(level=2, max_records=n_mb * 40 + 64)
+        step()
+        torch.cuda.synchronize()
+        p2 = rl.prof_stop()
+        alg_bytes = {
+            "hist": 4.0 * N * n_mb + 4.0 * E * n_mb,
+            "gather": 2.0 * h * N + 2.0 * h * T + 4.0 * N,
+            "combine_fwd": 2.0 * h * N + 2.0 * h * T + 8.0 * N,
+            "combine_bwd": 2.0 * h * T + 4.0 * h * N + 12.0 * N,
+            "combine_sum": 2.0 * h * N + 2.0 * h * T + 4.0 * N,
+        }
+        hbm = {}
+        for name, b in alg_bytes.items():
+            if name in p2:
+                avg = p2[name][0] / p2[name][1]
+                hbm[name] = {"avg_ms": avg, "GBps": b / (avg * 1e-3) / 1e9, "frac_of_8TBps": b / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        extras["hbm_kernels"] = hbm
+        extras["index_kernels_ms"] = {nm: p2[nm][0] / p2[nm][1] for nm in ("perm_count", "perm_scan", "perm_rank", "sched", "fill", "replica_sum") if nm in p2}
+
+        # ---- straggler rank: FFN fwd+bwd on the most loaded rank's groups, before / after the plan
+        M = cfg.M
+        un = {  # unplanned layout: expert e is group e on rank e // M, no replicas
+            "inst_ptr": np.tile(np.arange(E + 1, dtype=np.int32), (n_mb, 1)),
+            "inst_rows": counts_d.cpu().numpy().astype(np.int32),
+            "inst_group": np.tile(np.arange(E, dtype=np.int32), (n_mb, 1)),
+            "group_expert": np.tile(np.arange(E, dtype=np.int32), (n_mb, 1)),
+            "group_dw_slot": np.tile(np.arange(E, dtype=np.int32), (n_mb, 1)),
+        }
+        un["group_offset"] = np.concatenate([np.zeros((n_mb, 1), np.int32), np.cumsum(un["inst_rows"], 1, dtype=np.int32)], 1)
+        un_d = upload(un)
+
+        def straggler_ms(tabs_d, host, per_rank, mb):
+            go = host["group_offset"][mb]
+            loads = [(go[(g + 1) * per_rank] - go[g * per_rank]) for g in range(EP)]
+            g_star = int(np.argmax(loads))
+            X, dOut = tok[mb]
+            rl.relibra_permute(ids_all[mb], tabs_d["inst_ptr"][mb], tabs_d["inst_rows"][mb], tabs_d["inst_group"][mb],
+                               tabs_d["group_offset"][mb], X, E, tabs_d["group_expert"].shape[1], row_of=row_of,
+                               src_of=src_of, Xrows=Xrows, workspace=ws_perm, err_flag=err)
+            rng = (g_star * per_rank, (g_star + 1) * per_rank)
+            times = []
+            for it in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                rl.relibra_moe_ffn_fwd(Xrows, tabs_d["group_offset"][mb], tabs_d["group_expert"][mb], Wg, Wu, Wd,
+                                       g_begin=rng[0], g_end=rng[1], Gt=Gt, U=U, A=A, Yrows=Yrows, workspace=ws_ffn, err_flag=err)
+                rl.relibra_moe_ffn_bwd(Yrows, Xrows, Gt, U, A, tabs_d["group_offset"][mb], tabs_d["group_expert"][mb],
+                                       tabs_d["group_dw_slot"][mb], Wg, Wu, Wd, dWg, dWu, dWd, g_begin=rng[0], g_end=rng[1],
+                                       flags=rl.BWD_NO_REPLICA_SUM, dXrows=dXrows, workspace=ws_ffn, err_flag=err)
+                e1.record()
+                e1.synchronize()
+                times.append(e0.elapsed_time(e1))
+            return min(times), int(max(loads))
+
+        sb, sa = [], []
+        for mb in range(min(n_mb, 4)):
+            sb.append(straggler_ms(un_d, un, M, mb))
+            sa.append(straggler_ms(tabs, plan, M + r, mb))
+        extras["straggler"] = {
+            "micro_batches": len(sb),
+            "ms_before": float(np.mean([x[0] for x in sb])), "ms_after": float(np.mean([x[0] for x in sa])),
+            "rows_before": float(np.mean([x[1] for x in sb])), "rows_after": float(np.mean([x[1] for x in sa])),
+            "balanced_rows": N / EP,
+        }
+        assert err.item() == 0
+
+    # ---------------- the CPU oracle on a bounded sample, on this machine's host cores
+    cpu_baseline = None
+    if args.cpu_seconds > 0:
+        import oracle
+        rng = np.random.default_rng(0)
+        go, ge = plan["group_offset"][0], plan["group_expert"][0]
+
+        def oracle_sample(n_target):
+            groups, rows = [], 0
+            for g in range(G):
+                n = int(go[g + 1] - go[g])
+                if ge[g] >= 0 and n > 0:
+                    take = min(n, n_target - rows)
+                    groups.append((g, take))
+                    rows += take
+                    if rows >= n_target:
+                        break
+            experts = sorted(set(int(ge[g]) for g, _ in groups))
+            remap = {e: i for i, e in enumerate(experts)}
+            sub_go = np.concatenate([[0], np.cumsum([n for _, n in groups])]).astype(np.int32)
+            sub_ge = np.array([remap[int(ge[g])] for g, _ in groups], np.int32)
+            idx = torch.tensor(experts, device=dev)
+            w = [W[idx].cpu() for W in (Wg, Wu, Wd)]
+            bfr = lambda a: torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16)
+            Xs, dYs = bfr(rng.standard_normal((rows, h))), bfr(rng.standard_normal((rows, h)))
+            t0 = time.perf_counter()
+            oracle.ffn_fwd(Xs, sub_go, sub_ge, *w)
+            oracle.ffn_bwd(Xs, dYs, sub_go, sub_ge, *w)
+            return rows, time.perf_counter() - t0
+
+        rows0, dt0 = oracle_sample(128)
+        rate = rows0 / dt0
+        n_rows_s = int(max(256, min(N, rate * args.cpu_seconds)))
+        log(f"oracle probe: {rows0} rows in {dt0:.2f}s; sampling {n_rows_s} rows")
+        rows_s, dt = oracle_sample(n_rows_s)
+        cpu_baseline = {"value": 18.0 * h * hff * rows_s / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "seconds": dt,
+                        "sample": f"expert FFN fwd+bwd of the first {rows_s} routed rows (group order of micro-batch 0 "
+                                  f"under the plan) of {cfg.name}; double precision, plain loops"}
+
+    out = {
+        "metric": "MoE expert-layer fwd+bwd TFLOP/s (bf16)", "value": value, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: E={E} top-{k} h={h} h'={hff} {n_mb}x{T} tokens, simulated EP={EP}, r={r}; "
+                               "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd)",
+                   "flops_per_step": flops_step},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "gemm_kernels": kernels, "gemm_only_tflops": gemm_tflops, "plan_host_ms": float(np.mean(plan_ms)),
+        "skew_before": float(np.mean(plan["max_load_before"]) / (N / EP)),
+        "skew_after": float(np.mean(plan["max_load_after"]) / (N / EP)),
+    }
+    out.update(extras)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
