@@ -1,31 +1,28 @@
 // Expert FFN forward / backward as grouped bf16 MFMA GEMMs (gfx950, v_mfma_f32_32x32x16_bf16).
 //
-// One workgroup (4 wavefronts of 64 lanes, 2x2) owns a 128x128 output tile; a wavefront owns
-// 64x64 of it as 2x2 MFMA tiles with fp32 accumulators.  Operand tiles are staged through
-// LDS in [row][k] order with a 16-byte pad per row, so that every MFMA fragment is one
-// conflict-free 16-byte LDS read.  Global loads of the next k-slab are issued before the
-// MFMAs of the current one.
+// One workgroup of 8 wavefronts (512 lanes) owns a 256 x 256 output tile (256 x 128 for a
+// group's tail of at most 128 rows); a wavefront owns 128 x 64 of it as 4 x 2 MFMA tiles with
+// fp32 accumulators.  Operand slabs of 32 k-values go global -> LDS directly
+// (global_load_lds, 16 bytes per lane) through a four-deep ring; see gemm_tile.h for the tile
+// layouts and the pipeline.  The large tile is what the chip needs: two waves per SIMD keep the
+// MFMA pipe full and 256 x 256 halves the cache-to-LDS traffic per flop of a 128 x 128 tile.
 //
-// Three operand situations occur (rows = the non-contracted index of an operand):
-//   k-contiguous in memory  (X, A, dY, dGt, dU as left operands; Wg, Wu, Wd in the forward)
-//   k-strided in memory     (weights in the data-gradient GEMMs; both operands of the
-//                            weight-gradient GEMMs, whose contraction runs over a group's rows)
+// MFMA operand roles: the lanes carry the index that is contiguous in the output's memory
+// only for the fp32 weight gradients (128-byte runs per store); for the bf16 row tensors the
+// lanes carry the row index and each lane holds 4 consecutive columns (8-byte accesses).
 // The ragged dimension is always clamped (reads) and masked (writes); a ragged contraction
-// (weight gradients) is zero-filled.
-#include "common.h"
+// (weight gradients) is masked to zero in the fragments.
+//
+// Block index -> tile: consecutive tiles (same rows, next column block) are given to the same
+// XCD (blockIdx % 8), so that operand tiles shared by neighbouring tiles are served by one L2.
+#include "gemm_tile.h"
+
+#include <type_traits>
 
 namespace relibra {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDK = BK + 8;                 // padded LDS row, in elements
-constexpr int THREADS = 256;
-constexpr int TM = 2, TN = 2;               // MFMA tiles per wave, 32x32 each
-constexpr int CHUNKS = BM * BK / 8 / THREADS;   // 16-byte pieces per thread per operand tile (= 4)
-
-static_assert(BM == BN, "operand tiles share one loader");
+constexpr int BM = 256;                     // rows of a full row tile
+constexpr int THREADS = 512;
 
 // ---------------------------------------------------------------- schedule tables
 // Sanitised copies of the caller's group tables plus the list of row tiles, built on the
@@ -41,6 +38,7 @@ struct Sched {
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int max_row_tiles(int n_rows, int Gr) { return (n_rows + BM - 1) / BM + Gr; }
+constexpr int kLdsBytes = 4 * 512 * BK * 2;     // four slabs of 512 operand rows
 inline size_t sched_ints(int n_rows, int Gr) { return 8 + 4 * (size_t)Gr + (Gr + 1) + 3 * (size_t)max_row_tiles(n_rows, Gr) + 2 * (size_t)Gr; }
 inline size_t ffn_ws_bytes(int n_rows, int Gr, int hff, bool bwd)
 {
@@ -145,179 +143,153 @@ sched_kernel(const int32_t *__restrict__ group_offset, const int32_t *__restrict
     }
 }
 
-// ---------------------------------------------------------------- operand tiles
-struct Operand {
-    const bf16_t *base;   // element (row, k): base[row*ld + k] (k-contiguous) or base[k*ld + row] (k-strided)
-    int ld;
-    int row0;             // first row of the tile
-    int row_last;         // last valid row (reads of rows beyond it are clamped onto it)
+// ---------------------------------------------------------------- tile lookup
+struct RowTile {
+    int group, row0, rows, expert, col0;
+    bool valid;
 };
 
-struct Frag4 { uint4 v[CHUNKS]; };
-
-template <bool KS>
-__device__ __forceinline__ Frag4 load_tile(const Operand &op, int k0, int k_valid, int tid)
+// Physical block -> logical tile (row tile major, column tile minor), XCD-aware.
+__device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles, int col_tile_width)
 {
-    Frag4 f;
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-        const int c = tid + i * THREADS;
-        if (!KS) {
-            const int row = min(op.row0 + c / (BK / 8), op.row_last);
-            f.v[i] = *reinterpret_cast<const uint4 *>(op.base + (size_t)row * op.ld + k0 + (c % (BK / 8)) * 8);
-        } else {
-            const int kk = k0 + c / (BM / 8);
-            int r8 = op.row0 + (c % (BM / 8)) * 8;
-            if (r8 > op.row_last) r8 = op.row_last - 7;      // whole piece out of range: masked at the store
-            if (kk < k_valid)
-                f.v[i] = *reinterpret_cast<const uint4 *>(op.base + (size_t)kk * op.ld + r8);
-            else
-                f.v[i] = make_uint4(0, 0, 0, 0);
-        }
-    }
-    return f;
-}
-
-template <bool KS>
-__device__ __forceinline__ void store_tile(bf16_t (*s)[LDK], const Frag4 &f, int tid)
-{
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-        const int c = tid + i * THREADS;
-        if (!KS) {
-            *reinterpret_cast<uint4 *>(&s[c / (BK / 8)][(c % (BK / 8)) * 8]) = f.v[i];
-        } else {
-            const int kk = c / (BM / 8), r8 = (c % (BM / 8)) * 8;
-            const uint32_t w[4] = {f.v[i].x, f.v[i].y, f.v[i].z, f.v[i].w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                s[r8 + 2 * j][kk] = (bf16_t)(w[j] & 0xffffu);
-                s[r8 + 2 * j + 1][kk] = (bf16_t)(w[j] >> 16);
-            }
-        }
-    }
-}
-
-struct Smem {
-    bf16_t t[3][BM][LDK];     // left operands first, then right operands (at most three in all)
-};
-
-// acc[a*NB+b][i][j] += A_a(tile) * B_b(tile)^T over k in [k_begin, k_end).
-template <int NA, int NB, bool A_KS, bool B_KS>
-__device__ __forceinline__ void mainloop(f32x16_t (&acc)[NA * NB][TM][TN], const Operand (&A)[NA],
-                                         const Operand (&B)[NB], int k_begin, int k_end, int k_valid,
-                                         Smem &sm, int tid)
-{
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    Frag4 ra[NA], rb[NB];
-#pragma unroll
-    for (int a = 0; a < NA; ++a) ra[a] = load_tile<A_KS>(A[a], k_begin, k_valid, tid);
-#pragma unroll
-    for (int b = 0; b < NB; ++b) rb[b] = load_tile<B_KS>(B[b], k_begin, k_valid, tid);
-    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-        __syncthreads();
-#pragma unroll
-        for (int a = 0; a < NA; ++a) store_tile<A_KS>(sm.t[a], ra[a], tid);
-#pragma unroll
-        for (int b = 0; b < NB; ++b) store_tile<B_KS>(sm.t[NA + b], rb[b], tid);
-        __syncthreads();
-        if (k0 + BK < k_end) {
-#pragma unroll
-            for (int a = 0; a < NA; ++a) ra[a] = load_tile<A_KS>(A[a], k0 + BK, k_valid, tid);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) rb[b] = load_tile<B_KS>(B[b], k0 + BK, k_valid, tid);
-        }
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            const int kofs = kk + (lane >> 5) * 8;
-            bf16x8_t fa[NA][TM], fb[NB][TN];
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fa[a][i] = *reinterpret_cast<const bf16x8_t *>(&sm.t[a][wm * 64 + i * 32 + (lane & 31)][kofs]);
-#pragma unroll
-            for (int b = 0; b < NB; ++b)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[b][j] = *reinterpret_cast<const bf16x8_t *>(&sm.t[NA + b][wn * 64 + j * 32 + (lane & 31)][kofs]);
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[a * NB + b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                fa[a][i], fb[b][j], acc[a * NB + b][i][j], 0, 0, 0);
-        }
-    }
-}
-
-template <int N>
-__device__ __forceinline__ void zero_acc(f32x16_t (&acc)[N][TM][TN])
-{
-#pragma unroll
-    for (int n = 0; n < N; ++n)
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[n][i][j][v] = 0.0f;
-}
-
-// Visit every accumulator element of this lane: f(r, c, i, j, v) with (r, c) inside the 128x128 tile.
-template <typename F>
-__device__ __forceinline__ void for_each_acc(int tid, F f)
-{
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const int c = wn * 64 + j * 32 + (lane & 31);
-                f(r, c, i, j, v);
-            }
+    RowTile t;
+    const int total = s.hdr[0] * n_col_tiles;
+    const int per_xcd = (total + 7) >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    t.valid = logical < total && (int)(blockIdx.x >> 3) < per_xcd;
+    if (!t.valid) return t;
+    const int rt = logical / n_col_tiles;
+    t.group = s.tile_group[rt];
+    t.row0 = s.tile_row0[rt];
+    t.rows = s.tile_rows[rt];
+    t.expert = s.grp_expert[t.group];
+    t.col0 = (logical % n_col_tiles) * col_tile_width;
+    return t;
 }
 
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
-// ---------------------------------------------------------------- forward kernels
-// Gt = X Wg^T, U = X Wu^T (one pass over X), A = silu(Gt) * U.
+__device__ __forceinline__ uint2 pack4bf(float a, float b, float c, float d)
+{
+    uint2 w;
+    w.x = pack2bf(a, b);
+    w.y = pack2bf(c, d);
+    return w;
+}
+__device__ __forceinline__ void unpack4bf(uint2 w, float (&f)[4])
+{
+    f[0] = __uint_as_float(w.x << 16);
+    f[1] = __uint_as_float(w.x & 0xffff0000u);
+    f[2] = __uint_as_float(w.y << 16);
+    f[3] = __uint_as_float(w.y & 0xffff0000u);
+}
+
+// Wave layouts: full tiles (256 rows) 2 x 4, tail tiles (128 rows) 4 x 2.
+template <int BB> struct Waves { static constexpr int A = (BB == 256) ? 2 : 4, B = (BB == 256) ? 4 : 2; };
+
+// ---------------------------------------------------------------- forward
+// Gt = X Wg^T, U = X Wu^T (one pass over X), A = silu(Gt) * U.   Column tile: 128 of h'.
+template <int BB>
+__device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t *X, const bf16_t *Wg, const bf16_t *Wu,
+                                                 int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout, char *lds)
+{
+    using KL = KLoop<KcTile<128>, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false>;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t wofs = (size_t)t.expert * hff * h;
+    const Operand A[1][2] = {{{Wg + wofs, h, t.col0, hff - 1}, {Wu + wofs, h, t.col0, hff - 1}}};
+    const Operand B[1][1] = {{{X, h, t.row0, t.row0 + t.rows - 1}}};
+    typename KL::Acc acc;
+    KL::zero(acc);
+    KL::run(acc, A, B, h / BK, h, lds, tid);
+#pragma unroll
+    for (int tb = 0; tb < KL::TB; ++tb) {
+        const int r = KL::b_row(wave, lane, tb);
+        if (r >= t.rows) continue;
+        const size_t rbase = (size_t)(t.row0 + r) * hff;
+#pragma unroll
+        for (int ta = 0; ta < KL::TA; ++ta)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = t.col0 + KL::a_row(wave, lane, ta, q * 4);
+                if (c >= hff) continue;
+                float g[4], u[4], a[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    g[e] = acc[0][ta][tb][q * 4 + e];
+                    u[e] = acc[1][ta][tb][q * 4 + e];
+                    a[e] = g[e] * sigmoidf_(g[e]) * u[e];
+                }
+                *reinterpret_cast<uint2 *>(Gt + rbase + c) = pack4bf(g[0], g[1], g[2], g[3]);
+                *reinterpret_cast<uint2 *>(U + rbase + c) = pack4bf(u[0], u[1], u[2], u[3]);
+                *reinterpret_cast<uint2 *>(Aout + rbase + c) = pack4bf(a[0], a[1], a[2], a[3]);
+            }
+    }
+}
+
 __global__ void __launch_bounds__(THREADS)
 fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wg,
                    const bf16_t *__restrict__ Wu, int h, int hff, int n_col_tiles,
                    bf16_t *__restrict__ Gt, bf16_t *__restrict__ U, bf16_t *__restrict__ Aout)
 {
-    __shared__ Smem sm;
-    const int rt = blockIdx.x / n_col_tiles, ct = blockIdx.x % n_col_tiles;
-    if (rt >= s.hdr[0]) return;
-    const int tid = threadIdx.x;
-    const int g = s.tile_group[rt], row0 = s.tile_row0[rt], rows = s.tile_rows[rt];
-    const int e = s.grp_expert[g];
-    const size_t wofs = (size_t)e * hff * h;
-    const int col0 = ct * BN, cols = min(BN, hff - col0);
-    Operand A[1] = {{X, h, row0, row0 + rows - 1}};
-    Operand B[2] = {{Wg + wofs, h, col0, hff - 1}, {Wu + wofs, h, col0, hff - 1}};
-    f32x16_t acc[2][TM][TN];
-    zero_acc(acc);
-    mainloop<1, 2, false, false>(acc, A, B, 0, h, h, sm, tid);
-    for_each_acc(tid, [&](int r, int c, int i, int j, int v) {
-        if (r < rows && c < cols) {
-            const float gt = acc[0][i][j][v], u = acc[1][i][j][v];
-            const size_t o = (size_t)(row0 + r) * hff + col0 + c;
-            Gt[o] = f2bf(gt);
-            U[o] = f2bf(u);
-            Aout[o] = f2bf(gt * sigmoidf_(gt) * u);
-        }
-    });
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const RowTile t = find_row_tile(s, n_col_tiles, 128);
+    if (!t.valid) return;
+    if (t.rows > 128) fwd_gate_up_body<256>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    else fwd_gate_up_body<128>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
+}
+
+// Shared body of the three single-accumulator row-tiled GEMMs.  EPI: 0 = store bf16 (Y, dX);
+// 1 = dA -> dGt, dU (needs Gt, U).  W_KS: weights k-strided (data gradients).  NPH = 2 sums two
+// products (dX = dGt Wg + dU Wu).
+template <int BB, bool W_KS, int NPH, int EPI>
+__device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0, const bf16_t *P1, int ldp,
+                                              const bf16_t *W0, const bf16_t *W1, int ldw, int n_dim, int k_dim,
+                                              bf16_t *out0, bf16_t *out1, const bf16_t *Gt, const bf16_t *U, char *lds)
+{
+    using WT = typename std::conditional<W_KS, KsTile<256>, KcTile<256>>::type;
+    using KL = KLoop<WT, KcTile<BB>, 1, 1, 256, BB, Waves<BB>::A, Waves<BB>::B, NPH, false>;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Operand A[NPH][1], B[NPH][1];
+    A[0][0] = {W0, ldw, t.col0, n_dim - 1};
+    B[0][0] = {P0, ldp, t.row0, t.row0 + t.rows - 1};
+    if (NPH == 2) {
+        A[NPH - 1][0] = {W1, ldw, t.col0, n_dim - 1};
+        B[NPH - 1][0] = {P1, ldp, t.row0, t.row0 + t.rows - 1};
+    }
+    typename KL::Acc acc;
+    KL::zero(acc);
+    KL::run(acc, A, B, k_dim / BK, k_dim, lds, tid);
+#pragma unroll
+    for (int tb = 0; tb < KL::TB; ++tb) {
+        const int r = KL::b_row(wave, lane, tb);
+        if (r >= t.rows) continue;
+        const size_t rbase = (size_t)(t.row0 + r) * n_dim;
+#pragma unroll
+        for (int ta = 0; ta < KL::TA; ++ta)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = t.col0 + KL::a_row(wave, lane, ta, q * 4);
+                if (c >= n_dim) continue;
+                const float v0 = acc[0][ta][tb][q * 4], v1 = acc[0][ta][tb][q * 4 + 1],
+                            v2 = acc[0][ta][tb][q * 4 + 2], v3 = acc[0][ta][tb][q * 4 + 3];
+                if (EPI == 0) {
+                    *reinterpret_cast<uint2 *>(out0 + rbase + c) = pack4bf(v0, v1, v2, v3);
+                } else {
+                    const float da[4] = {v0, v1, v2, v3};
+                    float g[4], u[4], dg[4], du[4];
+                    unpack4bf(*reinterpret_cast<const uint2 *>(Gt + rbase + c), g);
+                    unpack4bf(*reinterpret_cast<const uint2 *>(U + rbase + c), u);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float sg = sigmoidf_(g[e]);
+                        dg[e] = da[e] * u[e] * (sg * (1.0f + g[e] * (1.0f - sg)));
+                        du[e] = da[e] * (g[e] * sg);
+                    }
+                    *reinterpret_cast<uint2 *>(out0 + rbase + c) = pack4bf(dg[0], dg[1], dg[2], dg[3]);
+                    *reinterpret_cast<uint2 *>(out1 + rbase + c) = pack4bf(du[0], du[1], du[2], du[3]);
+                }
+            }
+    }
 }
 
 // Y = A Wd^T.
@@ -325,50 +297,26 @@ __global__ void __launch_bounds__(THREADS)
 fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restrict__ Wd, int h, int hff,
                 int n_col_tiles, bf16_t *__restrict__ Y)
 {
-    __shared__ Smem sm;
-    const int rt = blockIdx.x / n_col_tiles, ct = blockIdx.x % n_col_tiles;
-    if (rt >= s.hdr[0]) return;
-    const int tid = threadIdx.x;
-    const int g = s.tile_group[rt], row0 = s.tile_row0[rt], rows = s.tile_rows[rt];
-    const int e = s.grp_expert[g];
-    const int col0 = ct * BN, cols = min(BN, h - col0);
-    Operand A[1] = {{Ain, hff, row0, row0 + rows - 1}};
-    Operand B[1] = {{Wd + (size_t)e * h * hff, hff, col0, h - 1}};
-    f32x16_t acc[1][TM][TN];
-    zero_acc(acc);
-    mainloop<1, 1, false, false>(acc, A, B, 0, hff, hff, sm, tid);
-    for_each_acc(tid, [&](int r, int c, int i, int j, int v) {
-        if (r < rows && c < cols) Y[(size_t)(row0 + r) * h + col0 + c] = f2bf(acc[0][i][j][v]);
-    });
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const RowTile t = find_row_tile(s, n_col_tiles, 256);
+    if (!t.valid) return;
+    const bf16_t *W = Wd + (size_t)t.expert * h * hff;
+    if (t.rows > 128) row_gemm_body<256, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
+    else row_gemm_body<128, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
 }
 
-// ---------------------------------------------------------------- backward kernels
+// ---------------------------------------------------------------- backward
 // dA = dY Wd, then dGt = dA * U * silu'(Gt), dU = dA * silu(Gt).
 __global__ void __launch_bounds__(THREADS)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
                const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles)
 {
-    __shared__ Smem sm;
-    const int rt = blockIdx.x / n_col_tiles, ct = blockIdx.x % n_col_tiles;
-    if (rt >= s.hdr[0]) return;
-    const int tid = threadIdx.x;
-    const int g = s.tile_group[rt], row0 = s.tile_row0[rt], rows = s.tile_rows[rt];
-    const int e = s.grp_expert[g];
-    const int col0 = ct * BN, cols = min(BN, hff - col0);
-    Operand A[1] = {{dY, h, row0, row0 + rows - 1}};
-    Operand B[1] = {{Wd + (size_t)e * h * hff, hff, col0, hff - 1}};     // (n in hff, k in h) at [k*hff + n]
-    f32x16_t acc[1][TM][TN];
-    zero_acc(acc);
-    mainloop<1, 1, false, true>(acc, A, B, 0, h, h, sm, tid);
-    for_each_acc(tid, [&](int r, int c, int i, int j, int v) {
-        if (r < rows && c < cols) {
-            const size_t o = (size_t)(row0 + r) * hff + col0 + c;
-            const float da = acc[0][i][j][v], gt = bf2f(Gt[o]), u = bf2f(U[o]);
-            const float sg = sigmoidf_(gt);
-            s.dGt[o] = f2bf(da * u * (sg * (1.0f + gt * (1.0f - sg))));
-            s.dU[o] = f2bf(da * (gt * sg));
-        }
-    });
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const RowTile t = find_row_tile(s, n_col_tiles, 256);
+    if (!t.valid) return;
+    const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n]
+    if (t.rows > 128) row_gemm_body<256, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
+    else row_gemm_body<128, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
 }
 
 // dX = dGt Wg + dU Wu (one accumulator, the contraction runs over both products).
@@ -376,73 +324,68 @@ __global__ void __launch_bounds__(THREADS)
 bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff,
               int n_col_tiles, bf16_t *__restrict__ dX)
 {
-    __shared__ Smem sm;
-    const int rt = blockIdx.x / n_col_tiles, ct = blockIdx.x % n_col_tiles;
-    if (rt >= s.hdr[0]) return;
-    const int tid = threadIdx.x;
-    const int g = s.tile_group[rt], row0 = s.tile_row0[rt], rows = s.tile_rows[rt];
-    const int e = s.grp_expert[g];
-    const size_t wofs = (size_t)e * hff * h;
-    const int col0 = ct * BN, cols = min(BN, h - col0);
-    f32x16_t acc[1][TM][TN];
-    zero_acc(acc);
-    {
-        Operand A[1] = {{s.dGt, hff, row0, row0 + rows - 1}};
-        Operand B[1] = {{Wg + wofs, h, col0, h - 1}};                    // (n in h, k in hff) at [k*h + n]
-        mainloop<1, 1, false, true>(acc, A, B, 0, hff, hff, sm, tid);
-    }
-    {
-        Operand A[1] = {{s.dU, hff, row0, row0 + rows - 1}};
-        Operand B[1] = {{Wu + wofs, h, col0, h - 1}};
-        mainloop<1, 1, false, true>(acc, A, B, 0, hff, hff, sm, tid);
-    }
-    for_each_acc(tid, [&](int r, int c, int i, int j, int v) {
-        if (r < rows && c < cols) dX[(size_t)(row0 + r) * h + col0 + c] = f2bf(acc[0][i][j][v]);
-    });
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const RowTile t = find_row_tile(s, n_col_tiles, 256);
+    if (!t.valid) return;
+    const size_t wofs = (size_t)t.expert * hff * h;         // (n in h, k in h') at [k*h + n]
+    if (t.rows > 128) row_gemm_body<256, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
+    else row_gemm_body<128, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
 }
 
 // Weight gradients: out[slot][m][n] (+)= sum over the group's rows of L[row][m] * R[row][n].
 // NA = 2 computes two left operands against one right operand (dGt and dU against X).
+// Tile: (NA x BA) x 256 with BA = 256 / NA.
 template <int NA>
 __global__ void __launch_bounds__(THREADS)
 wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ L1,
-             const bf16_t *__restrict__ R, int m_dim, int n_dim, int E, int accumulate,
+             const bf16_t *__restrict__ R, int m_dim, int n_dim, int E, int accumulate, int total,
              float *__restrict__ out0, float *__restrict__ out1)
 {
-    __shared__ Smem sm;
-    const int n_nt = (n_dim + BN - 1) / BN, n_mt = (m_dim + BM - 1) / BM;
+    constexpr int BA = 256 / NA;
+    using KL = KLoop<KsTile<BA>, KsTile<256>, NA, 1, BA, 256, 2, 4, 1, true>;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int n_nt = (n_dim + 255) / 256, n_mt = (m_dim + BA - 1) / BA;
     const int per_group = n_nt * n_mt;
-    const int gi = blockIdx.x / per_group, rem = blockIdx.x % per_group;
+    const int per_xcd = (total + 7) >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total) return;
+    const int gi = logical / per_group, rem = logical % per_group;
     const int e = s.grp_expert[gi];
     if (e < 0) return;
     const int slot = s.grp_slot[gi];
     const bool add = accumulate && slot < E;
     const int row0 = s.grp_row0[gi], rows = s.grp_rows[gi];
     if (rows == 0 && add) return;
-    const int tid = threadIdx.x;
-    const int m0 = (rem / n_nt) * BM, n0 = (rem % n_nt) * BN;
-    Operand A[NA];
-    A[0] = {L0 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
-    if (NA == 2) A[NA - 1] = {L1 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
-    Operand B[1] = {{R + (size_t)row0 * n_dim, n_dim, n0, n_dim - 1}};
-    f32x16_t acc[NA][TM][TN];
-    zero_acc(acc);
-    const int k_end = (rows + BK - 1) / BK * BK;
-    mainloop<NA, 1, true, true>(acc, A, B, 0, k_end, rows, sm, tid);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = (rem / n_nt) * BA, n0 = (rem % n_nt) * 256;
+    Operand A[1][NA], B[1][1];
+    A[0][0] = {L0 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
+    if (NA == 2) A[0][NA - 1] = {L1 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
+    B[0][0] = {R + (size_t)row0 * n_dim, n_dim, n0, n_dim - 1};
+    typename KL::Acc acc;
+    KL::zero(acc);
+    KL::run(acc, A, B, (rows + BK - 1) / BK, rows, lds, tid);
     const size_t base = (size_t)slot * m_dim * n_dim;
-    const int mv = min(BM, m_dim - m0), nv = min(BN, n_dim - n0);
-    for_each_acc(tid, [&](int r, int c, int i, int j, int v) {
-        if (r < mv && c < nv) {
-            const size_t o = base + (size_t)(m0 + r) * n_dim + n0 + c;
-            if (add) {
-                out0[o] += acc[0][i][j][v];
-                if (NA == 2) out1[o] += acc[NA - 1][i][j][v];
-            } else {
-                out0[o] = acc[0][i][j][v];
-                if (NA == 2) out1[o] = acc[NA - 1][i][j][v];
+#pragma unroll
+    for (int tb = 0; tb < KL::TB; ++tb) {
+        const int c = n0 + KL::b_row(wave, lane, tb);
+        if (c >= n_dim) continue;
+#pragma unroll
+        for (int ta = 0; ta < KL::TA; ++ta)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = m0 + KL::a_row(wave, lane, ta, v);
+                if (r >= m_dim) continue;
+                const size_t o = base + (size_t)r * n_dim + c;
+                if (add) {
+                    out0[o] += acc[0][ta][tb][v];
+                    if (NA == 2) out1[o] += acc[NA - 1][ta][tb][v];
+                } else {
+                    out0[o] = acc[0][ta][tb][v];
+                    if (NA == 2) out1[o] = acc[NA - 1][ta][tb][v];
+                }
             }
-        }
-    });
+    }
 }
 
 // Replica gradients return to the home copy (Section 5.1).  A thread owns element positions
@@ -490,6 +433,23 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     (void)h;
 }
 
+// Kernels use 128 KiB of dynamic LDS: raise the per-kernel limit once.
+static int ensure_lds_limits()
+{
+    static bool done = false;
+    if (done) return RELIBRA_OK;
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    done = true;
+    return RELIBRA_OK;
+}
+
+static inline unsigned grid8(long long tiles) { return (unsigned)((tiles + 7) / 8 * 8); }
+
 extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
                                    const int32_t *group_offset, const int32_t *group_expert,
                                    int G, int g_begin, int g_end, int E,
@@ -506,19 +466,20 @@ extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
         !Yrows || !ws || !err_flag)
         return RELIBRA_EINVAL;
     if (!aligned16(Xrows) || !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) || !aligned16(A_save) ||
-        !aligned16(ws))
+        !aligned16(Gt_save) || !aligned16(U_save) || !aligned16(Yrows) || !aligned16(ws))
         return RELIBRA_EINVAL;
     if (ws_bytes < ffn_ws_bytes(n_rows, Gr, hff, false)) return RELIBRA_EWORKSPACE;
+    if (int rc = ensure_lds_limits()) return rc;
     Sched s = carve(ws, n_rows, Gr, hff, false);
     RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, nullptr, g_begin, Gr, n_rows, E, 0, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
-    const int R = max_row_tiles(n_rows, Gr);
-    const int ct1 = (hff + BN - 1) / BN, ct2 = (h + BN - 1) / BN;
-    RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<<<(unsigned)(R * ct1), THREADS, 0, stream>>>(
+    const long long R = max_row_tiles(n_rows, Gr);
+    const int ct1 = (hff + 127) / 128, ct2 = (h + 255) / 256;
+    RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<<<grid8(R * ct1), THREADS, kLdsBytes, stream>>>(
         s, (const bf16_t *)Xrows, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
         (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save));
     RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<<<(unsigned)(R * ct2), THREADS, 0, stream>>>(
+    RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<<<grid8(R * ct2), THREADS, kLdsBytes, stream>>>(
         s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
@@ -542,32 +503,35 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     if (!dYrows || !Xrows || !Gt_save || !U_save || !A_save || !group_offset || !group_expert || !group_dw_slot ||
         !Wg || !Wu || !Wd || !dXrows || !dWg || !dWu || !dWd || !ws || !err_flag)
         return RELIBRA_EINVAL;
-    if (!aligned16(dYrows) || !aligned16(Xrows) || !aligned16(A_save) || !aligned16(Wg) || !aligned16(Wu) ||
-        !aligned16(Wd) || !aligned16(dWg) || !aligned16(dWu) || !aligned16(dWd) || !aligned16(ws))
+    if (!aligned16(dYrows) || !aligned16(Xrows) || !aligned16(A_save) || !aligned16(Gt_save) || !aligned16(U_save) ||
+        !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) || !aligned16(dXrows) || !aligned16(dWg) ||
+        !aligned16(dWu) || !aligned16(dWd) || !aligned16(ws))
         return RELIBRA_EINVAL;
     if (ws_bytes < ffn_ws_bytes(n_rows, Gr, hff, true)) return RELIBRA_EWORKSPACE;
+    if (int rc = ensure_lds_limits()) return rc;
     Sched s = carve(ws, n_rows, Gr, hff, true);
     RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, group_dw_slot, g_begin, Gr, n_rows, E,
                                         n_dw_slots, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
-    const int R = max_row_tiles(n_rows, Gr);
-    const int ct_ff = (hff + BN - 1) / BN, ct_h = (h + BN - 1) / BN;
+    const long long R = max_row_tiles(n_rows, Gr);
+    const int ct_ff = (hff + 255) / 256, ct_h = (h + 255) / 256;
     const int accumulate = (flags & RELIBRA_BWD_ACCUMULATE) ? 1 : 0;
     if (n_rows > 0) {
-        RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<<<(unsigned)(R * ct_ff), THREADS, 0, stream>>>(
+        RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
             s, (const bf16_t *)dYrows, (const bf16_t *)Wd, (const bf16_t *)Gt_save, (const bf16_t *)U_save,
             h, hff, ct_ff));
         RELIBRA_HIP_TRY(launch_check());
-        RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<<<(unsigned)(R * ct_h), THREADS, 0, stream>>>(
+        RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<<<grid8(R * ct_h), THREADS, kLdsBytes, stream>>>(
             s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, (bf16_t *)dXrows));
         RELIBRA_HIP_TRY(launch_check());
     }
-    const int tiles = ct_ff * ct_h;
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1><<<(unsigned)(Gr * tiles), THREADS, 0, stream>>>(
-        s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, dWd, nullptr));
+    const long long t_down = (long long)Gr * ct_h * ct_ff;                 // dWd: m in h (256), n in h' (256)
+    const long long t_gu = (long long)Gr * ((hff + 127) / 128) * ct_h;     // dWg, dWu: m in h' (128 each), n in h (256)
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1><<<grid8(t_down), THREADS, kLdsBytes, stream>>>(
+        s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, (int)t_down, dWd, nullptr));
     RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_kernel<2><<<(unsigned)(Gr * tiles), THREADS, 0, stream>>>(
-        s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, dWg, dWu));
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_kernel<2><<<grid8(t_gu), THREADS, kLdsBytes, stream>>>(
+        s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, (int)t_gu, dWg, dWu));
     RELIBRA_HIP_TRY(launch_check());
     if (!(flags & RELIBRA_BWD_NO_REPLICA_SUM) && n_dw_slots > E) {
         const size_t vec4 = (size_t)h * hff / 4;

@@ -1,0 +1,284 @@
+// Building blocks of the grouped bf16 MFMA GEMMs (gfx950): LDS operand tiles filled by
+// direct global->LDS loads, MFMA fragment reads, and a three-slab pipelined k-loop.
+//
+// An operand tile covers ROWS rows of the non-contracted index and 32 values of the contracted
+// index k.  Two memory situations:
+//   KcTile: k contiguous in memory (element (row,k) at base[row*ld + k]).  LDS holds [row][32],
+//           64 bytes per row, 16-byte pieces XOR-swizzled by the row so that the 16-byte
+//           fragment reads of 32 consecutive rows spread over all banks.
+//   KsTile: k strided in memory (element (row,k) at base[k*ld + row]).  LDS holds [k][ROWS] as
+//           it lies in memory; fragments are read with the transposing LDS read
+//           (ds_read_b64_tr_b16), 16-byte pieces XOR-swizzled by k.
+// global_load_lds writes 64 lanes x 16 bytes to 1 KiB of consecutive LDS; which global address
+// a lane fetches is free, so the swizzle is applied on the global side.
+#pragma once
+#include "common.h"
+
+namespace relibra {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int BK = 32;                      // contraction slab per pipeline stage (two k16 MFMA steps)
+
+#define RELIBRA_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+#define RELIBRA_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
+
+// s_waitcnt vmcnt(N) lgkmcnt(0) (gfx9 encoding; expcnt = 7 means "do not wait")
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm0()
+{
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | ((N >> 4) << 14));
+}
+
+struct Operand {
+    const bf16_t *base;   // see KcTile / KsTile for the addressing
+    int ld;               // leading dimension in elements
+    int row0;             // first row of the tile
+    int row_last;         // last valid row; rows beyond are clamped onto valid ones (masked later)
+};
+
+// k-contiguous operand: LDS [row][32], 64 bytes per row, 16 rows per 1 KiB load block.
+// Piece c of row r sits at piece c ^ g(r), g(r) = ((r>>1)&3) ^ ((r>>3)&1): the 16-byte reads of
+// any 8 (or 16) consecutive rows at one k offset fall into distinct 16-byte bank groups.
+template <int ROWS>
+struct KcTile {
+    static constexpr int BYTES = ROWS * BK * 2;
+    static constexpr int BLOCKS = ROWS / 16;
+
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Operand &op, int k0, int /*k_last*/, int wave, int lane)
+    {
+        static_assert(BLOCKS % NW == 0, "rows must split evenly over the waves");
+#pragma unroll
+        for (int i = 0; i < BLOCKS / NW; ++i) {
+            const int j = wave + i * NW;
+            const int r = j * 16 + (lane >> 2);
+            const int c = (lane & 3) ^ ((lane >> 3) & 3) ^ ((lane >> 5) & 1);
+            const int grow = min(op.row0 + r, op.row_last);
+            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)grow * op.ld + k0 + c * 8),
+                                             RELIBRA_LDS(lds + j * 1024), 16, 0, 0);
+        }
+    }
+
+    // fragment of rows r0..r0+31 (r0 % 32 == 0), k = kk*16 + (lane/32)*8 .. +7
+    static __device__ __forceinline__ bf16x8_t frag(const char *lds, int r0, int kk, int lane)
+    {
+        const int r = r0 + (lane & 31);
+        const int g = ((lane >> 1) & 3) ^ ((lane >> 3) & 1);
+        const int c = (kk * 2 + (lane >> 5)) ^ g;
+        return *reinterpret_cast<const bf16x8_t *>(lds + r * 64 + c * 16);
+    }
+};
+
+// k-strided operand: LDS [k][ROWS] as in memory; 16-byte pieces of a k-row XOR-ed with fk(k) so
+// that the 8-byte transposing reads of 4 k-rows x 16 (or 32) rows hit distinct banks.
+template <int ROWS>
+struct KsTile {
+    static constexpr int BYTES = ROWS * BK * 2;
+    static constexpr int SPR = ROWS / 8;              // 16-byte pieces per k-row
+    static constexpr int KPB = 64 / SPR;              // k-rows per 1 KiB block
+    static constexpr int BLOCKS = BK / KPB;
+    static_assert(ROWS >= 128 && ROWS <= 512, "tile height");
+
+    static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
+
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Operand &op, int k0, int k_last, int wave, int lane)
+    {
+        static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
+#pragma unroll
+        for (int i = 0; i < BLOCKS / NW; ++i) {
+            const int j = wave + i * NW;
+            const int k = j * KPB + lane / SPR;
+            const int s = (lane % SPR) ^ fk(k);
+            const int gk = min(k0 + k, k_last);
+            int grow = op.row0 + s * 8;
+            if (grow > op.row_last) grow = op.row_last - 7;
+            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)gk * op.ld + grow),
+                                             RELIBRA_LDS(lds + j * 1024), 16, 0, 0);
+        }
+    }
+
+    static __device__ __forceinline__ bf16x8_t frag(const char *lds, int r0, int kk, int lane)
+    {
+        const int b = lane >> 4, i = lane & 15;
+        const int m = r0 + (b & 1) * 16 + (i & 3) * 4;
+        const int kb = kk * 16 + (b >> 1) * 8 + (i >> 2);
+        const int piece = (((m >> 3) ^ fk(kb)) * 16) + ((m >> 2) & 1) * 8;
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4_t *)RELIBRA_LDS(lds + kb * (ROWS * 2) + piece));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4_t *)RELIBRA_LDS(lds + (kb + 4) * (ROWS * 2) + piece));
+        const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8_t, v);
+    }
+};
+
+// Zero the fragment elements whose k index is >= k_valid (ragged contraction, last slabs only).
+__device__ __forceinline__ bf16x8_t mask_frag(bf16x8_t f, int k_first, int k_valid)
+{
+    s16x8_t v = __builtin_bit_cast(s16x8_t, f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (k_first + e >= k_valid) v[e] = 0;
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// The k-loop.  "A side": operands whose row index lands in the accumulator registers (MFMA rows);
+// "B side": operands whose row index lands on the lanes (MFMA columns).
+//   acc[a*NB + b][ta][tb] += sum_k A_a[row_a][k] * B_b[row_b][k]
+// Every operand tile has BA (A side) or BB (B side) rows; WA x WB wavefronts tile BA x BB.  NPH
+// phases run back to back over the same accumulators with different operands (sum of products).
+//
+// Pipeline: a ring of STAGES LDS slabs of 32 k-values.  In step t the wave
+//   reads the k16 = 1 fragments of slab t, issues the MFMAs of k16 = 0,
+//   waits until its own loads of slab t+1 have landed (those of later slabs stay in flight) and
+//   meets the other waves: slab t+1 is complete and nobody reads slab t any more,
+//   so it issues the loads of slab t+STAGES into slab t's place, reads the k16 = 0 fragments of
+//   slab t+1 and issues the MFMAs of k16 = 1, which cover both latencies.
+template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0>
+struct KLoop {
+    static constexpr int NW = WA * WB;
+    static constexpr int TA = BA / WA / 32, TB = BB / WB / 32;
+    static constexpr int STAGE_BYTES = NA * AT::BYTES + NB * BT::BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int LOADS = (NA * AT::BLOCKS + NB * BT::BLOCKS) / NW;   // per wave per slab
+    typedef f32x16_t Acc[NA * NB][TA][TB];
+
+    struct Frags {
+        bf16x8_t a[NA][TA], b[NB][TB];
+    };
+
+    static __device__ __forceinline__ void issue(char *stage, const Operand (&A)[NPH][NA], const Operand (&B)[NPH][NB],
+                                                 int t, int steps_per_phase, int k_last, int wave, int lane)
+    {
+        const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
+        const int k0 = (t - ph * steps_per_phase) * BK;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, A[ph][a], k0, k_last, wave, lane);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+            BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, B[ph][b], k0, k_last, wave, lane);
+    }
+
+    static __device__ __forceinline__ void read_frags(Frags &f, const char *stage, int kk, int wa, int wb, int lane)
+    {
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int t = 0; t < TA; ++t) f.a[a][t] = AT::frag(stage + a * AT::BYTES, wa * (BA / WA) + t * 32, kk, lane);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+                f.b[b][t] = BT::frag(stage + NA * AT::BYTES + b * BT::BYTES, wb * (BB / WB) + t * 32, kk, lane);
+    }
+
+    static __device__ __forceinline__ void mask_frags(Frags &f, int k_first, int k_valid)
+    {
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int t = 0; t < TA; ++t) f.a[a][t] = mask_frag(f.a[a][t], k_first, k_valid);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int t = 0; t < TB; ++t) f.b[b][t] = mask_frag(f.b[b][t], k_first, k_valid);
+    }
+
+    static __device__ __forceinline__ void mfma_all(Acc &acc, const Frags &f)
+    {
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int ta = 0; ta < TA; ++ta)
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+                        acc[a * NB + b][ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            f.a[a][ta], f.b[b][tb], acc[a * NB + b][ta][tb], 0, 0, 0);
+    }
+
+    // k extent per phase = steps_per_phase * 32; k_valid (<= that) is the ragged contraction length.
+    static __device__ __forceinline__ void run(Acc &acc, const Operand (&A)[NPH][NA], const Operand (&B)[NPH][NB],
+                                               int steps_per_phase, int k_valid, char *lds, int tid)
+    {
+        const int lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int wa = wave / WB, wb = wave % WB;
+        const int n = steps_per_phase * NPH;
+        const int k_last = k_valid - 1;
+        if (n <= 0) return;
+        Frags f0, f1;
+#pragma unroll
+        for (int i = 0; i < STAGES; ++i)
+            if (i < n) issue(lds + i * STAGE_BYTES, A, B, i, steps_per_phase, k_last, wave, lane);
+        wait_younger(n - 1);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f0, lds, 0, wa, wb, lane);
+        int slot = 0;
+        for (int t = 0; t < n; ++t) {
+            char *cur = lds + slot * STAGE_BYTES;
+            slot = (slot == STAGES - 1) ? 0 : slot + 1;
+            char *nxt = lds + slot * STAGE_BYTES;
+            const bool tail = RAGGED_K && (t + 1) * BK > k_valid;
+            const int kf = t * BK + (lane >> 5) * 8;
+            if (DBG != 2) {
+                read_frags(f1, cur, 1, wa, wb, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                if (tail) mask_frags(f0, kf, k_valid);
+                mfma_all(acc, f0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + STAGES < n && DBG != 1) issue(cur, A, B, t + STAGES, steps_per_phase, k_last, wave, lane);
+            if (DBG != 2) {
+                if (t + 1 < n) read_frags(f0, nxt, 0, wa, wb, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                if (tail) mask_frags(f1, kf + 16, k_valid);
+                mfma_all(acc, f1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // Wait until at most min(younger, STAGES-2) slabs' worth of this wave's loads are outstanding,
+    // and until its LDS reads have returned.
+    static __device__ __forceinline__ void wait_younger(int younger)
+    {
+        static_assert(STAGES >= 2 && STAGES <= 5, "ring depth");
+        if (STAGES >= 5 && younger >= 3) wait_vm_lgkm0<3 * LOADS>();
+        else if (STAGES >= 4 && younger >= 2) wait_vm_lgkm0<2 * LOADS>();
+        else if (STAGES >= 3 && younger >= 1) wait_vm_lgkm0<1 * LOADS>();
+        else wait_vm_lgkm0<0>();
+    }
+
+    static __device__ __forceinline__ void zero(Acc &acc)
+    {
+#pragma unroll
+        for (int n = 0; n < NA * NB; ++n)
+#pragma unroll
+            for (int ta = 0; ta < TA; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[n][ta][tb][v] = 0.0f;
+    }
+
+    // Position of accumulator element v of MFMA tile (ta, tb) inside the BA x BB tile:
+    // row on the A side, row on the B side.
+    static __device__ __forceinline__ int a_row(int wave, int lane, int ta, int v)
+    {
+        return (wave / WB) * (BA / WA) + ta * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    }
+    static __device__ __forceinline__ int b_row(int wave, int lane, int tb) { return (wave % WB) * (BB / WB) + tb * 32 + (lane & 31); }
+};
+
+}  // namespace relibra
