@@ -184,6 +184,62 @@ __device__ __forceinline__ void unpack4bf(uint2 w, float (&f)[4])
     f[3] = __uint_as_float(w.y & 0xffff0000u);
 }
 
+// Per-wave LDS staging between the accumulator layout (a lane holds 4 consecutive columns of
+// its row) and the row-major layout (a row's columns spread over consecutive lanes), so that
+// global accesses of the epilogue are 16 bytes per lane along rows: full cache lines.
+// A wave stages 64 rows x NCOLS bf16; 16-byte pieces of a row are XOR-ed with the row number.
+template <int NCOLS>
+struct WaveStage {
+    static constexpr int PIECES = NCOLS / 8;
+    static constexpr int BYTES = 64 * NCOLS * 2;
+    static constexpr int ROWS_PER_PASS = 64 / PIECES;
+    static constexpr int PASSES = 64 / ROWS_PER_PASS;
+
+    // accumulator side: 8 bytes = columns col..col+3 (col % 4 == 0) of `row`
+    static __device__ __forceinline__ int acc_addr(int row, int col)
+    {
+        return row * (NCOLS * 2) + ((((col >> 3) ^ row) & (PIECES - 1)) << 4) + ((col >> 2) & 1) * 8;
+    }
+    static __device__ __forceinline__ void put(char *buf, int row, int col, uint2 v) { *reinterpret_cast<uint2 *>(buf + acc_addr(row, col)) = v; }
+    static __device__ __forceinline__ uint2 get(const char *buf, int row, int col) { return *reinterpret_cast<const uint2 *>(buf + acc_addr(row, col)); }
+
+    // row-major side: stage -> global, rows grow0.. of a tensor with leading dimension ld
+    static __device__ __forceinline__ void flush(const char *buf, bf16_t *out, int ld, int grow0, int row_end,
+                                                 int gcol0, int n_dim, int lane)
+    {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
+            const uint4 v = *reinterpret_cast<const uint4 *>(buf + r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4));
+            if (grow0 + r < row_end && gcol0 + piece * 8 < n_dim)
+                *reinterpret_cast<uint4 *>(out + (size_t)(grow0 + r) * ld + gcol0 + piece * 8) = v;
+        }
+    }
+    // global -> stage
+    static __device__ __forceinline__ void fill(char *buf, const bf16_t *in, int ld, int grow0, int row_end,
+                                                int gcol0, int n_dim, int lane)
+    {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (grow0 + r < row_end && gcol0 + piece * 8 < n_dim)
+                v = *reinterpret_cast<const uint4 *>(in + (size_t)(grow0 + r) * ld + gcol0 + piece * 8);
+            *reinterpret_cast<uint4 *>(buf + r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4)) = v;
+        }
+    }
+};
+
+// LDS operations of one wave execute in order; this keeps the compiler from moving them across
+// the hand-over between the two layouts and waits for the data.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Wave layouts: full tiles (256 rows) 2 x 4, tail tiles (128 rows) 4 x 2.
 template <int BB> struct Waves { static constexpr int A = (BB == 256) ? 2 : 4, B = (BB == 256) ? 4 : 2; };
 
@@ -201,28 +257,33 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     typename KL::Acc acc;
     KL::zero(acc);
     KL::run(acc, A, B, h / BK, h, lds, tid);
+    // epilogue: three tensors, one after the other through this wave's staging area
+    constexpr int WCOLS = 128 / Waves<BB>::A;                 // columns of this wave per tensor
+    using ST = WaveStage<WCOLS>;
+    static_assert(KL::TB == 2, "a wave owns 64 rows");
+    __syncthreads();                                          // every wave is done with the operand slabs
+    char *buf = lds + wave * ST::BYTES;
+    const int wrow0 = t.row0 + (wave % Waves<BB>::B) * 64, row_end = t.row0 + t.rows;
+    const int wcol0 = t.col0 + (wave / Waves<BB>::B) * WCOLS;
 #pragma unroll
-    for (int tb = 0; tb < KL::TB; ++tb) {
-        const int r = KL::b_row(wave, lane, tb);
-        if (r >= t.rows) continue;
-        const size_t rbase = (size_t)(t.row0 + r) * hff;
+    for (int which = 0; which < 3; ++which) {
 #pragma unroll
-        for (int ta = 0; ta < KL::TA; ++ta)
+        for (int tb = 0; tb < KL::TB; ++tb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = t.col0 + KL::a_row(wave, lane, ta, q * 4);
-                if (c >= hff) continue;
-                float g[4], u[4], a[4];
+            for (int ta = 0; ta < KL::TA; ++ta)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    g[e] = acc[0][ta][tb][q * 4 + e];
-                    u[e] = acc[1][ta][tb][q * 4 + e];
-                    a[e] = g[e] * sigmoidf_(g[e]) * u[e];
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float g = acc[0][ta][tb][q * 4 + e], u = acc[1][ta][tb][q * 4 + e];
+                        v[e] = which == 0 ? g : which == 1 ? u : g * sigmoidf_(g) * u;
+                    }
+                    ST::put(buf, tb * 32 + (lane & 31), ta * 32 + q * 8 + (lane >> 5) * 4, pack4bf(v[0], v[1], v[2], v[3]));
                 }
-                *reinterpret_cast<uint2 *>(Gt + rbase + c) = pack4bf(g[0], g[1], g[2], g[3]);
-                *reinterpret_cast<uint2 *>(U + rbase + c) = pack4bf(u[0], u[1], u[2], u[3]);
-                *reinterpret_cast<uint2 *>(Aout + rbase + c) = pack4bf(a[0], a[1], a[2], a[3]);
-            }
+        wave_lds_fence();
+        ST::flush(buf, which == 0 ? Gt : which == 1 ? U : Aout, hff, wrow0, row_end, wcol0, hff, lane);
+        wave_lds_fence();
     }
 }
 
@@ -259,36 +320,64 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
     typename KL::Acc acc;
     KL::zero(acc);
     KL::run(acc, A, B, k_dim / BK, k_dim, lds, tid);
+    constexpr int WCOLS = 256 / Waves<BB>::A;
+    using ST = WaveStage<WCOLS>;
+    static_assert(KL::TB == 2, "a wave owns 64 rows");
+    __syncthreads();                                          // every wave is done with the operand slabs
+    char *buf = lds + wave * ST::BYTES;
+    const int wrow0 = t.row0 + (wave % Waves<BB>::B) * 64, row_end = t.row0 + t.rows;
+    const int wcol0 = t.col0 + (wave / Waves<BB>::B) * WCOLS;
+    if (EPI == 0) {
 #pragma unroll
-    for (int tb = 0; tb < KL::TB; ++tb) {
-        const int r = KL::b_row(wave, lane, tb);
-        if (r >= t.rows) continue;
-        const size_t rbase = (size_t)(t.row0 + r) * n_dim;
+        for (int tb = 0; tb < KL::TB; ++tb)
 #pragma unroll
-        for (int ta = 0; ta < KL::TA; ++ta)
+            for (int ta = 0; ta < KL::TA; ++ta)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = t.col0 + KL::a_row(wave, lane, ta, q * 4);
-                if (c >= n_dim) continue;
-                const float v0 = acc[0][ta][tb][q * 4], v1 = acc[0][ta][tb][q * 4 + 1],
-                            v2 = acc[0][ta][tb][q * 4 + 2], v3 = acc[0][ta][tb][q * 4 + 3];
-                if (EPI == 0) {
-                    *reinterpret_cast<uint2 *>(out0 + rbase + c) = pack4bf(v0, v1, v2, v3);
-                } else {
-                    const float da[4] = {v0, v1, v2, v3};
-                    float g[4], u[4], dg[4], du[4];
-                    unpack4bf(*reinterpret_cast<const uint2 *>(Gt + rbase + c), g);
-                    unpack4bf(*reinterpret_cast<const uint2 *>(U + rbase + c), u);
+                for (int q = 0; q < 4; ++q)
+                    ST::put(buf, tb * 32 + (lane & 31), ta * 32 + q * 8 + (lane >> 5) * 4,
+                            pack4bf(acc[0][ta][tb][q * 4], acc[0][ta][tb][q * 4 + 1], acc[0][ta][tb][q * 4 + 2],
+                                    acc[0][ta][tb][q * 4 + 3]));
+        wave_lds_fence();
+        ST::flush(buf, out0, n_dim, wrow0, row_end, wcol0, n_dim, lane);
+    } else {
+        // dA (in the accumulators) -> dGt, dU, half of the wave's columns at a time: Gt and U come
+        // in through two staging areas and are overwritten in place by dGt and dU.
+        using SH = WaveStage<WCOLS / 2>;
+        constexpr int TAH = KL::TA / 2;
+        static_assert(TAH >= 1, "at least 64 columns per wave");
+        char *buf_g = buf, *buf_u = buf + SH::BYTES;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float sg = sigmoidf_(g[e]);
-                        dg[e] = da[e] * u[e] * (sg * (1.0f + g[e] * (1.0f - sg)));
-                        du[e] = da[e] * (g[e] * sg);
+        for (int half = 0; half < 2; ++half) {
+            const int hcol0 = wcol0 + half * (WCOLS / 2);
+            SH::fill(buf_g, Gt, n_dim, wrow0, row_end, hcol0, n_dim, lane);
+            SH::fill(buf_u, U, n_dim, wrow0, row_end, hcol0, n_dim, lane);
+            wave_lds_fence();
+#pragma unroll
+            for (int tb = 0; tb < KL::TB; ++tb)
+#pragma unroll
+                for (int th = 0; th < TAH; ++th)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int ta = half * TAH + th;
+                        const int row = tb * 32 + (lane & 31), col = th * 32 + q * 8 + (lane >> 5) * 4;
+                        float g[4], u[4], dg[4], du[4];
+                        unpack4bf(SH::get(buf_g, row, col), g);
+                        unpack4bf(SH::get(buf_u, row, col), u);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float da = acc[0][ta][tb][q * 4 + e];
+                            const float sg = sigmoidf_(g[e]);
+                            dg[e] = da * u[e] * (sg * (1.0f + g[e] * (1.0f - sg)));
+                            du[e] = da * (g[e] * sg);
+                        }
+                        SH::put(buf_g, row, col, pack4bf(dg[0], dg[1], dg[2], dg[3]));
+                        SH::put(buf_u, row, col, pack4bf(du[0], du[1], du[2], du[3]));
                     }
-                    *reinterpret_cast<uint2 *>(out0 + rbase + c) = pack4bf(dg[0], dg[1], dg[2], dg[3]);
-                    *reinterpret_cast<uint2 *>(out1 + rbase + c) = pack4bf(du[0], du[1], du[2], du[3]);
-                }
-            }
+            wave_lds_fence();
+            SH::flush(buf_g, out0, n_dim, wrow0, row_end, hcol0, n_dim, lane);
+            SH::flush(buf_u, out1, n_dim, wrow0, row_end, hcol0, n_dim, lane);
+            wave_lds_fence();
+        }
     }
 }
 
