@@ -454,27 +454,49 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
     typename KL::Acc acc;
     KL::zero(acc);
     KL::run(acc, A, B, (rows + BK - 1) / BK, rows, lds, tid);
+    // Epilogue.  The accumulators hold, per lane, one column n and 16 rows m of each MFMA tile;
+    // each 32 x 64 fp32 block of the wave goes through this wave's 8 KiB of LDS and leaves as
+    // 16 bytes per lane along n: 1 KiB per store (or load-add-store) instruction.
+    static_assert(KL::TB == 2, "a wave owns 64 columns");
+    __syncthreads();                                          // every wave is done with the operand slabs
+    float *buf = reinterpret_cast<float *>(lds + wave * 8192);
     const size_t base = (size_t)slot * m_dim * n_dim;
+    const int wm0 = m0 + (wave / 4) * (BA / 2), wn0 = n0 + (wave % 4) * 64;
+    const int col4 = lane & 15, gcol = wn0 + col4 * 4;
 #pragma unroll
-    for (int tb = 0; tb < KL::TB; ++tb) {
-        const int c = n0 + KL::b_row(wave, lane, tb);
-        if (c >= n_dim) continue;
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
-        for (int ta = 0; ta < KL::TA; ++ta)
+        for (int ta = 0; ta < KL::TA; ++ta) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = m0 + KL::a_row(wave, lane, ta, v);
-                if (r >= m_dim) continue;
-                const size_t o = base + (size_t)r * n_dim + c;
-                if (add) {
-                    out0[o] += acc[0][ta][tb][v];
-                    if (NA == 2) out1[o] += acc[NA - 1][ta][tb][v];
-                } else {
-                    out0[o] = acc[0][ta][tb][v];
-                    if (NA == 2) out1[o] = acc[NA - 1][ta][tb][v];
+            for (int tb = 0; tb < KL::TB; ++tb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    buf[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 64 + tb * 32 + (lane & 31)] = acc[a][ta][tb][v];
+            wave_lds_fence();
+            float *out = (a == 0 ? out0 : out1) + base;
+            float4 val[8];
+#pragma unroll
+            for (int p = 0; p < 8; ++p) val[p] = *reinterpret_cast<const float4 *>(buf + (p * 4 + (lane >> 4)) * 64 + col4 * 4);
+            if (add) {
+                float4 old[8];
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int r = wm0 + ta * 32 + p * 4 + (lane >> 4);
+                    old[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (r < m_dim && gcol < n_dim) old[p] = *reinterpret_cast<const float4 *>(out + (size_t)r * n_dim + gcol);
+                }
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    val[p].x += old[p].x; val[p].y += old[p].y; val[p].z += old[p].z; val[p].w += old[p].w;
                 }
             }
-    }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int r = wm0 + ta * 32 + p * 4 + (lane >> 4);
+                if (r < m_dim && gcol < n_dim) *reinterpret_cast<float4 *>(out + (size_t)r * n_dim + gcol) = val[p];
+            }
+            wave_lds_fence();
+        }
 }
 
 // Replica gradients return to the home copy (Section 5.1).  A thread owns element positions
