@@ -229,6 +229,11 @@ struct KLoop {
             const bool tail = RAGGED_K && (t + 1) * BK > k_valid;
             const int kf = t * BK + (lane >> 5) * 8;
             if (DBG != 2) {
+                // f0 was requested before the previous MFMA block: it is there by now.  Waiting for
+                // it here, before the next requests go out, lets the MFMAs below start at once
+                // instead of waiting for the requests issued just above them.
+                __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
                 read_frags(f1, cur, 1, wa, wb, lane);
                 __builtin_amdgcn_sched_barrier(0);
                 if (tail) mask_frags(f0, kf, k_valid);
@@ -236,9 +241,9 @@ struct KLoop {
                 __builtin_amdgcn_sched_barrier(0);
             }
             wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
-            __builtin_amdgcn_s_barrier();
+            if (DBG != 3) __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (t + STAGES < n && DBG != 1) issue(cur, A, B, t + STAGES, steps_per_phase, k_last, wave, lane);
+            if (t + STAGES < n && DBG != 1 && DBG != 3) issue(cur, A, B, t + STAGES, steps_per_phase, k_last, wave, lane);
             if (DBG != 2) {
                 if (t + 1 < n) read_frags(f0, nxt, 0, wa, wb, lane);
                 __builtin_amdgcn_sched_barrier(0);

@@ -1,0 +1,155 @@
+"""GPU parity at the full sizes of configs 2-5, through the same entry points and launch shapes
+that bench.py times.  Integer results are compared in full (the oracle's integer path is fast);
+floating-point results are compared on samples the oracle can compute one by one:
+whole tokens (all k routed rows: Y rows, Out, dgate, dX) and weight-gradient slices of whole
+experts (8 columns of h', every instance of the expert, which pins dWg/dWu rows and dWd columns).
+No oracle input comes from the GPU: the oracle runs its own permute, gather and combine."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2605_08639_amd as rl
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+DEV = "cuda"
+N_MB = 3           # micro-batches planned together (each at its full size); the layer runs on mb 0
+
+
+def rel_l2(got, want):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
+
+
+def bf16_round(a):
+    return torch.from_numpy(np.asarray(a, np.float32)).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_full_size_layer_matches_oracle_on_samples(idx):
+    cfg = wl.CONFIGS[idx]
+    E, k, h, hff, T, N, G = cfg.E, cfg.k, cfg.h, cfg.hff, cfg.T, cfg.N, cfg.G
+    n_mb = min(cfg.n_mb, N_MB)
+    rng = np.random.default_rng(100 + idx)
+    routed = [wl.make_routing(cfg, mb) for mb in range(n_mb)]
+    ids = np.stack([r[0] for r in routed])
+    gates = routed[0][1]
+    print(f"[{cfg.name}] routing drawn", flush=True)
+
+    # ---- integer path, in full
+    err = rl.new_err_flag()
+    ids_d = torch.from_numpy(ids).to(DEV)
+    counts = rl.relibra_route_hist(ids_d, E, err_flag=err).cpu().numpy()
+    counts_o, _ = oracle.route_hist(ids, E)
+    assert np.array_equal(counts, counts_o)
+    p = rl.relibra_plan(counts, k, cfg.EP, cfg.rpn, cfg.r)
+    po = oracle.plan(counts_o, cfg.EP, cfg.rpn, cfg.r)
+    for key in ("expert_to_slot", "replica_expert", "inst_ptr", "inst_rank", "inst_rows", "inst_group",
+                "group_expert", "group_offset"):
+        assert np.array_equal(p[key], po[key]), key
+    assert p["max_load_after"].sum() <= p["max_load_before"].sum()
+    mb = 0
+    row_o, src_o = oracle.permute(ids[mb], E, po["inst_ptr"][mb], po["inst_rows"][mb], po["inst_group"][mb],
+                                  po["group_offset"][mb])
+    print(f"[{cfg.name}] hist/plan/permute oracle done", flush=True)
+
+    # ---- the layer on the GPU (device-drawn inputs, copied back for the oracle)
+    X_d, dOut_d = wl.make_tokens_device(cfg, mb, DEV)
+    Wg_d, Wu_d, Wd_d = wl.make_weights(cfg, DEV)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    tabs = {key: t(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert",
+                                           "group_dw_slot")}
+    gates_d = t(gates)
+    row_of, src_of, Xrows = rl.relibra_permute(ids_d[mb], tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                               tabs["group_offset"], X_d, E, G, err_flag=err)
+    assert np.array_equal(row_of.cpu().numpy(), row_o)
+    assert np.array_equal(src_of.cpu().numpy(), src_o)
+    Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], Wg_d, Wu_d, Wd_d, err_flag=err)
+    Out = rl.relibra_unpermute_combine(rl.COMBINE_FWD, Y, row_of, T, k, gates=gates_d, err_flag=err)
+    dY, dgate = rl.relibra_unpermute_combine(rl.COMBINE_BWD, Y, row_of, T, k, gates=gates_d, tok=dOut_d, err_flag=err)
+    n_slots = E + cfg.EP * cfg.r
+    dWg = torch.empty((n_slots, hff, h), dtype=torch.float32, device=DEV)
+    dWu = torch.empty_like(dWg)
+    dWd = torch.empty((n_slots, h, hff), dtype=torch.float32, device=DEV)
+    dXrows = rl.relibra_moe_ffn_bwd(dY, Xrows, Gt, U, A, tabs["group_offset"], tabs["group_expert"],
+                                    tabs["group_dw_slot"], Wg_d, Wu_d, Wd_d, dWg, dWu, dWd, err_flag=err)
+    dX = rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, err_flag=err)
+    torch.cuda.synchronize()
+    assert err.item() == 0
+    print(f"[{cfg.name}] GPU layer done", flush=True)
+
+    # gathered rows are a bit copy (all of them)
+    X_h = X_d.cpu()
+    tok_of_row = torch.from_numpy(src_o.astype(np.int64) // k)
+    assert torch.equal(Xrows.cpu().view(torch.int16), X_h.view(torch.int16)[tok_of_row])
+    dOut_h = dOut_d.cpu()
+    go, ge = po["group_offset"][mb], po["group_expert"][mb]
+    grp_of_row = np.searchsorted(go, np.arange(N), side="right") - 1
+
+    # ---- sampled tokens: all k rows of each, through the oracle
+    rows_per_group = np.diff(go)
+    live = np.nonzero(rows_per_group > 0)[0]
+    big = live[np.argmax(rows_per_group[live])]
+    small = live[np.argmin(rows_per_group[live])]
+    pick_rows = [go[big], go[big] + 255 if rows_per_group[big] > 256 else go[big], go[big + 1] - 1, go[small],
+                 go[small + 1] - 1] + rng.integers(0, N, size=3).tolist()
+    toks = sorted(set(int(src_o[r]) // k for r in pick_rows))
+    s_rows = np.array([row_o[tk * k + s] for tk in toks for s in range(k)], np.int64)
+    s_exp = ge[grp_of_row[s_rows]]
+    experts = sorted(set(s_exp.tolist()))
+    remap = {e: i for i, e in enumerate(experts)}
+    idx_e = torch.tensor(experts, device=DEV)
+    w_sub = [W[idx_e].cpu() for W in (Wg_d, Wu_d, Wd_d)]
+    sub_go = np.arange(len(s_rows) + 1, dtype=np.int32)            # one row per group
+    sub_ge = np.array([remap[e] for e in s_exp], np.int32)
+    Xs = X_h[torch.from_numpy(src_o[s_rows].astype(np.int64) // k)]
+    _, _, _, Y_o = oracle.ffn_fwd(Xs, sub_go, sub_ge, *w_sub)
+    ident = np.arange(len(s_rows), dtype=np.int32)
+    g_s = gates[toks]
+    Out_o = oracle.combine_fwd(Y_o, g_s, ident, len(toks), k)
+    dY_o, dgate_o = oracle.combine_bwd(dOut_h[toks].double().numpy(), Y_o, g_s, ident, len(toks), k)
+    dXr_o, _, _, _ = oracle.ffn_bwd(Xs, bf16_round(dY_o), sub_go, sub_ge, *w_sub)
+    dX_o = oracle.combine_fwd(dXr_o, None, ident, len(toks), k)
+    sr = torch.from_numpy(s_rows).to(DEV)
+    assert rel_l2(Y[sr].double().cpu().numpy(), Y_o) <= TOL
+    tk = torch.tensor(toks, device=DEV)
+    assert rel_l2(Out[tk].double().cpu().numpy(), Out_o) <= TOL
+    assert rel_l2(dgate[tk].double().cpu().numpy(), dgate_o) <= TOL
+    assert rel_l2(dXrows[sr].double().cpu().numpy(), dXr_o) <= TOL
+    assert rel_l2(dX[tk].double().cpu().numpy(), dX_o) <= TOL
+    print(f"[{cfg.name}] sampled tokens ok", flush=True)
+
+    # ---- weight-gradient slices of whole experts: a replicated one (if any), the smallest, a mid one
+    inst_n = np.diff(po["inst_ptr"][mb])
+    cand = []
+    if (inst_n > 1).any():
+        repl = np.nonzero(inst_n > 1)[0]
+        cand.append(int(repl[np.argmin(counts_o[mb][repl])]))             # cheapest replicated expert
+    nz = np.nonzero(counts_o[mb] > 0)[0]
+    cand.append(int(nz[np.argmin(counts_o[mb][nz])]))
+    cand.append(int(nz[np.argsort(counts_o[mb][nz])[len(nz) // 2]]))
+    zero = np.nonzero(counts_o[mb] == 0)[0]
+    J = np.sort(rng.choice(hff, size=8, replace=False))
+    Jt = torch.from_numpy(J).to(DEV)
+    for e in dict.fromkeys(cand):
+        groups = [g for g in range(G) if ge[g] == e and rows_per_group[g] > 0]
+        rws = np.concatenate([np.arange(go[g], go[g + 1]) for g in groups]).astype(np.int64)
+        sgo = np.concatenate([[0], np.cumsum([rows_per_group[g] for g in groups])]).astype(np.int32)
+        sge = np.zeros(len(groups), np.int32)
+        Xe = X_h[torch.from_numpy(src_o[rws] // k)]
+        a_idx = src_o[rws].astype(np.int64)                               # assignment = t*k + s
+        # upstream row gradient as the path forms it: gate * dOut[t], rounded to bf16 once
+        dYe = bf16_round(gates.reshape(-1)[a_idx][:, None].astype(np.float64) * dOut_h[torch.from_numpy(a_idx // k)].double().numpy())
+        wg = Wg_d[e][Jt].cpu()[None]
+        wu = Wu_d[e][Jt].cpu()[None]
+        wd = Wd_d[e][:, Jt].cpu().contiguous()[None]
+        _, dWg_o, dWu_o, dWd_o = oracle.ffn_bwd(Xe, dYe, sgo, sge, wg, wu, wd)
+        assert rel_l2(dWg[e][Jt].double().cpu().numpy(), dWg_o[0]) <= TOL, ("dWg", e)
+        assert rel_l2(dWu[e][Jt].double().cpu().numpy(), dWu_o[0]) <= TOL, ("dWu", e)
+        assert rel_l2(dWd[e][:, Jt].double().cpu().numpy(), dWd_o[0]) <= TOL, ("dWd", e)
+        print(f"[{cfg.name}] dW slices of expert {e} ({len(rws)} rows, {len(groups)} instances) ok", flush=True)
+    for e in zero[:2].tolist():                                          # experts nobody routed to: exact zeros
+        assert (dWg[e] == 0).all() and (dWu[e] == 0).all() and (dWd[e] == 0).all()
