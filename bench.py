@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (default: the metric's config)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target length of the oracle sample (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="skip the straggler and bandwidth-kernel sections")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (each simulated EP rank's share executes on it); "
@@ -114,6 +116,14 @@ def main():
             layer(mb, tabs, first=(mb == 0))
         return plan, tabs
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---------------- warmup, then the timed region
     for _ in range(max(args.warmup, 0)):
         plan, tabs = step()
@@ -133,16 +143,55 @@ def main():
     flops_step = cfg.flops_per_mb * n_mb
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
+    # Algorithmic HBM bytes per launch: every tensor read or written once,
+    # a group's weights once per live group, weight gradients written per live group and, when
+    # accumulating, the home slots read first.  Averaged over the micro-batches of the step.
+    def alg_bytes(name):
+        tot = 0.0
+        for mb in range(n_mb):
+            rows_g = np.diff(plan["group_offset"][mb])
+            live = int((rows_g > 0).sum())
+            home_live = int(((rows_g > 0) & (plan["group_dw_slot"][mb] < E)).sum())
+            acc_mode = mb > 0
+            w1 = 2.0 * h * hff                       # one bf16 weight matrix
+            act_h, act_ff = 2.0 * h * N, 2.0 * hff * N
+            tot += {
+                "fwd_gate_up": act_h + 2 * w1 * live + 3 * act_ff,
+                "fwd_down": act_ff + w1 * live + act_h,
+                "bwd_act": act_h + w1 * live + 2 * act_ff + 2 * act_ff,
+                "bwd_dx": 2 * act_ff + 2 * w1 * live + act_h,
+                "wgrad_down": act_h + act_ff + 2 * w1 * live + (2 * w1 * home_live if acc_mode else 0.0),
+                "wgrad_gate_up": 2 * act_ff + act_h + 4 * w1 * live + (4 * w1 * home_live if acc_mode else 0.0),
+            }[name]
+        return tot / n_mb
+
+    traffic_file = os.path.join(ROOT, "profiles", f"bench_config{args.config + 1}_hbm_traffic.json")
+    measured = json.load(open(traffic_file))["kernels"] if os.path.exists(traffic_file) else {}
+
     kernels = {}
     for name, (ms, n) in prof.items():
         fl = GEMM_FLOP_FACTOR[name] * h * hff * N
-        kernels[name] = {"avg_ms": ms / n, "launches": n, "tflops": fl / (ms / n * 1e-3) / 1e12}
+        by = alg_bytes(name)
+        t_s = ms / n * 1e-3
+        kernels[name] = {"avg_ms": ms / n, "launches": n, "tflops": fl / t_s / 1e12, "alg_GBps": by / t_s / 1e9,
+                         "bound": "hbm" if by / (PEAK_HBM_GBS * 1e9) > fl / (PEAK_BF16_TFLOPS * 1e12) else "mfma",
+                         "flops_per_launch": fl, "alg_bytes_per_launch": by}
     gemm_ms_step = sum(ms for ms, _ in prof.values()) / args.steps
     dominant = max(prof, key=lambda nm: prof[nm][0])
-    roofline = {"bound": "mfma", "kernel": dominant, "achieved": kernels[dominant]["tflops"],
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dominant]["tflops"] / PEAK_BF16_TFLOPS,
-                "traffic": None, "avg_launch_ms": kernels[dominant]["avg_ms"],
-                "flops_per_launch": GEMM_FLOP_FACTOR[dominant] * h * hff * N}
+    kd = kernels[dominant]
+    tr = measured.get(dominant)
+    if kd["bound"] == "hbm":
+        roofline = {"bound": "hbm", "kernel": dominant, "achieved": kd["alg_GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": kd["alg_GBps"] / PEAK_HBM_GBS}
+    else:
+        roofline = {"bound": "mfma", "kernel": dominant, "achieved": kd["tflops"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": kd["tflops"] / PEAK_BF16_TFLOPS}
+    roofline.update({"traffic": (tr["read_bytes"] + tr["write_bytes"]) if tr else None, "avg_launch_ms": kd["avg_ms"],
+                     "flops_per_launch": kd["flops_per_launch"], "alg_bytes_per_launch": kd["alg_bytes_per_launch"],
+                     "mfma_frac": kd["tflops"] / PEAK_BF16_TFLOPS})
+    # mixed roofline of all six GEMM kernels: sum over kernels of max(flops/peak, bytes/bandwidth)
+    floor_ms = sum(max(v["flops_per_launch"] / (PEAK_BF16_TFLOPS * 1e12), v["alg_bytes_per_launch"] / (PEAK_HBM_GBS * 1e9))
+                   for v in kernels.values()) * 1e3
     gemm_tflops = flops_step / (gemm_ms_step * 1e-3) / 1e12
     log(f"step {ms_per_step:.2f} ms  value {value:.1f} TFLOP/s  grouped GEMMs alone {gemm_tflops:.1f} TFLOP/s")
 
@@ -263,7 +312,9 @@ def main():
                                "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd)",
                    "flops_per_step": flops_step},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
-        "gemm_kernels": kernels, "gemm_only_tflops": gemm_tflops, "plan_host_ms": float(np.mean(plan_ms)),
+        "gemm_kernels": kernels, "gemm_only_tflops": gemm_tflops,
+        "gemm_mixed_roofline": {"floor_ms_per_microbatch": floor_ms, "achieved_ms_per_microbatch": gemm_ms_step / n_mb,
+                                "frac": floor_ms / (gemm_ms_step / n_mb)}, "plan_host_ms": float(np.mean(plan_ms)),
         "skew_before": float(np.mean(plan["max_load_before"]) / (N / EP)),
         "skew_after": float(np.mean(plan["max_load_after"]) / (N / EP)),
     }
