@@ -1,11 +1,12 @@
 // Expert FFN forward / backward as grouped bf16 MFMA GEMMs (gfx950, v_mfma_f32_32x32x16_bf16).
 //
-// One workgroup of 8 wavefronts (512 lanes) owns a 256 x 256 output tile (256 x 128 for a
-// group's tail of at most 128 rows); a wavefront owns 128 x 64 of it as 4 x 2 MFMA tiles with
-// fp32 accumulators.  Operand slabs of 32 k-values go global -> LDS directly
-// (global_load_lds, 16 bytes per lane) through a four-deep ring; see gemm_tile.h for the tile
-// layouts and the pipeline.  The large tile is what the chip needs: two waves per SIMD keep the
-// MFMA pipe full and 256 x 256 halves the cache-to-LDS traffic per flop of a 128 x 128 tile.
+// One workgroup of 4 wavefronts owns a 128-row x 256-column output tile (64 x 256 for a group's
+// tail of at most 64 rows); a wavefront owns 64 rows x 128 columns of it as 4 x 2 MFMA tiles
+// with fp32 accumulators.  Operand slabs of 32 k-values go global -> LDS directly
+// (global_load_lds, 16 bytes per lane) through a three-deep ring; see gemm_tile.h for the tile
+// layouts and the pipeline.  72 KiB of LDS and ~200 VGPRs per workgroup let two workgroups
+// share a compute unit, so that one group's prologue, barrier waits and epilogue overlap the
+// other's MFMAs; a 256-row, 8-wave, one-workgroup-per-CU geometry is kept behind RELIBRA_ROWS.
 //
 // MFMA operand roles: the lanes carry the index that is contiguous in the output's memory
 // only for the fp32 weight gradients (128-byte runs per store); for the bf16 row tensors the
@@ -21,8 +22,17 @@
 
 namespace relibra {
 
-constexpr int BM = 256;                     // rows of a full row tile
-constexpr int THREADS = 512;
+// Tile geometry.  RELIBRA_ROWS = 256: 8 waves, 256 x 256 tiles, four LDS slabs, one workgroup per
+// compute unit.  RELIBRA_ROWS = 128: 4 waves, 128-row x 256-column tiles, three slabs, two
+// workgroups per compute unit (one group's prologue and epilogue overlap the other's MFMAs).
+#ifndef RELIBRA_ROWS
+#define RELIBRA_ROWS 128      // measured faster than 256 on the skewed-group workloads (many short groups)
+#endif
+constexpr int BM = RELIBRA_ROWS;            // rows of a full row tile
+constexpr int NWAVES = BM / 32;
+constexpr int THREADS = NWAVES * 64;
+constexpr int NSTAGES = BM == 256 ? 4 : 3;
+constexpr int WGN = BM;                     // output columns of a weight-gradient tile
 
 // ---------------------------------------------------------------- schedule tables
 // Sanitised copies of the caller's group tables plus the list of row tiles, built on the
@@ -38,7 +48,7 @@ struct Sched {
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int max_row_tiles(int n_rows, int Gr) { return (n_rows + BM - 1) / BM + Gr; }
-constexpr int kLdsBytes = 4 * 512 * BK * 2;     // four slabs of 512 operand rows
+constexpr int kLdsBytes = NSTAGES * (256 + BM) * BK * 2;   // NSTAGES slabs of 256 + BM operand rows
 inline size_t sched_ints(int n_rows, int Gr) { return 8 + 4 * (size_t)Gr + (Gr + 1) + 3 * (size_t)max_row_tiles(n_rows, Gr) + 2 * (size_t)Gr; }
 inline size_t ffn_ws_bytes(int n_rows, int Gr, int hff, bool bwd)
 {
@@ -240,8 +250,8 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Wave layouts: full tiles (256 rows) 2 x 4, tail tiles (128 rows) 4 x 2.
-template <int BB> struct Waves { static constexpr int A = (BB == 256) ? 2 : 4, B = (BB == 256) ? 4 : 2; };
+// Wave layouts: every wave owns 64 rows; the waves left over split the columns.
+template <int BB> struct Waves { static constexpr int B = BB / 64, A = NWAVES / B; };
 
 // ---------------------------------------------------------------- forward
 // Gt = X Wg^T, U = X Wu^T (one pass over X), A = silu(Gt) * U.   Column tile: 128 of h'.
@@ -249,7 +259,7 @@ template <int BB>
 __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t *X, const bf16_t *Wg, const bf16_t *Wu,
                                                  int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout, char *lds)
 {
-    using KL = KLoop<KcTile<128>, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false>;
+    using KL = KLoop<KcTile<128>, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false, NSTAGES>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t wofs = (size_t)t.expert * hff * h;
     const Operand A[1][2] = {{{Wg + wofs, h, t.col0, hff - 1}, {Wu + wofs, h, t.col0, hff - 1}}};
@@ -287,7 +297,7 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     }
 }
 
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)
 fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wg,
                    const bf16_t *__restrict__ Wu, int h, int hff, int n_col_tiles,
                    bf16_t *__restrict__ Gt, bf16_t *__restrict__ U, bf16_t *__restrict__ Aout)
@@ -295,8 +305,8 @@ fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const bf16_t *__restri
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, 128);
     if (!t.valid) return;
-    if (t.rows > 128) fwd_gate_up_body<256>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
-    else fwd_gate_up_body<128>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    if (t.rows > BM / 2) fwd_gate_up_body<BM>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    else fwd_gate_up_body<BM / 2>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
 }
 
 // Shared body of the three single-accumulator row-tiled GEMMs.  EPI: 0 = store bf16 (Y, dX);
@@ -308,7 +318,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
                                               bf16_t *out0, bf16_t *out1, const bf16_t *Gt, const bf16_t *U, char *lds)
 {
     using WT = typename std::conditional<W_KS, KsTile<256>, KcTile<256>>::type;
-    using KL = KLoop<WT, KcTile<BB>, 1, 1, 256, BB, Waves<BB>::A, Waves<BB>::B, NPH, false>;
+    using KL = KLoop<WT, KcTile<BB>, 1, 1, 256, BB, Waves<BB>::A, Waves<BB>::B, NPH, false, NSTAGES>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Operand A[NPH][1], B[NPH][1];
     A[0][0] = {W0, ldw, t.col0, n_dim - 1};
@@ -382,7 +392,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
 }
 
 // Y = A Wd^T.
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)
 fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restrict__ Wd, int h, int hff,
                 int n_col_tiles, bf16_t *__restrict__ Y)
 {
@@ -390,13 +400,13 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
     const RowTile t = find_row_tile(s, n_col_tiles, 256);
     if (!t.valid) return;
     const bf16_t *W = Wd + (size_t)t.expert * h * hff;
-    if (t.rows > 128) row_gemm_body<256, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
-    else row_gemm_body<128, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
+    if (t.rows > BM / 2) row_gemm_body<BM, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
+    else row_gemm_body<BM / 2, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
 }
 
 // ---------------------------------------------------------------- backward
 // dA = dY Wd, then dGt = dA * U * silu'(Gt), dU = dA * silu(Gt).
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
                const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles)
 {
@@ -404,12 +414,12 @@ bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict_
     const RowTile t = find_row_tile(s, n_col_tiles, 256);
     if (!t.valid) return;
     const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n]
-    if (t.rows > 128) row_gemm_body<256, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
-    else row_gemm_body<128, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
+    if (t.rows > BM / 2) row_gemm_body<BM, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
+    else row_gemm_body<BM / 2, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
 }
 
 // dX = dGt Wg + dU Wu (one accumulator, the contraction runs over both products).
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)
 bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff,
               int n_col_tiles, bf16_t *__restrict__ dX)
 {
@@ -417,23 +427,23 @@ bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__
     const RowTile t = find_row_tile(s, n_col_tiles, 256);
     if (!t.valid) return;
     const size_t wofs = (size_t)t.expert * hff * h;         // (n in h, k in h') at [k*h + n]
-    if (t.rows > 128) row_gemm_body<256, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
-    else row_gemm_body<128, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
+    if (t.rows > BM / 2) row_gemm_body<BM, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
+    else row_gemm_body<BM / 2, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
 }
 
 // Weight gradients: out[slot][m][n] (+)= sum over the group's rows of L[row][m] * R[row][n].
 // NA = 2 computes two left operands against one right operand (dGt and dU against X).
 // Tile: (NA x BA) x 256 with BA = 256 / NA.
 template <int NA>
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS, 2)
 wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ L1,
              const bf16_t *__restrict__ R, int m_dim, int n_dim, int E, int accumulate, int total,
              float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int BA = 256 / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<256>, NA, 1, BA, 256, 2, 4, 1, true>;
+    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, NSTAGES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const int n_nt = (n_dim + 255) / 256, n_mt = (m_dim + BA - 1) / BA;
+    const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
     const int per_group = n_nt * n_mt;
     const int per_xcd = (total + 7) >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -446,7 +456,7 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
     const int row0 = s.grp_row0[gi], rows = s.grp_rows[gi];
     if (rows == 0 && add) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = (rem / n_nt) * BA, n0 = (rem % n_nt) * 256;
+    const int m0 = (rem / n_nt) * BA, n0 = (rem % n_nt) * WGN;
     Operand A[1][NA], B[1][1];
     A[0][0] = {L0 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
     if (NA == 2) A[0][NA - 1] = {L1 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
@@ -461,7 +471,7 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
     __syncthreads();                                          // every wave is done with the operand slabs
     float *buf = reinterpret_cast<float *>(lds + wave * 8192);
     const size_t base = (size_t)slot * m_dim * n_dim;
-    const int wm0 = m0 + (wave / 4) * (BA / 2), wn0 = n0 + (wave % 4) * 64;
+    const int wm0 = m0 + (wave / (NWAVES / 2)) * (BA / 2), wn0 = n0 + (wave % (NWAVES / 2)) * 64;
     const int col4 = lane & 15, gcol = wn0 + col4 * 4;
 #pragma unroll
     for (int a = 0; a < NA; ++a)
@@ -636,8 +646,8 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
             s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, (bf16_t *)dXrows));
         RELIBRA_HIP_TRY(launch_check());
     }
-    const long long t_down = (long long)Gr * ct_h * ct_ff;                 // dWd: m in h (256), n in h' (256)
-    const long long t_gu = (long long)Gr * ((hff + 127) / 128) * ct_h;     // dWg, dWu: m in h' (128 each), n in h (256)
+    const long long t_down = (long long)Gr * ct_h * ((hff + WGN - 1) / WGN);                  // dWd: m in h (256), n in h' (WGN)
+    const long long t_gu = (long long)Gr * ((hff + 127) / 128) * ((h + WGN - 1) / WGN);      // dWg, dWu: m in h' (128 each), n in h (WGN)
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1><<<grid8(t_down), THREADS, kLdsBytes, stream>>>(
         s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, (int)t_down, dWd, nullptr));
     RELIBRA_HIP_TRY(launch_check());
