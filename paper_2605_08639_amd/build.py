@@ -12,8 +12,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
-if os.environ.get("RELIBRA_ROWS"):            # tile geometry of the grouped GEMMs (256 or 128), see ffn_kernels.hip
-    FLAGS.append("-DRELIBRA_ROWS=" + os.environ["RELIBRA_ROWS"])
+for _knob in ("RELIBRA_ROWS",):   # tile geometry of the grouped GEMMs, see ffn_kernels.hip
+    if os.environ.get(_knob):
+        FLAGS.append(f"-D{_knob}=" + os.environ[_knob])
 
 
 def build(verbose: bool = False) -> str:

@@ -159,21 +159,41 @@ struct RowTile {
     bool valid;
 };
 
-// Physical block -> logical tile (row tile major, column tile minor), XCD-aware.
+// Order of the tiles of an n_r x n_c grid: bands of kBand rows; inside a band column by column,
+// the band's rows innermost.  The ~64 tiles a set of compute units works on at one time then
+// form a roughly square patch (8 x 8), which shares 8 + 8 operand tiles instead of 1 + 64.
+constexpr int kBand = 8;
+__device__ __forceinline__ void band_order(int idx, int n_r, int n_c, int &r, int &c)
+{
+    const int band = idx / (kBand * n_c), within = idx - band * (kBand * n_c);
+    const int rows_here = min(kBand, n_r - band * kBand);
+    c = within / rows_here;
+    r = band * kBand + within - c * rows_here;
+}
+
+// Physical block -> tile.  The hardware deals blocks to the 8 XCDs round-robin (blockIdx % 8);
+// XCD x takes the x-th eighth of the ordered tile list, so neighbouring tiles share one L2.
 __device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles, int col_tile_width)
 {
     RowTile t;
-    const int total = s.hdr[0] * n_col_tiles;
+    const int n_rt = s.hdr[0];
+    const int total = n_rt * n_col_tiles;
     const int per_xcd = (total + 7) >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     t.valid = logical < total && (int)(blockIdx.x >> 3) < per_xcd;
     if (!t.valid) return t;
-    const int rt = logical / n_col_tiles;
+    int rt, ct;
+    if (n_col_tiles > kBand) {
+        band_order(logical, n_rt, n_col_tiles, rt, ct);
+    } else {                                  // few column tiles: a row tile's columns already run side by side
+        rt = logical / n_col_tiles;
+        ct = logical - rt * n_col_tiles;
+    }
     t.group = s.tile_group[rt];
     t.row0 = s.tile_row0[rt];
     t.rows = s.tile_rows[rt];
     t.expert = s.grp_expert[t.group];
-    t.col0 = (logical % n_col_tiles) * col_tile_width;
+    t.col0 = ct * col_tile_width;
     return t;
 }
 
@@ -433,15 +453,24 @@ bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__
 
 // Weight gradients: out[slot][m][n] (+)= sum over the group's rows of L[row][m] * R[row][n].
 // NA = 2 computes two left operands against one right operand (dGt and dU against X).
-// Tile: (NA x BA) x 256 with BA = 256 / NA.
-template <int NA>
-__global__ void __launch_bounds__(THREADS, 2)
+// Tile: (NA x BA) x WGN with BA = WGM / NA.  Two geometries: WGM = 256 (three slabs, two
+// workgroups per compute unit) for long groups, where the MFMA rate matters, and WGM = 128 (two
+// slabs, four workgroups per compute unit) for short groups, where the kernel is a stream of
+// fp32 read-add-writes and more waves in flight mean more HBM bandwidth.
+template <int WGM> struct WgradCfg {
+    static constexpr int STAGES = WGM == 256 ? NSTAGES : 2;
+    static constexpr int OCC = WGM == 256 ? 2 : 4;                  // waves per SIMD aimed at
+    static constexpr int SLABS = STAGES * (WGM + WGN) * BK * 2;
+    static constexpr int LDS = SLABS > NWAVES * 8192 ? SLABS : NWAVES * 8192;
+};
+template <int NA, int WGM>
+__global__ void __launch_bounds__(THREADS, WgradCfg<WGM>::OCC)
 wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ L1,
              const bf16_t *__restrict__ R, int m_dim, int n_dim, int E, int accumulate, int total,
              float *__restrict__ out0, float *__restrict__ out1)
 {
-    constexpr int BA = 256 / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, NSTAGES>;
+    constexpr int BA = WGM / NA;
+    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
     const int per_group = n_nt * n_mt;
@@ -456,7 +485,9 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
     const int row0 = s.grp_row0[gi], rows = s.grp_rows[gi];
     if (rows == 0 && add) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = (rem / n_nt) * BA, n0 = (rem % n_nt) * WGN;
+    int mt, nt;
+    band_order(rem, n_mt, n_nt, mt, nt);
+    const int m0 = mt * BA, n0 = nt * WGN;
     Operand A[1][NA], B[1][1];
     A[0][0] = {L0 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
     if (NA == 2) A[0][NA - 1] = {L1 + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
@@ -563,8 +594,10 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     done = true;
     return RELIBRA_OK;
 }
@@ -646,14 +679,26 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
             s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, (bf16_t *)dXrows));
         RELIBRA_HIP_TRY(launch_check());
     }
-    const long long t_down = (long long)Gr * ct_h * ((hff + WGN - 1) / WGN);                  // dWd: m in h (256), n in h' (WGN)
-    const long long t_gu = (long long)Gr * ((hff + 127) / 128) * ((h + WGN - 1) / WGN);      // dWg, dWu: m in h' (128 each), n in h (WGN)
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1><<<grid8(t_down), THREADS, kLdsBytes, stream>>>(
-        s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, (int)t_down, dWd, nullptr));
-    RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_kernel<2><<<grid8(t_gu), THREADS, kLdsBytes, stream>>>(
-        s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, (int)t_gu, dWg, dWu));
-    RELIBRA_HIP_TRY(launch_check());
+    // short groups (few rows per group on average): the small, high-occupancy geometry
+    const bool small_tiles = (long long)n_rows < 512LL * Gr;
+    const int wgm = small_tiles ? 128 : 256;
+    const long long t_down = (long long)Gr * ((h + wgm - 1) / wgm) * ((hff + WGN - 1) / WGN);              // dWd: m in h, n in h'
+    const long long t_gu = (long long)Gr * ((hff + wgm / 2 - 1) / (wgm / 2)) * ((h + WGN - 1) / WGN);      // dWg, dWu: m in h', n in h
+    if (small_tiles) {
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1, 128><<<grid8(t_down), THREADS, WgradCfg<128>::LDS, stream>>>(
+            s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, (int)t_down, dWd, nullptr));
+        RELIBRA_HIP_TRY(launch_check());
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_kernel<2, 128><<<grid8(t_gu), THREADS, WgradCfg<128>::LDS, stream>>>(
+            s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, (int)t_gu, dWg, dWu));
+        RELIBRA_HIP_TRY(launch_check());
+    } else {
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_kernel<1, 256><<<grid8(t_down), THREADS, WgradCfg<256>::LDS, stream>>>(
+            s, (const bf16_t *)dYrows, nullptr, (const bf16_t *)A_save, h, hff, E, accumulate, (int)t_down, dWd, nullptr));
+        RELIBRA_HIP_TRY(launch_check());
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_kernel<2, 256><<<grid8(t_gu), THREADS, WgradCfg<256>::LDS, stream>>>(
+            s, s.dGt, s.dU, (const bf16_t *)Xrows, hff, h, E, accumulate, (int)t_gu, dWg, dWu));
+        RELIBRA_HIP_TRY(launch_check());
+    }
     if (!(flags & RELIBRA_BWD_NO_REPLICA_SUM) && n_dw_slots > E) {
         const size_t vec4 = (size_t)h * hff / 4;
         const int grid = (int)((vec4 + 255) / 256 < 4096 ? (vec4 + 255) / 256 : 4096);

@@ -81,7 +81,7 @@ struct KsTile {
     static constexpr int SPR = ROWS / 8;              // 16-byte pieces per k-row
     static constexpr int KPB = 64 / SPR;              // k-rows per 1 KiB block
     static constexpr int BLOCKS = BK / KPB;
-    static_assert(ROWS >= 128 && ROWS <= 512, "tile height");
+    static_assert(ROWS >= 64 && ROWS <= 512, "tile height");
 
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
 

@@ -129,6 +129,8 @@ FFN_CASES = [
     dict(seed=2, E=3, h=128, hff=256, rows=(40, 513, 7), experts=(2, 0, 1)),
     dict(seed=3, E=2, h=64, hff=64, rows=(5, 3), experts=(1, 0)),
     dict(seed=4, E=2, h=320, hff=448, rows=(200, 0, 131), experts=(0, 1, 0)),
+    # long groups: the large weight-gradient tile geometry (512 or more rows per group on average)
+    dict(seed=7, E=2, h=128, hff=256, rows=(1100, 700), experts=(1, 0)),
 ]
 
 
