@@ -96,15 +96,29 @@ perm_count_kernel(const int32_t *__restrict__ ids, int N, int E, int32_t *__rest
         for (int e = lane; e < E; e += 64) unit_cnt[(size_t)unit * E + e] = bins[e];
 }
 
-__global__ void perm_scan_kernel(int32_t *unit_cnt, int n_units, int E)
+// One block per expert: exclusive scan of that expert's counts over the units.
+__global__ void __launch_bounds__(256) perm_scan_kernel(int32_t *unit_cnt, int n_units, int E)
 {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= E) return;
-    int run = 0;
-    for (int u = 0; u < n_units; ++u) {
-        const int c = unit_cnt[(size_t)u * E + e];
-        unit_cnt[(size_t)u * E + e] = run;
-        run += c;
+    __shared__ int32_t scan[256];
+    __shared__ int32_t carry;
+    const int e = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_units; base += 256) {
+        const int u = base + tid;
+        const int c = u < n_units ? unit_cnt[(size_t)u * E + e] : 0;
+        scan[tid] = c;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int v = tid >= off ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        if (u < n_units) unit_cnt[(size_t)u * E + e] = carry + scan[tid] - c;
+        __syncthreads();
+        if (tid == 255) carry += scan[255];
+        __syncthreads();
     }
 }
 
@@ -227,14 +241,30 @@ combine_fwd_kernel(const uint4 *__restrict__ rows, const float *__restrict__ gat
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         const int t = (int)(i / vec_per_row), c = (int)(i % vec_per_row);
         float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int s = 0; s < k; ++s) {
-            const int row = row_of[(size_t)t * k + s];
-            if ((unsigned)row >= (unsigned)N) { bad = true; continue; }
-            const float g = GATED ? gates[(size_t)t * k + s] : 1.0f;
-            float f[8];
-            unpack8(rows[(size_t)row * vec_per_row + c], f);
+        for (int s0 = 0; s0 < k; s0 += 8) {                 // eight row fetches in flight
+            uint4 v[8];
+            float g[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = fmaf(g, f[j], acc[j]);
+            for (int u = 0; u < 8; ++u) {
+                g[u] = 0.0f;
+                v[u] = make_uint4(0, 0, 0, 0);
+                if (s0 + u < k) {
+                    const int row = row_of[(size_t)t * k + s0 + u];
+                    if ((unsigned)row < (unsigned)N) {
+                        g[u] = GATED ? gates[(size_t)t * k + s0 + u] : 1.0f;
+                        v[u] = rows[(size_t)row * vec_per_row + c];
+                    } else {
+                        bad = true;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {                   // fp32 sum in slot order
+                float f[8];
+                unpack8(v[u], f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = fmaf(g[u], f[j], acc[j]);
+            }
         }
         out[i] = pack8(acc);
     }
@@ -335,7 +365,7 @@ extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_d
     while ((1 << ebits) < E) ++ebits;
     RELIBRA_LAUNCH(RELIBRA_K_PERM_COUNT, stream, perm_count_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, unit_cnt, src_of_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_PERM_SCAN, stream, perm_scan_kernel<<<(E + 255) / 256, 256, 0, stream>>>(unit_cnt, n_units, E));
+    RELIBRA_LAUNCH(RELIBRA_K_PERM_SCAN, stream, perm_scan_kernel<<<E, 256, 0, stream>>>(unit_cnt, n_units, E));
     RELIBRA_HIP_TRY(launch_check());
     RELIBRA_LAUNCH(RELIBRA_K_PERM_RANK, stream, perm_rank_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, G, ebits, unit_cnt, inst_ptr_dev,
                                                             inst_rows_dev, inst_group_dev, group_offset_dev,
