@@ -143,7 +143,7 @@ def main():
     flops_step = cfg.flops_per_mb * n_mb
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # Algorithmic HBM bytes per launch (DESIGN.md section 6): every tensor read or written once,
+    # Algorithmic HBM bytes per launch: every tensor read or written once,
     # a group's weights once per live group, weight gradients written per live group and, when
     # accumulating, the home slots read first.  Averaged over the micro-batches of the step.
     def alg_bytes(name):

@@ -12,9 +12,6 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
-for _knob in ("RELIBRA_ROWS",):   # tile geometry of the grouped GEMMs, see ffn_kernels.hip
-    if os.environ.get(_knob):
-        FLAGS.append(f"-D{_knob}=" + os.environ[_knob])
 
 
 def build(verbose: bool = False) -> str:

@@ -6,7 +6,8 @@
 // (global_load_lds, 16 bytes per lane) through a three-deep ring; see gemm_tile.h for the tile
 // layouts and the pipeline.  72 KiB of LDS and ~200 VGPRs per workgroup let two workgroups
 // share a compute unit, so that one group's prologue, barrier waits and epilogue overlap the
-// other's MFMAs; a 256-row, 8-wave, one-workgroup-per-CU geometry is kept behind RELIBRA_ROWS.
+// other's MFMAs.  (A 256-row, 8-wave, one-workgroup-per-CU geometry measured slower on every
+// workload shape tried, long groups included, and is not built.)
 //
 // MFMA operand roles: the lanes carry the index that is contiguous in the output's memory
 // only for the fp32 weight gradients (128-byte runs per store); for the bf16 row tensors the
@@ -22,16 +23,12 @@
 
 namespace relibra {
 
-// Tile geometry.  RELIBRA_ROWS = 256: 8 waves, 256 x 256 tiles, four LDS slabs, one workgroup per
-// compute unit.  RELIBRA_ROWS = 128: 4 waves, 128-row x 256-column tiles, three slabs, two
-// workgroups per compute unit (one group's prologue and epilogue overlap the other's MFMAs).
-#ifndef RELIBRA_ROWS
-#define RELIBRA_ROWS 128      // measured faster than 256 on the skewed-group workloads (many short groups)
-#endif
-constexpr int BM = RELIBRA_ROWS;            // rows of a full row tile
+// Tile geometry: 4 waves, 128-row x 256-column tiles, three LDS slabs, two workgroups per
+// compute unit (one group's prologue and epilogue overlap the other's MFMAs).
+constexpr int BM = 128;                     // rows of a full row tile
 constexpr int NWAVES = BM / 32;
 constexpr int THREADS = NWAVES * 64;
-constexpr int NSTAGES = BM == 256 ? 4 : 3;
+constexpr int NSTAGES = 3;
 constexpr int WGN = BM;                     // output columns of a weight-gradient tile
 
 // ---------------------------------------------------------------- schedule tables
@@ -542,10 +539,13 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
 
 // Replica gradients return to the home copy (Section 5.1).  A thread owns element positions
 // and walks the live replica slots in ascending slot order, so the sum has a fixed order.
+// blockIdx.y selects the tensor (all three have h * h' elements per expert).
 __global__ void __launch_bounds__(256)
-replica_sum_kernel(Sched s, size_t per_expert_vec4, float4 *__restrict__ dW)
+replica_sum_kernel(Sched s, size_t per_expert_vec4, float4 *__restrict__ dWg, float4 *__restrict__ dWu,
+                   float4 *__restrict__ dWd)
 {
     const int n_pairs = s.hdr[1];
+    float4 *__restrict__ dW = blockIdx.y == 0 ? dWg : blockIdx.y == 1 ? dWu : dWd;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < per_expert_vec4; i += (size_t)gridDim.x * 256)
         for (int p = 0; p < n_pairs; ++p) {
             const float4 src = dW[(size_t)s.pair_slot[p] * per_expert_vec4 + i];
@@ -585,7 +585,7 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     (void)h;
 }
 
-// Kernels use 128 KiB of dynamic LDS: raise the per-kernel limit once.
+// Kernels use more than 64 KiB of dynamic LDS: raise the per-kernel limit once.
 static int ensure_lds_limits()
 {
     static bool done = false;
@@ -702,9 +702,8 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     if (!(flags & RELIBRA_BWD_NO_REPLICA_SUM) && n_dw_slots > E) {
         const size_t vec4 = (size_t)h * hff / 4;
         const int grid = (int)((vec4 + 255) / 256 < 4096 ? (vec4 + 255) / 256 : 4096);
-        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWg));
-        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWu));
-        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<grid, 256, 0, stream>>>(s, vec4, (float4 *)dWd));
+        RELIBRA_LAUNCH(RELIBRA_K_REPLICA_SUM, stream, replica_sum_kernel<<<dim3(grid, 3), 256, 0, stream>>>(
+            s, vec4, (float4 *)dWg, (float4 *)dWu, (float4 *)dWd));
         RELIBRA_HIP_TRY(launch_check());
     }
     return RELIBRA_OK;
