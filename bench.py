@@ -264,6 +264,59 @@ def main():
         }
         assert err.item() == 0
 
+        # ---- layer-shared replica buffer (Section 5.1): the forward push of micro-batch 0's replicas,
+        # alone and on a second stream beside the FFN forward (the paper hides it behind attention,
+        # which is outside this path; the expert forward stands in as the compute it competes with)
+        if r > 0:
+            rep0 = torch.from_numpy(np.ascontiguousarray(plan["replica_expert"][0].reshape(-1))).to(dev)
+            live_slots = int((plan["replica_expert"][0] >= 0).sum())
+            pad = lambda W: torch.cat([W, torch.empty((EP * r, *W.shape[1:]), dtype=W.dtype, device=dev)])
+            Wb = [pad(W) for W in (Wg, Wu, Wd)]
+            side = torch.cuda.Stream()
+            ev = lambda: torch.cuda.Event(enable_timing=True)
+            mb = 0
+
+            def fwd():
+                rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
+                                       Gt=Gt, U=U, A=A, Yrows=Yrows, workspace=ws_ffn, err_flag=err)
+
+            def timed(run_push, run_fwd, n_wg):
+                best = [1e9, 1e9]
+                for _ in range(3):
+                    torch.cuda.synchronize()
+                    p0, p1, f0, f1 = ev(), ev(), ev(), ev()
+                    if run_push:
+                        with torch.cuda.stream(side):
+                            p0.record()
+                            rl.relibra_replica_push(*Wb, rep0, E, EP, r, n_workgroups=n_wg, err_flag=err)
+                            p1.record()
+                    if run_fwd:
+                        f0.record()
+                        fwd()
+                        f1.record()
+                    torch.cuda.synchronize()
+                    if run_push:
+                        best[0] = min(best[0], p0.elapsed_time(p1))
+                    if run_fwd:
+                        best[1] = min(best[1], f0.elapsed_time(f1))
+                return best
+
+            X0, _ = tok[mb]
+            rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
+                               tabs["group_offset"][mb], X0, E, G, row_of=row_of, src_of=src_of, Xrows=Xrows,
+                               workspace=ws_perm, err_flag=err)
+            fwd_alone = timed(False, True, 0)[1]
+            push_bytes = live_slots * 3 * 2.0 * h * hff * 2          # read + write of three bf16 blocks per slot
+            rows = []
+            for n_wg in (8, 32, 128):
+                alone = timed(True, False, n_wg)[0]
+                both = timed(True, True, n_wg)
+                rows.append({"n_workgroups": n_wg, "push_ms_alone": alone, "push_GBps_alone": push_bytes / (alone * 1e-3) / 1e9,
+                             "push_ms_beside_fwd": both[0], "fwd_ms_beside_push": both[1]})
+            extras["replica_push"] = {"live_slots": live_slots, "bytes": push_bytes, "fwd_ms_alone": fwd_alone, "runs": rows}
+            del Wb
+            assert err.item() == 0
+
     # ---------------- the CPU oracle on a bounded sample, on this machine's host cores
     cpu_baseline = None
     if args.cpu_seconds > 0:

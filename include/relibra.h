@@ -56,7 +56,9 @@ enum { RELIBRA_WS_PERMUTE = 0, RELIBRA_WS_FFN_FWD = 1, RELIBRA_WS_FFN_BWD = 2 };
 /* flags of relibra_moe_ffn_bwd */
 enum {
     RELIBRA_BWD_ACCUMULATE = 1,     /* home dW += this micro-batch's gradient (else overwrite) */
-    RELIBRA_BWD_NO_REPLICA_SUM = 2  /* leave replica-slot dW where it is (partial group range) */
+    RELIBRA_BWD_NO_REPLICA_SUM = 2, /* leave replica-slot dW where it is (partial group range) */
+    RELIBRA_BWD_REPLICA_WEIGHTS = 4 /* a group reads its parameters from slot group_dw_slot[g] of
+                                       Wg/Wu/Wd [n_dw_slots, ...] (filled by relibra_replica_push) */
 };
 
 /* modes of relibra_unpermute_combine */
@@ -140,6 +142,9 @@ int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const i
  *   Gt_save, U_save, A_save [n_rows, hff] bf16 out (kept for the backward pass)
  *   Yrows [n_rows, h] bf16 out.  Rows of groups outside the range are left untouched.
  *   n_rows: capacity of the row buffers; offsets beyond it raise RELIBRA_ERR_GROUP_TABLE.
+ * group_expert[g] is the index of the group's parameter block in Wg/Wu/Wd and E their number of
+ * blocks: with a physical replica buffer (relibra_replica_push) pass the plan's group_dw_slot
+ * table and E + EP*r here, and replica groups read their own copy.
  * Limits: h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.
  */
 int relibra_moe_ffn_fwd(const void *Xrows_dev, int n_rows,
@@ -177,6 +182,25 @@ int relibra_moe_ffn_bwd(const void *dYrows_dev, const void *Xrows_dev,
                         int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * Layer-shared replica buffer, forward push (Section 5.1: before a layer's expert computation
+ * every GPU pushes the experts that are replicated in this micro-batch into the replica slots
+ * of their target GPUs; the r slots per GPU are reused by every layer and micro-batch).
+ * On one GPU the parameter arrays hold the EP*r replica slots behind the E home blocks:
+ *   Wg, Wu [E + EP*r, hff, h], Wd [E + EP*r, h, hff] bf16, dev, in/out
+ *   replica_expert_dev [EP*r] int32, dev, in: the plan's table for this micro-batch
+ *                      (slot s = rank*r + j holds expert replica_expert[s], -1 = empty)
+ * and the call copies block e to block E + s for every live slot.  n_workgroups (>= 1) bounds
+ * the compute units the copy may occupy, so that it can run beside other kernels on a second
+ * stream (the paper overlaps it with attention and gives it few SMs).  Values >= E in the
+ * table are skipped and flagged RELIBRA_ERR_ID_RANGE.  The reverse direction (replica
+ * gradients back to the home block) is part of relibra_moe_ffn_bwd.
+ * Limits: h*hff % 8 == 0, 16-byte aligned tensors.
+ */
+int relibra_replica_push(void *Wg_dev, void *Wu_dev, void *Wd_dev,
+                         const int32_t *replica_expert_dev, int E, int EP, int r, int h, int hff,
+                         int n_workgroups, int32_t *err_flag_dev, relibra_stream stream);
+
+/*
  * Unpermute + gate-weighted combine and its backward (Section 2.1: the outputs of a token's
  * selected experts are combined; the local half of the combine all-to-all).
  *  mode RELIBRA_COMBINE_FWD: out_tok[t] = sum_s gates[t,s] * rows[row_of[t*k+s]]   (fp32 sum in
@@ -209,7 +233,7 @@ enum {
     RELIBRA_K_FILL = 0, RELIBRA_K_HIST, RELIBRA_K_PERM_COUNT, RELIBRA_K_PERM_SCAN, RELIBRA_K_PERM_RANK,
     RELIBRA_K_GATHER, RELIBRA_K_COMBINE_FWD, RELIBRA_K_COMBINE_BWD, RELIBRA_K_COMBINE_SUM, RELIBRA_K_SCHED,
     RELIBRA_K_FWD_GATE_UP, RELIBRA_K_FWD_DOWN, RELIBRA_K_BWD_ACT, RELIBRA_K_BWD_DX,
-    RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_COUNT
+    RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_REPLICA_PUSH, RELIBRA_K_COUNT
 };
 int relibra_prof_start(int level, int max_records);
 int relibra_prof_stop(double *ms_by_kernel_host, int64_t *launches_by_kernel_host);

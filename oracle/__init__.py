@@ -161,6 +161,16 @@ def gather_rows(X, src_of, k):
     return out
 
 
+def replica_push(W, replica_expert, E):
+    """W [E + slots, ...] bf16 bit patterns -> copy with every live replica slot filled from its home block."""
+    W = _u16(W).copy()
+    rep = _i32(replica_expert).reshape(-1)
+    assert W.shape[0] == E + rep.shape[0]
+    block = int(np.prod(W.shape[1:]))
+    lib().oracle_replica_push(_p(W), _p(rep), int(E), int(rep.shape[0]), C.c_size_t(block))
+    return W
+
+
 def ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None):
     """-> Gt, U, A [N,h'] and Y [N,h], float64 (rows outside the group range are NaN)."""
     Xrows, Wg, Wu, Wd = _u16(Xrows), _u16(Wg), _u16(Wu), _u16(Wd)

@@ -486,6 +486,19 @@ void oracle_gather_rows(const uint16_t *X, const int32_t *src_of, int N, int k, 
         memcpy(Xrows + (size_t)row * h, X + (size_t)(src_of[row] / k) * h, sizeof(uint16_t) * h);
 }
 
+/* Layer-shared replica buffer, forward push (Section 5.1): W holds n_home + n_slots parameter   */
+/* blocks of block_elems bf16 values; slot s with replica_expert[s] = e >= 0 receives a copy of  */
+/* block e at block n_home + s; empty slots (-1) keep whatever they held.                        */
+void oracle_replica_push(uint16_t *W, const int32_t *replica_expert, int n_home, int n_slots, size_t block_elems)
+{
+    for (int s = 0; s < n_slots; ++s) {
+        int e = replica_expert[s];
+        if (e < 0) continue;
+        for (size_t i = 0; i < block_elems; ++i)
+            W[(size_t)(n_home + s) * block_elems + i] = W[(size_t)e * block_elems + i];
+    }
+}
+
 /* Expert FFN forward over groups [g_begin, g_end) (Section 4.1: three GEMMs of   */
 /* 2hh' flops per token).  For a row x of a group whose expert is e:              */
 /*   Gt = Wg_e x, U = Wu_e x, A = silu(Gt) * U, y = Wd_e A.                        */

@@ -19,16 +19,16 @@ LIB_PATH = os.path.join(_HERE, "librelibra.so")
 OK, EINVAL, ERANGE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
 WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD = 0, 1, 2
-BWD_ACCUMULATE, BWD_NO_REPLICA_SUM = 1, 2
+BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS = 1, 2, 4
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_permute", "relibra_moe_ffn_fwd",
-           "relibra_moe_ffn_bwd", "relibra_unpermute_combine", "relibra_workspace_bytes",
+           "relibra_moe_ffn_bwd", "relibra_unpermute_combine", "relibra_replica_push", "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
 
 KERNELS = ("fill", "hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
            "combine_sum", "sched", "fwd_gate_up", "fwd_down", "bwd_act", "bwd_dx", "wgrad_down",
-           "wgrad_gate_up", "replica_sum")
+           "wgrad_gate_up", "replica_sum", "replica_push")
 
 _lib = None
 
@@ -162,7 +162,8 @@ def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,
 
 def relibra_moe_ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
                         Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None):
-    """Xrows [n_rows,h] bf16, weights bf16 -> (Gt, U, A [n_rows,h'], Yrows [n_rows,h]) bf16."""
+    """Xrows [n_rows,h] bf16, weights bf16 -> (Gt, U, A [n_rows,h'], Yrows [n_rows,h]) bf16.
+    group_expert indexes the parameter blocks of Wg/Wu/Wd (all Wg.shape[0] of them are addressable)."""
     n_rows, h = Xrows.shape
     E, hff = Wg.shape[0], Wg.shape[1]
     G = group_expert.shape[0]
@@ -189,10 +190,14 @@ def relibra_moe_ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0
 
 def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, group_dw_slot,
                         Wg, Wu, Wd, dWg, dWu, dWd, g_begin=0, g_end=None, flags=0,
-                        dXrows=None, workspace=None, err_flag=None):
-    """-> dXrows [n_rows,h] bf16; dWg, dWu [slots,h',h] and dWd [slots,h,h'] fp32 are written in place."""
+                        dXrows=None, workspace=None, err_flag=None, E=None):
+    """-> dXrows [n_rows,h] bf16; dWg, dWu [slots,h',h] and dWd [slots,h,h'] fp32 are written in place.
+    E = number of home experts (default Wg.shape[0]; pass it when the weights carry replica slots)."""
     n_rows, h = Xrows.shape
-    E, hff = Wg.shape[0], Wg.shape[1]
+    hff = Wg.shape[1]
+    E = Wg.shape[0] if E is None else int(E)
+    if flags & BWD_REPLICA_WEIGHTS:
+        assert Wg.shape[0] >= dWg.shape[0] and Wu.shape[0] >= dWg.shape[0] and Wd.shape[0] >= dWg.shape[0]
     G = group_expert.shape[0]
     g_end = G if g_end is None else g_end
     dev = Xrows.device
@@ -215,6 +220,20 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
                                    _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_moe_ffn_bwd", rc)
     return dXrows
+
+
+def relibra_replica_push(Wg, Wu, Wd, replica_expert, E, EP, r, n_workgroups=16, err_flag=None):
+    """Fill the EP*r replica slots behind the E home blocks of Wg, Wu, Wd (in place) for one micro-batch."""
+    assert Wg.shape[0] >= E + EP * r and Wu.shape[0] >= E + EP * r and Wd.shape[0] >= E + EP * r
+    assert replica_expert.numel() == EP * r
+    hff, h = Wg.shape[1], Wg.shape[2]
+    if err_flag is None:
+        err_flag = new_err_flag(Wg.device)
+    rc = lib().relibra_replica_push(_dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
+                                    _dp(replica_expert, torch.int32), int(E), int(EP), int(r), h, hff,
+                                    int(n_workgroups), _dp(err_flag), _stream())
+    _check("relibra_replica_push", rc)
+    return err_flag
 
 
 def relibra_unpermute_combine(mode, rows, row_of, T, k, gates=None, tok=None,

@@ -170,7 +170,7 @@ __device__ __forceinline__ void band_order(int idx, int n_r, int n_c, int &r, in
 
 // Physical block -> tile.  The hardware deals blocks to the 8 XCDs round-robin (blockIdx % 8);
 // XCD x takes the x-th eighth of the ordered tile list, so neighbouring tiles share one L2.
-__device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles, int col_tile_width)
+__device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles, int col_tile_width, bool w_from_slot = false)
 {
     RowTile t;
     const int n_rt = s.hdr[0];
@@ -189,7 +189,7 @@ __device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles
     t.group = s.tile_group[rt];
     t.row0 = s.tile_row0[rt];
     t.rows = s.tile_rows[rt];
-    t.expert = s.grp_expert[t.group];
+    t.expert = w_from_slot ? s.grp_slot[t.group] : s.grp_expert[t.group];   // index of the parameter block
     t.col0 = ct * col_tile_width;
     return t;
 }
@@ -425,10 +425,11 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
 // dA = dY Wd, then dGt = dA * U * silu'(Gt), dU = dA * silu(Gt).
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
-               const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles)
+               const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles,
+               int w_from_slot)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const RowTile t = find_row_tile(s, n_col_tiles, 256);
+    const RowTile t = find_row_tile(s, n_col_tiles, 256, w_from_slot != 0);
     if (!t.valid) return;
     const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n]
     if (t.rows > BM / 2) row_gemm_body<BM, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
@@ -438,10 +439,10 @@ bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict_
 // dX = dGt Wg + dU Wu (one accumulator, the contraction runs over both products).
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff,
-              int n_col_tiles, bf16_t *__restrict__ dX)
+              int n_col_tiles, int w_from_slot, bf16_t *__restrict__ dX)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const RowTile t = find_row_tile(s, n_col_tiles, 256);
+    const RowTile t = find_row_tile(s, n_col_tiles, 256, w_from_slot != 0);
     if (!t.valid) return;
     const size_t wofs = (size_t)t.expert * hff * h;         // (n in h, k in h') at [k*h + n]
     if (t.rows > BM / 2) row_gemm_body<BM, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
@@ -670,13 +671,14 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     const long long R = max_row_tiles(n_rows, Gr);
     const int ct_ff = (hff + 255) / 256, ct_h = (h + 255) / 256;
     const int accumulate = (flags & RELIBRA_BWD_ACCUMULATE) ? 1 : 0;
+    const int w_from_slot = (flags & RELIBRA_BWD_REPLICA_WEIGHTS) ? 1 : 0;
     if (n_rows > 0) {
         RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
             s, (const bf16_t *)dYrows, (const bf16_t *)Wd, (const bf16_t *)Gt_save, (const bf16_t *)U_save,
-            h, hff, ct_ff));
+            h, hff, ct_ff, w_from_slot));
         RELIBRA_HIP_TRY(launch_check());
         RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<<<grid8(R * ct_h), THREADS, kLdsBytes, stream>>>(
-            s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, (bf16_t *)dXrows));
+            s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows));
         RELIBRA_HIP_TRY(launch_check());
     }
     // short groups (few rows per group on average): the small, high-occupancy geometry

@@ -311,3 +311,71 @@ def test_whole_layer_matches_oracle(cfg):
         assert rel_l2(dW[0][:cfg.E], dWg_o) <= TOL
         assert rel_l2(dW[1][:cfg.E], dWu_o) <= TOL
         assert rel_l2(dW[2][:cfg.E], dWd_o) <= TOL
+
+
+# ------------------------------------------------------------------ layer-shared replica buffer
+def test_replica_push_fills_slots_and_ffn_reads_them():
+    """Section 5.1: the push copies each live replica's home parameters into its slot (bit copy,
+    checked against the oracle); the FFN reading replica groups' parameters from those slots must
+    give bit-identical results to reading them from the home blocks."""
+    cfg = wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=2, h=256, hff=192)
+    ids, gates = routing(cfg)
+    counts = oracle.route_hist(ids, cfg.E)[0]
+    p = plan_both(cfg, counts)
+    Wg, Wu, Wd = wl.make_weights(cfg)
+    n_slots = cfg.E + cfg.EP * cfg.r
+    assert (p["replica_expert"] >= 0).any(), "the case must place replicas"
+
+    def with_slots(W):      # home blocks followed by replica slots holding recognisable junk
+        junk = torch.full((cfg.EP * cfg.r, *W.shape[1:]), 7.0, dtype=torch.bfloat16)
+        return torch.cat([W, junk]).contiguous()
+
+    big = [with_slots(W) for W in (Wg, Wu, Wd)]
+    big_d = [W.to(DEV) for W in big]
+    home_d = [W.to(DEV) for W in (Wg, Wu, Wd)]
+    for mb in range(cfg.n_mb):
+        rep = p["replica_expert"][mb].reshape(-1)
+        err = rl.relibra_replica_push(*big_d, dev_i32(rep), cfg.E, cfg.EP, cfg.r, n_workgroups=3)
+        assert err.item() == 0
+        for W_d, W in zip(big_d, big):
+            want = oracle.replica_push(W.view(torch.uint16).numpy(), rep, cfg.E)
+            got = W_d.cpu().view(torch.uint16).numpy()
+            live = np.concatenate([np.ones(cfg.E, bool), rep >= 0])
+            assert np.array_equal(got[live], want[live])
+            W.copy_(W_d.cpu())              # slots keep their contents from one micro-batch to the next
+        X, dOut = wl.make_tokens(cfg, mb)
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+        tabs = {key: dev_i32(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset",
+                                                     "group_expert", "group_dw_slot")}
+        row_of, src_of, Xrows = rl.relibra_permute(t(ids[mb]), tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                                   tabs["group_offset"], X.to(DEV), cfg.E, cfg.G)
+        outs = []
+        for use_slots in (False, True):
+            err = rl.new_err_flag()
+            W3 = big_d if use_slots else home_d
+            ge = tabs["group_dw_slot"] if use_slots else tabs["group_expert"]
+            Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], ge, *W3, err_flag=err)
+            dW = [torch.zeros((n_slots, cfg.hff, cfg.h), dtype=torch.float32, device=DEV),
+                  torch.zeros((n_slots, cfg.hff, cfg.h), dtype=torch.float32, device=DEV),
+                  torch.zeros((n_slots, cfg.h, cfg.hff), dtype=torch.float32, device=DEV)]
+            dY = torch.randn(Y.shape, generator=torch.Generator().manual_seed(mb)).to(torch.bfloat16).to(DEV)
+            dXrows = rl.relibra_moe_ffn_bwd(dY, Xrows, Gt, U, A, tabs["group_offset"], tabs["group_expert"],
+                                            tabs["group_dw_slot"], *W3, *dW, err_flag=err, E=cfg.E,
+                                            flags=rl.BWD_REPLICA_WEIGHTS if use_slots else 0)
+            assert err.item() == 0
+            outs.append((Y, dXrows, dW[0][:cfg.E], dW[1][:cfg.E], dW[2][:cfg.E]))
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+
+
+def test_replica_push_flags_bad_table_and_leaves_empty_slots():
+    E, EP, r, h, hff = 4, 2, 2, 64, 64
+    W = [torch.arange((E + EP * r) * h * hff, dtype=torch.float32).reshape(E + EP * r, hff, h).to(torch.bfloat16).to(DEV)
+         for _ in range(3)]
+    before = [w.clone() for w in W]
+    err = rl.relibra_replica_push(*W, dev_i32([2, -1, 99, 0]), E, EP, r, n_workgroups=1)
+    assert err.item() == rl.ERR_ID_RANGE
+    for w, b in zip(W, before):
+        assert torch.equal(w[E + 0], b[2]) and torch.equal(w[E + 3], b[0])
+        assert torch.equal(w[E + 1], b[E + 1]) and torch.equal(w[E + 2], b[E + 2])
+        assert torch.equal(w[:E], b[:E])

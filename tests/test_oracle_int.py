@@ -453,3 +453,19 @@ def test_gather_rows_is_a_bit_copy():
     src_of = rng.permutation(30).astype(np.int32)
     out = oracle.gather_rows(X, src_of, 3)
     assert np.array_equal(out, X[src_of // 3])
+
+
+def test_replica_push_is_an_indexed_block_copy():
+    """Section 5.1 (layer-shared replica buffer): live slots receive their home block, empty slots
+    and home blocks are untouched.  Pinned against numpy's indexed assignment."""
+    rng = np.random.default_rng(5)
+    E, slots = 6, 4
+    W = rng.integers(0, 1 << 16, size=(E + slots, 3, 5), dtype=np.uint16)
+    rep = np.array([4, -1, 0, 4], np.int32)
+    got = oracle.replica_push(W, rep, E)
+    want = W.copy()
+    live = np.nonzero(rep >= 0)[0]
+    want[E + live] = W[rep[live]]
+    assert np.array_equal(got, want)
+    assert np.array_equal(got[E + 1], W[E + 1]) and np.array_equal(got[:E], W[:E])
+    assert not np.array_equal(got[E + 0], W[E + 0])
