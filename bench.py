@@ -317,6 +317,27 @@ def main():
             del Wb
             assert err.item() == 0
 
+        # ---- communication-aware model (Section 4.1) and Algorithm 1 on this batch: per-source
+        # histogram on the GPU, modelled T_MoE of the unplanned layout, of the plan's placement and of
+        # the annealed placement.  Model constants are MI355X-flavoured assumptions, not measurements:
+        # F = 0.5 PFLOP/s effective, intra-node 7 x 153.6 GB/s xGMI links, 50 GB/s (400 Gb/s) per NIC.
+        if T % EP == 0:
+            x_h = rl.relibra_route_hist_src(ids_all, E, EP, err_flag=err).sum(0).cpu().numpy().astype(np.int64)
+            cm = rl.cost_model(EP, cfg.rpn, h, hff, 5e14, 7 * 153.6e9, 50e9)
+            t_sa = time.perf_counter()
+            sa_rank, sa_stats = rl.relibra_reorder_sa(x_h, cm, n_seeds=8, seed=0)
+            t_sa = (time.perf_counter() - t_sa) * 1e3
+            placed = plan["expert_to_slot"] // cfg.M
+            ident = np.arange(E, dtype=np.int32) // cfg.M
+            extras["comm_model"] = {
+                "assumed": {"F": 5e14, "B_intra": 7 * 153.6e9, "B_inter": 50e9, "ranks_per_node": cfg.rpn},
+                "T_unplanned_ms": rl.relibra_moe_time(x_h, ident, cm)["T"] * 1e3,
+                "T_plan_placement_ms": rl.relibra_moe_time(x_h, placed, cm)["T"] * 1e3,
+                "T_lpt_ms": sa_stats["T_start"] * 1e3, "T_annealed_ms": sa_stats["T"] * 1e3,
+                "sa_iterations_per_seed": sa_stats["iterations"], "sa_seeds": 8, "sa_solve_ms": t_sa,
+            }
+            assert err.item() == 0
+
     # ---------------- the CPU oracle on a bounded sample, on this machine's host cores
     cpu_baseline = None
     if args.cpu_seconds > 0:

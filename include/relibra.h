@@ -111,6 +111,66 @@ int relibra_plan(const int32_t *counts_host, int n_mb, int E, int k, int EP, int
                  int64_t *max_load_before, int64_t *max_load_after);
 
 /*
+ * The same plan with the expert placement given by the caller: stage 1 is skipped, stage 2
+ * (Algorithm 2, per micro-batch) runs under expert_rank.  For placements found with another
+ * objective, e.g. relibra_reorder_sa.
+ *   expert_rank [E] int32 host in: rank of each expert, exactly E/EP experts per rank
+ *                                  (else RELIBRA_ERANGE)
+ * Everything else as relibra_plan.
+ */
+int relibra_plan_placed(const int32_t *counts_host, int n_mb, int E, int k, int EP, int ranks_per_node, int r,
+                        const int32_t *expert_rank,
+                        int32_t *expert_to_slot, int32_t *replica_expert,
+                        int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                        int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                        int64_t *max_load_before, int64_t *max_load_after);
+
+/*
+ * Cost model of the MoE module on a rail-optimised cluster (Section 4.1).  A token on source
+ * rank j routed to an expert on rank g is a local copy (j == g), crosses the intra-node link
+ * (same node), RDMA on the same rail (other node, same index inside the node) or both
+ * (cross rail: relayed over the intra-node link first).  Times per routed token:
+ *   sec_per_token_comp  = 6 h h' / F                      (Eq. 4)
+ *   sec_per_token_intra = bytes per token / B_intra-node  (Eq. 5; 2h bytes for bf16)
+ *   sec_per_token_inter = bytes per token / B_rdma
+ */
+typedef struct relibra_cost_model {
+    int EP, ranks_per_node;
+    double sec_per_token_comp, sec_per_token_intra, sec_per_token_inter;
+} relibra_cost_model;
+
+/*
+ * Evaluate the model for one placement (Eq. 1-6).  All pointers HOST.
+ *   x_host      [EP, E] int64 in   tokens on source rank j routed to expert e (token t of a
+ *                                  micro-batch sits on rank t / (T/EP): relibra_route_hist on
+ *                                  ids viewed as [n_mb*EP, T/EP, k] yields it)
+ *   expert_rank [E] int32 in       rank hosting each expert
+ *   out4        [4] double out     T_MoE = max comp + max comm (Eq. 6), max_g T_comp (Eq. 4),
+ *                                  max_g T_comm (Eq. 5), and the smoothed objective of Section 4.2
+ *                                  (every max replaced by LSE_beta, times divided by t_ref)
+ *   loads_out   [5, EP] int64 out or NULL: computation load (Eq. 1), intra-node send, receive
+ *                                  (Eq. 2-3), RDMA send, receive, in tokens
+ */
+int relibra_moe_time(const int64_t *x_host, int E, const relibra_cost_model *model,
+                     const int32_t *expert_rank, double beta, double t_ref,
+                     double *out4, int64_t *loads_out);
+
+/*
+ * Algorithm 1: swap-based simulated annealing from the greedy-LPT placement under the smoothed
+ * objective (Section 4.2), n_seeds independent runs in parallel threads, best final placement by
+ * the exact T_MoE (ties: lower seed).  The paper does not publish gamma, epsilon, the seed set or
+ * the generator: gamma, eps (on the smoothed objective, whose scale is the start's T_MoE = 1),
+ * n_seeds and seed are arguments; draws come from splitmix64 started at
+ * seed + s * 0xD1342543DE82EF95 for seed index s, three per iteration (e_a, e_b, u); a worse
+ * state is accepted with probability exp(-(T' - T)/theta).  Deterministic for given arguments.
+ *   expert_rank_out [E] int32 out; stats5 [5] double out: exact T_MoE of the start, of the
+ *   result, smoothed objective of the start, of the result, iterations per seed.
+ */
+int relibra_reorder_sa(const int64_t *x_host, int E, const relibra_cost_model *model,
+                       double beta, double gamma, double eps, int n_seeds, uint64_t seed,
+                       int32_t *expert_rank_out, double *stats5);
+
+/*
  * Token permutation of one micro-batch (Section 5.2, token splitting; the local half of the
  * dispatch all-to-all, Section 2.1).  Assignment a = t*k + s with expert e = ids[a] has
  * ordinal q among e's assignments in ascending a; the instances of e, in ascending rank, take

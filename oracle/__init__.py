@@ -33,6 +33,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         _lib.oracle_replicate_node.restype = C.c_longlong
+        _lib.oracle_lse.restype = C.c_double
     return _lib
 
 
@@ -109,8 +110,9 @@ def replicate_node(cnt, home, n, r):
     return z, a, int(mx)
 
 
-def plan(counts, EP, rpn, r):
-    """counts[n_mb,E] -> dict of plan tables (see oracle_plan in the C file)."""
+def plan(counts, EP, rpn, r, placed=None):
+    """counts[n_mb,E] -> dict of plan tables (see oracle_plan in the C file).
+    placed [E]: use this placement instead of the oracle's own stage 1."""
     counts = _i32(counts)
     n_mb, E = counts.shape
     M = E // EP if EP > 0 else 0
@@ -128,7 +130,8 @@ def plan(counts, EP, rpn, r):
         max_before=np.empty(n_mb, np.int64),
         max_after=np.empty(n_mb, np.int64),
     )
-    rc = lib().oracle_plan(_p(counts), n_mb, E, EP, rpn, r,
+    placed = None if placed is None else _i32(placed)
+    rc = lib().oracle_plan_ex(_p(counts), n_mb, E, EP, rpn, r, _p(placed),
                            _p(out["expert_to_slot"]), _p(out["replica_expert"]),
                            _p(out["inst_ptr"]), _p(out["inst_rank"]), _p(out["inst_rows"]),
                            _p(out["inst_group"]), _p(out["group_expert"]), _p(out["group_offset"]),
@@ -149,6 +152,65 @@ def permute(ids, E, inst_ptr, inst_rows, inst_group, group_offset):
     if rc:
         raise ValueError(f"oracle_permute: status {rc}")
     return row_of, src_of
+
+
+# ------------------------------------------------------------------ communication-aware model, Algorithm 1
+def cost_model(h, hff, F, B_intra, B_inter, bytes_per_value=2):
+    """[seconds per token of computation (Eq. 4), per token over the intra-node link, over RDMA (Eq. 5)]."""
+    return np.array([6.0 * h * hff / F, bytes_per_value * h / B_intra, bytes_per_value * h / B_inter], np.float64)
+
+
+def route_hist_src(ids_mb, E, EP):
+    """ids [T,k] of one micro-batch -> x [EP,E] int64 (tokens of source rank j routed to expert e)."""
+    ids_mb = _i32(ids_mb)
+    T, k = ids_mb.shape
+    x = np.empty((EP, E), np.int64)
+    rc = lib().oracle_route_hist_src(_p(ids_mb), T, k, E, EP, _p(x))
+    if rc:
+        raise ValueError(f"oracle_route_hist_src: status {rc}")
+    return x
+
+
+def tau(j, g, rpn):
+    return int(lib().oracle_tau(int(j), int(g), int(rpn)))
+
+
+def loads(x, rank_of, rpn):
+    """-> comp, nv_tx, nv_rx, rd_tx, rd_rx [EP] int64 (Eq. 1-3)."""
+    x, rank_of = _i64(x), _i32(rank_of)
+    EP, E = x.shape
+    out = [np.empty(EP, np.int64) for _ in range(5)]
+    lib().oracle_loads(_p(x), E, EP, int(rpn), _p(rank_of), *[_p(o) for o in out])
+    return out
+
+
+def lse(z, beta):
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    return float(lib().oracle_lse(_p(z), z.shape[0], C.c_double(beta)))
+
+
+def moe_time(x, rank_of, rpn, model, beta=20.0, t_ref=1.0):
+    """-> dict(T, T_comp, T_comm in seconds (Eq. 4-6), smooth = LSE-smoothed objective on times / t_ref)."""
+    x, rank_of = _i64(x), _i32(rank_of)
+    EP, E = x.shape
+    model = np.ascontiguousarray(model, dtype=np.float64)
+    out = np.empty(4, np.float64)
+    lib().oracle_moe_time(_p(x), E, EP, int(rpn), _p(rank_of), _p(model), C.c_double(beta), C.c_double(t_ref), _p(out))
+    return dict(T=out[0], T_comp=out[1], T_comm=out[2], smooth=out[3])
+
+
+def reorder_sa(x, rpn, model, beta=20.0, gamma=0.999, eps=1e-3, n_seeds=8, seed=0):
+    """Algorithm 1 -> (rank_of [E], dict(T_start, T, smooth_start, smooth, iterations))."""
+    x = _i64(x)
+    EP, E = x.shape
+    model = np.ascontiguousarray(model, dtype=np.float64)
+    rank_of = np.empty(E, np.int32)
+    st = np.empty(5, np.float64)
+    rc = lib().oracle_reorder_sa(_p(x), E, EP, int(rpn), _p(model), C.c_double(beta), C.c_double(gamma),
+                                 C.c_double(eps), int(n_seeds), C.c_uint64(seed), _p(rank_of), _p(st))
+    if rc:
+        raise ValueError(f"oracle_reorder_sa: status {rc}")
+    return rank_of, dict(T_start=st[0], T=st[1], smooth_start=st[2], smooth=st[3], iterations=int(st[4]))
 
 
 # ------------------------------------------------------------------ floating point

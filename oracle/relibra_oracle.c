@@ -7,8 +7,11 @@
  * everything that is floating point (inputs are bf16 bit patterns, widened exactly).
  * Each function names the passage of the paper it follows.
  *
- * Parity pins live in tests/test_oracle_*.py.  Unpinned: nothing in this file (the
- * randomized annealing of Algorithm 1 is not implemented here at all).
+ * Parity pins live in tests/test_oracle_*.py.  Pinned: everything except
+ * oracle_reorder_sa, the randomized annealing of Algorithm 1: PARITY UNPINNED for its
+ * trajectory (cooling rate, threshold, seed set and random generator are not published);
+ * its cost model, its smoothed objective and its invariants (never worse than its start
+ * in the smoothed objective, capacity kept) are pinned.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -155,6 +158,187 @@ void oracle_reorder(const i64 *l, int E, int EP, int32_t *rank_of)
     int lpt_better = phi_less(m2, s2, m1, s1);
     memcpy(rank_of, lpt_better ? p_lpt : p_id, sizeof(int32_t) * E);
     free(p_id); free(p_lpt);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Communication-aware cost model of the MoE module (Section 4.1, Eq. 1-6)    */
+/* and Algorithm 1 as printed (swap-based simulated annealing, Section 4.2).  */
+
+/* x[j][e]: tokens that sit on source rank j and are routed to expert e.       */
+/* Tokens of a micro-batch are dealt to the EP ranks in equal contiguous runs  */
+/* (data-parallel attention): token t sits on rank t / (T / EP).               */
+int oracle_route_hist_src(const int32_t *ids, int T, int k, int E, int EP, i64 *x)
+{
+    if (EP < 1 || T % EP) return -1;
+    for (int i = 0; i < EP * E; ++i) x[i] = 0;
+    for (int t = 0; t < T; ++t)
+        for (int s = 0; s < k; ++s) {
+            int e = ids[(size_t)t * k + s];
+            if (e < 0 || e >= E) return -2;
+            x[(size_t)(t / (T / EP)) * E + e] += 1;
+        }
+    return 0;
+}
+
+/* Source-destination type on a rail-optimised cluster of rpn-GPU nodes        */
+/* (Section 4.1): 0 local copy, 1 intra-node link, 2 inter-node same rail      */
+/* (GPUs with the same index inside their nodes), 3 inter-node cross rail.     */
+int oracle_tau(int j, int g, int rpn)
+{
+    if (j == g) return 0;
+    if (j / rpn == g / rpn) return 1;
+    if (j % rpn == g % rpn) return 2;
+    return 3;
+}
+
+/* Loads in tokens under placement rank_of (Eq. 1-3): computation load of g,   */
+/* intra-node link send/receive load (types nv and cr) and RDMA send/receive   */
+/* load (types sr and cr) during dispatch.                                     */
+void oracle_loads(const i64 *x, int E, int EP, int rpn, const int32_t *rank_of,
+                  i64 *comp, i64 *nv_tx, i64 *nv_rx, i64 *rd_tx, i64 *rd_rx)
+{
+    for (int g = 0; g < EP; ++g) comp[g] = nv_tx[g] = nv_rx[g] = rd_tx[g] = rd_rx[g] = 0;
+    for (int e = 0; e < E; ++e) {
+        int g = rank_of[e];
+        for (int j = 0; j < EP; ++j) {
+            i64 n = x[(size_t)j * E + e];
+            int tau = oracle_tau(j, g, rpn);
+            comp[g] += n;
+            if (tau == 1 || tau == 3) { nv_tx[j] += n; nv_rx[g] += n; }
+            if (tau == 2 || tau == 3) { rd_tx[j] += n; rd_rx[g] += n; }
+        }
+    }
+}
+
+/* LSE_beta(z) = log(sum exp(beta z)) / beta (Section 4.2, objective smoothing), */
+/* evaluated around the maximum.                                                */
+double oracle_lse(const double *z, int n, double beta)
+{
+    double m = z[0];
+    for (int i = 1; i < n; ++i) if (z[i] > m) m = z[i];
+    double acc = 0.0;
+    for (int i = 0; i < n; ++i) acc += exp(beta * (z[i] - m));
+    return m + log(acc) / beta;
+}
+
+/* model[0..4] = seconds per token of computation (6hh'/F, Eq. 4), seconds per  */
+/* token over the intra-node link and over RDMA (bytes per token / bandwidth,  */
+/* Eq. 5), then unused.  out[0] = T_MoE (Eq. 6) in seconds, out[1] = max_g      */
+/* T_comp, out[2] = max_g T_comm, out[3] = smoothed objective with every time   */
+/* divided by t_ref (so that beta acts on numbers of order one).               */
+void oracle_moe_time(const i64 *x, int E, int EP, int rpn, const int32_t *rank_of,
+                     const double *model, double beta, double t_ref, double *out)
+{
+    i64 *L = (i64 *)malloc(sizeof(i64) * 5 * EP);
+    i64 *comp = L, *nv_tx = L + EP, *nv_rx = L + 2 * EP, *rd_tx = L + 3 * EP, *rd_rx = L + 4 * EP;
+    double *zc = (double *)malloc(sizeof(double) * 2 * EP), *zm = zc + EP;
+    oracle_loads(x, E, EP, rpn, rank_of, comp, nv_tx, nv_rx, rd_tx, rd_rx);
+    double max_comp = 0.0, max_comm = 0.0;
+    for (int g = 0; g < EP; ++g) {
+        double tc = (double)comp[g] * model[0];
+        double t4[4] = {(double)nv_tx[g] * model[1], (double)nv_rx[g] * model[1],
+                        (double)rd_tx[g] * model[2], (double)rd_rx[g] * model[2]};
+        double tm = t4[0];
+        for (int i = 1; i < 4; ++i) if (t4[i] > tm) tm = t4[i];
+        if (tc > max_comp) max_comp = tc;
+        if (tm > max_comm) max_comm = tm;
+        for (int i = 0; i < 4; ++i) t4[i] /= t_ref;
+        zc[g] = tc / t_ref;
+        zm[g] = oracle_lse(t4, 4, beta);
+    }
+    out[0] = max_comp + max_comm;
+    out[1] = max_comp;
+    out[2] = max_comm;
+    out[3] = oracle_lse(zc, EP, beta) + oracle_lse(zm, EP, beta);
+    free(L);
+    free(zc);
+}
+
+/* splitmix64 (Steele, Lea, Flood 2014): the counter-based generator both the  */
+/* oracle and the library implement for the annealing's random draws.          */
+static uint64_t sm64_next(uint64_t *state)
+{
+    uint64_t z = (*state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+/* Algorithm 1.  Start: greedy LPT on l_e = sum_j x[j][e].  Per seed: repeat   */
+/* {draw two experts, swap their ranks, evaluate the smoothed objective, accept */
+/* if better or with probability exp(-(T' - T)/theta), remember the best,       */
+/* theta *= gamma} while theta > eps; theta starts at the start's objective.    */
+/* (The printed acceptance exponent has the opposite sign, which would accept   */
+/* every worsening move; read as the Metropolis rule.)  The seeds' best states  */
+/* are compared by the exact T_MoE; ties keep the lower seed.  Every time is    */
+/* divided by the start's exact T_MoE before smoothing.  Three draws per        */
+/* iteration in the order e_a, e_b, u; seed s starts its generator at           */
+/* seed + s * 0xD1342543DE82EF95.  stats[0] = exact T of the start, [1] = exact */
+/* T of the result, [2] = smoothed start, [3] = smoothed result, [4] = iterations per seed. */
+int oracle_reorder_sa(const i64 *x, int E, int EP, int rpn, const double *model,
+                      double beta, double gamma, double eps, int n_seeds, uint64_t seed,
+                      int32_t *rank_out, double *stats)
+{
+    if (E % EP || n_seeds < 1 || !(gamma > 0.0 && gamma < 1.0) || !(eps > 0.0)) return -1;
+    i64 *l = (i64 *)calloc(E, sizeof(i64));
+    for (int j = 0; j < EP; ++j)
+        for (int e = 0; e < E; ++e) l[e] += x[(size_t)j * E + e];
+    int32_t *start = (int32_t *)malloc(sizeof(int32_t) * E);
+    int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * E);
+    int32_t *best = (int32_t *)malloc(sizeof(int32_t) * E);
+    oracle_lpt(l, E, EP, start);
+    double o[4];
+    oracle_moe_time(x, E, EP, rpn, start, model, beta, 1.0, o);
+    const double t_ref = o[0] > 0.0 ? o[0] : 1.0;
+    oracle_moe_time(x, E, EP, rpn, start, model, beta, t_ref, o);
+    const double exact0 = o[0], smooth0 = o[3];
+    double best_exact = 0.0, best_smooth = 0.0;
+    i64 iters = 0;
+    for (int s = 0; s < n_seeds; ++s) {
+        uint64_t rng = seed + (uint64_t)s * 0xD1342543DE82EF95ull;
+        memcpy(cur, start, sizeof(int32_t) * E);
+        memcpy(best, start, sizeof(int32_t) * E);
+        double T = smooth0, T_best = smooth0, theta = smooth0;
+        iters = 0;
+        while (theta > eps) {
+            int ea = (int)(sm64_next(&rng) % (uint64_t)E);
+            int eb = (int)(sm64_next(&rng) % (uint64_t)E);
+            double u = (double)(sm64_next(&rng) >> 11) * (1.0 / 9007199254740992.0);
+            int32_t ra = cur[ea], rb = cur[eb];
+            cur[ea] = rb;
+            cur[eb] = ra;
+            oracle_moe_time(x, E, EP, rpn, cur, model, beta, t_ref, o);
+            double Tn = o[3];
+            if (Tn < T || u < exp(-(Tn - T) / theta)) {
+                T = Tn;
+            } else {
+                cur[ea] = ra;
+                cur[eb] = rb;
+            }
+            if (T < T_best) {
+                T_best = T;
+                memcpy(best, cur, sizeof(int32_t) * E);
+            }
+            theta *= gamma;
+            ++iters;
+        }
+        oracle_moe_time(x, E, EP, rpn, best, model, beta, t_ref, o);
+        if (s == 0 || o[0] < best_exact) {
+            best_exact = o[0];
+            best_smooth = o[3];
+            memcpy(rank_out, best, sizeof(int32_t) * E);
+        }
+    }
+    stats[0] = exact0;
+    stats[1] = best_exact;
+    stats[2] = smooth0;
+    stats[3] = best_smooth;
+    stats[4] = (double)iters;
+    free(l);
+    free(start);
+    free(cur);
+    free(best);
+    return 0;
 }
 
 /* ------------------------------------------------------------------------- */
@@ -342,11 +526,14 @@ static i64 replicate_mb(const int32_t *cnt_mb, const int32_t *rank_of, int E, in
 /*                               M home slots then r replica slots per rank            */
 /*   max_before[n_mb]            max rank load, unplanned layout, no replicas          */
 /*   max_after[n_mb]             max rank load under the plan                          */
-int oracle_plan(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r,
-                int32_t *expert_to_slot, int32_t *replica_expert,
-                int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
-                int32_t *group_expert, int32_t *group_offset,
-                i64 *max_before, i64 *max_after)
+/* placed != NULL: that placement (rank per expert, M per rank) is used as it is   */
+/* and only the per-micro-batch replication runs (a placement found under another */
+/* objective, e.g. by the annealing of Algorithm 1).                              */
+int oracle_plan_ex(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r, const int32_t *placed,
+                   int32_t *expert_to_slot, int32_t *replica_expert,
+                   int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                   int32_t *group_expert, int32_t *group_offset,
+                   i64 *max_before, i64 *max_after)
 {
     if (E <= 0 || EP <= 0 || E % EP || rpn <= 0 || EP % rpn || r < 0 || n_mb <= 0) return -1;
     int M = E / EP, G = EP * (M + r), cap_inst = E + EP * r;
@@ -359,7 +546,8 @@ int oracle_plan(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r,
     int32_t *p_id = (int32_t *)malloc(sizeof(int32_t) * E);
     int32_t *p_new = (int32_t *)malloc(sizeof(int32_t) * E);
     for (int e = 0; e < E; ++e) p_id[e] = e / M;
-    oracle_reorder(l, E, EP, p_new);
+    if (placed) memcpy(p_new, placed, sizeof(int32_t) * E);
+    else oracle_reorder(l, E, EP, p_new);
 
     size_t zsz = (size_t)E * EP;
     uint8_t *z_id = (uint8_t *)malloc(zsz * n_mb), *z_new = (uint8_t *)malloc(zsz * n_mb);
@@ -371,7 +559,7 @@ int oracle_plan(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r,
         mx_new[mb] = replicate_mb(counts + (size_t)mb * E, p_new, E, EP, rpn, r, z_new + zsz * mb, a_new + zsz * mb);
         J_id += mx_id[mb]; J_new += mx_new[mb];
     }
-    int use_new = J_new < J_id;
+    int use_new = placed ? 1 : (J_new < J_id);
     const int32_t *rank_of = use_new ? p_new : p_id;
     const uint8_t *zz = use_new ? z_new : z_id;
     const i64 *aa = use_new ? a_new : a_id;
@@ -658,4 +846,15 @@ int oracle_num_threads(void)
 #else
     return 1;
 #endif
+}
+
+/* The plan with stage 1 run by the oracle itself. */
+int oracle_plan(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r,
+                int32_t *expert_to_slot, int32_t *replica_expert,
+                int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                int32_t *group_expert, int32_t *group_offset,
+                i64 *max_before, i64 *max_after)
+{
+    return oracle_plan_ex(counts, n_mb, E, EP, rpn, r, NULL, expert_to_slot, replica_expert, inst_ptr, inst_rank,
+                          inst_rows, inst_group, group_expert, group_offset, max_before, max_after);
 }

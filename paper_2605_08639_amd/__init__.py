@@ -22,7 +22,8 @@ WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD = 0, 1, 2
 BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS = 1, 2, 4
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
-EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_permute", "relibra_moe_ffn_fwd",
+EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa",
+           "relibra_permute", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_unpermute_combine", "relibra_replica_push", "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
 
@@ -104,8 +105,9 @@ def relibra_route_hist(ids, E, counts=None, err_flag=None):
     return counts
 
 
-def relibra_plan(counts_host, k, EP, ranks_per_node, r):
-    """counts_host [n_mb,E] int32 numpy (host) -> dict of host numpy plan tables."""
+def relibra_plan(counts_host, k, EP, ranks_per_node, r, expert_rank=None):
+    """counts_host [n_mb,E] int32 numpy (host) -> dict of host numpy plan tables.
+    expert_rank [E] (optional): take this placement instead of running stage 1 (relibra_plan_placed)."""
     counts_host = np.ascontiguousarray(counts_host, dtype=np.int32)
     n_mb, E = counts_host.shape
     M = E // EP if EP > 0 and E % EP == 0 else 0
@@ -125,13 +127,70 @@ def relibra_plan(counts_host, k, EP, ranks_per_node, r):
         max_load_after=np.empty(n_mb, np.int64),
     )
     rep = out["replica_expert"]
-    rc = lib().relibra_plan(_hp(counts_host), n_mb, E, k, EP, ranks_per_node, r,
-                            _hp(out["expert_to_slot"]), _hp(rep) if rep.size else C.c_void_p(0),
-                            _hp(out["inst_ptr"]), _hp(out["inst_rank"]), _hp(out["inst_rows"]),
-                            _hp(out["inst_group"]), _hp(out["group_expert"]), _hp(out["group_offset"]),
-                            _hp(out["group_dw_slot"]), _hp(out["max_load_before"]), _hp(out["max_load_after"]))
-    _check("relibra_plan", rc)
+    tail = (_hp(out["expert_to_slot"]), _hp(rep) if rep.size else C.c_void_p(0),
+            _hp(out["inst_ptr"]), _hp(out["inst_rank"]), _hp(out["inst_rows"]),
+            _hp(out["inst_group"]), _hp(out["group_expert"]), _hp(out["group_offset"]),
+            _hp(out["group_dw_slot"]), _hp(out["max_load_before"]), _hp(out["max_load_after"]))
+    if expert_rank is None:
+        rc = lib().relibra_plan(_hp(counts_host), n_mb, E, k, EP, ranks_per_node, r, *tail)
+        _check("relibra_plan", rc)
+    else:
+        expert_rank = np.ascontiguousarray(expert_rank, dtype=np.int32)
+        assert expert_rank.shape == (E,)
+        rc = lib().relibra_plan_placed(_hp(counts_host), n_mb, E, k, EP, ranks_per_node, r, _hp(expert_rank), *tail)
+        _check("relibra_plan_placed", rc)
     return out
+
+
+class CostModel(C.Structure):
+    """relibra_cost_model (Section 4.1): seconds per routed token of computation, over the
+    intra-node link and over RDMA, on EP ranks in nodes of ranks_per_node."""
+    _fields_ = [("EP", C.c_int), ("ranks_per_node", C.c_int), ("sec_per_token_comp", C.c_double),
+                ("sec_per_token_intra", C.c_double), ("sec_per_token_inter", C.c_double)]
+
+
+def cost_model(EP, ranks_per_node, h, hff, F, B_intra, B_inter, bytes_per_value=2):
+    return CostModel(int(EP), int(ranks_per_node), 6.0 * h * hff / F, bytes_per_value * h / B_intra,
+                     bytes_per_value * h / B_inter)
+
+
+def relibra_route_hist_src(ids, E, EP, err_flag=None):
+    """ids [n_mb,T,k] int32 (device) -> x [n_mb,EP,E] int32 (device): tokens on source rank
+    j = t // (T/EP) routed to expert e.  The histogram kernel on ids viewed as [n_mb*EP, T/EP, k]."""
+    n_mb, T, k = ids.shape
+    assert T % EP == 0, "tokens must split evenly over the source ranks"
+    x = relibra_route_hist(ids.view(n_mb * EP, T // EP, k), E, err_flag=err_flag)
+    return x.view(n_mb, EP, E)
+
+
+def relibra_moe_time(x_host, expert_rank, model, beta=20.0, t_ref=1.0, with_loads=False):
+    """x_host [EP,E] int64 -> dict(T, T_comp, T_comm, smooth[, loads [5,EP]]) (Eq. 1-6)."""
+    x_host = np.ascontiguousarray(x_host, dtype=np.int64)
+    expert_rank = np.ascontiguousarray(expert_rank, dtype=np.int32)
+    EP, E = x_host.shape
+    assert EP == model.EP and expert_rank.shape == (E,)
+    out = np.empty(4, np.float64)
+    loads = np.empty((5, EP), np.int64) if with_loads else None
+    rc = lib().relibra_moe_time(_hp(x_host), E, C.byref(model), _hp(expert_rank), C.c_double(beta), C.c_double(t_ref),
+                                _hp(out), _hp(loads) if with_loads else C.c_void_p(0))
+    _check("relibra_moe_time", rc)
+    res = dict(T=out[0], T_comp=out[1], T_comm=out[2], smooth=out[3])
+    if with_loads:
+        res["loads"] = loads
+    return res
+
+
+def relibra_reorder_sa(x_host, model, beta=20.0, gamma=0.9995, eps=1e-4, n_seeds=8, seed=0):
+    """Algorithm 1 -> (expert_rank [E] int32, dict(T_start, T, smooth_start, smooth, iterations))."""
+    x_host = np.ascontiguousarray(x_host, dtype=np.int64)
+    EP, E = x_host.shape
+    assert EP == model.EP
+    rank = np.empty(E, np.int32)
+    st = np.empty(5, np.float64)
+    rc = lib().relibra_reorder_sa(_hp(x_host), E, C.byref(model), C.c_double(beta), C.c_double(gamma), C.c_double(eps),
+                                  int(n_seeds), C.c_uint64(seed), _hp(rank), _hp(st))
+    _check("relibra_reorder_sa", rc)
+    return rank, dict(T_start=st[0], T=st[1], smooth_start=st[2], smooth=st[3], iterations=int(st[4]))
 
 
 def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,

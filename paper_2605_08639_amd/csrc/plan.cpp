@@ -292,11 +292,13 @@ std::vector<MbPlan> replicate_batch(const int32_t *counts, int n_mb, const std::
 
 }  // namespace
 
-extern "C" int relibra_plan(const int32_t *counts, int n_mb, int E, int k, int EP, int rpn, int r,
-                            int32_t *expert_to_slot, int32_t *replica_expert,
-                            int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
-                            int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
-                            int64_t *max_load_before, int64_t *max_load_after)
+// Both entry points.  placed = nullptr: stage 1 chooses the placement; otherwise the caller's
+// placement (rank per expert, exactly M per rank) is taken as it is and only stage 2 runs.
+static int plan_impl(const int32_t *counts, int n_mb, int E, int k, int EP, int rpn, int r, const int32_t *placed,
+                     int32_t *expert_to_slot, int32_t *replica_expert,
+                     int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                     int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                     int64_t *max_load_before, int64_t *max_load_after)
 {
     if (!counts || !expert_to_slot || !inst_ptr || !inst_rank || !inst_rows || !inst_group ||
         !group_expert || !group_offset || !group_dw_slot || !max_load_before || !max_load_after)
@@ -314,26 +316,39 @@ extern "C" int relibra_plan(const int32_t *counts, int n_mb, int E, int k, int E
             batch_load[e] += c;
         }
 
-    // stage 1: descent from the unplanned layout and from LPT; ties keep the unplanned one
     std::vector<int> unplanned(E);
     for (int e = 0; e < E; ++e) unplanned[e] = e / M;
-    std::vector<int> from_id = unplanned, from_lpt = lpt_start(batch_load, EP);
-    const Cost c_id = swap_descent(batch_load, EP, from_id);
-    const Cost c_lpt = swap_descent(batch_load, EP, from_lpt);
-    const std::vector<int> &reordered = (c_lpt < c_id) ? from_lpt : from_id;
-
-    // stage 2 under both placements; the reordering must pay for itself over the batch
-    std::vector<MbPlan> with_id = replicate_batch(counts, n_mb, unplanned, E, EP, rpn, r);
-    bool keep_reorder = false;
-    std::vector<MbPlan> with_new;
-    if (reordered != unplanned) {
-        with_new = replicate_batch(counts, n_mb, reordered, E, EP, rpn, r);
-        i64 j_id = 0, j_new = 0;
-        for (int mb = 0; mb < n_mb; ++mb) { j_id += with_id[mb].peak; j_new += with_new[mb].peak; }
-        keep_reorder = j_new < j_id;
+    std::vector<int> chosen;
+    std::vector<MbPlan> chosen_plans;
+    if (placed) {
+        std::vector<int> held(EP, 0);
+        chosen.resize(E);
+        for (int e = 0; e < E; ++e) {
+            if (placed[e] < 0 || placed[e] >= EP || ++held[placed[e]] > M) return RELIBRA_ERANGE;
+            chosen[e] = placed[e];
+        }
+        chosen_plans = replicate_batch(counts, n_mb, chosen, E, EP, rpn, r);
+    } else {
+        // stage 1: descent from the unplanned layout and from LPT; ties keep the unplanned one
+        std::vector<int> from_id = unplanned, from_lpt = lpt_start(batch_load, EP);
+        const Cost c_id = swap_descent(batch_load, EP, from_id);
+        const Cost c_lpt = swap_descent(batch_load, EP, from_lpt);
+        const std::vector<int> &reordered = (c_lpt < c_id) ? from_lpt : from_id;
+        // stage 2 under both placements; the reordering must pay for itself over the batch
+        chosen = unplanned;
+        chosen_plans = replicate_batch(counts, n_mb, unplanned, E, EP, rpn, r);
+        if (reordered != unplanned) {
+            std::vector<MbPlan> with_new = replicate_batch(counts, n_mb, reordered, E, EP, rpn, r);
+            i64 j_id = 0, j_new = 0;
+            for (int mb = 0; mb < n_mb; ++mb) { j_id += chosen_plans[mb].peak; j_new += with_new[mb].peak; }
+            if (j_new < j_id) {
+                chosen = reordered;
+                chosen_plans.swap(with_new);
+            }
+        }
     }
-    const std::vector<int> &where = keep_reorder ? reordered : unplanned;
-    const std::vector<MbPlan> &plans = keep_reorder ? with_new : with_id;
+    const std::vector<int> &where = chosen;
+    const std::vector<MbPlan> &plans = chosen_plans;
 
     std::vector<int> filled(EP, 0);
     for (int e = 0; e < E; ++e) expert_to_slot[e] = where[e] * M + filled[where[e]]++;
@@ -391,4 +406,26 @@ extern "C" int relibra_plan(const int32_t *counts, int n_mb, int E, int k, int E
         max_load_after[mb] = P.peak;
     }
     return RELIBRA_OK;
+}
+
+extern "C" int relibra_plan(const int32_t *counts, int n_mb, int E, int k, int EP, int rpn, int r,
+                            int32_t *expert_to_slot, int32_t *replica_expert,
+                            int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                            int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                            int64_t *max_load_before, int64_t *max_load_after)
+{
+    return plan_impl(counts, n_mb, E, k, EP, rpn, r, nullptr, expert_to_slot, replica_expert, inst_ptr, inst_rank,
+                     inst_rows, inst_group, group_expert, group_offset, group_dw_slot, max_load_before, max_load_after);
+}
+
+extern "C" int relibra_plan_placed(const int32_t *counts, int n_mb, int E, int k, int EP, int rpn, int r,
+                                   const int32_t *expert_rank,
+                                   int32_t *expert_to_slot, int32_t *replica_expert,
+                                   int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                                   int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                                   int64_t *max_load_before, int64_t *max_load_after)
+{
+    if (!expert_rank) return RELIBRA_EINVAL;
+    return plan_impl(counts, n_mb, E, k, EP, rpn, r, expert_rank, expert_to_slot, replica_expert, inst_ptr, inst_rank,
+                     inst_rows, inst_group, group_expert, group_offset, group_dw_slot, max_load_before, max_load_after);
 }

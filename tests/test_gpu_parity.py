@@ -57,6 +57,18 @@ def test_route_hist_flags_bad_ids_and_handles_empty():
     assert got.shape == (2, 8) and got.sum().item() == 0
 
 
+def test_per_source_histogram_bit_exact():
+    """x[j][e] of Section 4.1 (tokens on source rank j routed to e): the histogram kernel on the ids
+    viewed as [n_mb*EP, T/EP, k] against the oracle's definition."""
+    cfg = wl.small_config(T=1024, k=4, E=32, EP=8, n_mb=2)
+    ids, _ = routing(cfg)
+    err = rl.new_err_flag()
+    got = rl.relibra_route_hist_src(torch.from_numpy(ids).to(DEV), cfg.E, cfg.EP, err_flag=err).cpu().numpy()
+    assert err.item() == 0 and got.shape == (cfg.n_mb, cfg.EP, cfg.E)
+    for mb in range(cfg.n_mb):
+        assert np.array_equal(got[mb], oracle.route_hist_src(ids[mb], cfg.E, cfg.EP))
+
+
 # ------------------------------------------------------------------ plan + permute
 def plan_both(cfg, counts):
     want = oracle.plan(counts, cfg.EP, cfg.rpn, cfg.r)

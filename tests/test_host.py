@@ -131,3 +131,92 @@ def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
                                  ctypes.c_size_t(0), z, z) == rl.EINVAL        # g_begin > g_end
     assert L.relibra_unpermute_combine(7, z, z, z, z, 4, 2, 128, z, z, z, z, z) == rl.EINVAL
     assert L.relibra_unpermute_combine(0, z, z, z, z, 4, 2, 100, z, z, z, z, z) == rl.EINVAL
+
+
+# ------------------------------------------------------------------ communication-aware model, Algorithm 1
+def _src_hist(cfg):
+    return sum(oracle.route_hist_src(wl.make_routing(cfg, mb)[0], cfg.E, cfg.EP) for mb in range(cfg.n_mb))
+
+
+def _skewed_sources(seed, E, EP):
+    rng = np.random.default_rng(seed)
+    aff = rng.permutation(np.repeat(np.arange(EP), E // EP))
+    x = rng.integers(5, 30, size=(EP, E)).astype(np.int64)
+    for e in range(E):
+        x[aff[e], e] += rng.integers(300, 600)
+    return x
+
+
+@pytest.mark.parametrize("EP,rpn,E", [(4, 2, 8), (8, 4, 32), (8, 8, 16), (16, 4, 64)])
+def test_moe_time_equals_oracle(EP, rpn, E):
+    """Eq. 1-6: integer loads identical, times and the smoothed objective to rounding."""
+    rng = np.random.default_rng(E + EP)
+    x = rng.integers(0, 5000, size=(EP, E)).astype(np.int64)
+    rank_of = rng.permutation(np.repeat(np.arange(EP), E // EP)).astype(np.int32)
+    m_or = oracle.cost_model(2048, 768, 5e14, 1.0e12, 5e10)
+    m_lib = rl.cost_model(EP, rpn, 2048, 768, 5e14, 1.0e12, 5e10)
+    for t_ref in (1.0, 3e-4):
+        want = oracle.moe_time(x, rank_of, rpn, m_or, beta=20.0, t_ref=t_ref)
+        got = rl.relibra_moe_time(x, rank_of, m_lib, beta=20.0, t_ref=t_ref, with_loads=True)
+        for a, b in zip(got["loads"], oracle.loads(x, rank_of, rpn)):
+            assert np.array_equal(a, b)
+        for key in ("T", "T_comp", "T_comm", "smooth"):
+            assert got[key] == pytest.approx(want[key], rel=1e-12), key
+
+
+def test_reorder_sa_matches_oracle_in_quality():
+    """Algorithm 1 in the library (incremental O(|G|) state update, one thread per seed) against the
+    oracle (objective recomputed from the definition at every step).  The trajectory depends on
+    unpublished constants, so the bar is quality: same start, capacity kept, never worse than the
+    start in the smoothed objective, final exact T_MoE within 2 % of the oracle's.  (With the
+    same generator and arithmetic the two usually agree exactly; that is not required.)"""
+    for seed, (E, EP, rpn) in enumerate([(32, 8, 4), (16, 4, 2), (64, 8, 8)]):
+        x = _skewed_sources(seed, E, EP)
+        m_or = oracle.cost_model(2048, 768, 5e14, 1.0e12, 5e10)
+        m_lib = rl.cost_model(EP, rpn, 2048, 768, 5e14, 1.0e12, 5e10)
+        r_or, s_or = oracle.reorder_sa(x, rpn, m_or, gamma=0.999, eps=1e-3, n_seeds=4, seed=11)
+        r_lib, s_lib = rl.relibra_reorder_sa(x, m_lib, gamma=0.999, eps=1e-3, n_seeds=4, seed=11)
+        assert sorted(np.bincount(r_lib, minlength=EP).tolist()) == [E // EP] * EP
+        assert s_lib["T_start"] == pytest.approx(s_or["T_start"], rel=1e-12)
+        assert s_lib["smooth"] <= s_lib["smooth_start"]
+        assert s_lib["iterations"] == s_or["iterations"]
+        assert s_lib["T"] == pytest.approx(oracle.moe_time(x, r_lib, rpn, m_or)["T"], rel=1e-12)
+        assert abs(s_lib["T"] - s_or["T"]) <= 0.02 * s_or["T"]
+        again, s2 = rl.relibra_reorder_sa(x, m_lib, gamma=0.999, eps=1e-3, n_seeds=4, seed=11)
+        assert np.array_equal(again, r_lib) and s2 == s_lib
+
+
+def test_plan_placed_equals_oracle_under_the_annealed_placement():
+    """Stage 2 under a placement found by Algorithm 1: every table bit-exact against the oracle."""
+    cfg = wl.small_config(E=32, k=4, EP=8, r=2, T=1024, n_mb=3, ranks_per_node=4)
+    counts = _counts(cfg)
+    x = _src_hist(cfg)
+    assert np.array_equal(x.sum(0), counts.sum(0))
+    rank, _ = rl.relibra_reorder_sa(x, rl.cost_model(cfg.EP, cfg.rpn, cfg.h, cfg.hff, 5e14, 1e12, 5e10),
+                                    gamma=0.995, eps=1e-2, n_seeds=2, seed=3)
+    want = oracle.plan(counts, cfg.EP, cfg.rpn, cfg.r, placed=rank)
+    got = rl.relibra_plan(counts, cfg.k, cfg.EP, cfg.rpn, cfg.r, expert_rank=rank)
+    for key in PLAN_KEYS:
+        assert np.array_equal(got[key], want[key]), key
+    assert np.array_equal(got["max_load_after"], want["max_after"])
+    assert np.array_equal(got["expert_to_slot"] // cfg.M, rank)
+    bad = rank.copy()
+    bad[0] = bad[1] = bad[2] = bad[3] = bad[4] = 0            # five experts on a rank that holds four
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_plan(counts, cfg.k, cfg.EP, cfg.rpn, cfg.r, expert_rank=bad)
+
+
+def test_comm_model_argument_errors():
+    x = np.ones((4, 8), np.int64)
+    rank = np.repeat(np.arange(4), 2).astype(np.int32)
+    m = rl.cost_model(4, 2, 64, 64, 1e12, 1e11, 1e10)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_reorder_sa(x, m, gamma=1.0)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_reorder_sa(x, m, n_seeds=0)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_moe_time(-x, rank, m)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_moe_time(x, rank + 3, m)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_moe_time(x, rank, rl.cost_model(4, 3, 64, 64, 1e12, 1e11, 1e10))
