@@ -189,7 +189,10 @@ struct KLoop {
             for (int t = 0; t < TB; ++t) f.b[b][t] = mask_frag(f.b[b][t], k_first, k_valid);
     }
 
-    static __device__ __forceinline__ void mfma_all(Acc &acc, const Frags &f)
+    // MFMAs number lo .. hi-1 of the NA*NB*TA*TB of one k16 step (all of them: 0 .. N_MFMA)
+    static constexpr int N_MFMA = NA * NB * TA * TB;
+    template <int LO, int HI>
+    static __device__ __forceinline__ void mfma_range(Acc &acc, const Frags &f)
     {
 #pragma unroll
         for (int a = 0; a < NA; ++a)
@@ -198,10 +201,14 @@ struct KLoop {
 #pragma unroll
                 for (int ta = 0; ta < TA; ++ta)
 #pragma unroll
-                    for (int tb = 0; tb < TB; ++tb)
-                        acc[a * NB + b][ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            f.a[a][ta], f.b[b][tb], acc[a * NB + b][ta][tb], 0, 0, 0);
+                    for (int tb = 0; tb < TB; ++tb) {
+                        const int idx = ((a * NB + b) * TA + ta) * TB + tb;
+                        if (idx >= LO && idx < HI)
+                            acc[a * NB + b][ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                f.a[a][ta], f.b[b][tb], acc[a * NB + b][ta][tb], 0, 0, 0);
+                    }
     }
+    static __device__ __forceinline__ void mfma_all(Acc &acc, const Frags &f) { mfma_range<0, N_MFMA>(acc, f); }
 
     // k extent per phase = steps_per_phase * 32; k_valid (<= that) is the ragged contraction length.
     static __device__ __forceinline__ void run(Acc &acc, const Operand (&A)[NPH][NA], const Operand (&B)[NPH][NB],
@@ -245,10 +252,16 @@ struct KLoop {
             __builtin_amdgcn_sched_barrier(0);
             if (t + STAGES < n && DBG != 1 && DBG != 3) issue(cur, A, B, t + STAGES, steps_per_phase, k_last, wave, lane);
             if (DBG != 2) {
-                if (t + 1 < n) read_frags(f0, nxt, 0, wa, wb, lane);
-                __builtin_amdgcn_sched_barrier(0);
+                // First half of the k16 = 1 MFMAs, then the requests for the next slab's k16 = 0
+                // fragments (always issued: after the last slab they fetch stale LDS that nobody
+                // uses, and a request that is not conditional lets the wait in front of these
+                // MFMAs count only the older requests), then the second half, which covers them.
                 if (tail) mask_frags(f1, kf + 16, k_valid);
-                mfma_all(acc, f1);
+                mfma_range<0, N_MFMA / 2>(acc, f1);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(f0, nxt, 0, wa, wb, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_range<N_MFMA / 2, N_MFMA>(acc, f1);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
