@@ -137,17 +137,32 @@ sched_kernel(const int32_t *__restrict__ group_offset, const int32_t *__restrict
         s.tile_row0[t] = s.grp_row0[lo] + j * BM;
         s.tile_rows[t] = min(BM, s.grp_rows[lo] - j * BM);
     }
-    if (tid == 0) {
-        int n = 0;
-        if (group_dw_slot)
-            for (int i = 0; i < Gr; ++i)
-                if (s.grp_expert[i] >= 0 && s.grp_slot[i] >= E) {
-                    s.pair_slot[n] = s.grp_slot[i];
-                    s.pair_expert[n] = s.grp_expert[i];
-                    ++n;
-                }
-        s.hdr[1] = n;
+    // live replica slots, in group order (256 groups at a time; a running count in LDS)
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    if (group_dw_slot) {
+        for (int base = 0; base < Gr; base += 256) {
+            const int i = base + tid;
+            const bool live = i < Gr && s.grp_expert[i] >= 0 && s.grp_slot[i] >= E;
+            scan[tid] = live ? 1 : 0;
+            __syncthreads();
+            for (int off = 1; off < 256; off <<= 1) {
+                const int v = tid >= off ? scan[tid - off] : 0;
+                __syncthreads();
+                scan[tid] += v;
+                __syncthreads();
+            }
+            if (live) {
+                const int at = carry + scan[tid] - 1;
+                s.pair_slot[at] = s.grp_slot[i];
+                s.pair_expert[at] = s.grp_expert[i];
+            }
+            __syncthreads();
+            if (tid == 255) carry += scan[255];
+            __syncthreads();
+        }
     }
+    if (tid == 0) s.hdr[1] = carry;
 }
 
 // ---------------------------------------------------------------- tile lookup

@@ -1,11 +1,13 @@
 // Building blocks of the grouped bf16 MFMA GEMMs (gfx950): LDS operand tiles filled by
 // direct global->LDS loads, MFMA fragment reads, and a three-slab pipelined k-loop.
 //
-// An operand tile covers ROWS rows of the non-contracted index and 32 values of the contracted
-// index k.  Two memory situations:
-//   KcTile: k contiguous in memory (element (row,k) at base[row*ld + k]).  LDS holds [row][32],
-//           64 bytes per row, 16-byte pieces XOR-swizzled by the row so that the 16-byte
-//           fragment reads of 32 consecutive rows spread over all banks.
+// An operand tile covers ROWS rows of the non-contracted index and BKT (32 or 64) values of the
+// contracted index k.  Two memory situations:
+//   KcTile: k contiguous in memory (element (row,k) at base[row*ld + k]).  LDS holds [row][BKT],
+//           64 or 128 bytes per row, 16-byte pieces XOR-swizzled by the row so that the 16-byte
+//           fragment reads of 32 consecutive rows spread over all banks.  With BKT = 64 a row
+//           is one full 128-byte line per load: the L1's outstanding requests, which bound the
+//           L2 -> LDS rate, carry twice the bytes (measured 17 against 12 TB/s, loads alone).
 //   KsTile: k strided in memory (element (row,k) at base[k*ld + row]).  LDS holds [k][ROWS] as
 //           it lies in memory; fragments are read with the transposing LDS read
 //           (ds_read_b64_tr_b16), 16-byte pieces XOR-swizzled by k.
@@ -21,7 +23,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
-constexpr int BK = 32;                      // contraction slab per pipeline stage (two k16 MFMA steps)
+constexpr int BK = 32;                      // default contraction slab per pipeline stage (two k16 MFMA steps)
 
 #define RELIBRA_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define RELIBRA_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -40,13 +42,26 @@ struct Operand {
     int row_last;         // last valid row; rows beyond are clamped onto valid ones (masked later)
 };
 
-// k-contiguous operand: LDS [row][32], 64 bytes per row, 16 rows per 1 KiB load block.
-// Piece c of row r sits at piece c ^ g(r), g(r) = ((r>>1)&3) ^ ((r>>3)&1): the 16-byte reads of
-// any 8 (or 16) consecutive rows at one k offset fall into distinct 16-byte bank groups.
-template <int ROWS>
+// k-contiguous operand: LDS [row][BKT].
+// BKT = 32: 64 bytes per row, 16 rows per 1 KiB load block; piece c of row r sits at piece
+//   c ^ g(r), g(r) = ((r>>1)&3) ^ ((r>>3)&1).
+// BKT = 64: 128 bytes per row, 8 rows per block; g(r) = (r&7) ^ ((r>>3)&1).
+// Either way the 16-byte reads of any 8 (or 16) consecutive rows at one k offset fall into
+// distinct 16-byte bank groups.
+template <int ROWS, int BKT = BK>
 struct KcTile {
-    static constexpr int BYTES = ROWS * BK * 2;
-    static constexpr int BLOCKS = ROWS / 16;
+    static_assert(BKT == 32 || BKT == 64, "slab depth");
+    static constexpr int DEPTH = BKT;
+    static constexpr int ROW_BYTES = BKT * 2;
+    static constexpr int PIECES = BKT / 8;            // 16-byte pieces per row
+    static constexpr int RPB = 64 / PIECES;           // rows per 1 KiB block
+    static constexpr int BYTES = ROWS * ROW_BYTES;
+    static constexpr int BLOCKS = ROWS / RPB;
+
+    static __device__ __forceinline__ int swz(int r)
+    {
+        return BKT == 32 ? (((r >> 1) & 3) ^ ((r >> 3) & 1)) : ((r & 7) ^ ((r >> 3) & 1));
+    }
 
     template <int NW>
     static __device__ __forceinline__ void load(char *lds, const Operand &op, int k0, int /*k_last*/, int wave, int lane)
@@ -55,8 +70,8 @@ struct KcTile {
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i) {
             const int j = wave + i * NW;
-            const int r = j * 16 + (lane >> 2);
-            const int c = (lane & 3) ^ ((lane >> 3) & 3) ^ ((lane >> 5) & 1);
+            const int r = j * RPB + lane / PIECES;
+            const int c = (lane % PIECES) ^ swz(r);
             const int grow = min(op.row0 + r, op.row_last);
             __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)grow * op.ld + k0 + c * 8),
                                              RELIBRA_LDS(lds + j * 1024), 16, 0, 0);
@@ -67,20 +82,20 @@ struct KcTile {
     static __device__ __forceinline__ bf16x8_t frag(const char *lds, int r0, int kk, int lane)
     {
         const int r = r0 + (lane & 31);
-        const int g = ((lane >> 1) & 3) ^ ((lane >> 3) & 1);
-        const int c = (kk * 2 + (lane >> 5)) ^ g;
-        return *reinterpret_cast<const bf16x8_t *>(lds + r * 64 + c * 16);
+        const int c = (kk * 2 + (lane >> 5)) ^ swz(lane & 31);
+        return *reinterpret_cast<const bf16x8_t *>(lds + r * ROW_BYTES + c * 16);
     }
 };
 
 // k-strided operand: LDS [k][ROWS] as in memory; 16-byte pieces of a k-row XOR-ed with fk(k) so
 // that the 8-byte transposing reads of 4 k-rows x 16 (or 32) rows hit distinct banks.
-template <int ROWS>
+template <int ROWS, int BKT = BK>
 struct KsTile {
-    static constexpr int BYTES = ROWS * BK * 2;
+    static constexpr int DEPTH = BKT;
+    static constexpr int BYTES = ROWS * BKT * 2;
     static constexpr int SPR = ROWS / 8;              // 16-byte pieces per k-row
     static constexpr int KPB = 64 / SPR;              // k-rows per 1 KiB block
-    static constexpr int BLOCKS = BK / KPB;
+    static constexpr int BLOCKS = BKT / KPB;
     static_assert(ROWS >= 64 && ROWS <= 512, "tile height");
 
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
@@ -133,15 +148,18 @@ __device__ __forceinline__ bf16x8_t mask_frag(bf16x8_t f, int k_first, int k_val
 // Every operand tile has BA (A side) or BB (B side) rows; WA x WB wavefronts tile BA x BB.  NPH
 // phases run back to back over the same accumulators with different operands (sum of products).
 //
-// Pipeline: a ring of STAGES LDS slabs of 32 k-values.  In step t the wave
-//   reads the k16 = 1 fragments of slab t, issues the MFMAs of k16 = 0,
+// Pipeline: a ring of STAGES LDS slabs of DEPTH k-values (DEPTH / 16 MFMA steps each).  Fragments
+// of the next MFMA step are always requested one step ahead.  In the last step of slab t the wave
 //   waits until its own loads of slab t+1 have landed (those of later slabs stay in flight) and
 //   meets the other waves: slab t+1 is complete and nobody reads slab t any more,
-//   so it issues the loads of slab t+STAGES into slab t's place, reads the k16 = 0 fragments of
-//   slab t+1 and issues the MFMAs of k16 = 1, which cover both latencies.
+//   so it issues the loads of slab t+STAGES into slab t's place, runs half of the step's MFMAs,
+//   requests the first fragments of slab t+1 and runs the other half, which covers them.
 template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0>
 struct KLoop {
     static constexpr int NW = WA * WB;
+    static constexpr int DEPTH = AT::DEPTH;           // k-values per slab
+    static constexpr int KSTEPS = DEPTH / 16;          // MFMA steps per slab
+    static_assert(AT::DEPTH == BT::DEPTH && KSTEPS >= 2 && KSTEPS % 2 == 0, "slab depth");
     static constexpr int TA = BA / WA / 32, TB = BB / WB / 32;
     static constexpr int STAGE_BYTES = NA * AT::BYTES + NB * BT::BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
@@ -156,7 +174,7 @@ struct KLoop {
                                                  int t, int steps_per_phase, int k_last, int wave, int lane)
     {
         const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
-        const int k0 = (t - ph * steps_per_phase) * BK;
+        const int k0 = (t - ph * steps_per_phase) * DEPTH;
 #pragma unroll
         for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, A[ph][a], k0, k_last, wave, lane);
 #pragma unroll
@@ -210,7 +228,7 @@ struct KLoop {
     }
     static __device__ __forceinline__ void mfma_all(Acc &acc, const Frags &f) { mfma_range<0, N_MFMA>(acc, f); }
 
-    // k extent per phase = steps_per_phase * 32; k_valid (<= that) is the ragged contraction length.
+    // k extent per phase = steps_per_phase * DEPTH; k_valid (<= that) is the ragged contraction length.
     static __device__ __forceinline__ void run(Acc &acc, const Operand (&A)[NPH][NA], const Operand (&B)[NPH][NB],
                                                int steps_per_phase, int k_valid, char *lds, int tid)
     {
@@ -220,48 +238,52 @@ struct KLoop {
         const int n = steps_per_phase * NPH;
         const int k_last = k_valid - 1;
         if (n <= 0) return;
-        Frags f0, f1;
+        Frags f[2];
 #pragma unroll
         for (int i = 0; i < STAGES; ++i)
             if (i < n) issue(lds + i * STAGE_BYTES, A, B, i, steps_per_phase, k_last, wave, lane);
         wait_younger(n - 1);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(f0, lds, 0, wa, wb, lane);
+        read_frags(f[0], lds, 0, wa, wb, lane);
         int slot = 0;
         for (int t = 0; t < n; ++t) {
             char *cur = lds + slot * STAGE_BYTES;
             slot = (slot == STAGES - 1) ? 0 : slot + 1;
             char *nxt = lds + slot * STAGE_BYTES;
-            const bool tail = RAGGED_K && (t + 1) * BK > k_valid;
-            const int kf = t * BK + (lane >> 5) * 8;
-            if (DBG != 2) {
-                // f0 was requested before the previous MFMA block: it is there by now.  Waiting for
-                // it here, before the next requests go out, lets the MFMAs below start at once
-                // instead of waiting for the requests issued just above them.
-                __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
-                __builtin_amdgcn_sched_barrier(0);
-                read_frags(f1, cur, 1, wa, wb, lane);
-                __builtin_amdgcn_sched_barrier(0);
-                if (tail) mask_frags(f0, kf, k_valid);
-                mfma_all(acc, f0);
-                __builtin_amdgcn_sched_barrier(0);
+            const bool tail = RAGGED_K && (t + 1) * DEPTH > k_valid;
+            const int kf = t * DEPTH + (lane >> 5) * 8;
+#pragma unroll
+            for (int s = 0; s < KSTEPS - 1; ++s) {
+                if (DBG != 2) {
+                    // f[s & 1] was requested before the previous MFMA block: it is there by now.
+                    // Waiting for it here, before the next requests go out, lets the MFMAs below
+                    // start at once instead of waiting for the requests issued just above them.
+                    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+                    __builtin_amdgcn_sched_barrier(0);
+                    read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (tail) mask_frags(f[s & 1], kf + s * 16, k_valid);
+                    mfma_all(acc, f[s & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
             if (DBG != 3) __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             if (t + STAGES < n && DBG != 1 && DBG != 3) issue(cur, A, B, t + STAGES, steps_per_phase, k_last, wave, lane);
             if (DBG != 2) {
-                // First half of the k16 = 1 MFMAs, then the requests for the next slab's k16 = 0
+                // First half of the last step's MFMAs, then the requests for the next slab's first
                 // fragments (always issued: after the last slab they fetch stale LDS that nobody
                 // uses, and a request that is not conditional lets the wait in front of these
                 // MFMAs count only the older requests), then the second half, which covers them.
-                if (tail) mask_frags(f1, kf + 16, k_valid);
-                mfma_range<0, N_MFMA / 2>(acc, f1);
+                constexpr int L = (KSTEPS - 1) & 1;
+                if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, k_valid);
+                mfma_range<0, N_MFMA / 2>(acc, f[L]);
                 __builtin_amdgcn_sched_barrier(0);
-                read_frags(f0, nxt, 0, wa, wb, lane);
+                read_frags(f[0], nxt, 0, wa, wb, lane);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_range<N_MFMA / 2, N_MFMA>(acc, f1);
+                mfma_range<N_MFMA / 2, N_MFMA>(acc, f[L]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -272,6 +294,7 @@ struct KLoop {
     static __device__ __forceinline__ void wait_younger(int younger)
     {
         static_assert(STAGES >= 2 && STAGES <= 5, "ring depth");
+        static_assert(3 * LOADS < 64, "vmcnt has 6 bits");
         if (STAGES >= 5 && younger >= 3) wait_vm_lgkm0<3 * LOADS>();
         else if (STAGES >= 4 && younger >= 2) wait_vm_lgkm0<2 * LOADS>();
         else if (STAGES >= 3 && younger >= 1) wait_vm_lgkm0<1 * LOADS>();
