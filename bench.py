@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into workloads.CONFIGS (default: the metric's config)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target length of the oracle sample (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="skip the straggler and bandwidth-kernel sections")
+    ap.add_argument("--wgrad", choices=("batched", "per-mb"), default="batched",
+                    help="weight gradients once per batch over all resident micro-batches (default), or "
+                         "accumulated into dW micro-batch by micro-batch")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -74,34 +77,52 @@ def main():
     counts_d = i32(n_mb, E)
     err = rl.new_err_flag(dev)
     row_of, src_of = i32(N), i32(N)
-    Xrows, Yrows, dYrows, dXrows = bf(N, h), bf(N, h), bf(N, h), bf(N, h)
-    Gt, U, A = bf(N, hff), bf(N, hff), bf(N, hff)
+    batched = args.wgrad == "batched"
+    assert not batched or n_mb <= rl.MAX_WGRAD_MB
+    n_keep = n_mb if batched else 1          # batched weight gradients keep every micro-batch's rows resident
+    Xrows_k = [bf(N, h) for _ in range(n_keep)]
+    dYrows_k = [bf(N, h) for _ in range(n_keep)]
+    A_k = [bf(N, hff) for _ in range(n_keep)]
+    Yrows, dXrows = bf(N, h), bf(N, h)
+    Gt, U = bf(N, hff), bf(N, hff)
     Out, dX = bf(T, h), bf(T, h)
     dgate = torch.empty((T, k), dtype=torch.float32, device=dev)
     dWg = torch.empty((n_slots, hff, h), dtype=torch.float32, device=dev)
     dWu = torch.empty_like(dWg)
     dWd = torch.empty((n_slots, h, hff), dtype=torch.float32, device=dev)
     ws_perm = torch.empty(rl.workspace_bytes(rl.WS_PERMUTE, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
-    ws_ffn = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
+    ws_ffn_k = [torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
+                for _ in range(n_keep)]
+    ws_wgrad = torch.empty(rl.workspace_bytes(rl.WS_WGRAD_BATCHED, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
+    Xrows, dYrows, A, ws_ffn = Xrows_k[0], dYrows_k[0], A_k[0], ws_ffn_k[0]
     TABLES = ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert", "group_dw_slot")
 
     def upload(plan):
         return {key: torch.from_numpy(plan[key]).to(dev, non_blocking=True) for key in TABLES}
 
-    def layer(mb, tabs, first, g_range=None, flags_extra=0):
+    def layer(mb, tabs, first):
         X, dOut = tok[mb]
+        i = mb if batched else 0
+        Xr, dYr, Ar, ws = Xrows_k[i], dYrows_k[i], A_k[i], ws_ffn_k[i]
         rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
                            tabs["group_offset"][mb], X, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
-                           Xrows=Xrows, workspace=ws_perm, err_flag=err)
-        rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
-                               Gt=Gt, U=U, A=A, Yrows=Yrows, workspace=ws_ffn, err_flag=err)
+                           Xrows=Xr, workspace=ws_perm, err_flag=err)
+        rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
+                               Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
-                                     out_rows=dYrows, dgate=dgate, err_flag=err)
-        rl.relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, tabs["group_offset"][mb], tabs["group_expert"][mb],
+                                     out_rows=dYr, dgate=dgate, err_flag=err)
+        flags = rl.BWD_DEFER_WGRAD if batched else (0 if first else rl.BWD_ACCUMULATE)
+        rl.relibra_moe_ffn_bwd(dYr, Xr, Gt, U, Ar, tabs["group_offset"][mb], tabs["group_expert"][mb],
                                tabs["group_dw_slot"][mb], Wg, Wu, Wd, dWg, dWu, dWd,
-                               flags=0 if first else rl.BWD_ACCUMULATE, dXrows=dXrows, workspace=ws_ffn, err_flag=err)
+                               flags=flags, dXrows=dXrows, workspace=ws, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, out_tok=dX, err_flag=err)
+
+    def weight_gradients(tabs):
+        mbs = [dict(dYrows=dYrows_k[mb], Xrows=Xrows_k[mb], A=A_k[mb], bwd_workspace=ws_ffn_k[mb],
+                    inst_ptr=tabs["inst_ptr"][mb], inst_group=tabs["inst_group"][mb], group_offset=tabs["group_offset"][mb])
+               for mb in range(n_mb)]
+        rl.relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, workspace=ws_wgrad, err_flag=err)
 
     plan_ms = []
 
@@ -114,6 +135,8 @@ def main():
         tabs = upload(plan)
         for mb in range(n_mb):
             layer(mb, tabs, first=(mb == 0))
+        if batched:
+            weight_gradients(tabs)
         return plan, tabs
 
     if args.copy_calibration:
@@ -147,14 +170,16 @@ def main():
     # a group's weights once per live group, weight gradients written per live group and, when
     # accumulating, the home slots read first.  Averaged over the micro-batches of the step.
     def alg_bytes(name):
+        w1 = 2.0 * h * hff                       # one bf16 weight matrix
+        act_h, act_ff = 2.0 * h * N, 2.0 * hff * N
+        if batched and name.startswith("wgrad"):   # one launch per batch: every micro-batch's rows read once, dW written once
+            return n_mb * (act_h + act_ff) + 2 * w1 * E if name == "wgrad_down" else n_mb * (2 * act_ff + act_h) + 4 * w1 * E
         tot = 0.0
         for mb in range(n_mb):
             rows_g = np.diff(plan["group_offset"][mb])
             live = int((rows_g > 0).sum())
             home_live = int(((rows_g > 0) & (plan["group_dw_slot"][mb] < E)).sum())
             acc_mode = mb > 0
-            w1 = 2.0 * h * hff                       # one bf16 weight matrix
-            act_h, act_ff = 2.0 * h * N, 2.0 * hff * N
             tot += {
                 "fwd_gate_up": act_h + 2 * w1 * live + 3 * act_ff,
                 "fwd_down": act_ff + w1 * live + act_h,
@@ -170,7 +195,7 @@ def main():
 
     kernels = {}
     for name, (ms, n) in prof.items():
-        fl = GEMM_FLOP_FACTOR[name] * h * hff * N
+        fl = GEMM_FLOP_FACTOR[name] * h * hff * N * (n_mb if batched and name.startswith("wgrad") else 1)
         by = alg_bytes(name)
         t_s = ms / n * 1e-3
         kernels[name] = {"avg_ms": ms / n, "launches": n, "tflops": fl / t_s / 1e12, "alg_GBps": by / t_s / 1e9,
@@ -191,7 +216,7 @@ def main():
                      "mfma_frac": kd["tflops"] / PEAK_BF16_TFLOPS})
     # mixed roofline of all six GEMM kernels: sum over kernels of max(flops/peak, bytes/bandwidth)
     floor_ms = sum(max(v["flops_per_launch"] / (PEAK_BF16_TFLOPS * 1e12), v["alg_bytes_per_launch"] / (PEAK_HBM_GBS * 1e9))
-                   for v in kernels.values()) * 1e3
+                   * v["launches"] / args.steps for v in kernels.values()) * 1e3          # per step
     gemm_tflops = flops_step / (gemm_ms_step * 1e-3) / 1e12
     log(f"step {ms_per_step:.2f} ms  value {value:.1f} TFLOP/s  grouped GEMMs alone {gemm_tflops:.1f} TFLOP/s")
 
@@ -383,12 +408,14 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: E={E} top-{k} h={h} h'={hff} {n_mb}x{T} tokens, simulated EP={EP}, r={r}; "
-                               "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd)",
+                               "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd); "
+                               + ("weight gradients once per batch over all resident micro-batches" if batched
+                                  else "weight gradients accumulated micro-batch by micro-batch"),
                    "flops_per_step": flops_step},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "gemm_kernels": kernels, "gemm_only_tflops": gemm_tflops,
-        "gemm_mixed_roofline": {"floor_ms_per_microbatch": floor_ms, "achieved_ms_per_microbatch": gemm_ms_step / n_mb,
-                                "frac": floor_ms / (gemm_ms_step / n_mb)}, "plan_host_ms": float(np.mean(plan_ms)),
+        "gemm_mixed_roofline": {"floor_ms_per_step": floor_ms, "achieved_ms_per_step": gemm_ms_step,
+                                "frac": floor_ms / gemm_ms_step}, "plan_host_ms": float(np.mean(plan_ms)),
         "skew_before": float(np.mean(plan["max_load_before"]) / (N / EP)),
         "skew_after": float(np.mean(plan["max_load_after"]) / (N / EP)),
     }

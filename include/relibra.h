@@ -51,14 +51,16 @@ enum {
 };
 
 /* which = */
-enum { RELIBRA_WS_PERMUTE = 0, RELIBRA_WS_FFN_FWD = 1, RELIBRA_WS_FFN_BWD = 2 };
+enum { RELIBRA_WS_PERMUTE = 0, RELIBRA_WS_FFN_FWD = 1, RELIBRA_WS_FFN_BWD = 2, RELIBRA_WS_WGRAD_BATCHED = 3 };
 
 /* flags of relibra_moe_ffn_bwd */
 enum {
     RELIBRA_BWD_ACCUMULATE = 1,     /* home dW += this micro-batch's gradient (else overwrite) */
     RELIBRA_BWD_NO_REPLICA_SUM = 2, /* leave replica-slot dW where it is (partial group range) */
-    RELIBRA_BWD_REPLICA_WEIGHTS = 4 /* a group reads its parameters from slot group_dw_slot[g] of
+    RELIBRA_BWD_REPLICA_WEIGHTS = 4, /* a group reads its parameters from slot group_dw_slot[g] of
                                        Wg/Wu/Wd [n_dw_slots, ...] (filled by relibra_replica_push) */
+    RELIBRA_BWD_DEFER_WGRAD = 8     /* data gradients only: dW untouched; dGt, dU stay in the
+                                       workspace for relibra_moe_ffn_wgrad_batched */
 };
 
 /* modes of relibra_unpermute_combine */
@@ -242,6 +244,43 @@ int relibra_moe_ffn_bwd(const void *dYrows_dev, const void *Xrows_dev,
                         int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * Weight gradients of a whole training batch in one pass (the gradient accumulation over
+ * micro-batches of Section 2.1, done in registers instead of in memory).  The per-micro-batch
+ * form adds each micro-batch's contribution into fp32 dW in HBM: 24 h h' bytes of traffic per
+ * live expert and micro-batch, which outweighs the GEMM itself for groups below ~1000 rows.
+ * With 288 GB of HBM every micro-batch's activations can stay resident instead, so that one
+ * kernel contracts over ALL rows an expert received in the batch (every micro-batch, home and
+ * replica instances alike) and writes dW once:
+ *   dWd[e] (+)= sum dy A^T,  dWg[e] (+)= sum dGt x^T,  dWu[e] (+)= sum dU x^T.
+ * The sum runs over micro-batches in ascending order and, inside one, over the expert's
+ * instances in the order of the plan's instance table: fixed order, no atomics.
+ * Usage: run relibra_moe_ffn_bwd of every micro-batch with RELIBRA_BWD_DEFER_WGRAD over all
+ * groups (g_begin = 0, g_end = G), each with its OWN row buffers and workspace, keep them,
+ * then call this once.  On several GPUs a rank would contract its own instances this way and
+ * push the partial dW of replicated experts to their home rank once per batch.
+ *   mbs_host [n_mb] host in: per micro-batch device pointers
+ *       dYrows, Xrows [n_rows,h], A_save [n_rows,hff] bf16; bwd_workspace = the workspace that
+ *       micro-batch's deferred backward call used (same n_rows, G, hff);
+ *       inst_ptr [E+1], inst_group [inst_cap], group_offset [G+1] int32: the plan's tables
+ *   dWg, dWu [E,hff,h], dWd [E,h,hff] fp32 dev: overwritten, or added to if accumulate != 0
+ *   workspace_dev: relibra_workspace_bytes(RELIBRA_WS_WGRAD_BATCHED, ...) bytes
+ * Table entries out of range are skipped and flagged RELIBRA_ERR_GROUP_TABLE.
+ * Limits: 1 <= n_mb <= RELIBRA_MAX_WGRAD_MB, h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.
+ */
+#define RELIBRA_MAX_WGRAD_MB 48
+typedef struct relibra_wgrad_mb {
+    const void *dYrows_dev, *Xrows_dev, *A_save_dev;
+    const void *bwd_workspace_dev;
+    const int32_t *inst_ptr_dev, *inst_group_dev, *group_offset_dev;
+} relibra_wgrad_mb;
+
+int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs_host, int n_mb, int n_rows,
+                                  int G, int inst_cap, int E, int h, int hff,
+                                  float *dWg_dev, float *dWu_dev, float *dWd_dev, int accumulate,
+                                  void *workspace_dev, size_t workspace_bytes,
+                                  int32_t *err_flag_dev, relibra_stream stream);
+
+/*
  * Layer-shared replica buffer, forward push (Section 5.1: before a layer's expert computation
  * every GPU pushes the experts that are replicated in this micro-batch into the replica slots
  * of their target GPUs; the r slots per GPU are reused by every layer and micro-batch).
@@ -293,7 +332,8 @@ enum {
     RELIBRA_K_FILL = 0, RELIBRA_K_HIST, RELIBRA_K_PERM_COUNT, RELIBRA_K_PERM_SCAN, RELIBRA_K_PERM_RANK,
     RELIBRA_K_GATHER, RELIBRA_K_COMBINE_FWD, RELIBRA_K_COMBINE_BWD, RELIBRA_K_COMBINE_SUM, RELIBRA_K_SCHED,
     RELIBRA_K_FWD_GATE_UP, RELIBRA_K_FWD_DOWN, RELIBRA_K_BWD_ACT, RELIBRA_K_BWD_DX,
-    RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_REPLICA_PUSH, RELIBRA_K_COUNT
+    RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_REPLICA_PUSH,
+    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_COUNT
 };
 int relibra_prof_start(int level, int max_records);
 int relibra_prof_stop(double *ms_by_kernel_host, int64_t *launches_by_kernel_host);

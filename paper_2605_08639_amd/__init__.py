@@ -18,18 +18,20 @@ LIB_PATH = os.path.join(_HERE, "librelibra.so")
 
 OK, EINVAL, ERANGE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
-WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD = 0, 1, 2
-BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS = 1, 2, 4
+WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD, WS_WGRAD_BATCHED = 0, 1, 2, 3
+BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD = 1, 2, 4, 8
+MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa",
            "relibra_permute", "relibra_moe_ffn_fwd",
-           "relibra_moe_ffn_bwd", "relibra_unpermute_combine", "relibra_replica_push", "relibra_workspace_bytes",
+           "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_unpermute_combine", "relibra_replica_push",
+           "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
 
 KERNELS = ("fill", "hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
            "combine_sum", "sched", "fwd_gate_up", "fwd_down", "bwd_act", "bwd_dx", "wgrad_down",
-           "wgrad_gate_up", "replica_sum", "replica_push")
+           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order")
 
 _lib = None
 
@@ -255,7 +257,7 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
     n_rows, h = Xrows.shape
     hff = Wg.shape[1]
     E = Wg.shape[0] if E is None else int(E)
-    if flags & BWD_REPLICA_WEIGHTS:
+    if flags & BWD_REPLICA_WEIGHTS and dWg is not None:
         assert Wg.shape[0] >= dWg.shape[0] and Wu.shape[0] >= dWg.shape[0] and Wd.shape[0] >= dWg.shape[0]
     G = group_expert.shape[0]
     g_end = G if g_end is None else g_end
@@ -267,8 +269,11 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
     if err_flag is None:
         err_flag = new_err_flag(dev)
-    n_slots = dWg.shape[0]
-    assert dWu.shape[0] == n_slots and dWd.shape[0] == n_slots
+    if flags & BWD_DEFER_WGRAD:
+        n_slots = E if dWg is None else dWg.shape[0]
+    else:
+        n_slots = dWg.shape[0]
+        assert dWu.shape[0] == n_slots and dWd.shape[0] == n_slots
     rc = lib().relibra_moe_ffn_bwd(_dp(dYrows, torch.bfloat16), _dp(Xrows, torch.bfloat16),
                                    _dp(Gt, torch.bfloat16), _dp(U, torch.bfloat16), _dp(A, torch.bfloat16), n_rows,
                                    _dp(group_offset, torch.int32), _dp(group_expert, torch.int32),
@@ -279,6 +284,44 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
                                    _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_moe_ffn_bwd", rc)
     return dXrows
+
+
+class WgradMb(C.Structure):
+    """relibra_wgrad_mb: one micro-batch's device pointers for the batched weight gradients."""
+    _fields_ = [("dYrows_dev", C.c_void_p), ("Xrows_dev", C.c_void_p), ("A_save_dev", C.c_void_p),
+                ("bwd_workspace_dev", C.c_void_p), ("inst_ptr_dev", C.c_void_p), ("inst_group_dev", C.c_void_p),
+                ("group_offset_dev", C.c_void_p)]
+
+
+def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, workspace=None, err_flag=None):
+    """mbs: list of dicts(dYrows, Xrows, A, bwd_workspace, inst_ptr, inst_group, group_offset) of device
+    tensors, one per micro-batch whose backward ran with BWD_DEFER_WGRAD.  Writes dWg, dWu [E,h',h],
+    dWd [E,h,h'] fp32 in place (sum over all micro-batches and instances)."""
+    n_mb = len(mbs)
+    first = mbs[0]
+    n_rows, h = first["Xrows"].shape
+    hff = first["A"].shape[1]
+    G = first["group_offset"].shape[0] - 1
+    inst_cap = first["inst_group"].shape[0]
+    dev = dWg.device
+    arr = (WgradMb * n_mb)()
+    for i, m in enumerate(mbs):
+        assert m["Xrows"].shape == (n_rows, h) and m["dYrows"].shape == (n_rows, h) and m["A"].shape == (n_rows, hff)
+        assert m["group_offset"].shape[0] == G + 1 and m["inst_group"].shape[0] == inst_cap and m["inst_ptr"].shape[0] == E + 1
+        assert m["bwd_workspace"].numel() >= workspace_bytes(WS_FFN_BWD, max(n_rows, 1), 1, E, G, h, hff)
+        arr[i] = WgradMb(_dp(m["dYrows"], torch.bfloat16), _dp(m["Xrows"], torch.bfloat16), _dp(m["A"], torch.bfloat16),
+                         _dp(m["bwd_workspace"]), _dp(m["inst_ptr"], torch.int32), _dp(m["inst_group"], torch.int32),
+                         _dp(m["group_offset"], torch.int32))
+    if workspace is None:
+        workspace = torch.empty(max(workspace_bytes(WS_WGRAD_BATCHED, 0, 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_moe_ffn_wgrad_batched(arr, n_mb, n_rows, G, inst_cap, int(E), h, hff,
+                                             _dp(dWg, torch.float32), _dp(dWu, torch.float32), _dp(dWd, torch.float32),
+                                             1 if accumulate else 0, _dp(workspace), C.c_size_t(workspace.numel()),
+                                             _dp(err_flag), _stream())
+    _check("relibra_moe_ffn_wgrad_batched", rc)
+    return err_flag
 
 
 def relibra_replica_push(Wg, Wu, Wd, replica_expert, E, EP, r, n_workgroups=16, err_flag=None):

@@ -464,6 +464,54 @@ bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__
     else row_gemm_body<BM / 2, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
 }
 
+// Weight-gradient epilogue.  The accumulators hold, per lane, one column n and 16 rows m of each
+// MFMA tile; each 32 x 64 fp32 block of the wave goes through this wave's 8 KiB of LDS and
+// leaves as 16 bytes per lane along n: 1 KiB per store (or load-add-store) instruction.
+template <class KL, int NA, int BA>
+__device__ __forceinline__ void wgrad_epilogue(typename KL::Acc &acc, char *lds, float *out0, float *out1, size_t base,
+                                               int m0, int n0, int m_dim, int n_dim, bool add, int wave, int lane)
+{
+    static_assert(KL::TB == 2, "a wave owns 64 columns");
+    __syncthreads();                                          // every wave is done with the operand slabs
+    float *buf = reinterpret_cast<float *>(lds + wave * 8192);
+    const int wm0 = m0 + (wave / (NWAVES / 2)) * (BA / 2), wn0 = n0 + (wave % (NWAVES / 2)) * 64;
+    const int col4 = lane & 15, gcol = wn0 + col4 * 4;
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int ta = 0; ta < KL::TA; ++ta) {
+#pragma unroll
+            for (int tb = 0; tb < KL::TB; ++tb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    buf[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 64 + tb * 32 + (lane & 31)] = acc[a][ta][tb][v];
+            wave_lds_fence();
+            float *out = (a == 0 ? out0 : out1) + base;
+            float4 val[8];
+#pragma unroll
+            for (int p = 0; p < 8; ++p) val[p] = *reinterpret_cast<const float4 *>(buf + (p * 4 + (lane >> 4)) * 64 + col4 * 4);
+            if (add) {
+                float4 old[8];
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int r = wm0 + ta * 32 + p * 4 + (lane >> 4);
+                    old[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (r < m_dim && gcol < n_dim) old[p] = *reinterpret_cast<const float4 *>(out + (size_t)r * n_dim + gcol);
+                }
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    val[p].x += old[p].x; val[p].y += old[p].y; val[p].z += old[p].z; val[p].w += old[p].w;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int r = wm0 + ta * 32 + p * 4 + (lane >> 4);
+                if (r < m_dim && gcol < n_dim) *reinterpret_cast<float4 *>(out + (size_t)r * n_dim + gcol) = val[p];
+            }
+            wave_lds_fence();
+        }
+}
+
 // Weight gradients: out[slot][m][n] (+)= sum over the group's rows of L[row][m] * R[row][n].
 // NA = 2 computes two left operands against one right operand (dGt and dU against X).
 // Tile: (NA x BA) x WGN with BA = WGM / NA.  Two geometries: WGM = 256 (three slabs, two
@@ -508,49 +556,120 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
     typename KL::Acc acc;
     KL::zero(acc);
     KL::run(acc, A, B, (rows + BK - 1) / BK, rows, lds, tid);
-    // Epilogue.  The accumulators hold, per lane, one column n and 16 rows m of each MFMA tile;
-    // each 32 x 64 fp32 block of the wave goes through this wave's 8 KiB of LDS and leaves as
-    // 16 bytes per lane along n: 1 KiB per store (or load-add-store) instruction.
-    static_assert(KL::TB == 2, "a wave owns 64 columns");
-    __syncthreads();                                          // every wave is done with the operand slabs
-    float *buf = reinterpret_cast<float *>(lds + wave * 8192);
-    const size_t base = (size_t)slot * m_dim * n_dim;
-    const int wm0 = m0 + (wave / (NWAVES / 2)) * (BA / 2), wn0 = n0 + (wave % (NWAVES / 2)) * 64;
-    const int col4 = lane & 15, gcol = wn0 + col4 * 4;
-#pragma unroll
-    for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int ta = 0; ta < KL::TA; ++ta) {
-#pragma unroll
-            for (int tb = 0; tb < KL::TB; ++tb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    buf[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 64 + tb * 32 + (lane & 31)] = acc[a][ta][tb][v];
-            wave_lds_fence();
-            float *out = (a == 0 ? out0 : out1) + base;
-            float4 val[8];
-#pragma unroll
-            for (int p = 0; p < 8; ++p) val[p] = *reinterpret_cast<const float4 *>(buf + (p * 4 + (lane >> 4)) * 64 + col4 * 4);
-            if (add) {
-                float4 old[8];
-#pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    const int r = wm0 + ta * 32 + p * 4 + (lane >> 4);
-                    old[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (r < m_dim && gcol < n_dim) old[p] = *reinterpret_cast<const float4 *>(out + (size_t)r * n_dim + gcol);
-                }
-#pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    val[p].x += old[p].x; val[p].y += old[p].y; val[p].z += old[p].z; val[p].w += old[p].w;
-                }
+    wgrad_epilogue<KL, NA, BA>(acc, lds, out0, out1, (size_t)slot * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
+}
+
+// ---------------------------------------------------------------- batched weight gradients
+// One pass over every micro-batch of a training batch: the tile of expert e contracts over all
+// rows e received, instance by instance, micro-batch by micro-batch, in registers, and writes
+// dW once.  Per-micro-batch device pointers travel as a kernel argument.
+constexpr int kMaxWgradMb = RELIBRA_MAX_WGRAD_MB;
+struct MbTable {
+    const bf16_t *dY[kMaxWgradMb], *X[kMaxWgradMb], *A[kMaxWgradMb], *dGt[kMaxWgradMb], *dU[kMaxWgradMb];
+    const int32_t *iptr[kMaxWgradMb], *igrp[kMaxWgradMb], *goff[kMaxWgradMb];
+};
+
+// Instance range of expert e in micro-batch mb, sanitised: [p0, p1) inside the instance table.
+__device__ __forceinline__ bool inst_range(const MbTable &tb, int mb, int e, int inst_cap, int &p0, int &p1)
+{
+    p0 = tb.iptr[mb][e];
+    p1 = tb.iptr[mb][e + 1];
+    if (p0 < 0 || p1 < p0 || p1 > inst_cap) { p0 = p1 = 0; return false; }
+    return true;
+}
+// Row range of instance p of micro-batch mb, sanitised: rows = 0 when a table entry is bad.
+__device__ __forceinline__ bool inst_rows(const MbTable &tb, int mb, int p, int G, int n_rows, int &row0, int &rows)
+{
+    row0 = rows = 0;
+    const int g = tb.igrp[mb][p];
+    if (g < 0 || g >= G) return false;
+    const int lo = tb.goff[mb][g], hi = tb.goff[mb][g + 1];
+    if (lo < 0 || hi < lo || hi > n_rows) return false;
+    row0 = lo;
+    rows = hi - lo;
+    return true;
+}
+
+// One block: rows per expert over the batch, and the experts in descending order of rows
+// (ties: lower id).  XCD x then serves the experts ranked x, x+8, ...: heaviest first, and the
+// eight L2s get near-equal work.
+__global__ void __launch_bounds__(256)
+wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
+                   int32_t *__restrict__ exp_rows, int32_t *__restrict__ exp_order, int32_t *err_flag)
+{
+    extern __shared__ int32_t rows_of[];
+    bool bad = false;
+    for (int e = threadIdx.x; e < E; e += 256) {
+        long long total = 0;
+        for (int mb = 0; mb < n_mb; ++mb) {
+            int p0, p1;
+            if (!inst_range(tb, mb, e, inst_cap, p0, p1)) bad = true;
+            for (int p = p0; p < p1; ++p) {
+                int row0, rows;
+                if (!inst_rows(tb, mb, p, G, n_rows, row0, rows)) bad = true;
+                total += rows;
             }
-#pragma unroll
-            for (int p = 0; p < 8; ++p) {
-                const int r = wm0 + ta * 32 + p * 4 + (lane >> 4);
-                if (r < m_dim && gcol < n_dim) *reinterpret_cast<float4 *>(out + (size_t)r * n_dim + gcol) = val[p];
-            }
-            wave_lds_fence();
         }
+        rows_of[e] = (int32_t)(total > 0x7fffffffLL ? 0x7fffffffLL : total);
+        exp_rows[e] = rows_of[e];
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_GROUP_TABLE);
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) {
+        const int mine = rows_of[e];
+        int rank = 0;
+        for (int o = 0; o < E; ++o) rank += (rows_of[o] > mine || (rows_of[o] == mine && o < e)) ? 1 : 0;
+        exp_order[rank] = e;
+    }
+}
+
+// NA = 1: dWd (L = dY, R = A).  NA = 2: dWg, dWu (L = dGt, dU; R = X).
+template <int NA>
+__global__ void __launch_bounds__(THREADS, WgradCfg<256>::OCC)
+wgrad_batched_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E, int m_dim, int n_dim,
+                     const int32_t *__restrict__ exp_rows, const int32_t *__restrict__ exp_order, int accumulate,
+                     float *__restrict__ out0, float *__restrict__ out1)
+{
+    constexpr int WGM = 256, BA = WGM / NA;
+    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES>;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
+    const int per_expert = n_nt * n_mt;
+    const int t = blockIdx.x >> 3;
+    const int rank = (blockIdx.x & 7) + 8 * (t / per_expert);
+    if (rank >= E) return;
+    const int e = exp_order[rank];
+    if ((unsigned)e >= (unsigned)E) return;
+    const bool add = accumulate != 0;
+    if (exp_rows[e] == 0 && add) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int mt, nt;
+    band_order(t % per_expert, n_mt, n_nt, mt, nt);
+    const int m0 = mt * BA, n0 = nt * WGN;
+    typename KL::Acc acc;
+    KL::zero(acc);
+    for (int mb = 0; mb < n_mb; ++mb) {
+        int p0, p1;
+        inst_range(tb, mb, e, inst_cap, p0, p1);
+        for (int p = p0; p < p1; ++p) {
+            int row0, rows;
+            inst_rows(tb, mb, p, G, n_rows, row0, rows);
+            if (rows == 0) continue;
+            Operand A[1][NA], B[1][1];
+            if (NA == 1) {
+                A[0][0] = {tb.dY[mb] + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
+                B[0][0] = {tb.A[mb] + (size_t)row0 * n_dim, n_dim, n0, n_dim - 1};
+            } else {
+                A[0][0] = {tb.dGt[mb] + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
+                A[0][NA - 1] = {tb.dU[mb] + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
+                B[0][0] = {tb.X[mb] + (size_t)row0 * n_dim, n_dim, n0, n_dim - 1};
+            }
+            // The loop's last barrier leaves no wave reading operand data from LDS, so the next
+            // instance's first loads may overwrite the ring at once.
+            KL::run(acc, A, B, (rows + BK - 1) / BK, rows, lds, tid);
+        }
+    }
+    wgrad_epilogue<KL, NA, BA>(acc, lds, out0, out1, (size_t)e * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
 }
 
 // Replica gradients return to the home copy (Section 5.1).  A thread owns element positions
@@ -596,6 +715,7 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     case RELIBRA_WS_PERMUTE: return round256((size_t)((N + 511) / 512 + 4) * E * sizeof(int32_t));
     case RELIBRA_WS_FFN_FWD: return ffn_ws_bytes(N, G, hff, false);
     case RELIBRA_WS_FFN_BWD: return ffn_ws_bytes(N, G, hff, true);
+    case RELIBRA_WS_WGRAD_BATCHED: return round256((size_t)(2 * E + 8) * sizeof(int32_t));
     default: return 0;
     }
     (void)h;
@@ -612,6 +732,8 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     done = true;
@@ -670,8 +792,9 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     if (n_dw_slots < E) return RELIBRA_EINVAL;
     const int Gr = g_end - g_begin;
     if (Gr == 0) return RELIBRA_OK;
+    const bool defer = (flags & RELIBRA_BWD_DEFER_WGRAD) != 0;    // then dW is not touched and may be null
     if (!dYrows || !Xrows || !Gt_save || !U_save || !A_save || !group_offset || !group_expert || !group_dw_slot ||
-        !Wg || !Wu || !Wd || !dXrows || !dWg || !dWu || !dWd || !ws || !err_flag)
+        !Wg || !Wu || !Wd || !dXrows || !ws || !err_flag || (!defer && (!dWg || !dWu || !dWd)))
         return RELIBRA_EINVAL;
     if (!aligned16(dYrows) || !aligned16(Xrows) || !aligned16(A_save) || !aligned16(Gt_save) || !aligned16(U_save) ||
         !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) || !aligned16(dXrows) || !aligned16(dWg) ||
@@ -680,7 +803,9 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     if (ws_bytes < ffn_ws_bytes(n_rows, Gr, hff, true)) return RELIBRA_EWORKSPACE;
     if (int rc = ensure_lds_limits()) return rc;
     Sched s = carve(ws, n_rows, Gr, hff, true);
-    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, group_dw_slot, g_begin, Gr, n_rows, E,
+    // the slot table matters only to kernels that write dW or read replica parameters
+    const int32_t *slot_table = (defer && !(flags & RELIBRA_BWD_REPLICA_WEIGHTS)) ? nullptr : group_dw_slot;
+    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, slot_table, g_begin, Gr, n_rows, E,
                                         n_dw_slots, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     const long long R = max_row_tiles(n_rows, Gr);
@@ -696,6 +821,7 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
             s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows));
         RELIBRA_HIP_TRY(launch_check());
     }
+    if (defer) return RELIBRA_OK;                                  // dGt, dU stay in the workspace
     // short groups (few rows per group on average): the small, high-occupancy geometry
     const bool small_tiles = (long long)n_rows < 512LL * Gr;
     const int wgm = small_tiles ? 128 : 256;
@@ -723,5 +849,54 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
             s, vec4, (float4 *)dWg, (float4 *)dWu, (float4 *)dWd));
         RELIBRA_HIP_TRY(launch_check());
     }
+    return RELIBRA_OK;
+}
+
+extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_mb, int n_rows,
+                                             int G, int inst_cap, int E, int h, int hff,
+                                             float *dWg, float *dWu, float *dWd, int accumulate,
+                                             void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    const FfnArgs a{n_rows, G, 0, G, E, h, hff};
+    if (int rc = check_ffn_args(a)) return rc;
+    if (!mbs || n_mb < 1 || n_mb > kMaxWgradMb || inst_cap < 1 || E > 4096) return RELIBRA_EINVAL;
+    if (!dWg || !dWu || !dWd || !ws || !err_flag || !aligned16(dWg) || !aligned16(dWu) || !aligned16(dWd) || !aligned16(ws))
+        return RELIBRA_EINVAL;
+    if (ws_bytes < relibra_workspace_bytes(RELIBRA_WS_WGRAD_BATCHED, 0, 1, E, G, h, hff)) return RELIBRA_EWORKSPACE;
+    MbTable tb;
+    for (int mb = 0; mb < kMaxWgradMb; ++mb) {
+        const relibra_wgrad_mb &m = mbs[mb < n_mb ? mb : 0];
+        if (mb < n_mb) {
+            if (!m.dYrows_dev || !m.Xrows_dev || !m.A_save_dev || !m.bwd_workspace_dev || !m.inst_ptr_dev ||
+                !m.inst_group_dev || !m.group_offset_dev)
+                return RELIBRA_EINVAL;
+            if (!aligned16(m.dYrows_dev) || !aligned16(m.Xrows_dev) || !aligned16(m.A_save_dev) || !aligned16(m.bwd_workspace_dev))
+                return RELIBRA_EINVAL;
+        }
+        const Sched s = carve(const_cast<void *>(m.bwd_workspace_dev), n_rows, G, hff, true);
+        tb.dY[mb] = (const bf16_t *)m.dYrows_dev;
+        tb.X[mb] = (const bf16_t *)m.Xrows_dev;
+        tb.A[mb] = (const bf16_t *)m.A_save_dev;
+        tb.dGt[mb] = s.dGt;
+        tb.dU[mb] = s.dU;
+        tb.iptr[mb] = m.inst_ptr_dev;
+        tb.igrp[mb] = m.inst_group_dev;
+        tb.goff[mb] = m.group_offset_dev;
+    }
+    if (int rc = ensure_lds_limits()) return rc;
+    int32_t *exp_rows = (int32_t *)ws, *exp_order = exp_rows + E;
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_ORDER, stream, wgrad_order_kernel<<<1, 256, E * sizeof(int32_t), stream>>>(
+        tb, n_mb, G, inst_cap, n_rows, E, exp_rows, exp_order, err_flag));
+    RELIBRA_HIP_TRY(launch_check());
+    const long long per_xcd = (E + 7) / 8;
+    const long long t_down = per_xcd * ((h + 255) / 256) * ((hff + WGN - 1) / WGN);       // dWd: m in h, n in h'
+    const long long t_gu = per_xcd * ((hff + 127) / 128) * ((h + WGN - 1) / WGN);         // dWg, dWu: m in h', n in h
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1><<<(unsigned)(8 * t_down), THREADS, WgradCfg<256>::LDS, stream>>>(
+        tb, n_mb, G, inst_cap, n_rows, E, h, hff, exp_rows, exp_order, accumulate, dWd, nullptr));
+    RELIBRA_HIP_TRY(launch_check());
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2><<<(unsigned)(8 * t_gu), THREADS, WgradCfg<256>::LDS, stream>>>(
+        tb, n_mb, G, inst_cap, n_rows, E, hff, h, exp_rows, exp_order, accumulate, dWg, dWu));
+    RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }

@@ -391,3 +391,61 @@ def test_replica_push_flags_bad_table_and_leaves_empty_slots():
         assert torch.equal(w[E + 0], b[2]) and torch.equal(w[E + 3], b[0])
         assert torch.equal(w[E + 1], b[E + 1]) and torch.equal(w[E + 2], b[E + 2])
         assert torch.equal(w[:E], b[:E])
+
+
+# ------------------------------------------------------------------ batched weight gradients
+def test_batched_weight_gradients_match_oracle_and_per_microbatch_path():
+    """dW of a whole batch in one pass (Section 2.1: gradients accumulate over micro-batches):
+    against the oracle's sum over micro-batches (all instances of an expert), and against the
+    per-micro-batch accumulate path of the library, which differs only in fp32 summation order."""
+    cfg = wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=3, h=256, hff=192)
+    ids, gates = routing(cfg)
+    counts = oracle.route_hist(ids, cfg.E)[0]
+    p = plan_both(cfg, counts)
+    Wg, Wu, Wd = wl.make_weights(cfg)
+    W_d = [W.to(DEV) for W in (Wg, Wu, Wd)]
+    n_slots = cfg.E + cfg.EP * cfg.r
+    shapes = [(cfg.hff, cfg.h), (cfg.hff, cfg.h), (cfg.h, cfg.hff)]
+    dW_ref = [np.zeros((cfg.E, *s)) for s in shapes]
+    dW_mb = [torch.empty((n_slots, *s), dtype=torch.float32, device=DEV) for s in shapes]
+    err = rl.new_err_flag()
+    kept = []
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    for mb in range(cfg.n_mb):
+        X, _ = wl.make_tokens(cfg, mb)
+        tabs = {key: dev_i32(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset",
+                                                     "group_expert", "group_dw_slot")}
+        row_of, src_of, Xrows = rl.relibra_permute(t(ids[mb]), tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                                   tabs["group_offset"], X.to(DEV), cfg.E, cfg.G, err_flag=err)
+        Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], *W_d, err_flag=err)
+        dY = torch.randn(Y.shape, generator=torch.Generator().manual_seed(100 + mb)).to(torch.bfloat16)
+        dY_d = dY.to(DEV)
+        ws = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, cfg.N, 1, cfg.E, cfg.G, cfg.h, cfg.hff), dtype=torch.uint8, device=DEV)
+        dX_deferred = rl.relibra_moe_ffn_bwd(dY_d, Xrows, Gt, U, A, tabs["group_offset"], tabs["group_expert"],
+                                             tabs["group_dw_slot"], *W_d, None, None, None, err_flag=err, E=cfg.E,
+                                             flags=rl.BWD_DEFER_WGRAD, workspace=ws)
+        kept.append(dict(dYrows=dY_d, Xrows=Xrows, A=A, bwd_workspace=ws, inst_ptr=tabs["inst_ptr"],
+                         inst_group=tabs["inst_group"], group_offset=tabs["group_offset"]))
+        dX_full = rl.relibra_moe_ffn_bwd(dY_d, Xrows, Gt, U, A, tabs["group_offset"], tabs["group_expert"],
+                                         tabs["group_dw_slot"], *W_d, *dW_mb, err_flag=err,
+                                         flags=rl.BWD_ACCUMULATE if mb else 0)
+        assert torch.equal(dX_deferred, dX_full)                 # the data gradients do not depend on the flag
+        _, dWg_o, dWu_o, dWd_o = oracle.ffn_bwd(Xrows.cpu(), dY, p["group_offset"][mb], p["group_expert"][mb], Wg, Wu, Wd)
+        for acc, o in zip(dW_ref, (dWg_o, dWu_o, dWd_o)):
+            acc += o
+    dW_b = [torch.full((cfg.E, *s), 3.0, dtype=torch.float32, device=DEV) for s in shapes]
+    rl.relibra_moe_ffn_wgrad_batched(kept, cfg.E, *dW_b, err_flag=err)
+    assert err.item() == 0
+    for got, want, per_mb in zip(dW_b, dW_ref, dW_mb):
+        assert rel_l2(got, want) <= TOL
+        assert rel_l2(got, per_mb[:cfg.E].double().cpu().numpy()) <= 1e-5
+    once = [w.clone() for w in dW_b]
+    rl.relibra_moe_ffn_wgrad_batched(kept, cfg.E, *dW_b, accumulate=True, err_flag=err)
+    for got, one in zip(dW_b, once):
+        assert torch.allclose(got, 2 * one, rtol=1e-6, atol=0)
+    # a corrupted table is skipped and flagged, never dereferenced
+    bad = dict(kept[1])
+    bad["inst_group"] = kept[1]["inst_group"].clone()
+    bad["inst_group"][0] = cfg.G + 5
+    err2 = rl.relibra_moe_ffn_wgrad_batched([kept[0], bad, kept[2]], cfg.E, *dW_b)
+    assert err2.item() == rl.ERR_GROUP_TABLE
