@@ -564,6 +564,7 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
 // rows e received, instance by instance, micro-batch by micro-batch, in registers, and writes
 // dW once.  Per-micro-batch device pointers travel as a kernel argument.
 constexpr int kMaxWgradMb = RELIBRA_MAX_WGRAD_MB;
+constexpr int kWgradChunk = 64;
 struct MbTable {
     const bf16_t *dY[kMaxWgradMb], *X[kMaxWgradMb], *A[kMaxWgradMb], *dGt[kMaxWgradMb], *dU[kMaxWgradMb];
     const int32_t *iptr[kMaxWgradMb], *igrp[kMaxWgradMb], *goff[kMaxWgradMb];
@@ -591,8 +592,7 @@ __device__ __forceinline__ bool inst_rows(const MbTable &tb, int mb, int p, int 
 }
 
 // One block: rows per expert over the batch, and the experts in descending order of rows
-// (ties: lower id).  XCD x then serves the experts ranked x, x+8, ...: heaviest first, and the
-// eight L2s get near-equal work.
+// (ties: lower id): the weight-gradient tiles are scheduled heaviest first.
 __global__ void __launch_bounds__(256)
 wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
                    int32_t *__restrict__ exp_rows, int32_t *__restrict__ exp_order, int32_t *err_flag)
@@ -635,16 +635,21 @@ wgrad_batched_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;
-    const int t = blockIdx.x >> 3;
-    const int rank = (blockIdx.x & 7) + 8 * (t / per_expert);
-    if (rank >= E) return;
+    // Tile list: experts in descending order of rows, each expert's tiles in band order, cut into
+    // chunks of kWgradChunk tiles (an 8 x 8 patch sharing operand tiles).  The chunks are dealt to
+    // the XCDs back and forth (0..7, 7..0, ...), so every L2 gets near-equal work, heaviest first.
+    const int x = blockIdx.x & 7, t = blockIdx.x >> 3;
+    const int q = t / kWgradChunk;
+    const long long tile = ((long long)q * 8 + ((q & 1) ? 7 - x : x)) * kWgradChunk + t % kWgradChunk;
+    if (tile >= (long long)E * per_expert) return;
+    const int rank = (int)(tile / per_expert);
     const int e = exp_order[rank];
     if ((unsigned)e >= (unsigned)E) return;
     const bool add = accumulate != 0;
     if (exp_rows[e] == 0 && add) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int mt, nt;
-    band_order(t % per_expert, n_mt, n_nt, mt, nt);
+    band_order((int)(tile % per_expert), n_mt, n_nt, mt, nt);
     const int m0 = mt * BA, n0 = nt * WGN;
     typename KL::Acc acc;
     KL::zero(acc);
@@ -889,13 +894,16 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_ORDER, stream, wgrad_order_kernel<<<1, 256, E * sizeof(int32_t), stream>>>(
         tb, n_mb, G, inst_cap, n_rows, E, exp_rows, exp_order, err_flag));
     RELIBRA_HIP_TRY(launch_check());
-    const long long per_xcd = (E + 7) / 8;
-    const long long t_down = per_xcd * ((h + 255) / 256) * ((hff + WGN - 1) / WGN);       // dWd: m in h, n in h'
-    const long long t_gu = per_xcd * ((hff + 127) / 128) * ((h + WGN - 1) / WGN);         // dWg, dWu: m in h', n in h
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1><<<(unsigned)(8 * t_down), THREADS, WgradCfg<256>::LDS, stream>>>(
+    auto grid_of = [&](long long tiles_per_expert) {          // blocks: 8 XCDs x chunks per XCD x tiles per chunk
+        const long long chunks = ((long long)E * tiles_per_expert + kWgradChunk - 1) / kWgradChunk;
+        return (unsigned)(8 * ((chunks + 7) / 8) * kWgradChunk);
+    };
+    const unsigned g_down = grid_of((long long)((h + 255) / 256) * ((hff + WGN - 1) / WGN));      // dWd: m in h, n in h'
+    const unsigned g_gu = grid_of((long long)((hff + 127) / 128) * ((h + WGN - 1) / WGN));        // dWg, dWu: m in h', n in h
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1><<<g_down, THREADS, WgradCfg<256>::LDS, stream>>>(
         tb, n_mb, G, inst_cap, n_rows, E, h, hff, exp_rows, exp_order, accumulate, dWd, nullptr));
     RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2><<<(unsigned)(8 * t_gu), THREADS, WgradCfg<256>::LDS, stream>>>(
+    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2><<<g_gu, THREADS, WgradCfg<256>::LDS, stream>>>(
         tb, n_mb, G, inst_cap, n_rows, E, hff, h, exp_rows, exp_order, accumulate, dWg, dWu));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
