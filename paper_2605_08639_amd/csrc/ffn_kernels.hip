@@ -591,43 +591,122 @@ __device__ __forceinline__ bool inst_rows(const MbTable &tb, int mb, int p, int 
     return true;
 }
 
-// One block: rows per expert over the batch, and the experts in descending order of rows
-// (ties: lower id): the weight-gradient tiles are scheduled heaviest first.
-__global__ void __launch_bounds__(256)
-wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
-                   int32_t *__restrict__ exp_rows, int32_t *__restrict__ exp_order, int32_t *err_flag)
+// Workspace of the batched weight gradients.
+struct WgradPlan {
+    int32_t *exp_rows;     // [E] rows of the expert over the whole batch
+    int32_t *exp_slabs;    // [E] k-loop slabs: sum over its pieces of ceil(rows / BK)
+    int32_t *exp_order;    // [E] experts in descending order of rows (ties: lower id)
+    int32_t *piece_ptr;    // [E+1] CSR over experts into the piece arrays
+    int32_t *piece_mb, *piece_row0, *piece_rows;   // [S] micro-batch, first row, rows (> 0) of a piece
+};
+inline size_t wgrad_plan_ints(int E, int G) { return 4 * (size_t)E + 1 + 3 * (size_t)kMaxWgradMb * ((size_t)E + G); }
+inline WgradPlan carve_wgrad(void *ws, int E, int G)
 {
-    extern __shared__ int32_t rows_of[];
+    WgradPlan w;
+    int32_t *p = (int32_t *)ws;
+    const size_t S = (size_t)kMaxWgradMb * ((size_t)E + G);
+    w.exp_rows = p; p += E;
+    w.exp_slabs = p; p += E;
+    w.exp_order = p; p += E;
+    w.piece_ptr = p; p += E + 1;
+    w.piece_mb = p; p += S;
+    w.piece_row0 = p; p += S;
+    w.piece_rows = p;
+    return w;
+}
+
+// One block.  Lists, per expert, the pieces of its contraction: every instance with rows, micro-
+// batch by micro-batch in the order of the plan's instance table (entries out of range are left
+// out and flagged), and ranks the experts by rows so that the tiles run heaviest first.
+__global__ void __launch_bounds__(256)
+wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E, WgradPlan w, int32_t *err_flag)
+{
+    extern __shared__ int32_t rows_of[];       // [E]
+    __shared__ int32_t scan[256];
+    __shared__ int32_t carry;
+    const int tid = threadIdx.x;
     bool bad = false;
-    for (int e = threadIdx.x; e < E; e += 256) {
-        long long total = 0;
-        for (int mb = 0; mb < n_mb; ++mb) {
-            int p0, p1;
-            if (!inst_range(tb, mb, e, inst_cap, p0, p1)) bad = true;
-            for (int p = p0; p < p1; ++p) {
-                int row0, rows;
-                if (!inst_rows(tb, mb, p, G, n_rows, row0, rows)) bad = true;
-                total += rows;
+    if (tid == 0) { carry = 0; w.piece_ptr[0] = 0; }
+    __syncthreads();
+    for (int base = 0; base < E; base += 256) {
+        const int e = base + tid;
+        int pieces = 0;
+        if (e < E) {
+            long long total = 0, slabs = 0;
+            for (int mb = 0; mb < n_mb; ++mb) {
+                int p0, p1;
+                if (!inst_range(tb, mb, e, inst_cap, p0, p1)) bad = true;
+                for (int p = p0; p < p1; ++p) {
+                    int row0, rows;
+                    if (!inst_rows(tb, mb, p, G, n_rows, row0, rows)) bad = true;
+                    if (rows > 0) { ++pieces; total += rows; slabs += (rows + BK - 1) / BK; }
+                }
+            }
+            rows_of[e] = (int32_t)(total > 0x7fffffffLL ? 0x7fffffffLL : total);
+            w.exp_rows[e] = rows_of[e];
+            w.exp_slabs[e] = (int32_t)(slabs > 0x7fffffffLL ? 0x7fffffffLL : slabs);
+        }
+        scan[tid] = pieces;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int v = tid >= off ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        if (e < E) {
+            int at = carry + scan[tid] - pieces;
+            w.piece_ptr[e + 1] = carry + scan[tid];
+            for (int mb = 0; mb < n_mb; ++mb) {
+                int p0, p1;
+                inst_range(tb, mb, e, inst_cap, p0, p1);
+                for (int p = p0; p < p1; ++p) {
+                    int row0, rows;
+                    inst_rows(tb, mb, p, G, n_rows, row0, rows);
+                    if (rows > 0) { w.piece_mb[at] = mb; w.piece_row0[at] = row0; w.piece_rows[at] = rows; ++at; }
+                }
             }
         }
-        rows_of[e] = (int32_t)(total > 0x7fffffffLL ? 0x7fffffffLL : total);
-        exp_rows[e] = rows_of[e];
+        __syncthreads();
+        if (tid == 255) carry += scan[255];
+        __syncthreads();
     }
     if (bad) atomicOr(err_flag, RELIBRA_ERR_GROUP_TABLE);
     __syncthreads();
-    for (int e = threadIdx.x; e < E; e += 256) {
+    for (int e = tid; e < E; e += 256) {
         const int mine = rows_of[e];
         int rank = 0;
         for (int o = 0; o < E; ++o) rank += (rows_of[o] > mine || (rows_of[o] == mine && o < e)) ? 1 : 0;
-        exp_order[rank] = e;
+        w.exp_order[rank] = e;
     }
 }
 
-// NA = 1: dWd (L = dY, R = A).  NA = 2: dWg, dWu (L = dGt, dU; R = X).
+// The pieces of one expert's contraction as the k-loop sees them.
+template <int NA>
+struct WgradPieces {
+    const MbTable &tb;
+    const int32_t *mb, *row0, *rows;       // this expert's slice of the piece arrays
+    int m_dim, n_dim, m0, n0;
+    __device__ __forceinline__ int valid(int i) const { return rows[i]; }
+    __device__ __forceinline__ void piece(int i, Operand (&A)[1][NA], Operand (&B)[1][1], int &k_valid) const
+    {
+        const int b = mb[i], r0 = row0[i];
+        k_valid = rows[i];
+        if (NA == 1) {      // dWd: L = dY, R = A
+            A[0][0] = {tb.dY[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
+            B[0][0] = {tb.A[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
+        } else {            // dWg, dWu: L = dGt, dU; R = X
+            A[0][0] = {tb.dGt[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
+            A[0][NA - 1] = {tb.dU[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
+            B[0][0] = {tb.X[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
+        }
+    }
+};
+
+// NA = 1: dWd.  NA = 2: dWg, dWu.
 template <int NA>
 __global__ void __launch_bounds__(THREADS, WgradCfg<256>::OCC)
-wgrad_batched_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E, int m_dim, int n_dim,
-                     const int32_t *__restrict__ exp_rows, const int32_t *__restrict__ exp_order, int accumulate,
+wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int accumulate,
                      float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int WGM = 256, BA = WGM / NA;
@@ -642,38 +721,19 @@ wgrad_batched_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int 
     const int q = t / kWgradChunk;
     const long long tile = ((long long)q * 8 + ((q & 1) ? 7 - x : x)) * kWgradChunk + t % kWgradChunk;
     if (tile >= (long long)E * per_expert) return;
-    const int rank = (int)(tile / per_expert);
-    const int e = exp_order[rank];
+    const int e = w.exp_order[tile / per_expert];
     if ((unsigned)e >= (unsigned)E) return;
     const bool add = accumulate != 0;
-    if (exp_rows[e] == 0 && add) return;
+    if (w.exp_rows[e] == 0 && add) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int mt, nt;
     band_order((int)(tile % per_expert), n_mt, n_nt, mt, nt);
     const int m0 = mt * BA, n0 = nt * WGN;
     typename KL::Acc acc;
     KL::zero(acc);
-    for (int mb = 0; mb < n_mb; ++mb) {
-        int p0, p1;
-        inst_range(tb, mb, e, inst_cap, p0, p1);
-        for (int p = p0; p < p1; ++p) {
-            int row0, rows;
-            inst_rows(tb, mb, p, G, n_rows, row0, rows);
-            if (rows == 0) continue;
-            Operand A[1][NA], B[1][1];
-            if (NA == 1) {
-                A[0][0] = {tb.dY[mb] + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
-                B[0][0] = {tb.A[mb] + (size_t)row0 * n_dim, n_dim, n0, n_dim - 1};
-            } else {
-                A[0][0] = {tb.dGt[mb] + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
-                A[0][NA - 1] = {tb.dU[mb] + (size_t)row0 * m_dim, m_dim, m0, m_dim - 1};
-                B[0][0] = {tb.X[mb] + (size_t)row0 * n_dim, n_dim, n0, n_dim - 1};
-            }
-            // The loop's last barrier leaves no wave reading operand data from LDS, so the next
-            // instance's first loads may overwrite the ring at once.
-            KL::run(acc, A, B, (rows + BK - 1) / BK, rows, lds, tid);
-        }
-    }
+    const int s0 = w.piece_ptr[e];
+    const WgradPieces<NA> src{tb, w.piece_mb + s0, w.piece_row0 + s0, w.piece_rows + s0, m_dim, n_dim, m0, n0};
+    KL::run_pieces(acc, src, w.piece_ptr[e + 1] - s0, w.exp_slabs[e], lds, tid);
     wgrad_epilogue<KL, NA, BA>(acc, lds, out0, out1, (size_t)e * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
 }
 
@@ -720,7 +780,7 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     case RELIBRA_WS_PERMUTE: return round256((size_t)((N + 511) / 512 + 4) * E * sizeof(int32_t));
     case RELIBRA_WS_FFN_FWD: return ffn_ws_bytes(N, G, hff, false);
     case RELIBRA_WS_FFN_BWD: return ffn_ws_bytes(N, G, hff, true);
-    case RELIBRA_WS_WGRAD_BATCHED: return round256((size_t)(2 * E + 8) * sizeof(int32_t));
+    case RELIBRA_WS_WGRAD_BATCHED: return round256(wgrad_plan_ints(E, G) * sizeof(int32_t));
     default: return 0;
     }
     (void)h;
@@ -890,9 +950,10 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
         tb.goff[mb] = m.group_offset_dev;
     }
     if (int rc = ensure_lds_limits()) return rc;
-    int32_t *exp_rows = (int32_t *)ws, *exp_order = exp_rows + E;
+    if (inst_cap > E + G) return RELIBRA_EINVAL;               // an instance is a group: at most G of them
+    const WgradPlan w = carve_wgrad(ws, E, G);
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_ORDER, stream, wgrad_order_kernel<<<1, 256, E * sizeof(int32_t), stream>>>(
-        tb, n_mb, G, inst_cap, n_rows, E, exp_rows, exp_order, err_flag));
+        tb, n_mb, G, inst_cap, n_rows, E, w, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     auto grid_of = [&](long long tiles_per_expert) {          // blocks: 8 XCDs x chunks per XCD x tiles per chunk
         const long long chunks = ((long long)E * tiles_per_expert + kWgradChunk - 1) / kWgradChunk;
@@ -901,10 +962,10 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
     const unsigned g_down = grid_of((long long)((h + 255) / 256) * ((hff + WGN - 1) / WGN));      // dWd: m in h, n in h'
     const unsigned g_gu = grid_of((long long)((hff + 127) / 128) * ((h + WGN - 1) / WGN));        // dWg, dWu: m in h', n in h
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1><<<g_down, THREADS, WgradCfg<256>::LDS, stream>>>(
-        tb, n_mb, G, inst_cap, n_rows, E, h, hff, exp_rows, exp_order, accumulate, dWd, nullptr));
+        tb, E, h, hff, w, accumulate, dWd, nullptr));
     RELIBRA_HIP_TRY(launch_check());
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2><<<g_gu, THREADS, WgradCfg<256>::LDS, stream>>>(
-        tb, n_mb, G, inst_cap, n_rows, E, hff, h, exp_rows, exp_order, accumulate, dWg, dWu));
+        tb, E, hff, h, w, accumulate, dWg, dWu));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }

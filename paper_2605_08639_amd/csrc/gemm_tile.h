@@ -289,6 +289,81 @@ struct KLoop {
         }
     }
 
+    // The same loop over a list of pieces of the contraction (single phase, ragged pieces): piece i
+    // has its own operands and length; a slab never spans two pieces (a piece's last slab is
+    // masked), and the ring keeps running across piece boundaries, so that short pieces do not
+    // pay a pipeline fill and drain each.  src.piece(i, A, B, k_valid) describes piece i
+    // (k_valid >= 1); n_pieces and total_slabs = sum of ceil(k_valid / DEPTH) come from the caller.
+    template <class Src>
+    static __device__ __forceinline__ void run_pieces(Acc &acc, const Src &src, int n_pieces, int total_slabs, char *lds, int tid)
+    {
+        static_assert(NPH == 1 && RAGGED_K, "pieces: one phase, ragged contraction");
+        const int lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int wa = wave / WB, wb = wave % WB;
+        const int n = total_slabs;
+        if (n <= 0 || n_pieces <= 0) return;
+        // cursor of the loads (runs STAGES slabs ahead) and cursor of the MFMAs
+        Operand Ai[1][NA], Bi[1][NB];
+        int ip = 0, it = 0, i_valid = 0, i_slabs = 0;
+        src.piece(0, Ai, Bi, i_valid);
+        i_slabs = (i_valid + DEPTH - 1) / DEPTH;
+        int ct = 0, c_valid = i_valid, c_slabs = i_slabs, cp = 0;
+        auto issue_next = [&](char *stage) {
+            issue(stage, Ai, Bi, it, i_slabs, i_valid - 1, wave, lane);
+            if (++it == i_slabs && ip + 1 < n_pieces) {
+                ++ip;
+                it = 0;
+                src.piece(ip, Ai, Bi, i_valid);
+                i_slabs = (i_valid + DEPTH - 1) / DEPTH;
+            }
+        };
+        Frags f[2];
+#pragma unroll
+        for (int i = 0; i < STAGES; ++i)
+            if (i < n) issue_next(lds + i * STAGE_BYTES);
+        wait_younger(n - 1);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f[0], lds, 0, wa, wb, lane);
+        int slot = 0;
+        for (int t = 0; t < n; ++t) {
+            char *cur = lds + slot * STAGE_BYTES;
+            slot = (slot == STAGES - 1) ? 0 : slot + 1;
+            char *nxt = lds + slot * STAGE_BYTES;
+            const bool tail = (ct + 1) * DEPTH > c_valid;
+            const int kf = ct * DEPTH + (lane >> 5) * 8;
+#pragma unroll
+            for (int s = 0; s < KSTEPS - 1; ++s) {
+                __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                if (tail) mask_frags(f[s & 1], kf + s * 16, c_valid);
+                mfma_all(acc, f[s & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_younger(n - t - 2);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + STAGES < n) issue_next(cur);
+            constexpr int L = (KSTEPS - 1) & 1;
+            if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, c_valid);
+            mfma_range<0, N_MFMA / 2>(acc, f[L]);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(f[0], nxt, 0, wa, wb, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_range<N_MFMA / 2, N_MFMA>(acc, f[L]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (++ct == c_slabs && cp + 1 < n_pieces) {      // the MFMAs move on to the next piece
+                ++cp;
+                ct = 0;
+                c_valid = src.valid(cp);
+                c_slabs = (c_valid + DEPTH - 1) / DEPTH;
+            }
+        }
+    }
+
     // Wait until at most min(younger, STAGES-2) slabs' worth of this wave's loads are outstanding,
     // and until its LDS reads have returned.
     static __device__ __forceinline__ void wait_younger(int younger)
