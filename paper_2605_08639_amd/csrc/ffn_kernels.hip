@@ -17,6 +17,10 @@
 //
 // Block index -> tile: consecutive tiles (same rows, next column block) are given to the same
 // XCD (blockIdx % 8), so that operand tiles shared by neighbouring tiles are served by one L2.
+//
+// Weight gradients exist in two forms: per micro-batch (read-add-write of fp32 dW, replica slots
+// summed into the home slot) and once per batch over every resident micro-batch, contracted in
+// registers (wgrad_batched_kernel), which avoids the dW traffic that dominates short groups.
 #include "gemm_tile.h"
 
 #include <type_traits>
