@@ -153,3 +153,24 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
         print(f"[{cfg.name}] dW slices of expert {e} ({len(rws)} rows, {len(groups)} instances) ok", flush=True)
     for e in zero[:2].tolist():                                          # experts nobody routed to: exact zeros
         assert (dWg[e] == 0).all() and (dWu[e] == 0).all() and (dWd[e] == 0).all()
+
+    # ---- the batched weight gradients at the same size: the micro-batch listed twice must give twice the
+    # per-micro-batch result (whose slices were checked against the oracle above), all elements
+    ws = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, N, 1, E, G, h, hff), dtype=torch.uint8, device=DEV)
+    dXrows2 = rl.relibra_moe_ffn_bwd(dY, Xrows, Gt, U, A, tabs["group_offset"], tabs["group_expert"], tabs["group_dw_slot"],
+                                     Wg_d, Wu_d, Wd_d, None, None, None, flags=rl.BWD_DEFER_WGRAD, workspace=ws,
+                                     err_flag=err, E=E)
+    assert torch.equal(dXrows2, dXrows)
+    one = dict(dYrows=dY, Xrows=Xrows, A=A, bwd_workspace=ws, inst_ptr=tabs["inst_ptr"], inst_group=tabs["inst_group"],
+               group_offset=tabs["group_offset"])
+    dWb = [torch.empty(s, dtype=torch.float32, device=DEV) for s in ((E, hff, h), (E, hff, h), (E, h, hff))]
+    rl.relibra_moe_ffn_wgrad_batched([one, one], E, *dWb, err_flag=err)
+    for name, got, full in zip(("dWg", "dWu", "dWd"), dWb, (dWg, dWu, dWd)):
+        num = den = 0.0
+        for e0 in range(0, E, 16):                        # in slabs of experts: no fp64 copy of a 15 GB tensor
+            w2 = 2.0 * full[:E][e0:e0 + 16].double()
+            num += torch.linalg.vector_norm(got[e0:e0 + 16].double() - w2).item() ** 2
+            den += torch.linalg.vector_norm(w2).item() ** 2
+        assert num ** 0.5 <= 1e-5 * den ** 0.5, (name, (num / max(den, 1e-300)) ** 0.5)
+    assert err.item() == 0
+    print(f"[{cfg.name}] batched weight gradients ok", flush=True)
