@@ -131,6 +131,19 @@ def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
                                  ctypes.c_size_t(0), z, z) == rl.EINVAL        # g_begin > g_end
     assert L.relibra_unpermute_combine(7, z, z, z, z, 4, 2, 128, z, z, z, z, z) == rl.EINVAL
     assert L.relibra_unpermute_combine(0, z, z, z, z, 4, 2, 100, z, z, z, z, z) == rl.EINVAL
+    # layer-shared replica buffer push
+    assert L.relibra_replica_push(z, z, z, z, 8, 4, 2, 128, 256, 0, z, z) == rl.EINVAL      # no workgroups
+    assert L.relibra_replica_push(z, z, z, z, 8, 4, 0, 128, 256, 4, z, z) == rl.OK          # r = 0: nothing to push
+    assert L.relibra_replica_push(z, z, z, z, 8, 4, 2, 128, 256, 4, z, z) == rl.EINVAL      # null tensors
+    # batched weight gradients
+    one = (rl.WgradMb * 1)()
+    f = ctypes.c_void_p(0)
+    assert L.relibra_moe_ffn_wgrad_batched(one, 0, 16, 12, 10, 8, 128, 256, f, f, f, 0, z, ctypes.c_size_t(0), z, z) == rl.EINVAL
+    assert L.relibra_moe_ffn_wgrad_batched(one, rl.MAX_WGRAD_MB + 1, 16, 12, 10, 8, 128, 256, f, f, f, 0, z,
+                                           ctypes.c_size_t(0), z, z) == rl.EINVAL
+    assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 100, 256, f, f, f, 0, z, ctypes.c_size_t(0), z, z) == rl.EUNSUPPORTED
+    assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 128, 256, f, f, f, 0, z, ctypes.c_size_t(0), z, z) == rl.EINVAL  # null dW
+    assert rl.workspace_bytes(rl.WS_WGRAD_BATCHED, 0, 1, 8, 12, 128, 256) > 0
 
 
 # ------------------------------------------------------------------ communication-aware model, Algorithm 1
