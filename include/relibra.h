@@ -128,6 +128,17 @@ int relibra_plan_placed(const int32_t *counts_host, int n_mb, int E, int k, int 
                         int64_t *max_load_before, int64_t *max_load_after);
 
 /*
+ * Imbalance diagnostics of Section 2.2, from the per-micro-batch histograms (all pointers HOST):
+ *   skewness[mb]     = largest expert load / mean expert load of the micro-batch (1 when empty)
+ *   intersection[mb] = |H_mb ∩ H_mb+1| / top, H = the `top` highest-load experts (ties: lower id),
+ *                      for mb = 0 .. n_mb-2 (may be NULL when n_mb == 1)
+ * For several layers pass their histograms one after the other (relibra_route_hist takes
+ * ids of [layers * n_mb, T, k] in one launch) and read the ratios within each layer's block.
+ */
+int relibra_load_stats(const int32_t *counts_host, int n_mb, int E, int top,
+                       double *skewness, double *intersection);
+
+/*
  * Cost model of the MoE module on a rail-optimised cluster (Section 4.1).  A token on source
  * rank j routed to an expert on rank g is a local copy (j == g), crosses the intra-node link
  * (same node), RDMA on the same rail (other node, same index inside the node) or both

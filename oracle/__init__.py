@@ -154,6 +154,16 @@ def permute(ids, E, inst_ptr, inst_rows, inst_group, group_offset):
     return row_of, src_of
 
 
+def load_stats(counts, top=8):
+    """-> (skewness [n_mb], intersection ratio of adjacent micro-batches' top hot sets [n_mb-1])."""
+    counts = _i32(counts)
+    n_mb, E = counts.shape
+    skew = np.empty(n_mb, np.float64)
+    inter = np.empty(max(n_mb - 1, 0), np.float64)
+    lib().oracle_load_stats(_p(counts), n_mb, E, int(top), _p(skew), _p(inter))
+    return skew, inter
+
+
 # ------------------------------------------------------------------ communication-aware model, Algorithm 1
 def cost_model(h, hff, F, B_intra, B_inter, bytes_per_value=2):
     """[seconds per token of computation (Eq. 4), per token over the intra-node link, over RDMA (Eq. 5)]."""

@@ -161,6 +161,33 @@ void oracle_reorder(const i64 *l, int E, int EP, int32_t *rank_of)
 }
 
 /* ------------------------------------------------------------------------- */
+/* Imbalance diagnostics (Section 2.2): load skewness of a micro-batch = largest */
+/* expert load over the mean expert load; intersection ratio of the `top`        */
+/* highest-load experts (ties: lower id) between adjacent micro-batches.         */
+void oracle_load_stats(const int32_t *counts, int n_mb, int E, int top, double *skew, double *inter)
+{
+    uint8_t *hot = (uint8_t *)calloc((size_t)n_mb * E, 1);
+    for (int mb = 0; mb < n_mb; ++mb) {
+        const int32_t *c = counts + (size_t)mb * E;
+        i64 sum = 0, peak = 0;
+        for (int e = 0; e < E; ++e) { sum += c[e]; if (c[e] > peak) peak = c[e]; }
+        skew[mb] = sum > 0 ? (double)peak / ((double)sum / E) : 1.0;
+        for (int pick = 0; pick < top; ++pick) {          /* selection: largest not yet taken, lowest id on ties */
+            int best = -1;
+            for (int e = 0; e < E; ++e)
+                if (!hot[(size_t)mb * E + e] && (best < 0 || c[e] > c[best])) best = e;
+            hot[(size_t)mb * E + best] = 1;
+        }
+    }
+    for (int mb = 0; mb + 1 < n_mb; ++mb) {
+        int both = 0;
+        for (int e = 0; e < E; ++e) both += hot[(size_t)mb * E + e] && hot[(size_t)(mb + 1) * E + e];
+        inter[mb] = (double)both / top;
+    }
+    free(hot);
+}
+
+/* ------------------------------------------------------------------------- */
 /* Communication-aware cost model of the MoE module (Section 4.1, Eq. 1-6)    */
 /* and Algorithm 1 as printed (swap-based simulated annealing, Section 4.2).  */
 

@@ -23,7 +23,7 @@ BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD = 1, 2,
 MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
-EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa",
+EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
            "relibra_permute", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_unpermute_combine", "relibra_replica_push",
            "relibra_workspace_bytes",
@@ -142,6 +142,17 @@ def relibra_plan(counts_host, k, EP, ranks_per_node, r, expert_rank=None):
         rc = lib().relibra_plan_placed(_hp(counts_host), n_mb, E, k, EP, ranks_per_node, r, _hp(expert_rank), *tail)
         _check("relibra_plan_placed", rc)
     return out
+
+
+def relibra_load_stats(counts_host, top=8):
+    """counts [n_mb,E] int32 (host) -> (skewness [n_mb], intersection ratio of the top hot sets [n_mb-1])."""
+    counts_host = np.ascontiguousarray(counts_host, dtype=np.int32)
+    n_mb, E = counts_host.shape
+    skew = np.empty(n_mb, np.float64)
+    inter = np.empty(max(n_mb - 1, 0), np.float64)
+    rc = lib().relibra_load_stats(_hp(counts_host), n_mb, E, int(top), _hp(skew), _hp(inter) if n_mb > 1 else C.c_void_p(0))
+    _check("relibra_load_stats", rc)
+    return skew, inter
 
 
 class CostModel(C.Structure):

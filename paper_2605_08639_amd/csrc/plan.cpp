@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <iterator>
 #include <numeric>
 #include <thread>
 #include <vector>
@@ -428,4 +429,34 @@ extern "C" int relibra_plan_placed(const int32_t *counts, int n_mb, int E, int k
     if (!expert_rank) return RELIBRA_EINVAL;
     return plan_impl(counts, n_mb, E, k, EP, rpn, r, expert_rank, expert_to_slot, replica_expert, inst_ptr, inst_rank,
                      inst_rows, inst_group, group_expert, group_offset, group_dw_slot, max_load_before, max_load_after);
+}
+
+// Imbalance diagnostics of Section 2.2.
+extern "C" int relibra_load_stats(const int32_t *counts, int n_mb, int E, int top,
+                                  double *skewness, double *intersection)
+{
+    if (!counts || !skewness || n_mb < 1 || E < 1 || top < 1 || top > E) return RELIBRA_EINVAL;
+    if (n_mb > 1 && !intersection) return RELIBRA_EINVAL;
+    std::vector<std::vector<int>> hot(n_mb);
+    for (int mb = 0; mb < n_mb; ++mb) {
+        const int32_t *c = counts + (size_t)mb * E;
+        i64 sum = 0, peak = 0;
+        for (int e = 0; e < E; ++e) {
+            if (c[e] < 0) return RELIBRA_ERANGE;
+            sum += c[e];
+            peak = std::max<i64>(peak, c[e]);
+        }
+        skewness[mb] = sum > 0 ? (double)peak * E / (double)sum : 1.0;
+        std::vector<int> order(E);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return c[a] > c[b]; });   // ties: lower id
+        hot[mb].assign(order.begin(), order.begin() + top);
+        std::sort(hot[mb].begin(), hot[mb].end());
+    }
+    for (int mb = 0; mb + 1 < n_mb; ++mb) {
+        std::vector<int> both;
+        std::set_intersection(hot[mb].begin(), hot[mb].end(), hot[mb + 1].begin(), hot[mb + 1].end(), std::back_inserter(both));
+        intersection[mb] = (double)both.size() / top;
+    }
+    return RELIBRA_OK;
 }

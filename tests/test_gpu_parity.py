@@ -69,6 +69,20 @@ def test_per_source_histogram_bit_exact():
         assert np.array_equal(got[mb], oracle.route_hist_src(ids[mb], cfg.E, cfg.EP))
 
 
+def test_histograms_of_several_layers_in_one_launch():
+    """Replayed routing of every layer is known before training (Section 3): the histograms of
+    [layers, n_mb] micro-batches come from one launch over ids of [layers * n_mb, T, k]."""
+    layers = 3
+    cfgs = [wl.small_config(T=640, k=4, E=64, EP=8, n_mb=4, index=90 + l) for l in range(layers)]
+    ids = np.concatenate([routing(c)[0] for c in cfgs])                    # [layers * n_mb, T, k]
+    got = rl.relibra_route_hist(torch.from_numpy(ids).to(DEV), 64).cpu().numpy().reshape(layers, 4, 64)
+    for l, c in enumerate(cfgs):
+        assert np.array_equal(got[l], oracle.route_hist(routing(c)[0], 64)[0])
+    skew, inter = rl.relibra_load_stats(got[0], top=8)
+    s_or, i_or = oracle.load_stats(got[0], top=8)
+    assert np.allclose(skew, s_or, rtol=1e-14, atol=0) and np.array_equal(inter, i_or)
+
+
 # ------------------------------------------------------------------ plan + permute
 def plan_both(cfg, counts):
     want = oracle.plan(counts, cfg.EP, cfg.rpn, cfg.r)

@@ -233,3 +233,15 @@ def test_comm_model_argument_errors():
         rl.relibra_moe_time(x, rank + 3, m)
     with pytest.raises(rl.RelibraError):
         rl.relibra_moe_time(x, rank, rl.cost_model(4, 3, 64, 64, 1e12, 1e11, 1e10))
+
+
+def test_load_stats_equal_oracle():
+    for idx in (0, 1, 4):
+        cfg = wl.CONFIGS[idx]
+        counts = _counts(cfg)
+        for top in (1, 4, min(8, cfg.E)):
+            s_lib, i_lib = rl.relibra_load_stats(counts, top)
+            s_or, i_or = oracle.load_stats(counts, top)
+            assert np.allclose(s_lib, s_or, rtol=1e-14, atol=0) and np.array_equal(i_lib, i_or)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_load_stats(np.ones((2, 4), np.int32), top=5)

@@ -469,3 +469,23 @@ def test_replica_push_is_an_indexed_block_copy():
     assert np.array_equal(got, want)
     assert np.array_equal(got[E + 1], W[E + 1]) and np.array_equal(got[:E], W[:E])
     assert not np.array_equal(got[E + 0], W[E + 0])
+
+
+def test_load_stats_against_numpy_definitions():
+    """Section 2.2: skewness = max / mean expert load; intersection ratio |H_t ∩ H_t+1| / top."""
+    rng = np.random.default_rng(9)
+    counts = rng.integers(0, 500, size=(6, 32)).astype(np.int32)
+    counts[3] = 0                                      # an empty micro-batch
+    counts[4, :8] = 100                                # ties: lower ids are the hot set
+    counts[4, 8:] = 100
+    skew, inter = oracle.load_stats(counts, top=4)
+    for mb in range(6):
+        c = counts[mb].astype(np.float64)
+        assert skew[mb] == pytest.approx(c.max() / c.mean() if c.sum() else 1.0, rel=1e-14)
+    hot = [set(np.argsort(-counts[mb], kind="stable")[:4].tolist()) for mb in range(6)]
+    assert hot[4] == {0, 1, 2, 3}
+    for mb in range(5):
+        assert inter[mb] == len(hot[mb] & hot[mb + 1]) / 4
+    uniform = np.full((2, 8), 7, np.int32)
+    s2, i2 = oracle.load_stats(uniform, top=8)
+    assert np.all(s2 == 1.0) and np.all(i2 == 1.0)
