@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--wgrad", choices=("batched", "per-mb"), default="batched",
                     help="weight gradients once per batch over all resident micro-batches (default), or "
                          "accumulated into dW micro-batch by micro-batch")
+    ap.add_argument("--plain-bwd-weights", action="store_true",
+                    help="data gradients read the forward pass's weight layout (default: transposed copies, "
+                         "made once per step inside the timed region)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -95,6 +98,10 @@ def main():
                 for _ in range(n_keep)]
     ws_wgrad = torch.empty(rl.workspace_bytes(rl.WS_WGRAD_BATCHED, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
     Xrows, dYrows, A, ws_ffn = Xrows_k[0], dYrows_k[0], A_k[0], ws_ffn_k[0]
+    transposed = not args.plain_bwd_weights
+    WgT = torch.empty((E, h, hff), dtype=torch.bfloat16, device=dev) if transposed else None
+    WuT = torch.empty_like(WgT) if transposed else None
+    WdT = torch.empty((E, hff, h), dtype=torch.bfloat16, device=dev) if transposed else None
     TABLES = ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert", "group_dw_slot")
 
     def upload(plan):
@@ -113,9 +120,11 @@ def main():
         rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
                                      out_rows=dYr, dgate=dgate, err_flag=err)
         flags = rl.BWD_DEFER_WGRAD if batched else (0 if first else rl.BWD_ACCUMULATE)
+        bw = (WgT, WuT, WdT) if transposed else (Wg, Wu, Wd)
         rl.relibra_moe_ffn_bwd(dYr, Xr, Gt, U, Ar, tabs["group_offset"][mb], tabs["group_expert"][mb],
-                               tabs["group_dw_slot"][mb], Wg, Wu, Wd, dWg, dWu, dWd,
-                               flags=flags, dXrows=dXrows, workspace=ws, err_flag=err)
+                               tabs["group_dw_slot"][mb], *bw, dWg, dWu, dWd, E=E,
+                               flags=flags | (rl.BWD_TRANSPOSED_WEIGHTS if transposed else 0), dXrows=dXrows,
+                               workspace=ws, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, out_tok=dX, err_flag=err)
 
     def weight_gradients(tabs):
@@ -133,6 +142,10 @@ def main():
         plan = rl.relibra_plan(counts_h, k, EP, cfg.rpn, r)
         plan_ms.append((time.perf_counter() - tp) * 1e3)
         tabs = upload(plan)
+        if transposed:                                          # the parameters of this step, in the backward layout
+            rl.relibra_transpose_experts(Wg, WgT)
+            rl.relibra_transpose_experts(Wu, WuT)
+            rl.relibra_transpose_experts(Wd, WdT)
         for mb in range(n_mb):
             layer(mb, tabs, first=(mb == 0))
         if batched:

@@ -59,8 +59,11 @@ enum {
     RELIBRA_BWD_NO_REPLICA_SUM = 2, /* leave replica-slot dW where it is (partial group range) */
     RELIBRA_BWD_REPLICA_WEIGHTS = 4, /* a group reads its parameters from slot group_dw_slot[g] of
                                        Wg/Wu/Wd [n_dw_slots, ...] (filled by relibra_replica_push) */
-    RELIBRA_BWD_DEFER_WGRAD = 8     /* data gradients only: dW untouched; dGt, dU stay in the
+    RELIBRA_BWD_DEFER_WGRAD = 8,    /* data gradients only: dW untouched; dGt, dU stay in the
                                        workspace for relibra_moe_ffn_wgrad_batched */
+    RELIBRA_BWD_TRANSPOSED_WEIGHTS = 16 /* Wg, Wu are given as [., h, hff] and Wd as [., hff, h]:
+                                       transposed copies (relibra_transpose_experts), which put the
+                                       data gradients' contraction index contiguous in memory */
 };
 
 /* modes of relibra_unpermute_combine */
@@ -255,6 +258,19 @@ int relibra_moe_ffn_bwd(const void *dYrows_dev, const void *Xrows_dev,
                         int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * Transposed copy of per-expert matrices: out[e][j][i] = in[e][i][j], bf16, e < n_blocks.
+ * The data gradients of the FFN contract over the index that is strided in the forward pass's
+ * weight layout; given transposed copies (RELIBRA_BWD_TRANSPOSED_WEIGHTS) they read their weight
+ * operand through the same, faster path as the forward pass.  Parameters change once per
+ * optimizer step, so the copies are made once per step (2x the weights' bytes of traffic) and
+ * serve every micro-batch; 288 GB of HBM hold both layouts.
+ *   in_dev [n_blocks, rows, cols], out_dev [n_blocks, cols, rows] bf16, dev; must not overlap.
+ * Limits: rows % 8 == 0, cols % 8 == 0, n_blocks <= 65535, 16-byte aligned.
+ */
+int relibra_transpose_experts(const void *in_dev, int n_blocks, int rows, int cols, void *out_dev,
+                              relibra_stream stream);
+
+/*
  * Weight gradients of a whole training batch in one pass (the gradient accumulation over
  * micro-batches of Section 2.1, done in registers instead of in memory).  The per-micro-batch
  * form adds each micro-batch's contribution into fp32 dW in HBM: 24 h h' bytes of traffic per
@@ -344,7 +360,7 @@ enum {
     RELIBRA_K_GATHER, RELIBRA_K_COMBINE_FWD, RELIBRA_K_COMBINE_BWD, RELIBRA_K_COMBINE_SUM, RELIBRA_K_SCHED,
     RELIBRA_K_FWD_GATE_UP, RELIBRA_K_FWD_DOWN, RELIBRA_K_BWD_ACT, RELIBRA_K_BWD_DX,
     RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_REPLICA_PUSH,
-    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_COUNT
+    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_TRANSPOSE, RELIBRA_K_COUNT
 };
 int relibra_prof_start(int level, int max_records);
 int relibra_prof_stop(double *ms_by_kernel_host, int64_t *launches_by_kernel_host);

@@ -19,19 +19,19 @@ LIB_PATH = os.path.join(_HERE, "librelibra.so")
 OK, EINVAL, ERANGE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
 WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD, WS_WGRAD_BATCHED = 0, 1, 2, 3
-BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD = 1, 2, 4, 8
+BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD, BWD_TRANSPOSED_WEIGHTS = 1, 2, 4, 8, 16
 MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
            "relibra_permute", "relibra_moe_ffn_fwd",
-           "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_unpermute_combine", "relibra_replica_push",
+           "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push",
            "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
 
 KERNELS = ("fill", "hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
            "combine_sum", "sched", "fwd_gate_up", "fwd_down", "bwd_act", "bwd_dx", "wgrad_down",
-           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order")
+           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order", "transpose")
 
 _lib = None
 
@@ -266,7 +266,7 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
     """-> dXrows [n_rows,h] bf16; dWg, dWu [slots,h',h] and dWd [slots,h,h'] fp32 are written in place.
     E = number of home experts (default Wg.shape[0]; pass it when the weights carry replica slots)."""
     n_rows, h = Xrows.shape
-    hff = Wg.shape[1]
+    hff = Wg.shape[2] if flags & BWD_TRANSPOSED_WEIGHTS else Wg.shape[1]
     E = Wg.shape[0] if E is None else int(E)
     if flags & BWD_REPLICA_WEIGHTS and dWg is not None:
         assert Wg.shape[0] >= dWg.shape[0] and Wu.shape[0] >= dWg.shape[0] and Wd.shape[0] >= dWg.shape[0]
@@ -295,6 +295,17 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
                                    _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_moe_ffn_bwd", rc)
     return dXrows
+
+
+def relibra_transpose_experts(W, out=None):
+    """W [n, a, b] bf16 (device) -> out [n, b, a] with out[e] = W[e].T."""
+    n, a, b = W.shape
+    if out is None:
+        out = torch.empty((n, b, a), dtype=torch.bfloat16, device=W.device)
+    assert out.shape == (n, b, a)
+    rc = lib().relibra_transpose_experts(_dp(W, torch.bfloat16), n, a, b, _dp(out, torch.bfloat16), _stream())
+    _check("relibra_transpose_experts", rc)
+    return out
 
 
 class WgradMb(C.Structure):

@@ -442,6 +442,10 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
 
 // ---------------------------------------------------------------- backward
 // dA = dY Wd, then dGt = dA * U * silu'(Gt), dU = dA * silu(Gt).
+// WT = false: Wd as the forward pass holds it, [h][h'], contraction index strided (transposing
+// LDS reads).  WT = true: a transposed copy [h'][h], contraction index contiguous (the faster
+// operand path; see relibra_transpose_experts).
+template <bool WT>
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
                const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles,
@@ -450,12 +454,15 @@ bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict_
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, 256, w_from_slot != 0);
     if (!t.valid) return;
-    const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n]
-    if (t.rows > BM / 2) row_gemm_body<BM, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
-    else row_gemm_body<BM / 2, true, 1, 1>(t, dY, nullptr, h, W, nullptr, hff, hff, h, s.dGt, s.dU, Gt, U, lds);
+    const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n], or at [n*h + k]
+    const int ldw = WT ? h : hff;
+    if (t.rows > BM / 2) row_gemm_body<BM, !WT, 1, 1>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds);
+    else row_gemm_body<BM / 2, !WT, 1, 1>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds);
 }
 
 // dX = dGt Wg + dU Wu (one accumulator, the contraction runs over both products).
+// WT as above: Wg, Wu [h'][h] as the forward pass holds them, or transposed copies [h][h'].
+template <bool WT>
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff,
               int n_col_tiles, int w_from_slot, bf16_t *__restrict__ dX)
@@ -463,9 +470,38 @@ bwd_dx_kernel(Sched s, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, 256, w_from_slot != 0);
     if (!t.valid) return;
-    const size_t wofs = (size_t)t.expert * hff * h;         // (n in h, k in h') at [k*h + n]
-    if (t.rows > BM / 2) row_gemm_body<BM, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
-    else row_gemm_body<BM / 2, true, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, h, h, hff, dX, nullptr, nullptr, nullptr, lds);
+    const size_t wofs = (size_t)t.expert * hff * h;         // (n in h, k in h') at [k*h + n], or at [n*h' + k]
+    const int ldw = WT ? hff : h;
+    if (t.rows > BM / 2) row_gemm_body<BM, !WT, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, ldw, h, hff, dX, nullptr, nullptr, nullptr, lds);
+    else row_gemm_body<BM / 2, !WT, 2, 0>(t, s.dGt, s.dU, hff, Wg + wofs, Wu + wofs, ldw, h, hff, dX, nullptr, nullptr, nullptr, lds);
+}
+
+// Transposed copy of per-expert matrices, out[e][j][i] = in[e][i][j]: 64 x 64 tiles through LDS,
+// 16-byte accesses on both sides.
+__global__ void __launch_bounds__(256)
+transpose_experts_kernel(const bf16_t *__restrict__ in, int rows, int cols, bf16_t *__restrict__ out)
+{
+    __shared__ bf16_t tile[64][64 + 8];
+    const size_t base = (size_t)blockIdx.z * rows * cols;
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = (tid >> 3) + i * 32, c = (tid & 7) * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r0 + r < rows && c0 + c < cols) v = *reinterpret_cast<const uint4 *>(in + base + (size_t)(r0 + r) * cols + c0 + c);
+        *reinterpret_cast<uint4 *>(&tile[r][c]) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = (tid >> 3) + i * 32, r = (tid & 7) * 8;        // output row c0 + c, output columns r0 + r ..
+        if (c0 + c < cols && r0 + r < rows) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = (uint32_t)tile[r + 2 * j][c] | ((uint32_t)tile[r + 2 * j + 1][c] << 16);
+            *reinterpret_cast<uint4 *>(out + base + (size_t)(c0 + c) * rows + r0 + r) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
 }
 
 // Weight-gradient epilogue.  The accumulators hold, per lane, one column n and 16 rows m of each
@@ -797,8 +833,10 @@ static int ensure_lds_limits()
     if (done) return RELIBRA_OK;
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
@@ -882,12 +920,21 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     const int accumulate = (flags & RELIBRA_BWD_ACCUMULATE) ? 1 : 0;
     const int w_from_slot = (flags & RELIBRA_BWD_REPLICA_WEIGHTS) ? 1 : 0;
     if (n_rows > 0) {
-        RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
-            s, (const bf16_t *)dYrows, (const bf16_t *)Wd, (const bf16_t *)Gt_save, (const bf16_t *)U_save,
-            h, hff, ct_ff, w_from_slot));
-        RELIBRA_HIP_TRY(launch_check());
-        RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<<<grid8(R * ct_h), THREADS, kLdsBytes, stream>>>(
-            s, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows));
+        const bf16_t *wd = (const bf16_t *)Wd, *wg = (const bf16_t *)Wg, *wu = (const bf16_t *)Wu;
+        const bf16_t *dy = (const bf16_t *)dYrows, *gt = (const bf16_t *)Gt_save, *us = (const bf16_t *)U_save;
+        if (flags & RELIBRA_BWD_TRANSPOSED_WEIGHTS) {
+            RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<true><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
+                s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot));
+            RELIBRA_HIP_TRY(launch_check());
+            RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<true><<<grid8(R * ct_h), THREADS, kLdsBytes, stream>>>(
+                s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows));
+        } else {
+            RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<false><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
+                s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot));
+            RELIBRA_HIP_TRY(launch_check());
+            RELIBRA_LAUNCH(RELIBRA_K_BWD_DX, stream, bwd_dx_kernel<false><<<grid8(R * ct_h), THREADS, kLdsBytes, stream>>>(
+                s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows));
+        }
         RELIBRA_HIP_TRY(launch_check());
     }
     if (defer) return RELIBRA_OK;                                  // dGt, dU stay in the workspace
@@ -970,6 +1017,21 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
     RELIBRA_HIP_TRY(launch_check());
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2><<<g_gu, THREADS, WgradCfg<256>::LDS, stream>>>(
         tb, E, hff, h, w, accumulate, dWg, dWu));
+    RELIBRA_HIP_TRY(launch_check());
+    return RELIBRA_OK;
+}
+
+extern "C" int relibra_transpose_experts(const void *in_dev, int n_blocks, int rows, int cols, void *out_dev,
+                                         relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (n_blocks < 0 || rows < 8 || cols < 8 || rows % 8 || cols % 8 || n_blocks > 65535) return RELIBRA_EINVAL;
+    if (n_blocks == 0) return RELIBRA_OK;
+    if (!in_dev || !out_dev || in_dev == out_dev || !aligned16(in_dev) || !aligned16(out_dev)) return RELIBRA_EINVAL;
+    if ((rows + 63) / 64 > 65535) return RELIBRA_EUNSUPPORTED;
+    const dim3 grid((cols + 63) / 64, (rows + 63) / 64, n_blocks);
+    RELIBRA_LAUNCH(RELIBRA_K_TRANSPOSE, stream, transpose_experts_kernel<<<grid, 256, 0, stream>>>(
+        (const bf16_t *)in_dev, rows, cols, (bf16_t *)out_dev));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }

@@ -463,3 +463,40 @@ def test_batched_weight_gradients_match_oracle_and_per_microbatch_path():
     bad["inst_group"][0] = cfg.G + 5
     err2 = rl.relibra_moe_ffn_wgrad_batched([kept[0], bad, kept[2]], cfg.E, *dW_b)
     assert err2.item() == rl.ERR_GROUP_TABLE
+
+
+# ------------------------------------------------------------------ transposed weights for the data gradients
+@pytest.mark.parametrize("n,a,b", [(3, 64, 64), (2, 192, 256), (5, 72, 136), (1, 8, 8)])
+def test_transpose_experts_is_exact(n, a, b):
+    W = torch.randn((n, a, b), generator=torch.Generator().manual_seed(a + b)).to(torch.bfloat16).to(DEV)
+    got = rl.relibra_transpose_experts(W)
+    assert torch.equal(got, W.transpose(1, 2).contiguous())
+
+
+@pytest.mark.parametrize("case", [FFN_CASES[0], FFN_CASES[3], FFN_CASES[4]])
+def test_backward_with_transposed_weights_matches_oracle_and_the_plain_layout(case):
+    """The data gradients read their weights from transposed copies: same mathematics, so the
+    result must meet the oracle's bar and agree with the plain-layout kernels."""
+    go, ge, X, dY, Wg, Wu, Wd = ffn_case(**case)
+    E = case["E"]
+    slots, n_slots = dw_slots(ge, E)
+    dev = lambda a: a.to(DEV)
+    Xd, dYd, W_d = dev(X), dev(dY), [dev(W) for W in (Wg, Wu, Wd)]
+    W_t = [rl.relibra_transpose_experts(W) for W in W_d]
+    go_d, ge_d, sl_d = dev_i32(go), dev_i32(ge), dev_i32(slots)
+    err = rl.new_err_flag()
+    Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xd, go_d, ge_d, *W_d, err_flag=err)
+    outs = []
+    for W3, flags in ((W_d, 0), (W_t, rl.BWD_TRANSPOSED_WEIGHTS)):
+        dW = [torch.zeros((n_slots, *s), dtype=torch.float32, device=DEV)
+              for s in ((case["hff"], case["h"]), (case["hff"], case["h"]), (case["h"], case["hff"]))]
+        dX = rl.relibra_moe_ffn_bwd(dYd, Xd, Gt, U, A, go_d, ge_d, sl_d, *W3, *dW, flags=flags, err_flag=err, E=E)
+        outs.append((dX, *dW))
+    assert err.item() == 0
+    live = np.concatenate([np.arange(go[g], go[g + 1]) for g in range(len(ge)) if ge[g] >= 0 and go[g + 1] > go[g]])
+    lv = torch.from_numpy(live).to(DEV)
+    assert rel_l2(outs[1][0][lv], outs[0][0][lv].double().cpu().numpy()) <= 1e-6      # data gradients: same sums
+    for a_, b_ in zip(outs[0][1:], outs[1][1:]):
+        assert torch.equal(a_, b_)                                                    # weight gradients do not read W
+    dX_o, _, _, _ = oracle.ffn_bwd(X, dY, go, ge, Wg, Wu, Wd)
+    assert rel_l2(outs[1][0][lv], dX_o[live]) <= TOL
