@@ -81,43 +81,75 @@ Cost cost_of(const std::vector<i64> &L)
     return c;
 }
 
-Cost swap_descent(const std::vector<i64> &load_of, int EP, std::vector<int> &where)
+// Steepest descent over pair swaps: in every step the swap with the smallest resulting
+// (peak, sum of squares), ties to the smallest (a, b), applied while it lowers the cost.
+// A swap of a (rank p) and b (rank q) moves d = l_b - l_a tokens from q to p: the sum of squares
+// changes by 2 d (L_p - L_q + d), so candidates are compared by (new peak, that change).  Over
+// all integer d the change is at least -floor((L_p - L_q)^2 / 4): a pair of ranks that cannot
+// lower the peak and whose bound cannot reach the best change found so far is skipped whole,
+// which leaves a handful of rank pairs to enumerate once the loads are nearly level.
+// D = the integer type of the change: 64 bits when the loads are small enough, else 128.
+template <class D>
+Cost swap_descent_t(const std::vector<i64> &load_of, int EP, std::vector<int> &where)
 {
     const int E = (int)load_of.size();
     std::vector<i64> L(EP, 0);
     for (int e = 0; e < E; ++e) L[where[e]] += load_of[e];
-    Cost cur = cost_of(L);
+    std::vector<std::vector<int>> on(EP);
+    for (int e = 0; e < E; ++e) on[where[e]].push_back(e);
+    struct RankPair { int p, q; i64 gap; };
+    std::vector<RankPair> pairs;
     Top3 top;
     for (;;) {
+        const Cost cur = cost_of(L);
         top.build(L);
+        pairs.clear();
+        for (int p = 0; p < EP; ++p)
+            for (int q = p + 1; q < EP; ++q) pairs.push_back({p, q, L[p] > L[q] ? L[p] - L[q] : L[q] - L[p]});
+        std::stable_sort(pairs.begin(), pairs.end(), [](const RankPair &x, const RankPair &y) { return x.gap > y.gap; });
         bool have = false;
-        Cost best{0, 0};
+        i64 best_peak = 0;
+        D best_delta = 0;
         int pa = -1, pb = -1;
-        for (int a = 0; a < E; ++a) {
-            const int ga = where[a];
-            const i64 la = load_of[a], La = L[ga];
-            for (int b = a + 1; b < E; ++b) {
-                const int gb = where[b];
-                if (gb == ga) continue;
-                const i64 d = load_of[b] - la;            // rank ga gains d, rank gb loses d
-                const i64 na = La + d, nb = L[gb] - d;
-                Cost c;
-                c.peak = std::max(std::max(na, nb), top.max_excluding(ga, gb));
-                c.sq = cur.sq - (u128)La * (u128)La - (u128)L[gb] * (u128)L[gb]
-                     + (u128)na * (u128)na + (u128)nb * (u128)nb;
-                if (!have || c < best) { have = true; best = c; pa = a; pb = b; }
+        for (const RankPair &rp : pairs) {
+            const bool touches_peak = L[rp.p] == cur.peak || L[rp.q] == cur.peak;
+            if (have && !touches_peak) {
+                if (best_peak < cur.peak) continue;                          // cannot lower the peak, the best one does
+                const D bound = -((D)(rp.gap / 2) * (D)(rp.gap - rp.gap / 2));
+                if (bound > best_delta) continue;                            // cannot reach the best change
             }
+            const i64 rest = top.max_excluding(rp.p, rp.q);
+            for (int x : on[rp.p])
+                for (int y : on[rp.q]) {
+                    const int a = x < y ? x : y, b = x < y ? y : x;
+                    const int ga = x < y ? rp.p : rp.q, gb = x < y ? rp.q : rp.p;
+                    const i64 d = load_of[b] - load_of[a];                  // rank ga gains d, rank gb loses d
+                    const i64 peak = std::max(std::max(L[ga] + d, L[gb] - d), rest);
+                    if (have && peak > best_peak) continue;
+                    const D delta = (D)d * (D)(L[ga] - L[gb] + d);           // half the change of the sum of squares
+                    const bool better = !have || peak < best_peak || delta < best_delta ||
+                                        (delta == best_delta && (a < pa || (a == pa && b < pb)));
+                    if (better) { have = true; best_peak = peak; best_delta = delta; pa = a; pb = b; }
+                }
         }
-        if (!have || !(best < cur)) break;
+        if (!have || !(best_peak < cur.peak || (best_peak == cur.peak && best_delta < 0))) return cur;
         const int ga = where[pa], gb = where[pb];
         const i64 d = load_of[pb] - load_of[pa];
         L[ga] += d;
         L[gb] -= d;
         where[pa] = gb;
         where[pb] = ga;
-        cur = best;
+        std::replace(on[ga].begin(), on[ga].end(), pa, pb);
+        std::replace(on[gb].begin(), on[gb].end(), pb, pa);
     }
-    return cur;
+}
+
+Cost swap_descent(const std::vector<i64> &load_of, int EP, std::vector<int> &where)
+{
+    i64 total = 0;
+    for (i64 x : load_of) total += x;
+    if (total < ((i64)1 << 30)) return swap_descent_t<i64>(load_of, EP, where);
+    return swap_descent_t<__int128>(load_of, EP, where);
 }
 
 // ---------------------------------------------------------------- stage 2
@@ -332,8 +364,10 @@ static int plan_impl(const int32_t *counts, int n_mb, int E, int k, int EP, int 
     } else {
         // stage 1: descent from the unplanned layout and from LPT; ties keep the unplanned one
         std::vector<int> from_id = unplanned, from_lpt = lpt_start(batch_load, EP);
-        const Cost c_id = swap_descent(batch_load, EP, from_id);
+        Cost c_id{0, 0};
+        std::thread other([&]() { c_id = swap_descent(batch_load, EP, from_id); });     // the two starts are independent
         const Cost c_lpt = swap_descent(batch_load, EP, from_lpt);
+        other.join();
         const std::vector<int> &reordered = (c_lpt < c_id) ? from_lpt : from_id;
         // stage 2 under both placements; the reordering must pay for itself over the batch
         chosen = unplanned;
