@@ -138,14 +138,14 @@ def main():
     def step():
         rl.relibra_route_hist(ids_all, E, counts=counts_d, err_flag=err)
         counts_h = counts_d.cpu().numpy()                       # the path's one device->host crossing
+        if transposed:          # this step's parameters in the backward layout: the GPU copies while the host plans
+            rl.relibra_transpose_experts(Wg, WgT)
+            rl.relibra_transpose_experts(Wu, WuT)
+            rl.relibra_transpose_experts(Wd, WdT)
         tp = time.perf_counter()
         plan = rl.relibra_plan(counts_h, k, EP, cfg.rpn, r)
         plan_ms.append((time.perf_counter() - tp) * 1e3)
         tabs = upload(plan)
-        if transposed:                                          # the parameters of this step, in the backward layout
-            rl.relibra_transpose_experts(Wg, WgT)
-            rl.relibra_transpose_experts(Wu, WuT)
-            rl.relibra_transpose_experts(Wd, WdT)
         for mb in range(n_mb):
             layer(mb, tabs, first=(mb == 0))
         if batched:
