@@ -1,5 +1,5 @@
 // Building blocks of the grouped bf16 MFMA GEMMs (gfx950): LDS operand tiles filled by
-// direct global->LDS loads, MFMA fragment reads, and a three-slab pipelined k-loop.
+// direct global->LDS loads, MFMA fragment reads, and a k-loop pipelined over a ring of LDS slabs.
 //
 // An operand tile covers ROWS rows of the non-contracted index and BKT (32 or 64) values of the
 // contracted index k.  Two memory situations:
@@ -154,6 +154,8 @@ __device__ __forceinline__ bf16x8_t mask_frag(bf16x8_t f, int k_first, int k_val
 //   meets the other waves: slab t+1 is complete and nobody reads slab t any more,
 //   so it issues the loads of slab t+STAGES into slab t's place, runs half of the step's MFMAs,
 //   requests the first fragments of slab t+1 and runs the other half, which covers them.
+// DBG switches parts of the loop off for timing experiments (1: no loads after the prologue,
+// 2: loads only, 3: no loads and no barrier); the library always builds DBG = 0.
 template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0>
 struct KLoop {
     static constexpr int NW = WA * WB;
