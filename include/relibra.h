@@ -232,6 +232,26 @@ int relibra_moe_ffn_fwd(const void *Xrows_dev, int n_rows,
                         int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * The permutation's row gather fused into the GEMMs that read the gathered rows (instead of
+ * materialising Xrows with relibra_permute and reading it back).  relibra_row_tokens turns the
+ * permutation's src_of into the token of every row, row_tok[row] = src_of[row] / k (entries
+ * outside [0, T*k) become token 0 and raise RELIBRA_ERR_PLAN_COVER).  relibra_moe_ffn_fwd_gather
+ * is relibra_moe_ffn_fwd reading row `row` of its input as X[row_tok[row]]: X [T, h] bf16 is the
+ * token tensor, row_tok [n_rows] int32; values are clamped into [0, T).  Results are identical to
+ * the two-step form bit for bit.  (The batched weight gradients take the same pair, see
+ * relibra_wgrad_mb.)
+ */
+int relibra_row_tokens(const int32_t *src_of_dev, int N, int k, int T, int32_t *row_tok_dev,
+                       int32_t *err_flag_dev, relibra_stream stream);
+int relibra_moe_ffn_fwd_gather(const void *X_dev, int T, const int32_t *row_tok_dev, int n_rows,
+                               const int32_t *group_offset_dev, const int32_t *group_expert_dev,
+                               int G, int g_begin, int g_end, int E,
+                               const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
+                               void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Yrows_dev,
+                               void *workspace_dev, size_t workspace_bytes,
+                               int32_t *err_flag_dev, relibra_stream stream);
+
+/*
  * Expert FFN backward over groups [g_begin, g_end).  With dy the upstream gradient of a row:
  *   dA = Wd_e^T dy;  dGt = dA * U * silu'(Gt);  dU = dA * silu(Gt);  dx = Wg_e^T dGt + Wu_e^T dU
  *   dWd += dy A^T;   dWg += dGt x^T;   dWu += dU x^T          (contraction over the group's rows)
@@ -360,7 +380,7 @@ enum {
     RELIBRA_K_GATHER, RELIBRA_K_COMBINE_FWD, RELIBRA_K_COMBINE_BWD, RELIBRA_K_COMBINE_SUM, RELIBRA_K_SCHED,
     RELIBRA_K_FWD_GATE_UP, RELIBRA_K_FWD_DOWN, RELIBRA_K_BWD_ACT, RELIBRA_K_BWD_DX,
     RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_REPLICA_PUSH,
-    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_TRANSPOSE, RELIBRA_K_COUNT
+    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_TRANSPOSE, RELIBRA_K_ROW_TOKENS, RELIBRA_K_COUNT
 };
 int relibra_prof_start(int level, int max_records);
 int relibra_prof_stop(double *ms_by_kernel_host, int64_t *launches_by_kernel_host);

@@ -24,14 +24,14 @@ MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
-           "relibra_permute", "relibra_moe_ffn_fwd",
+           "relibra_permute", "relibra_row_tokens", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push",
            "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
 
 KERNELS = ("fill", "hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
            "combine_sum", "sched", "fwd_gate_up", "fwd_down", "bwd_act", "bwd_dx", "wgrad_down",
-           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order", "transpose")
+           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order", "transpose", "row_tokens")
 
 _lib = None
 
@@ -257,6 +257,45 @@ def relibra_moe_ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0
                                    h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows),
                                    _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_moe_ffn_fwd", rc)
+    return Gt, U, A, Yrows
+
+
+def relibra_row_tokens(src_of, k, T, row_tok=None, err_flag=None):
+    """src_of [N] int32 (device, from relibra_permute) -> row_tok [N] int32: the token of every row."""
+    N = src_of.shape[0]
+    if row_tok is None:
+        row_tok = torch.empty(N, dtype=torch.int32, device=src_of.device)
+    if err_flag is None:
+        err_flag = new_err_flag(src_of.device)
+    rc = lib().relibra_row_tokens(_dp(src_of, torch.int32), N, int(k), int(T), _dp(row_tok, torch.int32), _dp(err_flag), _stream())
+    _check("relibra_row_tokens", rc)
+    return row_tok
+
+
+def relibra_moe_ffn_fwd_gather(X, row_tok, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
+                               Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None):
+    """relibra_moe_ffn_fwd with the row gather fused in: X [T,h] token tensor, row_tok [n_rows]."""
+    T, h = X.shape
+    n_rows = row_tok.shape[0]
+    E, hff = Wg.shape[0], Wg.shape[1]
+    G = group_expert.shape[0]
+    g_end = G if g_end is None else g_end
+    dev = X.device
+    mk = lambda cols: torch.empty((n_rows, cols), dtype=torch.bfloat16, device=dev)
+    Gt = mk(hff) if Gt is None else Gt
+    U = mk(hff) if U is None else U
+    A = mk(hff) if A is None else A
+    Yrows = mk(h) if Yrows is None else Yrows
+    if workspace is None:
+        workspace = torch.empty(max(workspace_bytes(WS_FFN_FWD, max(n_rows, 1), 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_moe_ffn_fwd_gather(_dp(X, torch.bfloat16), T, _dp(row_tok, torch.int32), n_rows,
+                                          _dp(group_offset, torch.int32), _dp(group_expert, torch.int32), G, g_begin, g_end, E,
+                                          _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
+                                          h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows),
+                                          _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
+    _check("relibra_moe_ffn_fwd_gather", rc)
     return Gt, U, A, Yrows
 
 

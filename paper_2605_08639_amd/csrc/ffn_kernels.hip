@@ -292,14 +292,16 @@ template <int BB> struct Waves { static constexpr int B = BB / 64, A = NWAVES / 
 // ---------------------------------------------------------------- forward
 // Gt = X Wg^T, U = X Wu^T (one pass over X), A = silu(Gt) * U.   Column tile: 128 of h'.
 template <int BB>
-__device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t *X, const bf16_t *Wg, const bf16_t *Wu,
+__device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t *X, const int32_t *row_tok, int tok_last,
+                                                 const bf16_t *Wg, const bf16_t *Wu,
                                                  int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout, char *lds)
 {
     using KL = KLoop<KcTile<128>, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false, NSTAGES>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t wofs = (size_t)t.expert * hff * h;
     const Operand A[1][2] = {{{Wg + wofs, h, t.col0, hff - 1}, {Wu + wofs, h, t.col0, hff - 1}}};
-    const Operand B[1][1] = {{{X, h, t.row0, t.row0 + t.rows - 1}}};
+    // rows of the group: a gathered copy (row_tok == nullptr), or token rows fetched through row_tok
+    const Operand B[1][1] = {{{X, h, t.row0, t.row0 + t.rows - 1, row_tok, tok_last}}};
     typename KL::Acc acc;
     KL::zero(acc);
     KL::run(acc, A, B, h / BK, h, lds, tid);
@@ -334,15 +336,15 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
 }
 
 __global__ void __launch_bounds__(THREADS, 2)
-fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wg,
-                   const bf16_t *__restrict__ Wu, int h, int hff, int n_col_tiles,
+fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const int32_t *__restrict__ row_tok, int tok_last,
+                   const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff, int n_col_tiles,
                    bf16_t *__restrict__ Gt, bf16_t *__restrict__ U, bf16_t *__restrict__ Aout)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, 128);
     if (!t.valid) return;
-    if (t.rows > BM / 2) fwd_gate_up_body<BM>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
-    else fwd_gate_up_body<BM / 2>(t, X, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    if (t.rows > BM / 2) fwd_gate_up_body<BM>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    else fwd_gate_up_body<BM / 2>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
 }
 
 // Shared body of the three single-accumulator row-tiled GEMMs.  EPI: 0 = store bf16 (Y, dX);
@@ -849,7 +851,8 @@ static int ensure_lds_limits()
 
 static inline unsigned grid8(long long tiles) { return (unsigned)((tiles + 7) / 8 * 8); }
 
-extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
+// Xrows: the group-ordered rows, or (row_tok != nullptr) the token tensor [T, h] they are gathered from.
+static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_rows,
                                    const int32_t *group_offset, const int32_t *group_expert,
                                    int G, int g_begin, int g_end, int E,
                                    const void *Wg, const void *Wu, const void *Wd, int h, int hff,
@@ -875,13 +878,36 @@ extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
     const long long R = max_row_tiles(n_rows, Gr);
     const int ct1 = (hff + 127) / 128, ct2 = (h + 255) / 256;
     RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<<<grid8(R * ct1), THREADS, kLdsBytes, stream>>>(
-        s, (const bf16_t *)Xrows, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
+        s, (const bf16_t *)Xrows, row_tok, T - 1, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
         (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save));
     RELIBRA_HIP_TRY(launch_check());
     RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<<<grid8(R * ct2), THREADS, kLdsBytes, stream>>>(
         s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
+}
+
+extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
+                                   const int32_t *group_offset, const int32_t *group_expert,
+                                   int G, int g_begin, int g_end, int E,
+                                   const void *Wg, const void *Wu, const void *Wd, int h, int hff,
+                                   void *Gt_save, void *U_save, void *A_save, void *Yrows,
+                                   void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+{
+    return ffn_fwd_impl(Xrows, nullptr, 1, n_rows, group_offset, group_expert, G, g_begin, g_end, E, Wg, Wu, Wd, h, hff,
+                        Gt_save, U_save, A_save, Yrows, ws, ws_bytes, err_flag, stream_);
+}
+
+extern "C" int relibra_moe_ffn_fwd_gather(const void *X, int T, const int32_t *row_tok, int n_rows,
+                                          const int32_t *group_offset, const int32_t *group_expert,
+                                          int G, int g_begin, int g_end, int E,
+                                          const void *Wg, const void *Wu, const void *Wd, int h, int hff,
+                                          void *Gt_save, void *U_save, void *A_save, void *Yrows,
+                                          void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+{
+    if (T < 1 || !row_tok) return RELIBRA_EINVAL;
+    return ffn_fwd_impl(X, row_tok, T, n_rows, group_offset, group_expert, G, g_begin, g_end, E, Wg, Wu, Wd, h, hff,
+                        Gt_save, U_save, A_save, Yrows, ws, ws_bytes, err_flag, stream_);
 }
 
 extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,

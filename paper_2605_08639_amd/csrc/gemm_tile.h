@@ -40,6 +40,11 @@ struct Operand {
     int ld;               // leading dimension in elements
     int row0;             // first row of the tile
     int row_last;         // last valid row; rows beyond are clamped onto valid ones (masked later)
+    // Row gather (optional): row r of the operand is row gather[r] of `base` (clamped into
+    // [0, gather_last]), so that rows of a token tensor are fetched in group order without a
+    // gathered copy.  KcTile: r = the tile row.  KsTile: r = the contraction index.
+    const int32_t *gather = nullptr;
+    int gather_last = 0;
 };
 
 // k-contiguous operand: LDS [row][BKT].
@@ -63,19 +68,34 @@ struct KcTile {
         return BKT == 32 ? (((r >> 1) & 3) ^ ((r >> 3) & 1)) : ((r & 7) ^ ((r >> 3) & 1));
     }
 
+    // Per-lane source addresses (at k = 0) of the load blocks this wave issues for every slab: they
+    // do not change along k, and a gathered row costs its index lookup once per tile.
     template <int NW>
-    static __device__ __forceinline__ void load(char *lds, const Operand &op, int k0, int /*k_last*/, int wave, int lane)
+    struct Lanes {
+        const bf16_t *p[BLOCKS / NW];
+    };
+    template <int NW>
+    static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int wave, int lane)
     {
         static_assert(BLOCKS % NW == 0, "rows must split evenly over the waves");
+        Lanes<NW> ln;
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i) {
             const int j = wave + i * NW;
             const int r = j * RPB + lane / PIECES;
             const int c = (lane % PIECES) ^ swz(r);
-            const int grow = min(op.row0 + r, op.row_last);
-            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)grow * op.ld + k0 + c * 8),
-                                             RELIBRA_LDS(lds + j * 1024), 16, 0, 0);
+            int grow = min(op.row0 + r, op.row_last);
+            if (op.gather) grow = min(max(op.gather[grow], 0), op.gather_last);
+            ln.p[i] = op.base + (size_t)grow * op.ld + c * 8;
         }
+        return ln;
+    }
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, int k0, int /*k_last*/, int wave, int /*lane*/)
+    {
+#pragma unroll
+        for (int i = 0; i < BLOCKS / NW; ++i)
+            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(ln.p[i] + k0), RELIBRA_LDS(lds + (wave + i * NW) * 1024), 16, 0, 0);
     }
 
     // fragment of rows r0..r0+31 (r0 % 32 == 0), k = kk*16 + (lane/32)*8 .. +7
@@ -101,9 +121,16 @@ struct KsTile {
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
 
     template <int NW>
-    static __device__ __forceinline__ void load(char *lds, const Operand &op, int k0, int k_last, int wave, int lane)
+    struct Lanes {
+        Operand op;
+    };
+    template <int NW>
+    static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int /*wave*/, int /*lane*/) { return Lanes<NW>{op}; }
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, int k0, int k_last, int wave, int lane)
     {
         static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
+        const Operand &op = ln.op;
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i) {
             const int j = wave + i * NW;
@@ -172,16 +199,39 @@ struct KLoop {
         bf16x8_t a[NA][TA], b[NB][TB];
     };
 
-    static __device__ __forceinline__ void issue(char *stage, const Operand (&A)[NPH][NA], const Operand (&B)[NPH][NB],
+    typedef typename AT::template Lanes<NW> LanesA;
+    typedef typename BT::template Lanes<NW> LanesB;
+
+    static __device__ __forceinline__ void prepare(LanesA (&PA)[NPH][NA], LanesB (&PB)[NPH][NB], const Operand (&A)[NPH][NA],
+                                                   const Operand (&B)[NPH][NB], int wave, int lane)
+    {
+#pragma unroll
+        for (int ph = 0; ph < NPH; ++ph) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) PA[ph][a] = AT::template prepare<NW>(A[ph][a], wave, lane);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) PB[ph][b] = BT::template prepare<NW>(B[ph][b], wave, lane);
+        }
+    }
+
+    static __device__ __forceinline__ void issue(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
                                                  int t, int steps_per_phase, int k_last, int wave, int lane)
     {
         const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
         const int k0 = (t - ph * steps_per_phase) * DEPTH;
+        if (NPH == 1 || ph == 0) {
 #pragma unroll
-        for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, A[ph][a], k0, k_last, wave, lane);
+            for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[0][a], k0, k_last, wave, lane);
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
-            BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, B[ph][b], k0, k_last, wave, lane);
+            for (int b = 0; b < NB; ++b)
+                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[0][b], k0, k_last, wave, lane);
+        } else {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[NPH - 1][a], k0, k_last, wave, lane);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[NPH - 1][b], k0, k_last, wave, lane);
+        }
     }
 
     static __device__ __forceinline__ void read_frags(Frags &f, const char *stage, int kk, int wa, int wb, int lane)
@@ -240,10 +290,13 @@ struct KLoop {
         const int n = steps_per_phase * NPH;
         const int k_last = k_valid - 1;
         if (n <= 0) return;
+        LanesA PA[NPH][NA];
+        LanesB PB[NPH][NB];
+        prepare(PA, PB, A, B, wave, lane);
         Frags f[2];
 #pragma unroll
         for (int i = 0; i < STAGES; ++i)
-            if (i < n) issue(lds + i * STAGE_BYTES, A, B, i, steps_per_phase, k_last, wave, lane);
+            if (i < n) issue(lds + i * STAGE_BYTES, PA, PB, i, steps_per_phase, k_last, wave, lane);
         wait_younger(n - 1);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
@@ -273,7 +326,7 @@ struct KLoop {
             wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
             if (DBG != 3) __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (t + STAGES < n && DBG != 1 && DBG != 3) issue(cur, A, B, t + STAGES, steps_per_phase, k_last, wave, lane);
+            if (t + STAGES < n && DBG != 1 && DBG != 3) issue(cur, PA, PB, t + STAGES, steps_per_phase, k_last, wave, lane);
             if (DBG != 2) {
                 // First half of the last step's MFMAs, then the requests for the next slab's first
                 // fragments (always issued: after the last slab they fetch stale LDS that nobody
@@ -307,16 +360,20 @@ struct KLoop {
         if (n <= 0 || n_pieces <= 0) return;
         // cursor of the loads (runs STAGES slabs ahead) and cursor of the MFMAs
         Operand Ai[1][NA], Bi[1][NB];
+        LanesA PA[1][NA];
+        LanesB PB[1][NB];
         int ip = 0, it = 0, i_valid = 0, i_slabs = 0;
         src.piece(0, Ai, Bi, i_valid);
+        prepare(PA, PB, Ai, Bi, wave, lane);
         i_slabs = (i_valid + DEPTH - 1) / DEPTH;
         int ct = 0, c_valid = i_valid, c_slabs = i_slabs, cp = 0;
         auto issue_next = [&](char *stage) {
-            issue(stage, Ai, Bi, it, i_slabs, i_valid - 1, wave, lane);
+            issue(stage, PA, PB, it, i_slabs, i_valid - 1, wave, lane);
             if (++it == i_slabs && ip + 1 < n_pieces) {
                 ++ip;
                 it = 0;
                 src.piece(ip, Ai, Bi, i_valid);
+                prepare(PA, PB, Ai, Bi, wave, lane);
                 i_slabs = (i_valid + DEPTH - 1) / DEPTH;
             }
         };

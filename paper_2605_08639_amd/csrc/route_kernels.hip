@@ -305,6 +305,21 @@ combine_bwd_kernel(const uint4 *__restrict__ Yrows, const uint4 *__restrict__ dO
     if (lane == 0) dgate[a] = dot;
 }
 
+// row -> token: row_tok[row] = src_of[row] / k (assignment a = t*k + s belongs to token t).
+__global__ void __launch_bounds__(256)
+row_tokens_kernel(const int32_t *__restrict__ src_of, int N, int k, int T, int32_t *__restrict__ row_tok,
+                  int32_t *__restrict__ err_flag)
+{
+    bool bad = false;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < N; i += gridDim.x * 256) {
+        const int a = src_of[i];
+        int t = 0;
+        if (a < 0 || a / k >= T) bad = true; else t = a / k;
+        row_tok[i] = t;
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_PLAN_COVER);
+}
+
 inline int grid_for(size_t work_items, int per_block, int cap)
 {
     size_t b = (work_items + per_block - 1) / per_block;
@@ -413,6 +428,19 @@ extern "C" int relibra_unpermute_combine(int mode, const void *rows_dev, const v
                                                                 T, k, N, vpr, (uint4 *)out_tok_dev, err_flag_dev));
         }
     }
+    RELIBRA_HIP_TRY(launch_check());
+    return RELIBRA_OK;
+}
+
+extern "C" int relibra_row_tokens(const int32_t *src_of_dev, int N, int k, int T, int32_t *row_tok_dev,
+                                  int32_t *err_flag_dev, relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (N < 0 || k < 1 || T < 1) return RELIBRA_EINVAL;
+    if (N == 0) return RELIBRA_OK;
+    if (!src_of_dev || !row_tok_dev || !err_flag_dev) return RELIBRA_EINVAL;
+    RELIBRA_LAUNCH(RELIBRA_K_ROW_TOKENS, stream, row_tokens_kernel<<<grid_for((size_t)N, 256, 1024), 256, 0, stream>>>(
+        src_of_dev, N, k, T, row_tok_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }

@@ -500,3 +500,36 @@ def test_backward_with_transposed_weights_matches_oracle_and_the_plain_layout(ca
         assert torch.equal(a_, b_)                                                    # weight gradients do not read W
     dX_o, _, _, _ = oracle.ffn_bwd(X, dY, go, ge, Wg, Wu, Wd)
     assert rel_l2(outs[1][0][lv], dX_o[live]) <= TOL
+
+
+# ------------------------------------------------------------------ row gather fused into the GEMMs
+def test_forward_with_fused_row_gather_is_bit_identical():
+    """relibra_moe_ffn_fwd_gather reads row `row` as X[row_tok[row]]: the same operands in the same
+    order as the two-step form (gather, then forward), so every output must match bit for bit;
+    row_tok itself is checked against the oracle's permutation."""
+    cfg = wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=2, h=256, hff=192)
+    ids, gates = routing(cfg)
+    counts = oracle.route_hist(ids, cfg.E)[0]
+    p = plan_both(cfg, counts)
+    Wg, Wu, Wd = [W.to(DEV) for W in wl.make_weights(cfg)]
+    for mb in range(cfg.n_mb):
+        X, _ = wl.make_tokens(cfg, mb)
+        Xd = X.to(DEV)
+        tabs = {key: dev_i32(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert")}
+        ids_d = torch.from_numpy(ids[mb]).to(DEV)
+        err = rl.new_err_flag()
+        row_of, src_of, Xrows = rl.relibra_permute(ids_d, tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                                   tabs["group_offset"], Xd, cfg.E, cfg.G, err_flag=err)
+        row_tok = rl.relibra_row_tokens(src_of, cfg.k, cfg.T, err_flag=err)
+        _, src_o = oracle.permute(ids[mb], cfg.E, p["inst_ptr"][mb], p["inst_rows"][mb], p["inst_group"][mb], p["group_offset"][mb])
+        assert np.array_equal(row_tok.cpu().numpy(), src_o // cfg.k)
+        two_step = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], Wg, Wu, Wd, err_flag=err)
+        fused = rl.relibra_moe_ffn_fwd_gather(Xd, row_tok, tabs["group_offset"], tabs["group_expert"], Wg, Wu, Wd, err_flag=err)
+        assert err.item() == 0
+        for a, b in zip(two_step, fused):
+            assert torch.equal(a, b)
+    bad = src_of.clone()
+    bad[3] = cfg.T * cfg.k + 7
+    err = rl.new_err_flag()
+    rt = rl.relibra_row_tokens(bad, cfg.k, cfg.T, err_flag=err)
+    assert err.item() == rl.ERR_PLAN_COVER and rt[3].item() == 0
