@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--wgrad", choices=("batched", "per-mb"), default="batched",
                     help="weight gradients once per batch over all resident micro-batches (default), or "
                          "accumulated into dW micro-batch by micro-batch")
+    ap.add_argument("--gathered-copy", action="store_true",
+                    help="materialise the group-ordered rows in the permutation (default with batched weight gradients: "
+                         "the GEMMs gather token rows themselves)")
     ap.add_argument("--plain-bwd-weights", action="store_true",
                     help="data gradients read the forward pass's weight layout (default: transposed copies, "
                          "made once per step inside the timed region)")
@@ -83,7 +86,9 @@ def main():
     batched = args.wgrad == "batched"
     assert not batched or n_mb <= rl.MAX_WGRAD_MB
     n_keep = n_mb if batched else 1          # batched weight gradients keep every micro-batch's rows resident
-    Xrows_k = [bf(N, h) for _ in range(n_keep)]
+    fused_gather = batched and not args.gathered_copy
+    Xrows_k = [bf(N, h) for _ in range(1 if fused_gather else n_keep)]
+    row_tok_k = [i32(N) for _ in range(n_keep)] if fused_gather else []
     dYrows_k = [bf(N, h) for _ in range(n_keep)]
     A_k = [bf(N, hff) for _ in range(n_keep)]
     Yrows, dXrows = bf(N, h), bf(N, h)
@@ -110,12 +115,22 @@ def main():
     def layer(mb, tabs, first):
         X, dOut = tok[mb]
         i = mb if batched else 0
-        Xr, dYr, Ar, ws = Xrows_k[i], dYrows_k[i], A_k[i], ws_ffn_k[i]
-        rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
-                           tabs["group_offset"][mb], X, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
-                           Xrows=Xr, workspace=ws_perm, err_flag=err)
-        rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
-                               Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err)
+        dYr, Ar, ws = dYrows_k[i], A_k[i], ws_ffn_k[i]
+        if fused_gather:                        # the GEMMs fetch token rows through row_tok: no gathered copy
+            Xr = None
+            rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
+                               tabs["group_offset"][mb], None, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
+                               workspace=ws_perm, err_flag=err)
+            rl.relibra_row_tokens(src_of, k, T, row_tok=row_tok_k[i], err_flag=err)
+            rl.relibra_moe_ffn_fwd_gather(X, row_tok_k[i], tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
+                                          Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err)
+        else:
+            Xr = Xrows_k[i]
+            rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
+                               tabs["group_offset"][mb], X, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
+                               Xrows=Xr, workspace=ws_perm, err_flag=err)
+            rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
+                                   Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
                                      out_rows=dYr, dgate=dgate, err_flag=err)
@@ -128,8 +143,9 @@ def main():
         rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, out_tok=dX, err_flag=err)
 
     def weight_gradients(tabs):
-        mbs = [dict(dYrows=dYrows_k[mb], Xrows=Xrows_k[mb], A=A_k[mb], bwd_workspace=ws_ffn_k[mb],
-                    inst_ptr=tabs["inst_ptr"][mb], inst_group=tabs["inst_group"][mb], group_offset=tabs["group_offset"][mb])
+        mbs = [dict(dYrows=dYrows_k[mb], A=A_k[mb], bwd_workspace=ws_ffn_k[mb],
+                    inst_ptr=tabs["inst_ptr"][mb], inst_group=tabs["inst_group"][mb], group_offset=tabs["group_offset"][mb],
+                    **(dict(X=tok[mb][0], row_tok=row_tok_k[mb]) if fused_gather else dict(Xrows=Xrows_k[mb])))
                for mb in range(n_mb)]
         rl.relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, workspace=ws_wgrad, err_flag=err)
 
@@ -185,8 +201,9 @@ def main():
     def alg_bytes(name):
         w1 = 2.0 * h * hff                       # one bf16 weight matrix
         act_h, act_ff = 2.0 * h * N, 2.0 * hff * N
+        act_x = 2.0 * h * T + 4.0 * N if fused_gather else act_h      # the layer's input rows: tokens + row table, or the gathered copy
         if batched and name.startswith("wgrad"):   # one launch per batch: every micro-batch's rows read once, dW written once
-            return n_mb * (act_h + act_ff) + 2 * w1 * E if name == "wgrad_down" else n_mb * (2 * act_ff + act_h) + 4 * w1 * E
+            return n_mb * (act_h + act_ff) + 2 * w1 * E if name == "wgrad_down" else n_mb * (2 * act_ff + act_x) + 4 * w1 * E
         tot = 0.0
         for mb in range(n_mb):
             rows_g = np.diff(plan["group_offset"][mb])
@@ -194,12 +211,12 @@ def main():
             home_live = int(((rows_g > 0) & (plan["group_dw_slot"][mb] < E)).sum())
             acc_mode = mb > 0
             tot += {
-                "fwd_gate_up": act_h + 2 * w1 * live + 3 * act_ff,
+                "fwd_gate_up": act_x + 2 * w1 * live + 3 * act_ff,
                 "fwd_down": act_ff + w1 * live + act_h,
                 "bwd_act": act_h + w1 * live + 2 * act_ff + 2 * act_ff,
                 "bwd_dx": 2 * act_ff + 2 * w1 * live + act_h,
                 "wgrad_down": act_h + act_ff + 2 * w1 * live + (2 * w1 * home_live if acc_mode else 0.0),
-                "wgrad_gate_up": 2 * act_ff + act_h + 4 * w1 * live + (4 * w1 * home_live if acc_mode else 0.0),
+                "wgrad_gate_up": 2 * act_ff + act_x + 4 * w1 * live + (4 * w1 * home_live if acc_mode else 0.0),
             }[name]
         return tot / n_mb
 
@@ -423,7 +440,8 @@ def main():
         "config": {"workload": f"{cfg.name}: E={E} top-{k} h={h} h'={hff} {n_mb}x{T} tokens, simulated EP={EP}, r={r}; "
                                "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd); "
                                + ("weight gradients once per batch over all resident micro-batches" if batched
-                                  else "weight gradients accumulated micro-batch by micro-batch"),
+                                  else "weight gradients accumulated micro-batch by micro-batch")
+                               + ("; row gather fused into the GEMMs" if fused_gather else ""),
                    "flops_per_step": flops_step},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "gemm_kernels": kernels, "gemm_only_tflops": gemm_tflops,

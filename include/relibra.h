@@ -59,8 +59,8 @@ enum {
     RELIBRA_BWD_NO_REPLICA_SUM = 2, /* leave replica-slot dW where it is (partial group range) */
     RELIBRA_BWD_REPLICA_WEIGHTS = 4, /* a group reads its parameters from slot group_dw_slot[g] of
                                        Wg/Wu/Wd [n_dw_slots, ...] (filled by relibra_replica_push) */
-    RELIBRA_BWD_DEFER_WGRAD = 8,    /* data gradients only: dW untouched; dGt, dU stay in the
-                                       workspace for relibra_moe_ffn_wgrad_batched */
+    RELIBRA_BWD_DEFER_WGRAD = 8,    /* data gradients only: dW untouched (dW and Xrows may be NULL);
+                                       dGt, dU stay in the workspace for relibra_moe_ffn_wgrad_batched */
     RELIBRA_BWD_TRANSPOSED_WEIGHTS = 16 /* Wg, Wu are given as [., h, hff] and Wd as [., hff, h]:
                                        transposed copies (relibra_transpose_experts), which put the
                                        data gradients' contraction index contiguous in memory */
@@ -306,7 +306,8 @@ int relibra_transpose_experts(const void *in_dev, int n_blocks, int rows, int co
  * then call this once.  On several GPUs a rank would contract its own instances this way and
  * push the partial dW of replicated experts to their home rank once per batch.
  *   mbs_host [n_mb] host in: per micro-batch device pointers
- *       dYrows, Xrows [n_rows,h], A_save [n_rows,hff] bf16; bwd_workspace = the workspace that
+ *       dYrows, Xrows [n_rows,h] (or X, row_tok: see the struct), A_save [n_rows,hff] bf16;
+ *       bwd_workspace = the workspace that
  *       micro-batch's deferred backward call used (same n_rows, G, hff);
  *       inst_ptr [E+1], inst_group [inst_cap], group_offset [G+1] int32: the plan's tables
  *   dWg, dWu [E,hff,h], dWd [E,h,hff] fp32 dev: overwritten, or added to if accumulate != 0
@@ -319,6 +320,11 @@ typedef struct relibra_wgrad_mb {
     const void *dYrows_dev, *Xrows_dev, *A_save_dev;
     const void *bwd_workspace_dev;
     const int32_t *inst_ptr_dev, *inst_group_dev, *group_offset_dev;
+    /* fused row gather: with Xrows_dev == NULL, row r of the micro-batch is X_dev[row_tok_dev[r]]
+       (X_dev [n_tokens, h] bf16 token tensor, row_tok_dev [n_rows] from relibra_row_tokens) */
+    const void *X_dev;
+    const int32_t *row_tok_dev;
+    int n_tokens;
 } relibra_wgrad_mb;
 
 int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs_host, int n_mb, int n_rows,

@@ -304,14 +304,14 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
                         dXrows=None, workspace=None, err_flag=None, E=None):
     """-> dXrows [n_rows,h] bf16; dWg, dWu [slots,h',h] and dWd [slots,h,h'] fp32 are written in place.
     E = number of home experts (default Wg.shape[0]; pass it when the weights carry replica slots)."""
-    n_rows, h = Xrows.shape
+    n_rows, h = dYrows.shape                 # Xrows may be None when the weight gradients are deferred
     hff = Wg.shape[2] if flags & BWD_TRANSPOSED_WEIGHTS else Wg.shape[1]
     E = Wg.shape[0] if E is None else int(E)
     if flags & BWD_REPLICA_WEIGHTS and dWg is not None:
         assert Wg.shape[0] >= dWg.shape[0] and Wu.shape[0] >= dWg.shape[0] and Wd.shape[0] >= dWg.shape[0]
     G = group_expert.shape[0]
     g_end = G if g_end is None else g_end
-    dev = Xrows.device
+    dev = dYrows.device
     if dXrows is None:
         dXrows = torch.empty((n_rows, h), dtype=torch.bfloat16, device=dev)
     if workspace is None:
@@ -324,7 +324,7 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
     else:
         n_slots = dWg.shape[0]
         assert dWu.shape[0] == n_slots and dWd.shape[0] == n_slots
-    rc = lib().relibra_moe_ffn_bwd(_dp(dYrows, torch.bfloat16), _dp(Xrows, torch.bfloat16),
+    rc = lib().relibra_moe_ffn_bwd(_dp(dYrows, torch.bfloat16), _dp(Xrows),
                                    _dp(Gt, torch.bfloat16), _dp(U, torch.bfloat16), _dp(A, torch.bfloat16), n_rows,
                                    _dp(group_offset, torch.int32), _dp(group_expert, torch.int32),
                                    _dp(group_dw_slot, torch.int32), G, g_begin, g_end, E, n_slots,
@@ -351,28 +351,34 @@ class WgradMb(C.Structure):
     """relibra_wgrad_mb: one micro-batch's device pointers for the batched weight gradients."""
     _fields_ = [("dYrows_dev", C.c_void_p), ("Xrows_dev", C.c_void_p), ("A_save_dev", C.c_void_p),
                 ("bwd_workspace_dev", C.c_void_p), ("inst_ptr_dev", C.c_void_p), ("inst_group_dev", C.c_void_p),
-                ("group_offset_dev", C.c_void_p)]
+                ("group_offset_dev", C.c_void_p), ("X_dev", C.c_void_p), ("row_tok_dev", C.c_void_p), ("n_tokens", C.c_int)]
 
 
 def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, workspace=None, err_flag=None):
-    """mbs: list of dicts(dYrows, Xrows, A, bwd_workspace, inst_ptr, inst_group, group_offset) of device
-    tensors, one per micro-batch whose backward ran with BWD_DEFER_WGRAD.  Writes dWg, dWu [E,h',h],
+    """mbs: list of dicts(dYrows, Xrows (or X and row_tok: fused gather), A, bwd_workspace, inst_ptr,
+    inst_group, group_offset) of device tensors, one per micro-batch whose backward ran with BWD_DEFER_WGRAD.  Writes dWg, dWu [E,h',h],
     dWd [E,h,h'] fp32 in place (sum over all micro-batches and instances)."""
     n_mb = len(mbs)
     first = mbs[0]
-    n_rows, h = first["Xrows"].shape
+    n_rows, h = first["dYrows"].shape
     hff = first["A"].shape[1]
     G = first["group_offset"].shape[0] - 1
     inst_cap = first["inst_group"].shape[0]
     dev = dWg.device
     arr = (WgradMb * n_mb)()
     for i, m in enumerate(mbs):
-        assert m["Xrows"].shape == (n_rows, h) and m["dYrows"].shape == (n_rows, h) and m["A"].shape == (n_rows, hff)
+        assert m["dYrows"].shape == (n_rows, h) and m["A"].shape == (n_rows, hff)
         assert m["group_offset"].shape[0] == G + 1 and m["inst_group"].shape[0] == inst_cap and m["inst_ptr"].shape[0] == E + 1
         assert m["bwd_workspace"].numel() >= workspace_bytes(WS_FFN_BWD, max(n_rows, 1), 1, E, G, h, hff)
-        arr[i] = WgradMb(_dp(m["dYrows"], torch.bfloat16), _dp(m["Xrows"], torch.bfloat16), _dp(m["A"], torch.bfloat16),
+        if m.get("Xrows") is not None:          # group-ordered rows
+            assert m["Xrows"].shape == (n_rows, h)
+            x_rows, x_tok, rtok, n_tok = _dp(m["Xrows"], torch.bfloat16), C.c_void_p(0), C.c_void_p(0), 0
+        else:                                   # token tensor + row -> token table (fused gather)
+            assert m["X"].shape[1] == h and m["row_tok"].shape == (n_rows,)
+            x_rows, x_tok, rtok, n_tok = C.c_void_p(0), _dp(m["X"], torch.bfloat16), _dp(m["row_tok"], torch.int32), m["X"].shape[0]
+        arr[i] = WgradMb(_dp(m["dYrows"], torch.bfloat16), x_rows, _dp(m["A"], torch.bfloat16),
                          _dp(m["bwd_workspace"]), _dp(m["inst_ptr"], torch.int32), _dp(m["inst_group"], torch.int32),
-                         _dp(m["group_offset"], torch.int32))
+                         _dp(m["group_offset"], torch.int32), x_tok, rtok, n_tok)
     if workspace is None:
         workspace = torch.empty(max(workspace_bytes(WS_WGRAD_BATCHED, 0, 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
     if err_flag is None:

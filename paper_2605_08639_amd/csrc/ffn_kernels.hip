@@ -610,6 +610,8 @@ constexpr int kWgradChunk = 64;
 struct MbTable {
     const bf16_t *dY[kMaxWgradMb], *X[kMaxWgradMb], *A[kMaxWgradMb], *dGt[kMaxWgradMb], *dU[kMaxWgradMb];
     const int32_t *iptr[kMaxWgradMb], *igrp[kMaxWgradMb], *goff[kMaxWgradMb];
+    const int32_t *rtok[kMaxWgradMb];      // null: X holds group-ordered rows; else X holds tokens and row r is X[rtok[r]]
+    int tok_last[kMaxWgradMb];
 };
 
 // Instance range of expert e in micro-batch mb, sanitised: [p0, p1) inside the instance table.
@@ -727,7 +729,8 @@ wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
 template <int NA>
 struct WgradPieces {
     const MbTable &tb;
-    const int32_t *mb, *row0, *rows;       // this expert's slice of the piece arrays
+    const_i32_ptr mb, row0, rows;          // this expert's slice of the piece arrays (read as scalars: they
+                                           // were written by an earlier launch and are the same for every lane)
     int m_dim, n_dim, m0, n0;
     __device__ __forceinline__ int valid(int i) const { return rows[i]; }
     __device__ __forceinline__ void piece(int i, Operand (&A)[1][NA], Operand (&B)[1][1], int &k_valid) const
@@ -740,7 +743,8 @@ struct WgradPieces {
         } else {            // dWg, dWu: L = dGt, dU; R = X
             A[0][0] = {tb.dGt[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
             A[0][NA - 1] = {tb.dU[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
-            B[0][0] = {tb.X[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
+            if (tb.rtok[b]) B[0][0] = {tb.X[b], n_dim, n0, n_dim - 1, tb.rtok[b] + r0, tb.tok_last[b]};
+            else B[0][0] = {tb.X[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
         }
     }
 };
@@ -774,7 +778,8 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
     typename KL::Acc acc;
     KL::zero(acc);
     const int s0 = w.piece_ptr[e];
-    const WgradPieces<NA> src{tb, w.piece_mb + s0, w.piece_row0 + s0, w.piece_rows + s0, m_dim, n_dim, m0, n0};
+    const WgradPieces<NA> src{tb, (const_i32_ptr)(uintptr_t)(w.piece_mb + s0), (const_i32_ptr)(uintptr_t)(w.piece_row0 + s0),
+                              (const_i32_ptr)(uintptr_t)(w.piece_rows + s0), m_dim, n_dim, m0, n0};
     KL::run_pieces(acc, src, w.piece_ptr[e + 1] - s0, w.exp_slabs[e], lds, tid);
     wgrad_epilogue<KL, NA, BA>(acc, lds, out0, out1, (size_t)e * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
 }
@@ -926,8 +931,9 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     const int Gr = g_end - g_begin;
     if (Gr == 0) return RELIBRA_OK;
     const bool defer = (flags & RELIBRA_BWD_DEFER_WGRAD) != 0;    // then dW is not touched and may be null
-    if (!dYrows || !Xrows || !Gt_save || !U_save || !A_save || !group_offset || !group_expert || !group_dw_slot ||
-        !Wg || !Wu || !Wd || !dXrows || !ws || !err_flag || (!defer && (!dWg || !dWu || !dWd)))
+    // Xrows is an operand of the weight gradients only
+    if (!dYrows || !Gt_save || !U_save || !A_save || !group_offset || !group_expert || !group_dw_slot ||
+        !Wg || !Wu || !Wd || !dXrows || !ws || !err_flag || (!defer && (!Xrows || !dWg || !dWu || !dWd)))
         return RELIBRA_EINVAL;
     if (!aligned16(dYrows) || !aligned16(Xrows) || !aligned16(A_save) || !aligned16(Gt_save) || !aligned16(U_save) ||
         !aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) || !aligned16(dXrows) || !aligned16(dWg) ||
@@ -1010,15 +1016,19 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
     for (int mb = 0; mb < kMaxWgradMb; ++mb) {
         const relibra_wgrad_mb &m = mbs[mb < n_mb ? mb : 0];
         if (mb < n_mb) {
-            if (!m.dYrows_dev || !m.Xrows_dev || !m.A_save_dev || !m.bwd_workspace_dev || !m.inst_ptr_dev ||
-                !m.inst_group_dev || !m.group_offset_dev)
+            const bool gathered = m.Xrows_dev == nullptr;
+            if (!m.dYrows_dev || !m.A_save_dev || !m.bwd_workspace_dev || !m.inst_ptr_dev || !m.inst_group_dev ||
+                !m.group_offset_dev || (gathered && (!m.X_dev || !m.row_tok_dev || m.n_tokens < 1)))
                 return RELIBRA_EINVAL;
-            if (!aligned16(m.dYrows_dev) || !aligned16(m.Xrows_dev) || !aligned16(m.A_save_dev) || !aligned16(m.bwd_workspace_dev))
+            if (!aligned16(m.dYrows_dev) || !aligned16(gathered ? m.X_dev : m.Xrows_dev) || !aligned16(m.A_save_dev) ||
+                !aligned16(m.bwd_workspace_dev))
                 return RELIBRA_EINVAL;
         }
         const Sched s = carve(const_cast<void *>(m.bwd_workspace_dev), n_rows, G, hff, true);
         tb.dY[mb] = (const bf16_t *)m.dYrows_dev;
-        tb.X[mb] = (const bf16_t *)m.Xrows_dev;
+        tb.X[mb] = (const bf16_t *)(m.Xrows_dev ? m.Xrows_dev : m.X_dev);
+        tb.rtok[mb] = m.Xrows_dev ? nullptr : m.row_tok_dev;
+        tb.tok_last[mb] = m.Xrows_dev ? 0 : m.n_tokens - 1;
         tb.A[mb] = (const bf16_t *)m.A_save_dev;
         tb.dGt[mb] = s.dGt;
         tb.dU[mb] = s.dU;

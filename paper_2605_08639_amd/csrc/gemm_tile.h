@@ -25,6 +25,10 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int BK = 32;                      // default contraction slab per pipeline stage (two k16 MFMA steps)
 
+// Uniform loads through this type are scalar loads (tracked by lgkmcnt, not by the vmcnt the
+// pipeline counts by hand); the memory must not change while the kernel runs.
+typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+
 #define RELIBRA_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define RELIBRA_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
@@ -91,7 +95,12 @@ struct KcTile {
         return ln;
     }
     template <int NW>
-    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, int k0, int /*k_last*/, int wave, int /*lane*/)
+    struct Idx {};                                     // nothing to look up per slab
+    template <int NW>
+    static __device__ __forceinline__ void fetch(Idx<NW> &, const Lanes<NW> &, int, int, int) {}
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &, int k0, int /*k_last*/, int wave,
+                                                int /*lane*/)
     {
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i)
@@ -126,8 +135,26 @@ struct KsTile {
     };
     template <int NW>
     static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int /*wave*/, int /*lane*/) { return Lanes<NW>{op}; }
+
+    // A gathered operand (contraction index -> row of `base`) needs, per slab, the rows of the KPB
+    // k-rows of each of this wave's load blocks: fetched as scalars (fetch) ahead of the loads.
     template <int NW>
-    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, int k0, int k_last, int wave, int lane)
+    struct Idx {
+        int v[BLOCKS / NW][KPB];
+    };
+    template <int NW>
+    static __device__ __forceinline__ void fetch(Idx<NW> &ix, const Lanes<NW> &ln, int k0, int k_last, int wave)
+    {
+        if (!ln.op.gather) return;
+        const_i32_ptr g = (const_i32_ptr)(uintptr_t)ln.op.gather;
+#pragma unroll
+        for (int i = 0; i < BLOCKS / NW; ++i)
+#pragma unroll
+            for (int q = 0; q < KPB; ++q) ix.v[i][q] = g[min(k0 + (wave + i * NW) * KPB + q, k_last)];
+    }
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
+                                                int lane)
     {
         static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
         const Operand &op = ln.op;
@@ -136,10 +163,20 @@ struct KsTile {
             const int j = wave + i * NW;
             const int k = j * KPB + lane / SPR;
             const int s = (lane % SPR) ^ fk(k);
-            const int gk = min(k0 + k, k_last);
             int grow = op.row0 + s * 8;
             if (grow > op.row_last) grow = op.row_last - 7;
-            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)gk * op.ld + grow),
+            int mrow;                                   // row of `base` that holds this k-row
+            if (op.gather) {
+                // this lane's k-row picks its lookup by masks (a select over the array would be turned
+                // into a dynamically indexed, hence memory-resident, array)
+                mrow = 0;
+#pragma unroll
+                for (int q = 0; q < KPB; ++q) mrow |= ix.v[i][q] & -(int)(lane / SPR == q);
+                mrow = min(max(mrow, 0), op.gather_last);
+            } else {
+                mrow = min(k0 + k, k_last);
+            }
+            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)mrow * op.ld + grow),
                                              RELIBRA_LDS(lds + j * 1024), 16, 0, 0);
         }
     }
@@ -201,6 +238,12 @@ struct KLoop {
 
     typedef typename AT::template Lanes<NW> LanesA;
     typedef typename BT::template Lanes<NW> LanesB;
+    typedef typename AT::template Idx<NW> IdxA;
+    typedef typename BT::template Idx<NW> IdxB;
+    struct Lookups {                                    // per-slab row lookups of gathered k-strided operands
+        IdxA a[NA];
+        IdxB b[NB];
+    };
 
     static __device__ __forceinline__ void prepare(LanesA (&PA)[NPH][NA], LanesB (&PB)[NPH][NB], const Operand (&A)[NPH][NA],
                                                    const Operand (&B)[NPH][NB], int wave, int lane)
@@ -214,23 +257,44 @@ struct KLoop {
         }
     }
 
-    static __device__ __forceinline__ void issue(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
-                                                 int t, int steps_per_phase, int k_last, int wave, int lane)
+    // Scalar row lookups of gathered k-strided operands for slab t (no-ops otherwise); to be called
+    // before issue() of the same slab, early enough for the values to have arrived.
+    static __device__ __forceinline__ void fetch(Lookups &lk, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB], int t,
+                                                 int steps_per_phase, int k_last, int wave)
     {
         const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
         const int k0 = (t - ph * steps_per_phase) * DEPTH;
         if (NPH == 1 || ph == 0) {
 #pragma unroll
-            for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[0][a], k0, k_last, wave, lane);
+            for (int a = 0; a < NA; ++a) AT::template fetch<NW>(lk.a[a], PA[0][a], k0, k_last, wave);
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[0][b], k0, k_last, wave, lane);
+            for (int b = 0; b < NB; ++b) BT::template fetch<NW>(lk.b[b], PB[0][b], k0, k_last, wave);
         } else {
 #pragma unroll
-            for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[NPH - 1][a], k0, k_last, wave, lane);
+            for (int a = 0; a < NA; ++a) AT::template fetch<NW>(lk.a[a], PA[NPH - 1][a], k0, k_last, wave);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) BT::template fetch<NW>(lk.b[b], PB[NPH - 1][b], k0, k_last, wave);
+        }
+    }
+
+    static __device__ __forceinline__ void issue(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
+                                                 const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane)
+    {
+        const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
+        const int k0 = (t - ph * steps_per_phase) * DEPTH;
+        if (NPH == 1 || ph == 0) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[0][a], lk.a[a], k0, k_last, wave, lane);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
-                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[NPH - 1][b], k0, k_last, wave, lane);
+                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[0][b], lk.b[b], k0, k_last, wave, lane);
+        } else {
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+                AT::template load<NW>(stage + a * AT::BYTES, PA[NPH - 1][a], lk.a[a], k0, k_last, wave, lane);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[NPH - 1][b], lk.b[b], k0, k_last, wave, lane);
         }
     }
 
@@ -293,10 +357,14 @@ struct KLoop {
         LanesA PA[NPH][NA];
         LanesB PB[NPH][NB];
         prepare(PA, PB, A, B, wave, lane);
+        Lookups lk;
         Frags f[2];
 #pragma unroll
         for (int i = 0; i < STAGES; ++i)
-            if (i < n) issue(lds + i * STAGE_BYTES, PA, PB, i, steps_per_phase, k_last, wave, lane);
+            if (i < n) {
+                fetch(lk, PA, PB, i, steps_per_phase, k_last, wave);
+                issue(lds + i * STAGE_BYTES, PA, PB, lk, i, steps_per_phase, k_last, wave, lane);
+            }
         wait_younger(n - 1);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
@@ -326,7 +394,10 @@ struct KLoop {
             wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
             if (DBG != 3) __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (t + STAGES < n && DBG != 1 && DBG != 3) issue(cur, PA, PB, t + STAGES, steps_per_phase, k_last, wave, lane);
+            if (t + STAGES < n && DBG != 1 && DBG != 3) {
+                fetch(lk, PA, PB, t + STAGES, steps_per_phase, k_last, wave);
+                issue(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane);
+            }
             if (DBG != 2) {
                 // First half of the last step's MFMAs, then the requests for the next slab's first
                 // fragments (always issued: after the last slab they fetch stale LDS that nobody
@@ -367,8 +438,10 @@ struct KLoop {
         prepare(PA, PB, Ai, Bi, wave, lane);
         i_slabs = (i_valid + DEPTH - 1) / DEPTH;
         int ct = 0, c_valid = i_valid, c_slabs = i_slabs, cp = 0;
+        Lookups lk;
+        auto fetch_next = [&]() { fetch(lk, PA, PB, it, i_slabs, i_valid - 1, wave); };
         auto issue_next = [&](char *stage) {
-            issue(stage, PA, PB, it, i_slabs, i_valid - 1, wave, lane);
+            issue(stage, PA, PB, lk, it, i_slabs, i_valid - 1, wave, lane);
             if (++it == i_slabs && ip + 1 < n_pieces) {
                 ++ip;
                 it = 0;
@@ -380,7 +453,10 @@ struct KLoop {
         Frags f[2];
 #pragma unroll
         for (int i = 0; i < STAGES; ++i)
-            if (i < n) issue_next(lds + i * STAGE_BYTES);
+            if (i < n) {
+                fetch_next();
+                issue_next(lds + i * STAGE_BYTES);
+            }
         wait_younger(n - 1);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
@@ -397,6 +473,8 @@ struct KLoop {
                 __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
                 __builtin_amdgcn_sched_barrier(0);
                 read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
+                // row lookups of the slab issued below: requested a whole MFMA block ahead
+                if (s == 0 && t + STAGES < n) fetch_next();
                 __builtin_amdgcn_sched_barrier(0);
                 if (tail) mask_frags(f[s & 1], kf + s * 16, c_valid);
                 mfma_all(acc, f[s & 1]);

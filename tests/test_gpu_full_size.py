@@ -174,3 +174,18 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
         assert num ** 0.5 <= 1e-5 * den ** 0.5, (name, (num / max(den, 1e-300)) ** 0.5)
     assert err.item() == 0
     print(f"[{cfg.name}] batched weight gradients ok", flush=True)
+
+    # ---- the row gather fused into the GEMMs (what bench.py runs): bit-identical to the two-step form
+    row_tok = rl.relibra_row_tokens(src_of, k, T, err_flag=err)
+    assert np.array_equal(row_tok.cpu().numpy(), src_o // k)
+    fused = rl.relibra_moe_ffn_fwd_gather(X_d, row_tok, tabs["group_offset"], tabs["group_expert"], Wg_d, Wu_d, Wd_d, err_flag=err)
+    for a_, b_ in zip(fused, (Gt, U, A, Y)):
+        assert torch.equal(a_, b_)
+    del fused
+    one_f = dict(one, Xrows=None, X=X_d, row_tok=row_tok)
+    dWf = [torch.empty(s, dtype=torch.float32, device=DEV) for s in ((E, hff, h), (E, hff, h), (E, h, hff))]
+    rl.relibra_moe_ffn_wgrad_batched([one_f, one_f], E, *dWf, err_flag=err)
+    for a_, b_ in zip(dWf, dWb):
+        assert torch.equal(a_, b_)
+    assert err.item() == 0
+    print(f"[{cfg.name}] fused row gather ok", flush=True)

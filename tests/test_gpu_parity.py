@@ -423,14 +423,16 @@ def test_batched_weight_gradients_match_oracle_and_per_microbatch_path():
     dW_ref = [np.zeros((cfg.E, *s)) for s in shapes]
     dW_mb = [torch.empty((n_slots, *s), dtype=torch.float32, device=DEV) for s in shapes]
     err = rl.new_err_flag()
-    kept = []
+    kept, fused_in = [], []
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
     for mb in range(cfg.n_mb):
         X, _ = wl.make_tokens(cfg, mb)
         tabs = {key: dev_i32(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset",
                                                      "group_expert", "group_dw_slot")}
+        Xd = X.to(DEV)
         row_of, src_of, Xrows = rl.relibra_permute(t(ids[mb]), tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
-                                                   tabs["group_offset"], X.to(DEV), cfg.E, cfg.G, err_flag=err)
+                                                   tabs["group_offset"], Xd, cfg.E, cfg.G, err_flag=err)
+        fused_in.append((Xd, rl.relibra_row_tokens(src_of, cfg.k, cfg.T, err_flag=err)))
         Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], *W_d, err_flag=err)
         dY = torch.randn(Y.shape, generator=torch.Generator().manual_seed(100 + mb)).to(torch.bfloat16)
         dY_d = dY.to(DEV)
@@ -453,6 +455,14 @@ def test_batched_weight_gradients_match_oracle_and_per_microbatch_path():
     for got, want, per_mb in zip(dW_b, dW_ref, dW_mb):
         assert rel_l2(got, want) <= TOL
         assert rel_l2(got, per_mb[:cfg.E].double().cpu().numpy()) <= 1e-5
+    # the row gather fused in (token tensor + row -> token table instead of gathered rows): same operands,
+    # same order, bit-identical weight gradients
+    fused = [dict(m, Xrows=None, X=xd, row_tok=rt) for m, (xd, rt) in zip(kept, fused_in)]
+    dW_f = [torch.empty((cfg.E, *s), dtype=torch.float32, device=DEV) for s in shapes]
+    rl.relibra_moe_ffn_wgrad_batched(fused, cfg.E, *dW_f, err_flag=err)
+    assert err.item() == 0
+    for a_, b_ in zip(dW_f, dW_b):
+        assert torch.equal(a_, b_)
     once = [w.clone() for w in dW_b]
     rl.relibra_moe_ffn_wgrad_batched(kept, cfg.E, *dW_b, accumulate=True, err_flag=err)
     for got, one in zip(dW_b, once):
