@@ -39,6 +39,23 @@ __device__ __forceinline__ void wait_vm_lgkm0()
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | ((N >> 4) << 14));
 }
 
+// One direct global->LDS load: 64 lanes x 16 bytes from the lanes' addresses g to the 1 KiB at the
+// wave-uniform LDS address block.  Written as assembly so that the compiler keeps no record of
+// LDS being filled behind its back: with the builtin it puts a wait for ALL of the wave's
+// outstanding loads in front of every transposing LDS read, which empties the ring of slabs in
+// flight; the k-loop counts vmcnt by hand anyway.  M0 carries the LDS address (one wait state
+// between its write and the load).
+// (M0 is a reserved register that the compiler does not otherwise use in these kernels; naming it
+// as clobbered draws a warning that says so.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_lds16(const bf16_t *g, char *block)
+{
+    const uint32_t m = (uint32_t)(uintptr_t)RELIBRA_LDS(block);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(m) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 struct Operand {
     const bf16_t *base;   // see KcTile / KsTile for the addressing
     int ld;               // leading dimension in elements
@@ -104,7 +121,7 @@ struct KcTile {
     {
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i)
-            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(ln.p[i] + k0), RELIBRA_LDS(lds + (wave + i * NW) * 1024), 16, 0, 0);
+            load_lds16(ln.p[i] + k0, lds + (wave + i * NW) * 1024);
     }
 
     // fragment of rows r0..r0+31 (r0 % 32 == 0), k = kk*16 + (lane/32)*8 .. +7
@@ -176,8 +193,7 @@ struct KsTile {
             } else {
                 mrow = min(k0 + k, k_last);
             }
-            __builtin_amdgcn_global_load_lds(RELIBRA_GLB(op.base + (size_t)mrow * op.ld + grow),
-                                             RELIBRA_LDS(lds + j * 1024), 16, 0, 0);
+            load_lds16(op.base + (size_t)mrow * op.ld + grow, lds + j * 1024);
         }
     }
 
