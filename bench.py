@@ -42,9 +42,11 @@ def main():
     ap.add_argument("--gathered-copy", action="store_true",
                     help="materialise the group-ordered rows in the permutation (default with batched weight gradients: "
                          "the GEMMs gather token rows themselves)")
-    ap.add_argument("--plain-bwd-weights", action="store_true",
-                    help="data gradients read the forward pass's weight layout (default: transposed copies, "
-                         "made once per step inside the timed region)")
+    ap.add_argument("--weights", choices=("fwd-transposed", "bwd-transposed", "plain"), default="fwd-transposed",
+                    help="which GEMMs read transposed weight copies (made once per step inside the timed region) so that "
+                         "their weight operand is contraction-strided: the forward ones (default; the data gradients "
+                         "read the stored layout that way already), the data gradients (both passes then read "
+                         "contraction-contiguous weights), or none")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -103,7 +105,8 @@ def main():
                 for _ in range(n_keep)]
     ws_wgrad = torch.empty(rl.workspace_bytes(rl.WS_WGRAD_BATCHED, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
     Xrows, dYrows, A, ws_ffn = Xrows_k[0], dYrows_k[0], A_k[0], ws_ffn_k[0]
-    transposed = not args.plain_bwd_weights
+    transposed = args.weights != "plain"
+    fwd_t, bwd_t = args.weights == "fwd-transposed", args.weights == "bwd-transposed"
     WgT = torch.empty((E, h, hff), dtype=torch.bfloat16, device=dev) if transposed else None
     WuT = torch.empty_like(WgT) if transposed else None
     WdT = torch.empty((E, hff, h), dtype=torch.bfloat16, device=dev) if transposed else None
@@ -116,29 +119,31 @@ def main():
         X, dOut = tok[mb]
         i = mb if batched else 0
         dYr, Ar, ws = dYrows_k[i], A_k[i], ws_ffn_k[i]
+        fw = (WgT, WuT, WdT) if fwd_t else (Wg, Wu, Wd)
+        fwd_flags = rl.FWD_TRANSPOSED_WEIGHTS if fwd_t else 0
         if fused_gather:                        # the GEMMs fetch token rows through row_tok: no gathered copy
             Xr = None
             rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
                                tabs["group_offset"][mb], None, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
                                workspace=ws_perm, err_flag=err)
             rl.relibra_row_tokens(src_of, k, T, row_tok=row_tok_k[i], err_flag=err)
-            rl.relibra_moe_ffn_fwd_gather(X, row_tok_k[i], tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
-                                          Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err)
+            rl.relibra_moe_ffn_fwd_gather(X, row_tok_k[i], tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
+                                          Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
         else:
             Xr = Xrows_k[i]
             rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
                                tabs["group_offset"][mb], X, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
                                Xrows=Xr, workspace=ws_perm, err_flag=err)
-            rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], Wg, Wu, Wd,
-                                   Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err)
+            rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
+                                   Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
         rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
                                      out_rows=dYr, dgate=dgate, err_flag=err)
         flags = rl.BWD_DEFER_WGRAD if batched else (0 if first else rl.BWD_ACCUMULATE)
-        bw = (WgT, WuT, WdT) if transposed else (Wg, Wu, Wd)
+        bw = (WgT, WuT, WdT) if bwd_t else (Wg, Wu, Wd)
         rl.relibra_moe_ffn_bwd(dYr, Xr, Gt, U, Ar, tabs["group_offset"][mb], tabs["group_expert"][mb],
                                tabs["group_dw_slot"][mb], *bw, dWg, dWu, dWd, E=E,
-                               flags=flags | (rl.BWD_TRANSPOSED_WEIGHTS if transposed else 0), dXrows=dXrows,
+                               flags=flags | (rl.BWD_TRANSPOSED_WEIGHTS if bwd_t else 0), dXrows=dXrows,
                                workspace=ws, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, out_tok=dX, err_flag=err)
 
@@ -154,7 +159,7 @@ def main():
     def step():
         rl.relibra_route_hist(ids_all, E, counts=counts_d, err_flag=err)
         counts_h = counts_d.cpu().numpy()                       # the path's one device->host crossing
-        if transposed:          # this step's parameters in the backward layout: the GPU copies while the host plans
+        if transposed:          # this step's parameters in the transposed layout: the GPU copies while the host plans
             rl.relibra_transpose_experts(Wg, WgT)
             rl.relibra_transpose_experts(Wu, WuT)
             rl.relibra_transpose_experts(Wd, WdT)

@@ -221,13 +221,19 @@ int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const i
  * group_expert[g] is the index of the group's parameter block in Wg/Wu/Wd and E their number of
  * blocks: with a physical replica buffer (relibra_replica_push) pass the plan's group_dw_slot
  * table and E + EP*r here, and replica groups read their own copy.
+ * flags: 0, or RELIBRA_FWD_TRANSPOSED_WEIGHTS: Wg, Wu, Wd point to transposed copies
+ * ([E, h, hff], [E, h, hff], [E, hff, h], made by relibra_transpose_experts); the results are
+ * identical bit for bit.  The weight operand is then read along full cache lines through the
+ * transposing LDS reads, which measures a few percent faster; the copies cost one pass over the
+ * weights per optimizer step.  Other flag bits: RELIBRA_EINVAL.
  * Limits: h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.
  */
+#define RELIBRA_FWD_TRANSPOSED_WEIGHTS 1
 int relibra_moe_ffn_fwd(const void *Xrows_dev, int n_rows,
                         const int32_t *group_offset_dev, const int32_t *group_expert_dev,
                         int G, int g_begin, int g_end, int E,
                         const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
-                        void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Yrows_dev,
+                        void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Yrows_dev, int flags,
                         void *workspace_dev, size_t workspace_bytes,
                         int32_t *err_flag_dev, relibra_stream stream);
 
@@ -247,7 +253,7 @@ int relibra_moe_ffn_fwd_gather(const void *X_dev, int T, const int32_t *row_tok_
                                const int32_t *group_offset_dev, const int32_t *group_expert_dev,
                                int G, int g_begin, int g_end, int E,
                                const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
-                               void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Yrows_dev,
+                               void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Yrows_dev, int flags,
                                void *workspace_dev, size_t workspace_bytes,
                                int32_t *err_flag_dev, relibra_stream stream);
 

@@ -20,6 +20,7 @@ OK, EINVAL, ERANGE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
 WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD, WS_WGRAD_BATCHED = 0, 1, 2, 3
 BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD, BWD_TRANSPOSED_WEIGHTS = 1, 2, 4, 8, 16
+FWD_TRANSPOSED_WEIGHTS = 1
 MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
@@ -233,11 +234,12 @@ def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,
 
 
 def relibra_moe_ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
-                        Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None):
+                        Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None, flags=0):
     """Xrows [n_rows,h] bf16, weights bf16 -> (Gt, U, A [n_rows,h'], Yrows [n_rows,h]) bf16.
-    group_expert indexes the parameter blocks of Wg/Wu/Wd (all Wg.shape[0] of them are addressable)."""
+    group_expert indexes the parameter blocks of Wg/Wu/Wd (all Wg.shape[0] of them are addressable).
+    flags = FWD_TRANSPOSED_WEIGHTS: the weights are the transposed copies ([E,h,h'], [E,h,h'], [E,h',h])."""
     n_rows, h = Xrows.shape
-    E, hff = Wg.shape[0], Wg.shape[1]
+    E, hff = Wg.shape[0], (Wg.shape[2] if flags & FWD_TRANSPOSED_WEIGHTS else Wg.shape[1])
     G = group_expert.shape[0]
     g_end = G if g_end is None else g_end
     dev = Xrows.device
@@ -254,7 +256,7 @@ def relibra_moe_ffn_fwd(Xrows, group_offset, group_expert, Wg, Wu, Wd, g_begin=0
     rc = lib().relibra_moe_ffn_fwd(_dp(Xrows, torch.bfloat16), n_rows, _dp(group_offset, torch.int32),
                                    _dp(group_expert, torch.int32), G, g_begin, g_end, E,
                                    _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
-                                   h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows),
+                                   h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows), int(flags),
                                    _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_moe_ffn_fwd", rc)
     return Gt, U, A, Yrows
@@ -273,11 +275,11 @@ def relibra_row_tokens(src_of, k, T, row_tok=None, err_flag=None):
 
 
 def relibra_moe_ffn_fwd_gather(X, row_tok, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
-                               Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None):
+                               Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None, flags=0):
     """relibra_moe_ffn_fwd with the row gather fused in: X [T,h] token tensor, row_tok [n_rows]."""
     T, h = X.shape
     n_rows = row_tok.shape[0]
-    E, hff = Wg.shape[0], Wg.shape[1]
+    E, hff = Wg.shape[0], (Wg.shape[2] if flags & FWD_TRANSPOSED_WEIGHTS else Wg.shape[1])
     G = group_expert.shape[0]
     g_end = G if g_end is None else g_end
     dev = X.device
@@ -293,7 +295,7 @@ def relibra_moe_ffn_fwd_gather(X, row_tok, group_offset, group_expert, Wg, Wu, W
     rc = lib().relibra_moe_ffn_fwd_gather(_dp(X, torch.bfloat16), T, _dp(row_tok, torch.int32), n_rows,
                                           _dp(group_offset, torch.int32), _dp(group_expert, torch.int32), G, g_begin, g_end, E,
                                           _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
-                                          h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows),
+                                          h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Yrows), int(flags),
                                           _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_moe_ffn_fwd_gather", rc)
     return Gt, U, A, Yrows

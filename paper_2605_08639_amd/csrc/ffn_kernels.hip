@@ -291,15 +291,17 @@ template <int BB> struct Waves { static constexpr int B = BB / 64, A = NWAVES / 
 
 // ---------------------------------------------------------------- forward
 // Gt = X Wg^T, U = X Wu^T (one pass over X), A = silu(Gt) * U.   Column tile: 128 of h'.
-template <int BB>
+template <int BB, bool WT>
 __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t *X, const int32_t *row_tok, int tok_last,
                                                  const bf16_t *Wg, const bf16_t *Wu,
                                                  int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout, char *lds)
 {
-    using KL = KLoop<KcTile<128>, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false, NSTAGES>;
+    using WTile = typename std::conditional<WT, KsTile<128>, KcTile<128>>::type;
+    using KL = KLoop<WTile, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false, NSTAGES>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t wofs = (size_t)t.expert * hff * h;
-    const Operand A[1][2] = {{{Wg + wofs, h, t.col0, hff - 1}, {Wu + wofs, h, t.col0, hff - 1}}};
+    const int ldw = WT ? hff : h;                             // (n in h', k in h) at [n*h + k], or at [k*h' + n]
+    const Operand A[1][2] = {{{Wg + wofs, ldw, t.col0, hff - 1}, {Wu + wofs, ldw, t.col0, hff - 1}}};
     // rows of the group: a gathered copy (row_tok == nullptr), or token rows fetched through row_tok
     const Operand B[1][1] = {{{X, h, t.row0, t.row0 + t.rows - 1, row_tok, tok_last}}};
     typename KL::Acc acc;
@@ -335,6 +337,8 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     }
 }
 
+// WT: Wg, Wu given as transposed copies [h][h'] (contraction index strided, transposing LDS reads).
+template <bool WT>
 __global__ void __launch_bounds__(THREADS, 2)
 fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const int32_t *__restrict__ row_tok, int tok_last,
                    const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff, int n_col_tiles,
@@ -343,8 +347,8 @@ fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const int32_t *__restr
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, 128);
     if (!t.valid) return;
-    if (t.rows > BM / 2) fwd_gate_up_body<BM>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
-    else fwd_gate_up_body<BM / 2>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    if (t.rows > BM / 2) fwd_gate_up_body<BM, WT>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    else fwd_gate_up_body<BM / 2, WT>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
 }
 
 // Shared body of the three single-accumulator row-tiled GEMMs.  EPI: 0 = store bf16 (Y, dX);
@@ -429,7 +433,8 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
     }
 }
 
-// Y = A Wd^T.
+// Y = A Wd^T.  WT: Wd given as a transposed copy [h'][h].
+template <bool WT>
 __global__ void __launch_bounds__(THREADS, 2)
 fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restrict__ Wd, int h, int hff,
                 int n_col_tiles, bf16_t *__restrict__ Y)
@@ -438,8 +443,9 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
     const RowTile t = find_row_tile(s, n_col_tiles, 256);
     if (!t.valid) return;
     const bf16_t *W = Wd + (size_t)t.expert * h * hff;
-    if (t.rows > BM / 2) row_gemm_body<BM, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
-    else row_gemm_body<BM / 2, false, 1, 0>(t, Ain, nullptr, hff, W, nullptr, hff, h, hff, Y, nullptr, nullptr, nullptr, lds);
+    const int ldw = WT ? h : hff;                             // (n in h, k in h') at [n*h' + k], or at [k*h + n]
+    if (t.rows > BM / 2) row_gemm_body<BM, WT, 1, 0>(t, Ain, nullptr, hff, W, nullptr, ldw, h, hff, Y, nullptr, nullptr, nullptr, lds);
+    else row_gemm_body<BM / 2, WT, 1, 0>(t, Ain, nullptr, hff, W, nullptr, ldw, h, hff, Y, nullptr, nullptr, nullptr, lds);
 }
 
 // ---------------------------------------------------------------- backward
@@ -838,8 +844,10 @@ static int ensure_lds_limits()
 {
     static bool done = false;
     if (done) return RELIBRA_OK;
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
@@ -861,10 +869,12 @@ static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_
                                    const int32_t *group_offset, const int32_t *group_expert,
                                    int G, int g_begin, int g_end, int E,
                                    const void *Wg, const void *Wu, const void *Wd, int h, int hff,
-                                   void *Gt_save, void *U_save, void *A_save, void *Yrows,
+                                   void *Gt_save, void *U_save, void *A_save, void *Yrows, int flags,
                                    void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
+    if (flags & ~RELIBRA_FWD_TRANSPOSED_WEIGHTS) return RELIBRA_EINVAL;
+    const bool wt = (flags & RELIBRA_FWD_TRANSPOSED_WEIGHTS) != 0;
     const FfnArgs a{n_rows, G, g_begin, g_end, E, h, hff};
     if (int rc = check_ffn_args(a)) return rc;
     const int Gr = g_end - g_begin;
@@ -882,13 +892,23 @@ static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_
     RELIBRA_HIP_TRY(launch_check());
     const long long R = max_row_tiles(n_rows, Gr);
     const int ct1 = (hff + 127) / 128, ct2 = (h + 255) / 256;
-    RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<<<grid8(R * ct1), THREADS, kLdsBytes, stream>>>(
-        s, (const bf16_t *)Xrows, row_tok, T - 1, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
-        (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save));
-    RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<<<grid8(R * ct2), THREADS, kLdsBytes, stream>>>(
-        s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows));
-    RELIBRA_HIP_TRY(launch_check());
+    if (wt) {
+        RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<true><<<grid8(R * ct1), THREADS, kLdsBytes, stream>>>(
+            s, (const bf16_t *)Xrows, row_tok, T - 1, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
+            (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save));
+        RELIBRA_HIP_TRY(launch_check());
+        RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<true><<<grid8(R * ct2), THREADS, kLdsBytes, stream>>>(
+            s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows));
+        RELIBRA_HIP_TRY(launch_check());
+    } else {
+        RELIBRA_LAUNCH(RELIBRA_K_FWD_GATE_UP, stream, fwd_gate_up_kernel<false><<<grid8(R * ct1), THREADS, kLdsBytes, stream>>>(
+            s, (const bf16_t *)Xrows, row_tok, T - 1, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
+            (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save));
+        RELIBRA_HIP_TRY(launch_check());
+        RELIBRA_LAUNCH(RELIBRA_K_FWD_DOWN, stream, fwd_down_kernel<false><<<grid8(R * ct2), THREADS, kLdsBytes, stream>>>(
+            s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows));
+        RELIBRA_HIP_TRY(launch_check());
+    }
     return RELIBRA_OK;
 }
 
@@ -896,23 +916,23 @@ extern "C" int relibra_moe_ffn_fwd(const void *Xrows, int n_rows,
                                    const int32_t *group_offset, const int32_t *group_expert,
                                    int G, int g_begin, int g_end, int E,
                                    const void *Wg, const void *Wu, const void *Wd, int h, int hff,
-                                   void *Gt_save, void *U_save, void *A_save, void *Yrows,
+                                   void *Gt_save, void *U_save, void *A_save, void *Yrows, int flags,
                                    void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
 {
     return ffn_fwd_impl(Xrows, nullptr, 1, n_rows, group_offset, group_expert, G, g_begin, g_end, E, Wg, Wu, Wd, h, hff,
-                        Gt_save, U_save, A_save, Yrows, ws, ws_bytes, err_flag, stream_);
+                        Gt_save, U_save, A_save, Yrows, flags, ws, ws_bytes, err_flag, stream_);
 }
 
 extern "C" int relibra_moe_ffn_fwd_gather(const void *X, int T, const int32_t *row_tok, int n_rows,
                                           const int32_t *group_offset, const int32_t *group_expert,
                                           int G, int g_begin, int g_end, int E,
                                           const void *Wg, const void *Wu, const void *Wd, int h, int hff,
-                                          void *Gt_save, void *U_save, void *A_save, void *Yrows,
+                                          void *Gt_save, void *U_save, void *A_save, void *Yrows, int flags,
                                           void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
 {
     if (T < 1 || !row_tok) return RELIBRA_EINVAL;
     return ffn_fwd_impl(X, row_tok, T, n_rows, group_offset, group_expert, G, g_begin, g_end, E, Wg, Wu, Wd, h, hff,
-                        Gt_save, U_save, A_save, Yrows, ws, ws_bytes, err_flag, stream_);
+                        Gt_save, U_save, A_save, Yrows, flags, ws, ws_bytes, err_flag, stream_);
 }
 
 extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,

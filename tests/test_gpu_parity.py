@@ -512,6 +512,29 @@ def test_backward_with_transposed_weights_matches_oracle_and_the_plain_layout(ca
     assert rel_l2(outs[1][0][lv], dX_o[live]) <= TOL
 
 
+@pytest.mark.parametrize("case", [FFN_CASES[0], FFN_CASES[3], FFN_CASES[4]])
+def test_forward_with_transposed_weights_is_bit_identical(case):
+    """Forward GEMMs reading transposed weight copies multiply the same operands in the same
+    order: every stored tensor must equal the plain-layout result bit for bit (which the other
+    tests hold against the oracle)."""
+    go, ge, X, dY, Wg, Wu, Wd = ffn_case(**case)
+    Xd, W_d = X.to(DEV), [W.to(DEV) for W in (Wg, Wu, Wd)]
+    W_t = [rl.relibra_transpose_experts(W) for W in W_d]
+    go_d, ge_d = dev_i32(go), dev_i32(ge)
+    err = rl.new_err_flag()
+    plain = rl.relibra_moe_ffn_fwd(Xd, go_d, ge_d, *W_d, err_flag=err)
+    mk = lambda t: torch.zeros_like(t)
+    swapped = rl.relibra_moe_ffn_fwd(Xd, go_d, ge_d, *W_t, Gt=mk(plain[0]), U=mk(plain[1]), A=mk(plain[2]), Yrows=mk(plain[3]),
+                                     err_flag=err, flags=rl.FWD_TRANSPOSED_WEIGHTS)
+    assert err.item() == 0
+    live = np.concatenate([np.arange(go[g], go[g + 1]) for g in range(len(ge)) if ge[g] >= 0 and go[g + 1] > go[g]])
+    lv = torch.from_numpy(live).to(DEV)
+    for a_, b_ in zip(plain, swapped):
+        assert torch.equal(a_[lv], b_[lv])
+    Y_o = oracle.ffn_fwd(X, go, ge, Wg, Wu, Wd)[3]
+    assert rel_l2(swapped[3][lv], Y_o[live]) <= TOL
+
+
 # ------------------------------------------------------------------ row gather fused into the GEMMs
 def test_forward_with_fused_row_gather_is_bit_identical():
     """relibra_moe_ffn_fwd_gather reads row `row` as X[row_tok[row]]: the same operands in the same

@@ -125,10 +125,12 @@ def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
     assert L.relibra_route_hist(z, 0, 4, 2, 8, z, z, z) == rl.OK              # empty batch
     assert L.relibra_permute(z, z, z, z, z, z, 4, 2, 5000, 12, 128, z, z, z, z, ctypes.c_size_t(0), z, z) == rl.EINVAL
     assert L.relibra_permute(z, z, z, z, z, z, 0, 2, 8, 12, 128, z, z, z, z, ctypes.c_size_t(0), z, z) == rl.OK
-    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 0, 12, 8, z, z, z, 100, 256, z, z, z, z, z,
+    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 0, 12, 8, z, z, z, 100, 256, z, z, z, z, 0, z,
                                  ctypes.c_size_t(0), z, z) == rl.EUNSUPPORTED  # h % 64
-    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 5, 3, 8, z, z, z, 128, 256, z, z, z, z, z,
+    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 5, 3, 8, z, z, z, 128, 256, z, z, z, z, 0, z,
                                  ctypes.c_size_t(0), z, z) == rl.EINVAL        # g_begin > g_end
+    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 0, 12, 8, z, z, z, 128, 256, z, z, z, z, 2, z,
+                                 ctypes.c_size_t(0), z, z) == rl.EINVAL        # unknown flag bit
     assert L.relibra_unpermute_combine(7, z, z, z, z, 4, 2, 128, z, z, z, z, z) == rl.EINVAL
     assert L.relibra_unpermute_combine(0, z, z, z, z, 4, 2, 100, z, z, z, z, z) == rl.EINVAL
     # layer-shared replica buffer push
