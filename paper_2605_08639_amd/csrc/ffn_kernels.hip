@@ -43,6 +43,7 @@ struct Sched {
     int32_t *grp_row0, *grp_rows, *grp_expert, *grp_slot;   // [Gr]
     int32_t *tile_prefix;  // [Gr+1]
     int32_t *tile_group, *tile_row0, *tile_rows;            // [Rmax]
+    int32_t *tile_band;    // [Rmax] band of the row tile: first row tile | number of row tiles << 24
     int32_t *pair_slot, *pair_expert;                       // [Gr]
     bf16_t *dGt, *dU;      // [n_rows, hff] (backward only)
 };
@@ -50,7 +51,7 @@ struct Sched {
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int max_row_tiles(int n_rows, int Gr) { return (n_rows + BM - 1) / BM + Gr; }
 constexpr int kLdsBytes = NSTAGES * (256 + BM) * BK * 2;   // NSTAGES slabs of 256 + BM operand rows
-inline size_t sched_ints(int n_rows, int Gr) { return 8 + 4 * (size_t)Gr + (Gr + 1) + 3 * (size_t)max_row_tiles(n_rows, Gr) + 2 * (size_t)Gr; }
+inline size_t sched_ints(int n_rows, int Gr) { return 8 + 4 * (size_t)Gr + (Gr + 1) + 4 * (size_t)max_row_tiles(n_rows, Gr) + 2 * (size_t)Gr; }
 inline size_t ffn_ws_bytes(int n_rows, int Gr, int hff, bool bwd)
 {
     size_t b = round256(sched_ints(n_rows, Gr) * sizeof(int32_t));
@@ -71,6 +72,7 @@ inline Sched carve(void *ws, int n_rows, int Gr, int hff, bool bwd)
     s.tile_group = p; p += R;
     s.tile_row0 = p; p += R;
     s.tile_rows = p; p += R;
+    s.tile_band = p; p += R;
     s.pair_slot = p; p += Gr;
     s.pair_expert = p; p += Gr;
     char *q = (char *)ws + round256(sched_ints(n_rows, Gr) * sizeof(int32_t));
@@ -81,6 +83,14 @@ inline Sched carve(void *ws, int n_rows, int Gr, int hff, bool bwd)
     }
     return s;
 }
+
+// Order of the tiles.  A group's row tiles are cut into bands of kBand; the tiles of a band run
+// column tile by column tile, the band's row tiles innermost, so that the tiles a set of compute
+// units works on at one time share weight column tiles as well as row tiles.  Against row-major
+// order over the group this takes 15 to 27 % off the HBM reads of the forward gate/up and the
+// dX kernels (measured, bands of 8) and about 1 % off their time: the L2 misses are not what
+// bounds them.
+constexpr int kBand = 8;
 
 // One block.  Validates the group tables of [g_begin, g_end) (bad groups become empty and raise
 // the flag), lists the row tiles group by group, and lists the live replica slots.
@@ -140,6 +150,8 @@ sched_kernel(const int32_t *__restrict__ group_offset, const int32_t *__restrict
         s.tile_group[t] = lo;
         s.tile_row0[t] = s.grp_row0[lo] + j * BM;
         s.tile_rows[t] = min(BM, s.grp_rows[lo] - j * BM);
+        const int m = s.tile_prefix[lo + 1] - s.tile_prefix[lo], b0 = j / kBand * kBand;
+        s.tile_band[t] = (s.tile_prefix[lo] + b0) | (min(kBand, m - b0) << 24);
     }
     // live replica slots, in group order (256 groups at a time; a running count in LDS)
     if (tid == 0) carry = 0;
@@ -175,16 +187,17 @@ struct RowTile {
     bool valid;
 };
 
-// Order of the tiles of an n_r x n_c grid: bands of kBand rows; inside a band column by column,
-// the band's rows innermost.  The ~64 tiles a set of compute units works on at one time then
-// form a roughly square patch (8 x 8), which shares 8 + 8 operand tiles instead of 1 + 64.
-constexpr int kBand = 8;
+// Order of the tiles of an n_r x n_c grid (weight gradients): bands of kGridBand rows; inside a
+// band column by column, the band's rows innermost.  The ~64 tiles a set of compute units works
+// on at one time then form a roughly square patch (8 x 8), which shares 8 + 8 operand tiles
+// instead of 1 + 64.
+constexpr int kGridBand = 8;
 __device__ __forceinline__ void band_order(int idx, int n_r, int n_c, int &r, int &c)
 {
-    const int band = idx / (kBand * n_c), within = idx - band * (kBand * n_c);
-    const int rows_here = min(kBand, n_r - band * kBand);
+    const int band = idx / (kGridBand * n_c), within = idx - band * (kGridBand * n_c);
+    const int rows_here = min(kGridBand, n_r - band * kGridBand);
     c = within / rows_here;
-    r = band * kBand + within - c * rows_here;
+    r = band * kGridBand + within - c * rows_here;
 }
 
 // Physical block -> tile.  The hardware deals blocks to the 8 XCDs round-robin (blockIdx % 8);
@@ -198,13 +211,11 @@ __device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     t.valid = logical < total && (int)(blockIdx.x >> 3) < per_xcd;
     if (!t.valid) return t;
-    int rt, ct;
-    if (n_col_tiles > kBand) {
-        band_order(logical, n_rt, n_col_tiles, rt, ct);
-    } else {                                  // few column tiles: a row tile's columns already run side by side
-        rt = logical / n_col_tiles;
-        ct = logical - rt * n_col_tiles;
-    }
+    // the band that holds row tile logical / n_col_tiles holds tile `logical`
+    const int band = s.tile_band[logical / n_col_tiles];
+    const int first = band & 0xffffff, rows_here = band >> 24;
+    const int within = logical - first * n_col_tiles;
+    const int ct = within / rows_here, rt = first + within - ct * rows_here;
     t.group = s.tile_group[rt];
     t.row0 = s.tile_row0[rt];
     t.rows = s.tile_rows[rt];
