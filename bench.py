@@ -446,7 +446,10 @@ def main():
                                "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd); "
                                + ("weight gradients once per batch over all resident micro-batches" if batched
                                   else "weight gradients accumulated micro-batch by micro-batch")
-                               + ("; row gather fused into the GEMMs" if fused_gather else ""),
+                               + ("; row gather fused into the GEMMs" if fused_gather else "")
+                               + {"fwd-transposed": "; forward GEMMs on transposed weight copies made once per step",
+                                  "bwd-transposed": "; data gradients on transposed weight copies made once per step",
+                                  "plain": ""}[args.weights],
                    "flops_per_step": flops_step},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "gemm_kernels": kernels, "gemm_only_tflops": gemm_tflops,
