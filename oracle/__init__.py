@@ -209,6 +209,42 @@ def moe_time(x, rank_of, rpn, model, beta=20.0, t_ref=1.0):
     return dict(T=out[0], T_comp=out[1], T_comm=out[2], smooth=out[3])
 
 
+def assign_sources(x, rpn, inst_ptr, inst_rank, inst_rows):
+    """x [EP,E] + one micro-batch's instance tables -> y [n_inst, EP] int64 (tokens of source j served by instance i)."""
+    x = _i64(x)
+    EP, E = x.shape
+    inst_ptr, inst_rank, inst_rows = _i32(inst_ptr), _i32(inst_rank), _i32(inst_rows)
+    y = np.zeros((inst_rank.shape[0], EP), np.int64)
+    rc = lib().oracle_assign_sources(_p(x), E, EP, int(rpn), _p(inst_ptr), _p(inst_rank), _p(inst_rows), _p(y))
+    if rc:
+        raise ValueError(f"oracle_assign_sources: status {rc}")
+    return y
+
+
+def moe_time_split(y, inst_rank, rpn, model):
+    """-> dict(T, T_comp, T_comm) in seconds (Eq. 4-6) and loads [5, EP] in tokens under the split y."""
+    y, inst_rank = _i64(y), _i32(inst_rank)
+    n_inst, EP = y.shape
+    model = np.ascontiguousarray(model, dtype=np.float64)
+    out = np.empty(3, np.float64)
+    loads_ = np.empty((5, EP), np.int64)
+    lib().oracle_moe_time_split(_p(y), n_inst, EP, int(rpn), _p(inst_rank), _p(model), _p(out), _p(loads_))
+    return dict(T=out[0], T_comp=out[1], T_comm=out[2]), loads_
+
+
+def permute_src(ids, E, EP, inst_ptr, inst_group, group_offset, y):
+    """Permutation that honours the per-source split y -> (row_of[N], src_of[N])."""
+    ids = _i32(ids)
+    T, k = ids.shape
+    row_of = np.full(T * k, -1, np.int32)
+    src_of = np.full(T * k, -1, np.int32)
+    rc = lib().oracle_permute_src(_p(ids), T, k, E, EP, _p(_i32(inst_ptr)), _p(_i32(inst_group)),
+                                  _p(_i32(group_offset)), _p(_i64(y)), _p(row_of), _p(src_of))
+    if rc:
+        raise ValueError(f"oracle_permute_src: status {rc}")
+    return row_of, src_of
+
+
 def reorder_sa(x, rpn, model, beta=20.0, gamma=0.999, eps=1e-3, n_seeds=8, seed=0):
     """Algorithm 1 -> (rank_of [E], dict(T_start, T, smooth_start, smooth, iterations))."""
     x = _i64(x)

@@ -687,6 +687,126 @@ int oracle_permute(const int32_t *ids, int T, int k, int E,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Source-aware token split (Section 5.2: y_{j,e,g}, the share of source GPU   */
+/* j's tokens of expert e that GPU g serves; Section 4.1 for the link types).   */
+/* The plan fixes how many tokens each instance of an expert serves (the        */
+/* computation split).  Which SOURCES fill an instance is still free, and it    */
+/* decides the traffic: all instances of e sit in one node, so for source j     */
+/* exactly one rank of that node is "aligned" with j (j itself inside the node, */
+/* the rank with j's index inside its node otherwise); a token served there     */
+/* is a local copy or a same-rail transfer, served anywhere else in the node    */
+/* it crosses the intra-node link once more.  RDMA volume does not depend on    */
+/* the choice.  Per expert:                                                     */
+/*   1. every instance takes tokens of its own rank (local copies);             */
+/*   2. every instance, ascending, takes tokens of the other sources aligned    */
+/*      with it, ascending source;                                              */
+/*   3. what is left goes source by source (ascending) to the instances that    */
+/*      still have room (ascending).                                            */
+/* Steps 1-2 give every instance min(room, aligned tokens): the aligned sets of  */
+/* different instances are disjoint, so the number of tokens that cross the      */
+/* intra-node link is the smallest any split with these instance sizes can have. */
+/* y[i*EP + j] = tokens of source j served by instance i (CSR order of the plan). */
+/* returns 0, or -3 if an expert's instance sizes do not add up to its tokens.   */
+int oracle_assign_sources(const i64 *x, int E, int EP, int rpn, const int32_t *inst_ptr,
+                          const int32_t *inst_rank, const int32_t *inst_rows, i64 *y)
+{
+    i64 *left = (i64 *)malloc(sizeof(i64) * EP);
+    for (int e = 0; e < E; ++e) {
+        int lo = inst_ptr[e], hi = inst_ptr[e + 1];
+        i64 have = 0, want = 0;
+        for (int j = 0; j < EP; ++j) { left[j] = x[(size_t)j * E + e]; have += left[j]; }
+        for (int i = lo; i < hi; ++i) {
+            want += inst_rows[i];
+            for (int j = 0; j < EP; ++j) y[(size_t)i * EP + j] = 0;
+        }
+        if (have != want) { free(left); return -3; }
+        i64 *room = (i64 *)malloc(sizeof(i64) * (hi - lo + 1));
+        for (int i = lo; i < hi; ++i) room[i - lo] = inst_rows[i];
+        for (int i = lo; i < hi; ++i) {                      /* 1: local copies */
+            int j = inst_rank[i];
+            i64 m = left[j] < room[i - lo] ? left[j] : room[i - lo];
+            y[(size_t)i * EP + j] += m; left[j] -= m; room[i - lo] -= m;
+        }
+        for (int i = lo; i < hi; ++i)                        /* 2: same rail, other nodes */
+            for (int j = 0; j < EP; ++j) {
+                if (oracle_tau(j, inst_rank[i], rpn) != 2) continue;
+                i64 m = left[j] < room[i - lo] ? left[j] : room[i - lo];
+                y[(size_t)i * EP + j] += m; left[j] -= m; room[i - lo] -= m;
+            }
+        for (int j = 0; j < EP; ++j)                         /* 3: the rest */
+            for (int i = lo; i < hi; ++i) {
+                i64 m = left[j] < room[i - lo] ? left[j] : room[i - lo];
+                y[(size_t)i * EP + j] += m; left[j] -= m; room[i - lo] -= m;
+            }
+        free(room);
+    }
+    free(left);
+    return 0;
+}
+
+/* Loads (Eq. 1-3) and times (Eq. 4-6) of a micro-batch under a split y: instance i  */
+/* on rank inst_rank[i] serves y[i][j] tokens of source j.  model as in             */
+/* oracle_moe_time; out[0] = T_MoE, out[1] = max T_comp, out[2] = max T_comm;        */
+/* loads[5][EP] = computation, intra-node send, receive, RDMA send, receive (tokens). */
+void oracle_moe_time_split(const i64 *y, int n_inst, int EP, int rpn, const int32_t *inst_rank,
+                           const double *model, double *out, i64 *loads)
+{
+    i64 *comp = loads, *nv_tx = loads + EP, *nv_rx = loads + 2 * EP, *rd_tx = loads + 3 * EP, *rd_rx = loads + 4 * EP;
+    for (int g = 0; g < 5 * EP; ++g) loads[g] = 0;
+    for (int i = 0; i < n_inst; ++i) {
+        int g = inst_rank[i];
+        if (g < 0) continue;
+        for (int j = 0; j < EP; ++j) {
+            i64 n = y[(size_t)i * EP + j];
+            int tau = oracle_tau(j, g, rpn);
+            comp[g] += n;
+            if (tau == 1 || tau == 3) { nv_tx[j] += n; nv_rx[g] += n; }
+            if (tau == 2 || tau == 3) { rd_tx[j] += n; rd_rx[g] += n; }
+        }
+    }
+    double tc = 0, tm = 0;
+    for (int g = 0; g < EP; ++g) {
+        double c = model[0] * (double)comp[g];
+        double nv = model[1] * (double)(nv_tx[g] > nv_rx[g] ? nv_tx[g] : nv_rx[g]);
+        double rd = model[2] * (double)(rd_tx[g] > rd_rx[g] ? rd_tx[g] : rd_rx[g]);
+        double m = nv > rd ? nv : rd;
+        if (c > tc) tc = c;
+        if (m > tm) tm = m;
+    }
+    out[0] = tc + tm; out[1] = tc; out[2] = tm;
+}
+
+/* Permutation under a source-aware split: assignment a = t*k + s, token t on source  */
+/* j = t / (T/EP), expert e, ordinal q among the assignments of (j, e) in ascending a. */
+/* The instances of e (CSR order) take runs of y[i][j] ordinals of source j; inside   */
+/* instance i the rows are laid out source after source.                              */
+int oracle_permute_src(const int32_t *ids, int T, int k, int E, int EP,
+                       const int32_t *inst_ptr, const int32_t *inst_group, const int32_t *group_offset,
+                       const i64 *y, int32_t *row_of, int32_t *src_of)
+{
+    int N = T * k;
+    if (EP < 1 || T % EP) return -1;
+    int per = T / EP;
+    int32_t *seen = (int32_t *)calloc((size_t)EP * E, sizeof(int32_t));
+    for (int a = 0; a < N; ++a) {
+        int e = ids[a], j = (a / k) / per;
+        if (e < 0 || e >= E) { free(seen); return -2; }
+        int q = seen[(size_t)j * E + e]++;
+        int i = inst_ptr[e];
+        i64 before = 0;
+        while (i < inst_ptr[e + 1] && q >= before + y[(size_t)i * EP + j]) { before += y[(size_t)i * EP + j]; ++i; }
+        if (i >= inst_ptr[e + 1]) { free(seen); return -3; }
+        i64 base = 0;
+        for (int jj = 0; jj < j; ++jj) base += y[(size_t)i * EP + jj];
+        int row = group_offset[inst_group[i]] + (int)(base + (q - before));
+        row_of[a] = row;
+        src_of[row] = a;
+    }
+    free(seen);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Floating point.  bf16 bit patterns widen exactly to double.                */
 static inline double bf(uint16_t b)
 {
