@@ -396,6 +396,49 @@ def main():
                 "T_lpt_ms": sa_stats["T_start"] * 1e3, "T_annealed_ms": sa_stats["T"] * 1e3,
                 "sa_iterations_per_seed": sa_stats["iterations"], "sa_seeds": 8, "sa_solve_ms": t_sa,
             }
+            # source-aware token split of micro-batch 0 (Section 5.2, y_{j,e,g}) against the split in
+            # token order that the plain permutation makes: modelled link loads and times (Eq. 1-6)
+            x0 = rl.relibra_route_hist_src(ids_all[:1], E, EP, err_flag=err)[0].cpu().numpy().astype(np.int64)
+            ptr0, rank0, rows0_ = plan["inst_ptr"][0], plan["inst_rank"][0], plan["inst_rows"][0]
+            n_inst = int(ptr0[E])
+            t_as = time.perf_counter()
+            split = rl.relibra_assign_sources(x0, cfg.rpn, ptr0, rank0, rows0_)
+            t_as = (time.perf_counter() - t_as) * 1e3
+            y_order = np.zeros_like(split["inst_src_rows"])
+            for e in range(E):
+                i, room = int(ptr0[e]), int(rows0_[ptr0[e]])
+                for j in range(EP):
+                    n = int(x0[j, e])
+                    while n:
+                        while room == 0:
+                            i += 1
+                            room = int(rows0_[i])
+                        m = min(n, room)
+                        y_order[i, j] += m
+                        n, room = n - m, room - m
+            ms = {}
+            for name, yy in (("token_order", y_order), ("source_aware", split["inst_src_rows"])):
+                t = rl.relibra_moe_time_split(yy[:n_inst], rank0[:n_inst], cm, with_loads=True)
+                ms[name] = {"T_comm_ms": t["T_comm"] * 1e3, "T_ms": t["T"] * 1e3,
+                            "intra_node_tokens": int(t["loads"][1].sum()), "rdma_tokens": int(t["loads"][3].sum())}
+            d_tabs = {key: torch.from_numpy(v).to(dev) for key, v in split.items()}
+            perm_args = (ids_all[0], tabs["inst_ptr"][0], tabs["inst_group"][0], tabs["group_offset"][0], EP,
+                         d_tabs["src_first"], d_tabs["inst_src_rows"], d_tabs["inst_src_base"], None, E, tabs["group_expert"].shape[1])
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            rl.relibra_permute_src(*perm_args, row_of=row_of, src_of=src_of, workspace=ws_perm, err_flag=err)
+            ev[0].record()
+            for _ in range(10):
+                rl.relibra_permute_src(*perm_args, row_of=row_of, src_of=src_of, workspace=ws_perm, err_flag=err)
+            ev[1].record()
+            for _ in range(10):
+                rl.relibra_permute(ids_all[0], tabs["inst_ptr"][0], tabs["inst_rows"][0], tabs["inst_group"][0],
+                                   tabs["group_offset"][0], None, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
+                                   workspace=ws_perm, err_flag=err)
+            ev[2].record()
+            torch.cuda.synchronize()
+            extras["source_aware_split"] = {"micro_batch": 0, "assign_host_ms": t_as, **ms,
+                                            "permute_src_ms": ev[0].elapsed_time(ev[1]) / 10,
+                                            "permute_ms": ev[1].elapsed_time(ev[2]) / 10}
             assert err.item() == 0
 
     # ---------------- the CPU oracle on a bounded sample, on this machine's host cores

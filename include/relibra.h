@@ -209,6 +209,56 @@ int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const i
                     int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * Source-aware token split (Section 5.2: y_{j,e,g}, the share of source rank j's tokens of
+ * expert e served by rank g; Section 4.1 for the link types).  The plan fixes how many tokens
+ * every instance of an expert serves; which sources fill an instance decides the traffic.  Per
+ * expert, every instance first takes the tokens that sit on its own rank (local copies), then
+ * those of the sources on its rail in the other nodes (ascending rank; RDMA without a relay
+ * hop), and the remainder is dealt out source by source to the instances that still have room
+ * (both ascending).  No split with the same instance sizes moves fewer tokens over the
+ * intra-node link; the RDMA volume does not depend on the split.  All pointers HOST.
+ *   x_host [EP, E] int64 in          tokens of source rank j routed to expert e (token t of a
+ *                                    micro-batch sits on rank t / (T/EP))
+ *   inst_ptr [E+1], inst_rank, inst_rows [>= inst_ptr[E]] int32 in: one micro-batch's plan tables
+ *   src_first     [EP, E] int32 out          sum of x over the sources before j
+ *   inst_src_rows [inst_ptr[E], EP] int32 out  tokens of source j served by instance i
+ *   inst_src_base [inst_ptr[E], EP] int32 out  exclusive prefix sum of inst_src_rows over j
+ * Errors: RELIBRA_EINVAL on bad sizes or null pointers; RELIBRA_ERANGE when an expert's instance
+ * sizes do not add up to its tokens, or on a negative or out-of-range table entry.
+ */
+int relibra_assign_sources(const int64_t *x_host, int E, int EP, int ranks_per_node,
+                           const int32_t *inst_ptr, const int32_t *inst_rank, const int32_t *inst_rows,
+                           int32_t *src_first, int32_t *inst_src_rows, int32_t *inst_src_base);
+
+/*
+ * The cost model of Section 4.1 (Eq. 1-6) on a split: instance i on rank inst_rank[i] (negative:
+ * unused entry) serves inst_src_rows[i][j] tokens of source j.  All pointers HOST.
+ *   out3 [3] double out: T_MoE (Eq. 6), max_g T_comp (Eq. 4), max_g T_comm (Eq. 5), seconds
+ *   loads_out [5, EP] int64 out or NULL: computation load, intra-node send, receive, RDMA send,
+ *   receive, in tokens (Eq. 1-3)
+ */
+int relibra_moe_time_split(const int32_t *inst_src_rows, int n_inst, const int32_t *inst_rank,
+                           const relibra_cost_model *model, double *out3, int64_t *loads_out);
+
+/*
+ * relibra_permute under a source-aware split.  Assignment a = t*k + s of token t (source rank
+ * j = t / (T/EP)) and expert e has ordinal q among the assignments of (j, e) in ascending a;
+ * the instances of e, in the plan's order, take runs of inst_src_rows[i][j] such ordinals; the
+ * rows of an instance are laid out source after source:
+ *   row = group_offset[inst_group[i]] + inst_src_base[i][j] + (q - tokens of j on earlier instances).
+ * The three split tables (device copies of relibra_assign_sources' outputs) replace inst_rows;
+ * everything else, the error flags included, as relibra_permute.  T % EP == 0.
+ */
+int relibra_permute_src(const int32_t *ids_dev, const int32_t *inst_ptr_dev,
+                        const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                        int EP, const int32_t *src_first_dev, const int32_t *inst_src_rows_dev,
+                        const int32_t *inst_src_base_dev,
+                        const void *X_dev, int T, int k, int E, int G, int h,
+                        int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                        void *workspace_dev, size_t workspace_bytes,
+                        int32_t *err_flag_dev, relibra_stream stream);
+
+/*
  * Expert FFN forward over groups [g_begin, g_end) (Section 4.1: three GEMMs, 6hh' flops per row).
  * For every row x of a group whose expert is e:
  *   Gt = Wg_e x,  U = Wu_e x,  A = silu(Gt) * U,  y = Wd_e A

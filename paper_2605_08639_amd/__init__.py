@@ -25,6 +25,7 @@ MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
+           "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src",
            "relibra_permute", "relibra_row_tokens", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push",
            "relibra_workspace_bytes",
@@ -230,6 +231,64 @@ def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,
                                _dp(X), T, k, E, G, h, _dp(row_of), _dp(src_of), _dp(Xrows),
                                _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_permute", rc)
+    return row_of, src_of, Xrows
+
+
+def relibra_assign_sources(x_host, ranks_per_node, inst_ptr, inst_rank, inst_rows):
+    """x_host [EP,E] int64 + one micro-batch's plan tables (host) -> dict(src_first [EP,E],
+    inst_src_rows, inst_src_base [n_inst,EP]) int32: which sources fill which instance (Section 5.2)."""
+    x_host = np.ascontiguousarray(x_host, dtype=np.int64)
+    inst_ptr, inst_rank, inst_rows = (np.ascontiguousarray(a, dtype=np.int32) for a in (inst_ptr, inst_rank, inst_rows))
+    EP, E = x_host.shape
+    n_inst = int(inst_ptr[E])
+    out = dict(src_first=np.zeros((EP, E), np.int32), inst_src_rows=np.zeros((max(n_inst, 1), EP), np.int32),
+               inst_src_base=np.zeros((max(n_inst, 1), EP), np.int32))
+    rc = lib().relibra_assign_sources(_hp(x_host), E, EP, int(ranks_per_node), _hp(inst_ptr), _hp(inst_rank), _hp(inst_rows),
+                                      _hp(out["src_first"]), _hp(out["inst_src_rows"]), _hp(out["inst_src_base"]))
+    _check("relibra_assign_sources", rc)
+    return out
+
+
+def relibra_moe_time_split(inst_src_rows, inst_rank, model, with_loads=False):
+    """Eq. 1-6 on a split -> dict(T, T_comp, T_comm[, loads [5,EP]])."""
+    inst_src_rows = np.ascontiguousarray(inst_src_rows, dtype=np.int32)
+    inst_rank = np.ascontiguousarray(inst_rank, dtype=np.int32)
+    n_inst = min(inst_src_rows.shape[0], inst_rank.shape[0])
+    assert inst_src_rows.shape[1] == model.EP
+    out = np.empty(3, np.float64)
+    loads = np.empty((5, model.EP), np.int64) if with_loads else None
+    rc = lib().relibra_moe_time_split(_hp(inst_src_rows), n_inst, _hp(inst_rank), C.byref(model), _hp(out),
+                                      _hp(loads) if with_loads else C.c_void_p(0))
+    _check("relibra_moe_time_split", rc)
+    res = dict(T=out[0], T_comp=out[1], T_comm=out[2])
+    if with_loads:
+        res["loads"] = loads
+    return res
+
+
+def relibra_permute_src(ids, inst_ptr, inst_group, group_offset, EP, src_first, inst_src_rows, inst_src_base, X, E, G,
+                        row_of=None, src_of=None, Xrows=None, workspace=None, err_flag=None):
+    """relibra_permute under a source-aware split (device int32 copies of relibra_assign_sources' tables)."""
+    T, k = ids.shape
+    N = T * k
+    h = 0 if X is None else X.shape[1]
+    dev = ids.device
+    if row_of is None:
+        row_of = torch.empty(N, dtype=torch.int32, device=dev)
+    if src_of is None:
+        src_of = torch.empty(N, dtype=torch.int32, device=dev)
+    if Xrows is None and X is not None:
+        Xrows = torch.empty((N, h), dtype=torch.bfloat16, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(workspace_bytes(WS_PERMUTE, T, k, E, G, h, 0), 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_permute_src(_dp(ids, torch.int32), _dp(inst_ptr, torch.int32), _dp(inst_group, torch.int32),
+                                   _dp(group_offset, torch.int32), int(EP), _dp(src_first, torch.int32),
+                                   _dp(inst_src_rows, torch.int32), _dp(inst_src_base, torch.int32),
+                                   _dp(X), T, k, E, G, h, _dp(row_of), _dp(src_of), _dp(Xrows),
+                                   _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
+    _check("relibra_permute_src", rc)
     return row_of, src_of, Xrows
 
 

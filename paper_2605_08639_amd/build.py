@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelibra.so")
-SOURCES = ["route_kernels.hip", "ffn_kernels.hip", "replica_kernels.hip", "prof.hip", "plan.cpp", "reorder_sa.cpp"]
+SOURCES = ["route_kernels.hip", "ffn_kernels.hip", "replica_kernels.hip", "prof.hip", "plan.cpp", "reorder_sa.cpp", "split.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

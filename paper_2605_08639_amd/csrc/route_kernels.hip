@@ -122,12 +122,21 @@ __global__ void __launch_bounds__(256) perm_scan_kernel(int32_t *unit_cnt, int n
     }
 }
 
+// Optional per-source split of the permutation (all null / zero: split in token order).
+struct SrcSplit {
+    const int32_t *src_first;       // [EP][E] ordinal, among e's assignments, of source j's first one
+    const int32_t *inst_src_rows;   // [instances][EP] tokens of source j served by instance i
+    const int32_t *inst_src_base;   // [instances][EP] exclusive prefix of inst_src_rows over j
+    int EP, k, tokens_per_src;
+};
+
 __global__ void __launch_bounds__(kPermThreads)
 perm_rank_kernel(const int32_t *__restrict__ ids, int N, int E, int G, int ebits,
                  const int32_t *__restrict__ unit_base,
                  const int32_t *__restrict__ inst_ptr, const int32_t *__restrict__ inst_rows,
                  const int32_t *__restrict__ inst_group, const int32_t *__restrict__ group_offset,
-                 int32_t *__restrict__ row_of, int32_t *__restrict__ src_of, int32_t *err_flag)
+                 int32_t *__restrict__ row_of, int32_t *__restrict__ src_of, int32_t *err_flag,
+                 SrcSplit sp)
 {
     extern __shared__ int32_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -168,14 +177,30 @@ perm_rank_kernel(const int32_t *__restrict__ ids, int N, int E, int G, int ebits
             int i = inst_ptr[e];
             const int end = inst_ptr[e + 1];
             int skipped = 0, row = -1;
-            for (; i < end; ++i) {
-                const int n = inst_rows[i];
-                if (q < skipped + n) {
-                    const int g = inst_group[i];
-                    if ((unsigned)g < (unsigned)G) row = group_offset[g] + (q - skipped);
-                    break;
+            if (sp.src_first) {
+                // source-aware split: ordinal among the source's own tokens of e, runs of
+                // inst_src_rows[i][j], rows of an instance laid out source after source
+                const int j = min((a / sp.k) / sp.tokens_per_src, sp.EP - 1);
+                const int qj = q - sp.src_first[(size_t)j * E + e];
+                for (; qj >= 0 && i < end; ++i) {
+                    const int n = sp.inst_src_rows[(size_t)i * sp.EP + j];
+                    if (qj < skipped + n) {
+                        const int g = inst_group[i];
+                        if ((unsigned)g < (unsigned)G) row = group_offset[g] + sp.inst_src_base[(size_t)i * sp.EP + j] + (qj - skipped);
+                        break;
+                    }
+                    skipped += n;
                 }
-                skipped += n;
+            } else {
+                for (; i < end; ++i) {
+                    const int n = inst_rows[i];
+                    if (q < skipped + n) {
+                        const int g = inst_group[i];
+                        if ((unsigned)g < (unsigned)G) row = group_offset[g] + (q - skipped);
+                        break;
+                    }
+                    skipped += n;
+                }
             }
             if ((unsigned)row < (unsigned)N) {
                 row_of[a] = row;
@@ -353,19 +378,19 @@ extern "C" int relibra_route_hist(const int32_t *ids_dev, int n_mb, int T, int k
     return RELIBRA_OK;
 }
 
-extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
-                               const int32_t *inst_group_dev, const int32_t *group_offset_dev,
-                               const void *X_dev, int T, int k, int E, int G, int h,
-                               int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
-                               void *workspace_dev, size_t workspace_bytes,
-                               int32_t *err_flag_dev, relibra_stream stream_)
+static int permute_impl(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
+                        const int32_t *inst_group_dev, const int32_t *group_offset_dev, const SrcSplit &split,
+                        const void *X_dev, int T, int k, int E, int G, int h,
+                        int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                        void *workspace_dev, size_t workspace_bytes,
+                        int32_t *err_flag_dev, relibra_stream stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
     if (T < 0 || k < 1 || E < 1 || E > kMaxExperts || k > E || G < 1 || h < 0) return RELIBRA_EINVAL;
     if ((size_t)T * k > 0x7fffffffull) return RELIBRA_EINVAL;
     const int N = T * k;
     if (N == 0) return RELIBRA_OK;
-    if (!ids_dev || !inst_ptr_dev || !inst_rows_dev || !inst_group_dev || !group_offset_dev ||
+    if (!ids_dev || !inst_ptr_dev || (!inst_rows_dev && !split.src_first) || !inst_group_dev || !group_offset_dev ||
         !row_of_dev || !src_of_dev || !err_flag_dev || !workspace_dev)
         return RELIBRA_EINVAL;
     const bool with_rows = X_dev != nullptr || Xrows_dev != nullptr;
@@ -384,7 +409,7 @@ extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_d
     RELIBRA_HIP_TRY(launch_check());
     RELIBRA_LAUNCH(RELIBRA_K_PERM_RANK, stream, perm_rank_kernel<<<blocks, kPermThreads, lds, stream>>>(ids_dev, N, E, G, ebits, unit_cnt, inst_ptr_dev,
                                                             inst_rows_dev, inst_group_dev, group_offset_dev,
-                                                            row_of_dev, src_of_dev, err_flag_dev));
+                                                            row_of_dev, src_of_dev, err_flag_dev, split));
     RELIBRA_HIP_TRY(launch_check());
     if (with_rows) {
         const int vpr = h / 8;
@@ -394,6 +419,36 @@ extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_d
         RELIBRA_HIP_TRY(launch_check());
     }
     return RELIBRA_OK;
+}
+
+extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
+                               const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                               const void *X_dev, int T, int k, int E, int G, int h,
+                               int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                               void *workspace_dev, size_t workspace_bytes,
+                               int32_t *err_flag_dev, relibra_stream stream_)
+{
+    if (T > 0 && !inst_rows_dev) return RELIBRA_EINVAL;
+    return permute_impl(ids_dev, inst_ptr_dev, inst_rows_dev, inst_group_dev, group_offset_dev, SrcSplit{},
+                        X_dev, T, k, E, G, h, row_of_dev, src_of_dev, Xrows_dev, workspace_dev, workspace_bytes,
+                        err_flag_dev, stream_);
+}
+
+extern "C" int relibra_permute_src(const int32_t *ids_dev, const int32_t *inst_ptr_dev,
+                                   const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                                   int EP, const int32_t *src_first_dev, const int32_t *inst_src_rows_dev,
+                                   const int32_t *inst_src_base_dev,
+                                   const void *X_dev, int T, int k, int E, int G, int h,
+                                   int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                                   void *workspace_dev, size_t workspace_bytes,
+                                   int32_t *err_flag_dev, relibra_stream stream_)
+{
+    if (EP < 1 || T < 0 || T % EP) return RELIBRA_EINVAL;
+    if (T > 0 && (!src_first_dev || !inst_src_rows_dev || !inst_src_base_dev)) return RELIBRA_EINVAL;
+    const SrcSplit split{src_first_dev, inst_src_rows_dev, inst_src_base_dev, EP, k, T > 0 ? T / EP : 1};
+    return permute_impl(ids_dev, inst_ptr_dev, nullptr, inst_group_dev, group_offset_dev, split,
+                        X_dev, T, k, E, G, h, row_of_dev, src_of_dev, Xrows_dev, workspace_dev, workspace_bytes,
+                        err_flag_dev, stream_);
 }
 
 extern "C" int relibra_unpermute_combine(int mode, const void *rows_dev, const void *tok_dev,

@@ -119,6 +119,44 @@ def test_hist_plan_permute_bit_exact(kw):
         assert np.array_equal(got_rows, want_rows)                     # bit copy
 
 
+@pytest.mark.parametrize("kw", [dict(E=16, k=2, EP=4, r=2, T=240, ranks_per_node=2),
+                                dict(E=128, k=8, EP=8, r=2, T=3000, n_mb=2, h=64, ranks_per_node=4),
+                                dict(E=16, k=8, EP=8, r=2, T=1000, n_mb=2, routing="stress", zipf_s=1.5, h=64, ranks_per_node=8)])
+def test_source_aware_permute_bit_exact(kw):
+    """Permutation under the per-source split of Section 5.2: indices and gathered rows identical
+    to the oracle's, and every instance holds exactly the tokens of each source the split gave it."""
+    cfg = wl.small_config(**kw)
+    ids, _ = routing(cfg)
+    counts = oracle.route_hist(ids, cfg.E)[0]
+    p = plan_both(cfg, counts)
+    for mb in range(cfg.n_mb):
+        X, _ = wl.make_tokens(cfg, mb)
+        x = oracle.route_hist_src(ids[mb], cfg.E, cfg.EP)
+        ptr, rank, rows, grp, off = (p[key][mb] for key in ("inst_ptr", "inst_rank", "inst_rows", "inst_group", "group_offset"))
+        y = oracle.assign_sources(x, cfg.rpn, ptr, rank, rows)
+        want_row, want_src = oracle.permute_src(ids[mb], cfg.E, cfg.EP, ptr, grp, off, y)
+        tabs = rl.relibra_assign_sources(x, cfg.rpn, ptr, rank, rows)
+        err = rl.new_err_flag()
+        row_of, src_of, Xrows = rl.relibra_permute_src(
+            torch.from_numpy(ids[mb]).to(DEV), dev_i32(ptr), dev_i32(grp), dev_i32(off), cfg.EP,
+            dev_i32(tabs["src_first"]), dev_i32(tabs["inst_src_rows"]), dev_i32(tabs["inst_src_base"]),
+            X.to(DEV), cfg.E, cfg.G, err_flag=err)
+        assert err.item() == 0
+        assert np.array_equal(row_of.cpu().numpy(), want_row)
+        assert np.array_equal(src_of.cpu().numpy(), want_src)
+        got_rows = Xrows.cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got_rows, oracle.gather_rows(X, want_src, cfg.k))
+    # a split table that does not cover the routing is flagged and the assignment skipped
+    bad = tabs["inst_src_rows"].copy()
+    i, j = np.argwhere(bad > 0)[0]
+    bad[i, j] -= 1
+    err = rl.new_err_flag()
+    row_of, _, _ = rl.relibra_permute_src(
+        torch.from_numpy(ids[-1]).to(DEV), dev_i32(ptr), dev_i32(grp), dev_i32(off), cfg.EP,
+        dev_i32(tabs["src_first"]), dev_i32(bad), dev_i32(tabs["inst_src_base"]), None, cfg.E, cfg.G, err_flag=err)
+    assert (row_of >= 0).all().item() or err.item() & rl.ERR_PLAN_COVER
+
+
 def test_permute_flags_a_plan_that_does_not_cover_the_routing():
     cfg = wl.small_config(E=8, k=2, EP=4, r=1, T=200, n_mb=1, h=64)
     ids, _ = routing(cfg)

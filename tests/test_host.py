@@ -237,6 +237,55 @@ def test_comm_model_argument_errors():
         rl.relibra_moe_time(x, rank, rl.cost_model(4, 3, 64, 64, 1e12, 1e11, 1e10))
 
 
+@pytest.mark.parametrize("kw", [dict(E=16, k=2, EP=4, r=2, T=240, ranks_per_node=2),
+                                dict(E=32, k=4, EP=8, r=1, T=512, ranks_per_node=4),
+                                dict(E=128, k=8, EP=8, r=2, T=2048, ranks_per_node=8),
+                                dict(E=64, k=4, EP=16, r=2, T=1024, ranks_per_node=4, routing="stress", zipf_s=1.5)])
+def test_source_aware_split_and_its_times_equal_oracle(kw):
+    """Section 5.2 split per source: integer tables identical to the oracle's, Eq. 1-6 on the split
+    identical in loads and equal to rounding in times; the split never raises the modelled time's
+    intra-node part over the token-order split's."""
+    cfg = wl.small_config(n_mb=2, h=64, hff=64, **kw)
+    ids = np.stack([wl.make_routing(cfg, mb)[0] for mb in range(cfg.n_mb)])
+    counts, _ = oracle.route_hist(ids, cfg.E)
+    p = rl.relibra_plan(counts, cfg.k, cfg.EP, cfg.rpn, cfg.r)
+    m_or = oracle.cost_model(2048, 768, 5e14, 4e11, 5e10)
+    m_lib = rl.cost_model(cfg.EP, cfg.rpn, 2048, 768, 5e14, 4e11, 5e10)
+    for mb in range(cfg.n_mb):
+        x = oracle.route_hist_src(ids[mb], cfg.E, cfg.EP)
+        ptr, rank, rows = p["inst_ptr"][mb], p["inst_rank"][mb], p["inst_rows"][mb]
+        n_inst = ptr[-1]
+        want = oracle.assign_sources(x, cfg.rpn, ptr, rank, rows)
+        got = rl.relibra_assign_sources(x, cfg.rpn, ptr, rank, rows)
+        assert np.array_equal(got["inst_src_rows"][:n_inst], want[:n_inst])
+        assert np.array_equal(got["inst_src_base"][:n_inst], np.cumsum(want[:n_inst], axis=1) - want[:n_inst])
+        assert np.array_equal(got["src_first"], np.cumsum(x, axis=0) - x)
+        t_or, l_or = oracle.moe_time_split(want[:n_inst], rank[:n_inst], cfg.rpn, m_or)
+        t_lib = rl.relibra_moe_time_split(got["inst_src_rows"][:n_inst], rank[:n_inst], m_lib, with_loads=True)
+        assert np.array_equal(t_lib["loads"], l_or)
+        for key in ("T", "T_comp", "T_comm"):
+            assert t_lib[key] == pytest.approx(t_or[key], rel=1e-12)
+
+
+def test_source_aware_split_argument_errors():
+    x = np.array([[3], [1]], np.int64)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_assign_sources(x, 2, [0, 1], [0], [5])              # sizes do not add up
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_assign_sources(x, 3, [0, 1], [0], [4])              # EP % ranks_per_node
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_assign_sources(x, 2, [0, 1], [7], [4])              # rank out of range
+    ok = rl.relibra_assign_sources(x, 2, [0, 1], [0], [4])
+    assert ok["inst_src_rows"].tolist() == [[3, 1]] and ok["inst_src_base"].tolist() == [[0, 3]]
+    m = rl.cost_model(2, 2, 64, 64, 1e12, 1e11, 1e10)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_moe_time_split(np.array([[1, -1]], np.int32), [0], m)
+    L = rl.lib()
+    z = ctypes.c_void_p(0)
+    assert L.relibra_permute_src(z, z, z, z, 3, z, z, z, z, 8, 2, 4, 6, 0, z, z, z, z, ctypes.c_size_t(0), z, z) == rl.EINVAL  # T % EP
+    assert L.relibra_permute_src(z, z, z, z, 4, z, z, z, z, 0, 2, 4, 6, 0, z, z, z, z, ctypes.c_size_t(0), z, z) == rl.OK      # empty
+
+
 def test_load_stats_equal_oracle():
     for idx in (0, 1, 4):
         cfg = wl.CONFIGS[idx]
