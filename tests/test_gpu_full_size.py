@@ -182,6 +182,12 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
     for a_, b_ in zip(fused, (Gt, U, A, Y)):
         assert torch.equal(a_, b_)
     del fused
+    W_t = [rl.relibra_transpose_experts(W) for W in (Wg_d, Wu_d, Wd_d)]
+    fused_t = rl.relibra_moe_ffn_fwd_gather(X_d, row_tok, tabs["group_offset"], tabs["group_expert"], *W_t, err_flag=err,
+                                            flags=rl.FWD_TRANSPOSED_WEIGHTS)
+    for a_, b_ in zip(fused_t, (Gt, U, A, Y)):
+        assert torch.equal(a_, b_)
+    del fused_t, W_t
     one_f = dict(one, Xrows=None, X=X_d, row_tok=row_tok)
     dWf = [torch.empty(s, dtype=torch.float32, device=DEV) for s in ((E, hff, h), (E, hff, h), (E, h, hff))]
     rl.relibra_moe_ffn_wgrad_batched([one_f, one_f], E, *dWf, err_flag=err)

@@ -599,6 +599,13 @@ def test_forward_with_fused_row_gather_is_bit_identical():
         assert err.item() == 0
         for a, b in zip(two_step, fused):
             assert torch.equal(a, b)
+        # and together with transposed weight copies (the benchmark's default forward)
+        W_t = [rl.relibra_transpose_experts(W) for W in (Wg, Wu, Wd)]
+        both = rl.relibra_moe_ffn_fwd_gather(Xd, row_tok, tabs["group_offset"], tabs["group_expert"], *W_t, err_flag=err,
+                                             flags=rl.FWD_TRANSPOSED_WEIGHTS)
+        assert err.item() == 0
+        for a, b in zip(two_step, both):
+            assert torch.equal(a, b)
     bad = src_of.clone()
     bad[3] = cfg.T * cfg.k + 7
     err = rl.new_err_flag()
