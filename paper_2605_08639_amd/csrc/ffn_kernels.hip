@@ -462,8 +462,8 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
 // ---------------------------------------------------------------- backward
 // dA = dY Wd, then dGt = dA * U * silu'(Gt), dU = dA * silu(Gt).
 // WT = false: Wd as the forward pass holds it, [h][h'], contraction index strided (transposing
-// LDS reads).  WT = true: a transposed copy [h'][h], contraction index contiguous (the faster
-// operand path; see relibra_transpose_experts).
+// LDS reads, full-line loads: the faster operand path).  WT = true: a transposed copy [h'][h],
+// contraction index contiguous.
 template <bool WT>
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
