@@ -228,6 +228,9 @@ def main():
     traffic_file = os.path.join(ROOT, "profiles", f"bench_config{args.config + 1}_hbm_traffic.json")
     measured = json.load(open(traffic_file))["kernels"] if os.path.exists(traffic_file) else {}
 
+    util_file = os.path.join(ROOT, "profiles", f"bench_config{args.config + 1}_mfma_util.json")
+    util = json.load(open(util_file))["kernels"] if os.path.exists(util_file) else {}
+
     kernels = {}
     for name, (ms, n) in prof.items():
         fl = GEMM_FLOP_FACTOR[name] * h * hff * N * (n_mb if batched and name.startswith("wgrad") else 1)
@@ -248,7 +251,10 @@ def main():
                     "unit": "TFLOP/s", "frac": kd["tflops"] / PEAK_BF16_TFLOPS}
     roofline.update({"traffic": (tr["read_bytes"] + tr["write_bytes"]) if tr else None, "avg_launch_ms": kd["avg_ms"],
                      "flops_per_launch": kd["flops_per_launch"], "alg_bytes_per_launch": kd["alg_bytes_per_launch"],
-                     "mfma_frac": kd["tflops"] / PEAK_BF16_TFLOPS})
+                     "mfma_frac": kd["tflops"] / PEAK_BF16_TFLOPS,
+                     # from a committed rocprofv3 counter run of this command (profiles/): the matrix pipes' busy share
+                     # of the cycles the chip actually ran, and that clock (the published peak assumes 2.4 GHz)
+                     "mfma_util_counter": util.get(dominant)})
     # mixed roofline of all six GEMM kernels: sum over kernels of max(flops/peak, bytes/bandwidth)
     floor_ms = sum(max(v["flops_per_launch"] / (PEAK_BF16_TFLOPS * 1e12), v["alg_bytes_per_launch"] / (PEAK_HBM_GBS * 1e9))
                    * v["launches"] / args.steps for v in kernels.values()) * 1e3          # per step
