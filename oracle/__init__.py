@@ -141,6 +141,45 @@ def plan(counts, EP, rpn, r, placed=None):
     return out
 
 
+def replicate_comm(x, rank_of, rpn, r, model):
+    """Algorithm 2 with the time of Section 4.1 as objective, one micro-batch:
+    x [EP,E] -> (z [E,EP] uint8, a [E,EP] int64, dict(T_before, T_after, max_load))."""
+    x, rank_of = _i64(x), _i32(rank_of)
+    EP, E = x.shape
+    model = np.ascontiguousarray(model, dtype=np.float64)
+    z = np.zeros((E, EP), np.uint8)
+    a = np.zeros((E, EP), np.int64)
+    T2 = np.zeros(2, np.float64)
+    lib().oracle_replicate_comm.restype = C.c_longlong
+    mx = lib().oracle_replicate_comm(_p(x), _p(rank_of), E, EP, int(rpn), int(r), _p(model), _p(z), _p(a), _p(T2))
+    return z, a, dict(T_before=T2[0], T_after=T2[1], max_load=int(mx))
+
+
+def plan_comm(x, rpn, r, placed, model):
+    """x [n_mb,EP,E] per-source histograms + placement -> plan tables with the time-aware replication."""
+    x = _i64(x)
+    n_mb, EP, E = x.shape
+    M = E // EP
+    G = EP * (M + r)
+    cap = E + EP * r
+    out = dict(
+        expert_to_slot=np.empty(E, np.int32), replica_expert=np.empty((n_mb, EP, r), np.int32),
+        inst_ptr=np.empty((n_mb, E + 1), np.int32), inst_rank=np.empty((n_mb, cap), np.int32),
+        inst_rows=np.empty((n_mb, cap), np.int32), inst_group=np.empty((n_mb, cap), np.int32),
+        group_expert=np.empty((n_mb, G), np.int32), group_offset=np.empty((n_mb, G + 1), np.int32),
+        max_before=np.empty(n_mb, np.int64), max_after=np.empty(n_mb, np.int64),
+        t_before=np.empty(n_mb, np.float64), t_after=np.empty(n_mb, np.float64))
+    model = np.ascontiguousarray(model, dtype=np.float64)
+    rc = lib().oracle_plan_comm(_p(x), n_mb, E, EP, int(rpn), int(r), _p(_i32(placed)), _p(model),
+                                _p(out["expert_to_slot"]), _p(out["replica_expert"]),
+                                _p(out["inst_ptr"]), _p(out["inst_rank"]), _p(out["inst_rows"]),
+                                _p(out["inst_group"]), _p(out["group_expert"]), _p(out["group_offset"]),
+                                _p(out["max_before"]), _p(out["max_after"]), _p(out["t_before"]), _p(out["t_after"]))
+    if rc:
+        raise ValueError(f"oracle_plan_comm: status {rc}")
+    return out
+
+
 def permute(ids, E, inst_ptr, inst_rows, inst_group, group_offset):
     """ids[T,k] + one micro-batch's plan tables -> (row_of[N], src_of[N])."""
     ids = _i32(ids)

@@ -540,58 +540,157 @@ static i64 replicate_mb(const int32_t *cnt_mb, const int32_t *rank_of, int E, in
     return worst;
 }
 
-/* Whole plan (Sections 4 and 5): reorder once per batch, replicate per micro-batch, */
-/* and keep the reordering only if it lowers J = sum over micro-batches of the max    */
-/* rank load after replication (ties keep the unplanned layout, which moves no        */
-/* expert).  Output tables:                                                           */
-/*   expert_to_slot[E]           rank*M + local slot (local slots by ascending id)     */
-/*   replica_expert[n_mb][EP][r] expert in each replica slot (ascending id), -1 empty  */
-/*   inst_ptr[n_mb][E+1], inst_rank/rows/group[n_mb][E+EP*r]                           */
-/*                               instances of each expert, ascending rank; the home    */
-/*                               instance is always listed                             */
-/*   group_expert[n_mb][G], group_offset[n_mb][G+1], G = EP*(M+r), rank-major:         */
-/*                               M home slots then r replica slots per rank            */
-/*   max_before[n_mb]            max rank load, unplanned layout, no replicas          */
-/*   max_after[n_mb]             max rank load under the plan                          */
-/* placed != NULL: that placement (rank per expert, M per rank) is used as it is   */
-/* and only the per-micro-batch replication runs (a placement found under another */
-/* objective, e.g. by the annealing of Algorithm 1).                              */
-int oracle_plan_ex(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r, const int32_t *placed,
-                   int32_t *expert_to_slot, int32_t *replica_expert,
-                   int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
-                   int32_t *group_expert, int32_t *group_offset,
-                   i64 *max_before, i64 *max_after)
+/* ------------------------------------------------------------------------- */
+/* Algorithm 2 with the execution time of Section 4.1 as its objective          */
+/* (Section 5.2: bottleneck GPU and least-loaded GPU by T_MoE,g, computation     */
+/* plus communication).  One micro-batch, whole EP group.                        */
+/*                                                                              */
+/* The state is z[e][g] / a[e][g] as above.  Its time: the instances of every    */
+/* expert (ranks with z = 1, ascending) get their sources from                   */
+/* oracle_assign_sources, the loads and times follow Eq. 1-6                     */
+/* (oracle_moe_time_split); T_g = T_g^comp + T_g^comm per GPU.                   */
+/* Loop: g_b = GPU of largest T_g (lowest id on ties); its experts with tokens   */
+/* served there, most tokens first (lower id on ties), are tried in turn: the    */
+/* target is the GPU of g_b's node without a copy of the expert and with a free  */
+/* slot whose T_g is smallest (lowest id); the copy is placed, the node's tokens */
+/* are split again (oracle_balance_split, warm start) and the move is kept if    */
+/* (T_MoE of Eq. 6, sum_g T_g^2) got lexicographically smaller (the second       */
+/* component moves when the maximum sits on a plateau, as in stage 1), otherwise */
+/* undone and the next expert is tried.  The loop ends when no expert of the     */
+/* bottleneck GPU gives a gain.                                                  */
+/* Copies that end with no tokens are dropped.  T2[0], T2[1] = T_MoE before and  */
+/* after; returns the largest computation load after.                            */
+int oracle_assign_sources(const i64 *x, int E, int EP, int rpn, const int32_t *inst_ptr,
+                          const int32_t *inst_rank, const int32_t *inst_rows, i64 *y);
+void oracle_moe_time_split(const i64 *y, int n_inst, int EP, int rpn, const int32_t *inst_rank,
+                           const double *model, double *out, i64 *loads);
+
+static double eval_state(const i64 *x, int E, int EP, int rpn, const uint8_t *z, const i64 *a,
+                         const double *model, double *tg, i64 *max_comp)
 {
-    if (E <= 0 || EP <= 0 || E % EP || rpn <= 0 || EP % rpn || r < 0 || n_mb <= 0) return -1;
-    int M = E / EP, G = EP * (M + r), cap_inst = E + EP * r;
-    i64 *l = (i64 *)calloc(E, sizeof(i64));
-    for (int mb = 0; mb < n_mb; ++mb)
-        for (int e = 0; e < E; ++e) {
-            if (counts[mb * E + e] < 0) { free(l); return -1; }
-            l[e] += counts[mb * E + e];
-        }
-    int32_t *p_id = (int32_t *)malloc(sizeof(int32_t) * E);
-    int32_t *p_new = (int32_t *)malloc(sizeof(int32_t) * E);
-    for (int e = 0; e < E; ++e) p_id[e] = e / M;
-    if (placed) memcpy(p_new, placed, sizeof(int32_t) * E);
-    else oracle_reorder(l, E, EP, p_new);
-
-    size_t zsz = (size_t)E * EP;
-    uint8_t *z_id = (uint8_t *)malloc(zsz * n_mb), *z_new = (uint8_t *)malloc(zsz * n_mb);
-    i64 *a_id = (i64 *)malloc(sizeof(i64) * zsz * n_mb), *a_new = (i64 *)malloc(sizeof(i64) * zsz * n_mb);
-    i64 *mx_id = (i64 *)malloc(sizeof(i64) * n_mb), *mx_new = (i64 *)malloc(sizeof(i64) * n_mb);
-    i64 J_id = 0, J_new = 0;
-    for (int mb = 0; mb < n_mb; ++mb) {
-        mx_id[mb] = replicate_mb(counts + (size_t)mb * E, p_id, E, EP, rpn, r, z_id + zsz * mb, a_id + zsz * mb);
-        mx_new[mb] = replicate_mb(counts + (size_t)mb * E, p_new, E, EP, rpn, r, z_new + zsz * mb, a_new + zsz * mb);
-        J_id += mx_id[mb]; J_new += mx_new[mb];
+    int cap = E * EP;
+    int32_t *ptr = (int32_t *)malloc(sizeof(int32_t) * (E + 1));
+    int32_t *rank = (int32_t *)malloc(sizeof(int32_t) * cap);
+    int32_t *rows = (int32_t *)malloc(sizeof(int32_t) * cap);
+    int p = 0;
+    for (int e = 0; e < E; ++e) {
+        ptr[e] = p;
+        for (int g = 0; g < EP; ++g)
+            if (z[(size_t)e * EP + g]) { rank[p] = g; rows[p] = (int32_t)a[(size_t)e * EP + g]; ++p; }
     }
-    int use_new = placed ? 1 : (J_new < J_id);
-    const int32_t *rank_of = use_new ? p_new : p_id;
-    const uint8_t *zz = use_new ? z_new : z_id;
-    const i64 *aa = use_new ? a_new : a_id;
-    const i64 *mx = use_new ? mx_new : mx_id;
+    ptr[E] = p;
+    i64 *y = (i64 *)malloc(sizeof(i64) * (size_t)(p ? p : 1) * EP);
+    i64 *loads = (i64 *)malloc(sizeof(i64) * 5 * EP);
+    double out[3];
+    oracle_assign_sources(x, E, EP, rpn, ptr, rank, rows, y);
+    oracle_moe_time_split(y, p, EP, rpn, rank, model, out, loads);
+    i64 mc = 0;
+    for (int g = 0; g < EP; ++g) {
+        double nv = model[1] * (double)(loads[EP + g] > loads[2 * EP + g] ? loads[EP + g] : loads[2 * EP + g]);
+        double rd = model[2] * (double)(loads[3 * EP + g] > loads[4 * EP + g] ? loads[3 * EP + g] : loads[4 * EP + g]);
+        tg[g] = model[0] * (double)loads[g] + (nv > rd ? nv : rd);
+        if (loads[g] > mc) mc = loads[g];
+    }
+    if (max_comp) *max_comp = mc;
+    free(ptr); free(rank); free(rows); free(y); free(loads);
+    return out[0];
+}
 
+/* the balanced split of oracle_balance_split applied to the experts of one node */
+static void node_split(int nd, const int32_t *rank_of, int E, int EP, int rpn, const uint8_t *z, i64 *a)
+{
+    int *ex = (int *)malloc(sizeof(int) * E), ne = 0;
+    for (int e = 0; e < E; ++e) if (rank_of[e] / rpn == nd) ex[ne++] = e;
+    uint8_t *zn = (uint8_t *)malloc((size_t)(ne ? ne : 1) * rpn);
+    i64 *an = (i64 *)malloc(sizeof(i64) * (size_t)(ne ? ne : 1) * rpn);
+    for (int i = 0; i < ne; ++i)
+        for (int g = 0; g < rpn; ++g) {
+            zn[i * rpn + g] = z[(size_t)ex[i] * EP + nd * rpn + g];
+            an[i * rpn + g] = a[(size_t)ex[i] * EP + nd * rpn + g];
+        }
+    oracle_balance_split(zn, ne, rpn, an);
+    for (int i = 0; i < ne; ++i)
+        for (int g = 0; g < rpn; ++g) a[(size_t)ex[i] * EP + nd * rpn + g] = an[i * rpn + g];
+    free(ex); free(zn); free(an);
+}
+
+i64 oracle_replicate_comm(const i64 *x, const int32_t *rank_of, int E, int EP, int rpn, int r,
+                          const double *model, uint8_t *z, i64 *a, double *T2)
+{
+    size_t zsz = (size_t)E * EP;
+    memset(z, 0, zsz);
+    memset(a, 0, sizeof(i64) * zsz);
+    for (int e = 0; e < E; ++e) {
+        i64 l = 0;
+        for (int j = 0; j < EP; ++j) l += x[(size_t)j * E + e];
+        z[(size_t)e * EP + rank_of[e]] = 1;
+        a[(size_t)e * EP + rank_of[e]] = l;
+    }
+    int *used = (int *)calloc(EP, sizeof(int));
+    double *tg = (double *)malloc(sizeof(double) * EP), *tg_try = (double *)malloc(sizeof(double) * EP);
+    i64 *a_keep = (i64 *)malloc(sizeof(i64) * zsz);
+    uint8_t *tried = (uint8_t *)malloc(E);
+    double T = eval_state(x, E, EP, rpn, z, a, model, tg, NULL);
+    double S = 0;
+    for (int g = 0; g < EP; ++g) S += tg[g] * tg[g];
+    T2[0] = T;
+    for (;;) {
+        int gb = 0;
+        for (int g = 1; g < EP; ++g) if (tg[g] > tg[gb]) gb = g;
+        int nd = gb / rpn, accepted = 0;
+        memset(tried, 0, E);
+        for (;;) {
+            int e_star = -1;
+            for (int e = 0; e < E; ++e) {
+                if (tried[e] || a[(size_t)e * EP + gb] <= 0) continue;
+                if (e_star < 0 || a[(size_t)e * EP + gb] > a[(size_t)e_star * EP + gb]) e_star = e;
+            }
+            if (e_star < 0) break;
+            tried[e_star] = 1;
+            int gt = -1;
+            for (int g = nd * rpn; g < (nd + 1) * rpn; ++g) {
+                if (z[(size_t)e_star * EP + g] || used[g] >= r) continue;
+                if (gt < 0 || tg[g] < tg[gt]) gt = g;
+            }
+            if (gt < 0) continue;
+            memcpy(a_keep, a, sizeof(i64) * zsz);
+            z[(size_t)e_star * EP + gt] = 1;
+            node_split(nd, rank_of, E, EP, rpn, z, a);
+            double T_try = eval_state(x, E, EP, rpn, z, a, model, tg_try, NULL);
+            double S_try = 0;
+            for (int g = 0; g < EP; ++g) S_try += tg_try[g] * tg_try[g];
+            if (T_try < T || (T_try == T && S_try < S)) {
+                T = T_try;
+                S = S_try;
+                memcpy(tg, tg_try, sizeof(double) * EP);
+                used[gt] += 1;
+                accepted = 1;
+                break;
+            }
+            z[(size_t)e_star * EP + gt] = 0;
+            memcpy(a, a_keep, sizeof(i64) * zsz);
+        }
+        if (!accepted) break;
+    }
+    for (int e = 0; e < E; ++e)
+        for (int g = 0; g < EP; ++g)
+            if (g != rank_of[e] && z[(size_t)e * EP + g] && a[(size_t)e * EP + g] == 0) z[(size_t)e * EP + g] = 0;
+    i64 mc = 0;
+    T2[1] = eval_state(x, E, EP, rpn, z, a, model, tg, &mc);
+    free(used); free(tg); free(tg_try); free(a_keep); free(tried);
+    return mc;
+}
+
+/* Plan tables from a placement and, per micro-batch, the placement bits zz[mb][e][g] and the   */
+/* token shares aa[mb][e][g] (table layout: see oracle_plan_ex).                              */
+static void emit_tables(const int32_t *counts, int n_mb, int E, int EP, int r, const int32_t *rank_of,
+                        const uint8_t *zz, const i64 *aa, const i64 *mx,
+                        int32_t *expert_to_slot, int32_t *replica_expert,
+                        int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                        int32_t *group_expert, int32_t *group_offset, i64 *max_before, i64 *max_after)
+{
+    int M = E / EP, G = EP * (M + r), cap_inst = E + EP * r;
+    size_t zsz = (size_t)E * EP;
     /* local slots: ascending expert id within a rank */
     int *next_local = (int *)calloc(EP, sizeof(int));
     for (int e = 0; e < E; ++e) expert_to_slot[e] = rank_of[e] * M + next_local[rank_of[e]]++;
@@ -654,8 +753,98 @@ int oracle_plan_ex(const int32_t *counts, int n_mb, int E, int EP, int rpn, int 
         max_before[mb] = worst;
         max_after[mb] = mx[mb];
     }
+}
+
+/* Whole plan (Sections 4 and 5): reorder once per batch, replicate per micro-batch, */
+/* and keep the reordering only if it lowers J = sum over micro-batches of the max    */
+/* rank load after replication (ties keep the unplanned layout, which moves no        */
+/* expert).  Output tables:                                                           */
+/*   expert_to_slot[E]           rank*M + local slot (local slots by ascending id)     */
+/*   replica_expert[n_mb][EP][r] expert in each replica slot (ascending id), -1 empty  */
+/*   inst_ptr[n_mb][E+1], inst_rank/rows/group[n_mb][E+EP*r]                           */
+/*                               instances of each expert, ascending rank; the home    */
+/*                               instance is always listed                             */
+/*   group_expert[n_mb][G], group_offset[n_mb][G+1], G = EP*(M+r), rank-major:         */
+/*                               M home slots then r replica slots per rank            */
+/*   max_before[n_mb]            max rank load, unplanned layout, no replicas          */
+/*   max_after[n_mb]             max rank load under the plan                          */
+/* placed != NULL: that placement (rank per expert, M per rank) is used as it is   */
+/* and only the per-micro-batch replication runs (a placement found under another */
+/* objective, e.g. by the annealing of Algorithm 1).                              */
+int oracle_plan_ex(const int32_t *counts, int n_mb, int E, int EP, int rpn, int r, const int32_t *placed,
+                   int32_t *expert_to_slot, int32_t *replica_expert,
+                   int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                   int32_t *group_expert, int32_t *group_offset,
+                   i64 *max_before, i64 *max_after)
+{
+    if (E <= 0 || EP <= 0 || E % EP || rpn <= 0 || EP % rpn || r < 0 || n_mb <= 0) return -1;
+    int M = E / EP, G = EP * (M + r), cap_inst = E + EP * r;
+    i64 *l = (i64 *)calloc(E, sizeof(i64));
+    for (int mb = 0; mb < n_mb; ++mb)
+        for (int e = 0; e < E; ++e) {
+            if (counts[mb * E + e] < 0) { free(l); return -1; }
+            l[e] += counts[mb * E + e];
+        }
+    int32_t *p_id = (int32_t *)malloc(sizeof(int32_t) * E);
+    int32_t *p_new = (int32_t *)malloc(sizeof(int32_t) * E);
+    for (int e = 0; e < E; ++e) p_id[e] = e / M;
+    if (placed) memcpy(p_new, placed, sizeof(int32_t) * E);
+    else oracle_reorder(l, E, EP, p_new);
+
+    size_t zsz = (size_t)E * EP;
+    uint8_t *z_id = (uint8_t *)malloc(zsz * n_mb), *z_new = (uint8_t *)malloc(zsz * n_mb);
+    i64 *a_id = (i64 *)malloc(sizeof(i64) * zsz * n_mb), *a_new = (i64 *)malloc(sizeof(i64) * zsz * n_mb);
+    i64 *mx_id = (i64 *)malloc(sizeof(i64) * n_mb), *mx_new = (i64 *)malloc(sizeof(i64) * n_mb);
+    i64 J_id = 0, J_new = 0;
+    for (int mb = 0; mb < n_mb; ++mb) {
+        mx_id[mb] = replicate_mb(counts + (size_t)mb * E, p_id, E, EP, rpn, r, z_id + zsz * mb, a_id + zsz * mb);
+        mx_new[mb] = replicate_mb(counts + (size_t)mb * E, p_new, E, EP, rpn, r, z_new + zsz * mb, a_new + zsz * mb);
+        J_id += mx_id[mb]; J_new += mx_new[mb];
+    }
+    int use_new = placed ? 1 : (J_new < J_id);
+    const int32_t *rank_of = use_new ? p_new : p_id;
+    const uint8_t *zz = use_new ? z_new : z_id;
+    const i64 *aa = use_new ? a_new : a_id;
+    const i64 *mx = use_new ? mx_new : mx_id;
+
+    emit_tables(counts, n_mb, E, EP, r, rank_of, zz, aa, mx, expert_to_slot, replica_expert, inst_ptr, inst_rank,
+                inst_rows, inst_group, group_expert, group_offset, max_before, max_after);
     free(l); free(p_id); free(p_new); free(z_id); free(z_new); free(a_id); free(a_new);
     free(mx_id); free(mx_new);
+    return 0;
+}
+
+/* Plan under a given placement with the time-aware replication above: x[mb][j][e] per-source */
+/* histograms, placed[e] the rank of every expert (M per rank).  Tables as oracle_plan_ex;    */
+/* t_before / t_after [n_mb]: T_MoE (Eq. 6) of every micro-batch without and with replicas.    */
+int oracle_plan_comm(const i64 *x, int n_mb, int E, int EP, int rpn, int r, const int32_t *placed,
+                     const double *model,
+                     int32_t *expert_to_slot, int32_t *replica_expert,
+                     int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                     int32_t *group_expert, int32_t *group_offset,
+                     i64 *max_before, i64 *max_after, double *t_before, double *t_after)
+{
+    if (E <= 0 || EP <= 0 || E % EP || rpn <= 0 || EP % rpn || r < 0 || n_mb <= 0 || !placed) return -1;
+    size_t zsz = (size_t)E * EP;
+    uint8_t *zz = (uint8_t *)malloc(zsz * n_mb);
+    i64 *aa = (i64 *)malloc(sizeof(i64) * zsz * n_mb);
+    i64 *mx = (i64 *)malloc(sizeof(i64) * n_mb);
+    int32_t *counts = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_mb * E);
+    for (int mb = 0; mb < n_mb; ++mb) {
+        const i64 *xm = x + (size_t)mb * EP * E;
+        for (int e = 0; e < E; ++e) {
+            i64 l = 0;
+            for (int j = 0; j < EP; ++j) l += xm[(size_t)j * E + e];
+            counts[(size_t)mb * E + e] = (int32_t)l;
+        }
+        double T2[2];
+        mx[mb] = oracle_replicate_comm(xm, placed, E, EP, rpn, r, model, zz + zsz * mb, aa + zsz * mb, T2);
+        t_before[mb] = T2[0];
+        t_after[mb] = T2[1];
+    }
+    emit_tables(counts, n_mb, E, EP, r, placed, zz, aa, mx, expert_to_slot, replica_expert, inst_ptr, inst_rank,
+                inst_rows, inst_group, group_expert, group_offset, max_before, max_after);
+    free(zz); free(aa); free(mx); free(counts);
     return 0;
 }
 

@@ -162,3 +162,93 @@ def test_assign_sources_rejects_instance_sizes_that_do_not_add_up():
     x = np.array([[3], [1]], np.int64)
     with pytest.raises(ValueError):
         oracle.assign_sources(x, 2, [0, 1], [0], [5])
+
+
+# ------------------------------------------------------------------ Algorithm 2 with the time of Section 4.1 as objective
+def _inst_tables(z, a):
+    E, EP = z.shape
+    ptr, rank, rows = [0], [], []
+    for e in range(E):
+        for g in range(EP):
+            if z[e, g]:
+                rank.append(g)
+                rows.append(int(a[e, g]))
+        ptr.append(len(rank))
+    return np.array(ptr, np.int32), np.array(rank, np.int32), np.array(rows, np.int32)
+
+
+def _time_of(x, z, a, rpn, model):
+    ptr, rank, rows = _inst_tables(z, a)
+    y = oracle.assign_sources(x, rpn, ptr, rank, rows)
+    return oracle.moe_time_split(y[:len(rank)], rank, rpn, model)[0]["T"]
+
+
+def _hot_instance(seed, EP, E):
+    rng = np.random.default_rng(seed)
+    x = rng.integers(0, 30, size=(EP, E)).astype(np.int64)
+    x[:, rng.integers(0, E)] += rng.integers(50, 150, size=EP)
+    return x, np.repeat(np.arange(EP), E // EP).astype(np.int32)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_time_aware_replication_reaches_the_brute_force_optimum_on_tiny_instances(seed):
+    """Two nodes of two GPUs, eight experts, one replica slot per GPU: every placement of at most
+    one replica per GPU is enumerated, each with the balanced split (pinned on its own) and the
+    time of Eq. 1-6 on the source-aware split (pinned on its own); the greedy loop must end at the
+    smallest T_MoE among them."""
+    EP, rpn, E, r = 4, 2, 8, 1
+    model = [1.0, 0.3, 1.5]
+    x, rank_of = _hot_instance(seed, EP, E)
+    z, a, st = oracle.replicate_comm(x, rank_of, rpn, r, model)
+    assert st["T_after"] == pytest.approx(_time_of(x, z, a, rpn, model), rel=1e-12)
+    best = None
+    options = [[None] + [e for e in range(E) if rank_of[e] // rpn == g // rpn and rank_of[e] != g] for g in range(EP)]
+    for choice in itertools.product(*options):
+        zz = np.zeros((E, EP), np.uint8)
+        aa = np.zeros((E, EP), np.int64)
+        for e in range(E):
+            zz[e, rank_of[e]] = 1
+            aa[e, rank_of[e]] = x[:, e].sum()
+        for g, e in enumerate(choice):
+            if e is not None:
+                zz[e, g] = 1
+        for nd in range(EP // rpn):
+            ex = [e for e in range(E) if rank_of[e] // rpn == nd]
+            an = oracle.balance_split(zz[ex][:, nd * rpn:(nd + 1) * rpn].copy(), aa[ex][:, nd * rpn:(nd + 1) * rpn].copy())
+            for i, e in enumerate(ex):
+                aa[e, nd * rpn:(nd + 1) * rpn] = an[i]
+        t = _time_of(x, zz, aa, rpn, model)
+        best = t if best is None else min(best, t)
+    assert st["T_after"] <= best * (1 + 1e-12)
+    assert st["T_after"] <= st["T_before"]
+
+
+@pytest.mark.parametrize("EP,rpn,E,r,seed", [(4, 2, 16, 2, 0), (8, 4, 32, 1, 1), (8, 8, 16, 2, 2), (16, 4, 64, 2, 3)])
+def test_time_aware_replication_invariants(EP, rpn, E, r, seed):
+    x, rank_of = _hot_instance(seed, EP, E)
+    rng = np.random.default_rng(seed + 100)
+    rank_of = rng.permutation(rank_of).astype(np.int32)
+    model = oracle.cost_model(2048, 768, 5e14, 4e11, 5e10)
+    z, a, st = oracle.replicate_comm(x, rank_of, rpn, r, model)
+    assert (a.sum(axis=1) == x.sum(axis=0)).all()                           # every token served once
+    assert (a[z == 0] == 0).all() and (a >= 0).all()
+    for e in range(E):
+        assert z[e, rank_of[e]] == 1                                        # the home copy stays
+        assert all(g // rpn == rank_of[e] // rpn for g in np.flatnonzero(z[e]))   # replicas stay in the node
+    replicas = z.sum(axis=0) - np.bincount(rank_of, minlength=EP)
+    assert (replicas <= r).all()
+    assert st["T_after"] <= st["T_before"]
+    assert st["max_load"] == a.sum(axis=0).max()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_time_aware_replication_without_communication_cost_balances_like_the_load_only_one(seed):
+    """With free communication T_MoE is the largest computation load: the loop must then end no
+    higher than the load-only Algorithm 2 (whose result is pinned to the brute-force optimum)."""
+    EP, rpn, E, r = 4, 4, 16, 2
+    x, rank_of = _hot_instance(seed, EP, E)
+    cnt = x.sum(axis=0)
+    z, a, st = oracle.replicate_comm(x, rank_of, rpn, r, [1.0, 0.0, 0.0])
+    _, _, peak = oracle.replicate_node(cnt, rank_of, rpn, r)
+    assert st["max_load"] <= peak
+    assert st["max_load"] >= -(-int(cnt.sum()) // EP)
