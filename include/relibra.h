@@ -241,6 +241,28 @@ int relibra_moe_time_split(const int32_t *inst_src_rows, int n_inst, const int32
                            const relibra_cost_model *model, double *out3, int64_t *loads_out);
 
 /*
+ * Plan under a given placement with Algorithm 2 as printed in Section 5.2: the bottleneck GPU and
+ * the GPU that receives a replica are chosen by T_MoE,g = T_g^comp + T_g^comm (Section 4.1)
+ * instead of by load alone.  Per micro-batch, over the whole EP group: the GPU of largest T_g
+ * (lowest id on ties) is the bottleneck; its experts with tokens served there are tried, most
+ * tokens first (lower id on ties); the replica goes to the GPU of the same node without a copy
+ * and with a free slot whose T_g is smallest; tokens are split again (the computation split of
+ * relibra_plan, then the sources of relibra_assign_sources) and the replica is kept if
+ * (T_MoE of Eq. 6, sum_g T_g^2) got lexicographically smaller, else the next expert is tried;
+ * the loop ends when no expert of the bottleneck GPU gives a gain.  All pointers HOST.
+ *   x_host [n_mb, EP, E] int64 in   per-source histograms (model->EP, model->ranks_per_node)
+ *   expert_rank [E] int32 in        placement, exactly E/EP experts per rank (e.g. relibra_reorder_sa)
+ *   t_before, t_after [n_mb] double out  T_MoE of every micro-batch without and with the replicas
+ * Tables and the other outputs as relibra_plan_placed.  Deterministic.
+ */
+int relibra_plan_timed(const int64_t *x_host, int n_mb, int E, int k, const relibra_cost_model *model, int r,
+                       const int32_t *expert_rank,
+                       int32_t *expert_to_slot, int32_t *replica_expert,
+                       int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                       int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                       int64_t *max_load_before, int64_t *max_load_after, double *t_before, double *t_after);
+
+/*
  * relibra_permute under a source-aware split.  Assignment a = t*k + s of token t (source rank
  * j = t / (T/EP)) and expert e has ordinal q among the assignments of (j, e) in ascending a;
  * the instances of e, in the plan's order, take runs of inst_src_rows[i][j] such ordinals; the

@@ -25,7 +25,7 @@ MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
-           "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src",
+           "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src", "relibra_plan_timed",
            "relibra_permute", "relibra_row_tokens", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push",
            "relibra_workspace_bytes",
@@ -143,6 +143,36 @@ def relibra_plan(counts_host, k, EP, ranks_per_node, r, expert_rank=None):
         assert expert_rank.shape == (E,)
         rc = lib().relibra_plan_placed(_hp(counts_host), n_mb, E, k, EP, ranks_per_node, r, _hp(expert_rank), *tail)
         _check("relibra_plan_placed", rc)
+    return out
+
+
+def relibra_plan_timed(x_host, k, model, r, expert_rank):
+    """x_host [n_mb,EP,E] int64 per-source histograms + placement -> plan tables with Algorithm 2 driven by
+    T_MoE,g (Section 4.1), plus t_before / t_after [n_mb] (seconds)."""
+    x_host = np.ascontiguousarray(x_host, dtype=np.int64)
+    n_mb, EP, E = x_host.shape
+    assert EP == model.EP
+    expert_rank = np.ascontiguousarray(expert_rank, dtype=np.int32)
+    assert expert_rank.shape == (E,)
+    M = E // EP if E % EP == 0 else 0
+    G = max(EP * (M + r), 1) if r >= 0 else 1
+    cap = max(E + EP * max(r, 0), 1)
+    out = dict(
+        expert_to_slot=np.empty(E, np.int32), replica_expert=np.empty((n_mb, EP, max(r, 0)), np.int32),
+        inst_ptr=np.empty((n_mb, E + 1), np.int32), inst_rank=np.empty((n_mb, cap), np.int32),
+        inst_rows=np.empty((n_mb, cap), np.int32), inst_group=np.empty((n_mb, cap), np.int32),
+        group_expert=np.empty((n_mb, G), np.int32), group_offset=np.empty((n_mb, G + 1), np.int32),
+        group_dw_slot=np.empty((n_mb, G), np.int32),
+        max_load_before=np.empty(n_mb, np.int64), max_load_after=np.empty(n_mb, np.int64),
+        t_before=np.empty(n_mb, np.float64), t_after=np.empty(n_mb, np.float64))
+    rep = out["replica_expert"]
+    rc = lib().relibra_plan_timed(_hp(x_host), n_mb, E, int(k), C.byref(model), int(r), _hp(expert_rank),
+                                  _hp(out["expert_to_slot"]), _hp(rep) if rep.size else C.c_void_p(0),
+                                  _hp(out["inst_ptr"]), _hp(out["inst_rank"]), _hp(out["inst_rows"]),
+                                  _hp(out["inst_group"]), _hp(out["group_expert"]), _hp(out["group_offset"]),
+                                  _hp(out["group_dw_slot"]), _hp(out["max_load_before"]), _hp(out["max_load_after"]),
+                                  _hp(out["t_before"]), _hp(out["t_after"]))
+    _check("relibra_plan_timed", rc)
     return out
 
 

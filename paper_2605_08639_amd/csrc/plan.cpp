@@ -323,7 +323,153 @@ std::vector<MbPlan> replicate_batch(const int32_t *counts, int n_mb, const std::
     return plans;
 }
 
+// Stage 2 with the execution time of Section 4.1 as objective (Algorithm 2 as printed: bottleneck
+// and target GPU by T_MoE,g = T_g^comp + T_g^comm), one micro-batch, all nodes at once.  A state's
+// time: every expert's instances take their sources by relibra_assign_sources, loads and times
+// follow Eq. 1-6 (relibra_moe_time_split).  A replica is kept if (T_MoE, sum_g T_g^2) gets
+// lexicographically smaller; the candidates are the bottleneck GPU's experts, most tokens first.
+struct TimedState {
+    const int64_t *x;
+    const relibra_cost_model *model;
+    int E, EP, rpn;
+    const std::vector<int> &where;
+    std::vector<Node> &nodes;
+    std::vector<int> local;                 // index of expert e inside its node
+    std::vector<int32_t> ptr, rank, rows, first, y, ybase;
+    std::vector<int64_t> loads;
+
+    TimedState(const int64_t *x_, const relibra_cost_model *m, int E_, const std::vector<int> &w, std::vector<Node> &n)
+        : x(x_), model(m), E(E_), EP(m->EP), rpn(m->ranks_per_node), where(w), nodes(n), local(E_), ptr(E_ + 1),
+          first((size_t)m->EP * E_), loads(5 * (size_t)m->EP)
+    {
+    }
+
+    // T_MoE of the current state; per[g] = T_g
+    double time(std::vector<double> &per)
+    {
+        rank.clear();
+        rows.clear();
+        for (int e = 0; e < E; ++e) {
+            ptr[e] = (int32_t)rank.size();
+            const Node &nd = nodes[where[e] / rpn];
+            const int base = where[e] / rpn * rpn, i = local[e];
+            for (int g = 0; g < rpn; ++g)
+                if (nd.allowed[i] >> g & 1) {
+                    rank.push_back(base + g);
+                    rows.push_back((int32_t)nd.share[i][g]);
+                }
+        }
+        ptr[E] = (int32_t)rank.size();
+        const size_t cells = rank.size() * (size_t)EP;
+        y.resize(cells);
+        ybase.resize(cells);
+        double out3[3] = {0, 0, 0};
+        relibra_assign_sources(x, E, EP, rpn, ptr.data(), rank.data(), rows.data(), first.data(), y.data(), ybase.data());
+        relibra_moe_time_split(y.data(), (int)rank.size(), rank.data(), model, out3, loads.data());
+        const int64_t *comp = loads.data(), *itx = comp + EP, *irx = comp + 2 * EP, *rtx = comp + 3 * EP, *rrx = comp + 4 * EP;
+        for (int g = 0; g < EP; ++g) {
+            const double intra = model->sec_per_token_intra * (double)std::max(itx[g], irx[g]);
+            const double rdma = model->sec_per_token_inter * (double)std::max(rtx[g], rrx[g]);
+            per[g] = model->sec_per_token_comp * (double)comp[g] + std::max(intra, rdma);
+        }
+        return out3[0];
+    }
+};
+
+MbPlan replicate_microbatch_timed(const int64_t *x, const relibra_cost_model *model, const std::vector<int> &where,
+                                  int E, int r, double &t_before, double &t_after)
+{
+    const int EP = model->EP, rpn = model->ranks_per_node;
+    std::vector<Node> nodes(EP / rpn);
+    std::vector<std::vector<int>> members(EP / rpn);
+    TimedState st(x, model, E, where, nodes);
+    for (int e = 0; e < E; ++e) {
+        Node &nd = nodes[where[e] / rpn];
+        i64 tokens = 0;
+        for (int j = 0; j < EP; ++j) tokens += x[(size_t)j * E + e];
+        st.local[e] = (int)nd.cnt.size();
+        members[where[e] / rpn].push_back(e);
+        nd.cnt.push_back(tokens);
+        nd.home.push_back(where[e] % rpn);
+    }
+    for (Node &nd : nodes) {
+        nd.n = rpn;
+        nd.r = r;
+        const int ne = (int)nd.cnt.size();
+        nd.share.assign(ne, std::vector<i64>(rpn, 0));
+        nd.allowed.assign(ne, 0);
+        nd.L.assign(rpn, 0);
+        for (int i = 0; i < ne; ++i) {
+            nd.allowed[i] = 1u << nd.home[i];
+            nd.share[i][nd.home[i]] = nd.cnt[i];
+        }
+    }
+    auto squares = [](const std::vector<double> &v) {
+        double s = 0;
+        for (double t : v) s += t * t;
+        return s;
+    };
+    std::vector<double> per(EP), per_try(EP);
+    std::vector<int> slots_used(EP, 0), cand;
+    double T = st.time(per), S = squares(per);
+    t_before = T;
+    for (;;) {
+        const int gb = (int)(std::max_element(per.begin(), per.end()) - per.begin());      // first maximum
+        Node &nd = nodes[gb / rpn];
+        const int base = gb / rpn * rpn, lb = gb - base, ne = (int)nd.cnt.size();
+        cand.clear();
+        for (int i = 0; i < ne; ++i)
+            if (nd.share[i][lb] > 0) cand.push_back(i);
+        std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return nd.share[a][lb] > nd.share[b][lb]; });
+        bool kept = false;
+        for (int i : cand) {
+            int gt = -1;
+            for (int g = 0; g < rpn; ++g) {
+                if ((nd.allowed[i] >> g & 1) || slots_used[base + g] >= r) continue;
+                if (gt < 0 || per[base + g] < per[base + gt]) gt = g;
+            }
+            if (gt < 0) continue;
+            const std::vector<std::vector<i64>> share_before = nd.share;
+            nd.allowed[i] |= 1u << gt;
+            nd.balance();
+            const double T_try = st.time(per_try), S_try = squares(per_try);
+            if (T_try < T || (T_try == T && S_try < S)) {
+                T = T_try;
+                S = S_try;
+                per.swap(per_try);
+                ++slots_used[base + gt];
+                kept = true;
+                break;
+            }
+            nd.allowed[i] &= ~(1u << gt);
+            nd.share = share_before;
+        }
+        if (!kept) break;
+    }
+    MbPlan out;
+    out.inst.resize(E);
+    for (size_t n = 0; n < nodes.size(); ++n) {
+        Node &nd = nodes[n];
+        for (size_t i = 0; i < members[n].size(); ++i)
+            for (int g = 0; g < rpn; ++g) {
+                if (g != nd.home[i] && (nd.allowed[i] >> g & 1) && nd.share[i][g] == 0) nd.allowed[i] &= ~(1u << g);
+                if (nd.allowed[i] >> g & 1) out.inst[members[n][i]].push_back({(int)n * rpn + g, nd.share[i][g]});
+            }
+        nd.recompute_loads();
+        out.peak = std::max(out.peak, *std::max_element(nd.L.begin(), nd.L.end()));
+    }
+    t_after = st.time(per);
+    return out;
+}
+
 }  // namespace
+
+static void write_tables(const int32_t *counts, int n_mb, int E, int EP, int r, const std::vector<int> &where,
+                         const std::vector<MbPlan> &plans,
+                         int32_t *expert_to_slot, int32_t *replica_expert,
+                         int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                         int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                         int64_t *max_load_before, int64_t *max_load_after);
 
 // Both entry points.  placed = nullptr: stage 1 chooses the placement; otherwise the caller's
 // placement (rank per expert, exactly M per rank) is taken as it is and only stage 2 runs.
@@ -339,7 +485,7 @@ static int plan_impl(const int32_t *counts, int n_mb, int E, int k, int EP, int 
     if (n_mb < 1 || E < 1 || EP < 1 || E % EP || rpn < 1 || rpn > 32 || EP % rpn || r < 0 || k < 1 || k > E)
         return RELIBRA_EINVAL;
     if (r > 0 && !replica_expert) return RELIBRA_EINVAL;
-    const int M = E / EP, S = M + r, G = EP * S, inst_cap = E + EP * r;
+    const int M = E / EP;
 
     std::vector<i64> batch_load(E, 0);
     for (int mb = 0; mb < n_mb; ++mb)
@@ -382,9 +528,20 @@ static int plan_impl(const int32_t *counts, int n_mb, int E, int k, int EP, int 
             }
         }
     }
-    const std::vector<int> &where = chosen;
-    const std::vector<MbPlan> &plans = chosen_plans;
+    write_tables(counts, n_mb, E, EP, r, chosen, chosen_plans, expert_to_slot, replica_expert, inst_ptr, inst_rank, inst_rows,
+                 inst_group, group_expert, group_offset, group_dw_slot, max_load_before, max_load_after);
+    return RELIBRA_OK;
+}
 
+// The plan tables of a placement and its per-micro-batch replication (layout: relibra_plan).
+static void write_tables(const int32_t *counts, int n_mb, int E, int EP, int r, const std::vector<int> &where,
+                         const std::vector<MbPlan> &plans,
+                         int32_t *expert_to_slot, int32_t *replica_expert,
+                         int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                         int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                         int64_t *max_load_before, int64_t *max_load_after)
+{
+    const int M = E / EP, S = M + r, G = EP * S, inst_cap = E + EP * r;
     std::vector<int> filled(EP, 0);
     for (int e = 0; e < E; ++e) expert_to_slot[e] = where[e] * M + filled[where[e]]++;
 
@@ -440,7 +597,6 @@ static int plan_impl(const int32_t *counts, int n_mb, int E, int k, int EP, int 
         max_load_before[mb] = worst;
         max_load_after[mb] = P.peak;
     }
-    return RELIBRA_OK;
 }
 
 extern "C" int relibra_plan(const int32_t *counts, int n_mb, int E, int k, int EP, int rpn, int r,
@@ -463,6 +619,56 @@ extern "C" int relibra_plan_placed(const int32_t *counts, int n_mb, int E, int k
     if (!expert_rank) return RELIBRA_EINVAL;
     return plan_impl(counts, n_mb, E, k, EP, rpn, r, expert_rank, expert_to_slot, replica_expert, inst_ptr, inst_rank,
                      inst_rows, inst_group, group_expert, group_offset, group_dw_slot, max_load_before, max_load_after);
+}
+
+extern "C" int relibra_plan_timed(const int64_t *x_host, int n_mb, int E, int k, const relibra_cost_model *model, int r,
+                                  const int32_t *expert_rank,
+                                  int32_t *expert_to_slot, int32_t *replica_expert,
+                                  int32_t *inst_ptr, int32_t *inst_rank, int32_t *inst_rows, int32_t *inst_group,
+                                  int32_t *group_expert, int32_t *group_offset, int32_t *group_dw_slot,
+                                  int64_t *max_load_before, int64_t *max_load_after, double *t_before, double *t_after)
+{
+    if (!x_host || !model || !expert_rank || !expert_to_slot || !inst_ptr || !inst_rank || !inst_rows || !inst_group ||
+        !group_expert || !group_offset || !group_dw_slot || !max_load_before || !max_load_after || !t_before || !t_after)
+        return RELIBRA_EINVAL;
+    const int EP = model->EP, rpn = model->ranks_per_node;
+    if (n_mb < 1 || E < 1 || EP < 1 || E % EP || rpn < 1 || rpn > 32 || EP % rpn || r < 0 || k < 1 || k > E)
+        return RELIBRA_EINVAL;
+    if (model->sec_per_token_comp < 0 || model->sec_per_token_intra < 0 || model->sec_per_token_inter < 0) return RELIBRA_EINVAL;
+    if (r > 0 && !replica_expert) return RELIBRA_EINVAL;
+    const int M = E / EP;
+    std::vector<int> where(E), held(EP, 0);
+    for (int e = 0; e < E; ++e) {
+        if (expert_rank[e] < 0 || expert_rank[e] >= EP || ++held[expert_rank[e]] > M) return RELIBRA_ERANGE;
+        where[e] = expert_rank[e];
+    }
+    std::vector<int32_t> counts((size_t)n_mb * E);
+    for (int mb = 0; mb < n_mb; ++mb)
+        for (int e = 0; e < E; ++e) {
+            i64 tokens = 0;
+            for (int j = 0; j < EP; ++j) {
+                const int64_t v = x_host[((size_t)mb * EP + j) * E + e];
+                if (v < 0 || v > 0x7fffffffLL) return RELIBRA_ERANGE;
+                tokens += v;
+            }
+            if (tokens > 0x7fffffffLL) return RELIBRA_ERANGE;
+            counts[(size_t)mb * E + e] = (int32_t)tokens;
+        }
+    std::vector<MbPlan> plans(n_mb);
+    {
+        unsigned hw = std::thread::hardware_concurrency();
+        const int workers = std::max(1, std::min({(int)(hw ? hw : 1u), n_mb, 16}));
+        std::vector<std::thread> pool;
+        for (int w = 0; w < workers; ++w)
+            pool.emplace_back([&, w]() {
+                for (int mb = w; mb < n_mb; mb += workers)
+                    plans[mb] = replicate_microbatch_timed(x_host + (size_t)mb * EP * E, model, where, E, r, t_before[mb], t_after[mb]);
+            });
+        for (auto &t : pool) t.join();
+    }
+    write_tables(counts.data(), n_mb, E, EP, r, where, plans, expert_to_slot, replica_expert, inst_ptr, inst_rank, inst_rows,
+                 inst_group, group_expert, group_offset, group_dw_slot, max_load_before, max_load_after);
+    return RELIBRA_OK;
 }
 
 // Imbalance diagnostics of Section 2.2.

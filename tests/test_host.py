@@ -267,6 +267,48 @@ def test_source_aware_split_and_its_times_equal_oracle(kw):
             assert t_lib[key] == pytest.approx(t_or[key], rel=1e-12)
 
 
+@pytest.mark.parametrize("kw", [dict(E=16, k=2, EP=4, r=2, T=240, ranks_per_node=2),
+                                dict(E=32, k=4, EP=8, r=1, T=512, ranks_per_node=4),
+                                dict(E=128, k=8, EP=8, r=2, T=2048, ranks_per_node=8),
+                                dict(E=64, k=4, EP=16, r=2, T=1024, ranks_per_node=4, routing="stress", zipf_s=1.5)])
+def test_timed_plan_equals_oracle(kw):
+    """Algorithm 2 driven by T_MoE,g: every table identical to the oracle's, times equal to rounding;
+    under an identity placement and under an annealed one."""
+    cfg = wl.small_config(n_mb=3, h=64, hff=64, **kw)
+    ids = np.stack([wl.make_routing(cfg, mb)[0] for mb in range(cfg.n_mb)])
+    x = np.stack([oracle.route_hist_src(ids[mb], cfg.E, cfg.EP) for mb in range(cfg.n_mb)])
+    m_or = oracle.cost_model(2048, 768, 5e14, 4e11, 5e10)
+    m_lib = rl.cost_model(cfg.EP, cfg.rpn, 2048, 768, 5e14, 4e11, 5e10)
+    ident = (np.arange(cfg.E) // cfg.M).astype(np.int32)
+    annealed, _ = rl.relibra_reorder_sa(x.sum(0), m_lib, n_seeds=2, seed=3)
+    for placed in (ident, annealed):
+        want = oracle.plan_comm(x, cfg.rpn, cfg.r, placed, m_or)
+        got = rl.relibra_plan_timed(x, cfg.k, m_lib, cfg.r, placed)
+        for key in ("expert_to_slot", "replica_expert", "inst_ptr", "inst_rank", "inst_rows", "inst_group",
+                    "group_expert", "group_offset"):
+            assert np.array_equal(got[key], want[key]), key
+        assert np.array_equal(got["max_load_after"], want["max_after"])
+        assert np.allclose(got["t_before"], want["t_before"], rtol=1e-12)
+        assert np.allclose(got["t_after"], want["t_after"], rtol=1e-12)
+        assert (got["t_after"] <= got["t_before"]).all()
+        # the tables are a valid plan: group sizes add up and every slot index is in range
+        assert (got["group_offset"][:, -1] == cfg.T * cfg.k).all()
+        assert ((got["group_dw_slot"] >= 0) & (got["group_dw_slot"] < cfg.E + cfg.EP * cfg.r)).all()
+
+
+def test_timed_plan_argument_errors():
+    x = np.ones((1, 4, 8), np.int64)
+    m = rl.cost_model(4, 2, 64, 64, 1e12, 1e11, 1e10)
+    rank = np.repeat(np.arange(4), 2).astype(np.int32)
+    rl.relibra_plan_timed(x, 2, m, 1, rank)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_plan_timed(x, 2, m, 1, np.zeros(8, np.int32))         # more than M experts on a rank
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_plan_timed(-x, 2, m, 1, rank)
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_plan_timed(x, 2, m, -1, rank)
+
+
 def test_source_aware_split_argument_errors():
     x = np.array([[3], [1]], np.int64)
     with pytest.raises(rl.RelibraError):
