@@ -157,6 +157,33 @@ def test_source_aware_permute_bit_exact(kw):
     assert (row_of >= 0).all().item() or err.item() & rl.ERR_PLAN_COVER
 
 
+def test_timed_plan_drives_the_device_path():
+    """Tables of the time-driven Algorithm 2 (equal to the oracle's, checked on the host) through
+    permutation and expert FFN forward: indices bit-exact, outputs within the bar."""
+    cfg = wl.small_config(E=32, k=4, EP=8, r=2, T=1024, n_mb=1, h=128, hff=192, ranks_per_node=4)
+    ids, _ = routing(cfg)
+    x = np.stack([oracle.route_hist_src(ids[0], cfg.E, cfg.EP)])
+    model = rl.cost_model(cfg.EP, cfg.rpn, 2048, 768, 5e14, 4e11, 5e10)
+    placed = (np.arange(cfg.E) // cfg.M).astype(np.int32)
+    p = rl.relibra_plan_timed(x, cfg.k, model, cfg.r, placed)
+    want = oracle.plan_comm(x, cfg.rpn, cfg.r, placed, oracle.cost_model(2048, 768, 5e14, 4e11, 5e10))
+    for key in ("inst_ptr", "inst_rank", "inst_rows", "inst_group", "group_expert", "group_offset"):
+        assert np.array_equal(p[key], want[key]), key
+    X, _ = wl.make_tokens(cfg, 0)
+    Wg, Wu, Wd = wl.make_weights(cfg)
+    tabs = {key: dev_i32(p[key][0]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert")}
+    err = rl.new_err_flag()
+    row_of, src_of, Xrows = rl.relibra_permute(torch.from_numpy(ids[0]).to(DEV), tabs["inst_ptr"], tabs["inst_rows"],
+                                               tabs["inst_group"], tabs["group_offset"], X.to(DEV), cfg.E, cfg.G, err_flag=err)
+    want_row, want_src = oracle.permute(ids[0], cfg.E, p["inst_ptr"][0], p["inst_rows"][0], p["inst_group"][0], p["group_offset"][0])
+    assert err.item() == 0
+    assert np.array_equal(row_of.cpu().numpy(), want_row) and np.array_equal(src_of.cpu().numpy(), want_src)
+    Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], Wg.to(DEV), Wu.to(DEV), Wd.to(DEV), err_flag=err)[3]
+    Y_o = oracle.ffn_fwd(oracle.gather_rows(X, want_src, cfg.k), p["group_offset"][0], p["group_expert"][0], Wg, Wu, Wd)[3]
+    assert err.item() == 0
+    assert rel_l2(Y, Y_o) <= TOL
+
+
 def test_permute_flags_a_plan_that_does_not_cover_the_routing():
     cfg = wl.small_config(E=8, k=2, EP=4, r=1, T=200, n_mb=1, h=64)
     ids, _ = routing(cfg)
