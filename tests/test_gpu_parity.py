@@ -157,6 +157,26 @@ def test_source_aware_permute_bit_exact(kw):
     assert (row_of >= 0).all().item() or err.item() & rl.ERR_PLAN_COVER
 
 
+def test_source_aware_permute_one_token_per_source():
+    """Smallest shape the source-aware permutation accepts: T = EP tokens, k = 1."""
+    E = EP = 4
+    ids = np.array([[2], [2], [0], [2]], np.int32)
+    x = oracle.route_hist_src(ids, E, EP)
+    # expert 2 (home rank 2) has a replica on rank 0 taking one of its three tokens
+    ptr, rank, rows, grp = [0, 1, 2, 4, 5], [0, 1, 0, 2, 3], [1, 0, 1, 2, 0], [0, 2, 1, 4, 6]
+    off = [0, 1, 2, 2, 2, 4, 4, 4, 4]                       # G = 8 groups: (home, replica) per rank
+    y = oracle.assign_sources(x, 4, ptr, rank, rows)
+    want_row, want_src = oracle.permute_src(ids, E, EP, ptr, grp, off, y)
+    tabs = rl.relibra_assign_sources(x, 4, ptr, rank, rows)
+    err = rl.new_err_flag()
+    row_of, src_of, _ = rl.relibra_permute_src(torch.from_numpy(ids).to(DEV), dev_i32(ptr), dev_i32(grp), dev_i32(off), EP,
+                                               dev_i32(tabs["src_first"]), dev_i32(tabs["inst_src_rows"]),
+                                               dev_i32(tabs["inst_src_base"]), None, E, 8, err_flag=err)
+    assert err.item() == 0
+    assert row_of.cpu().tolist() == want_row.tolist() and src_of.cpu().tolist() == want_src.tolist()
+    assert want_row.tolist() == [1, 2, 0, 3]                # token 0 (source 0) is the one the replica on rank 0 serves
+
+
 def test_timed_plan_drives_the_device_path():
     """Tables of the time-driven Algorithm 2 (equal to the oracle's, checked on the host) through
     permutation and expert FFN forward: indices bit-exact, outputs within the bar."""

@@ -309,6 +309,22 @@ def test_timed_plan_argument_errors():
         rl.relibra_plan_timed(x, 2, m, -1, rank)
 
 
+def test_source_aware_split_degenerate_cases():
+    """Experts without tokens, a source without tokens, one token per source, a single rank."""
+    # E = 4 on EP = 2 ranks of one node; expert 1 and source 1 are empty; expert 0 has a replica on rank 1
+    x = np.array([[6, 0, 2, 1], [0, 0, 0, 0]], np.int64)
+    ptr, rank, rows = [0, 2, 3, 4, 5], [0, 1, 0, 1, 1], [2, 4, 0, 2, 1]
+    got = rl.relibra_assign_sources(x, 2, ptr, rank, rows)
+    want = oracle.assign_sources(x, 2, ptr, rank, rows)
+    assert np.array_equal(got["inst_src_rows"], want)
+    assert got["inst_src_rows"].tolist() == [[2, 0], [4, 0], [0, 0], [2, 0], [1, 0]]
+    # a single rank: everything is a local copy, no link is loaded
+    x1 = np.array([[5, 7, 0]], np.int64)
+    one = rl.relibra_assign_sources(x1, 1, [0, 1, 2, 3], [0, 0, 0], [5, 7, 0])
+    t = rl.relibra_moe_time_split(one["inst_src_rows"], [0, 0, 0], rl.cost_model(1, 1, 64, 64, 1e12, 1e11, 1e10), with_loads=True)
+    assert t["loads"].tolist() == [[12], [0], [0], [0], [0]] and t["T_comm"] == 0.0
+
+
 def test_source_aware_split_argument_errors():
     x = np.array([[3], [1]], np.int64)
     with pytest.raises(rl.RelibraError):
