@@ -16,6 +16,7 @@ import argparse
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -47,6 +48,9 @@ def main():
                          "their weight operand is contraction-strided: the forward ones (default; the data gradients "
                          "read the stored layout that way already), the data gradients (both passes then read "
                          "contraction-contiguous weights), or none")
+    ap.add_argument("--plan", choices=("ahead", "inline"), default="ahead",
+                    help="histogram and host plan of the next batch overlapped with this step's kernels (default: replayed "
+                         "routing is known before a batch trains), or at the head of the step that uses them")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -156,16 +160,49 @@ def main():
 
     plan_ms = []
 
-    def step():
-        rl.relibra_route_hist(ids_all, E, counts=counts_d, err_flag=err)
-        counts_h = counts_d.cpu().numpy()                       # the path's one device->host crossing
-        if transposed:          # this step's parameters in the transposed layout: the GPU copies while the host plans
-            rl.relibra_transpose_experts(Wg, WgT)
-            rl.relibra_transpose_experts(Wu, WuT)
-            rl.relibra_transpose_experts(Wd, WdT)
+    # The plan of a batch needs only its replayed routing, which is known before the batch trains
+    # (Section 3: the control plane solves while earlier work still runs, off the critical path).
+    # --plan ahead: the histogram of the NEXT batch is launched at the start of a step, copied to pinned
+    # host memory asynchronously, and a host thread plans it while this step's kernels run; every step
+    # still launches one histogram, makes one device->host crossing and computes one plan.
+    # --plan inline: histogram, crossing and plan at the head of the step that uses them.
+    counts_pin = torch.empty((n_mb, E), dtype=torch.int32, pin_memory=True)
+    ahead = {"thread": None, "plan": None}
+
+    def plan_from(counts_h):
         tp = time.perf_counter()
         plan = rl.relibra_plan(counts_h, k, EP, cfg.rpn, r)
         plan_ms.append((time.perf_counter() - tp) * 1e3)
+        return plan
+
+    def launch_planning():
+        rl.relibra_route_hist(ids_all, E, counts=counts_d, err_flag=err)
+        counts_pin.copy_(counts_d, non_blocking=True)           # the path's one device->host crossing
+        ev = torch.cuda.Event()
+        ev.record()
+
+        def work():
+            ev.synchronize()
+            ahead["plan"] = plan_from(counts_pin.numpy())
+        ahead["thread"] = threading.Thread(target=work)
+        ahead["thread"].start()
+
+    def step():
+        if args.plan == "ahead":
+            if ahead["thread"] is None:                         # very first step: nothing was prepared
+                launch_planning()
+            ahead["thread"].join()
+            plan = ahead["plan"]
+            launch_planning()                                   # for the step after this one
+        else:
+            rl.relibra_route_hist(ids_all, E, counts=counts_d, err_flag=err)
+            counts_h = counts_d.cpu().numpy()                   # the path's one device->host crossing
+        if transposed:          # this step's parameters in the transposed layout, once per step
+            rl.relibra_transpose_experts(Wg, WgT)
+            rl.relibra_transpose_experts(Wu, WuT)
+            rl.relibra_transpose_experts(Wd, WdT)
+        if args.plan != "ahead":
+            plan = plan_from(counts_h)
         tabs = upload(plan)
         for mb in range(n_mb):
             layer(mb, tabs, first=(mb == 0))
@@ -192,6 +229,8 @@ def main():
     t_begin = time.perf_counter()
     for _ in range(args.steps):
         plan, tabs = step()
+    if ahead["thread"] is not None:
+        ahead["thread"].join()          # the plan prepared during the last step belongs to the timed work
     torch.cuda.synchronize()
     t_end = time.perf_counter()
     prof = rl.prof_stop()
@@ -512,6 +551,8 @@ def main():
                                + ("weight gradients once per batch over all resident micro-batches" if batched
                                   else "weight gradients accumulated micro-batch by micro-batch")
                                + ("; row gather fused into the GEMMs" if fused_gather else "")
+                               + ("; histogram and host plan of the next batch overlapped with the step" if args.plan == "ahead"
+                                  else "; histogram and host plan at the head of the step")
                                + {"fwd-transposed": "; forward GEMMs on transposed weight copies made once per step",
                                   "bwd-transposed": "; data gradients on transposed weight copies made once per step",
                                   "plain": ""}[args.weights],
