@@ -390,12 +390,18 @@ int relibra_transpose_experts(const void *in_dev, int n_blocks, int rows, int co
  *       bwd_workspace = the workspace that
  *       micro-batch's deferred backward call used (same n_rows, G, hff);
  *       inst_ptr [E+1], inst_group [inst_cap], group_offset [G+1] int32: the plan's tables
- *   dWg, dWu [E,hff,h], dWd [E,h,hff] fp32 dev: overwritten, or added to if accumulate != 0
+ *   dWg, dWu [E,hff,h], dWd [E,h,hff] fp32 dev: overwritten, or added to with RELIBRA_WGRAD_ACCUMULATE
+ *   flags: RELIBRA_WGRAD_ACCUMULATE, and optionally one of RELIBRA_WGRAD_TILE_NARROW / _WIDE to fix the
+ *       output tile (256 x 128, two workgroups per compute unit, or 256 x 256, one): by default the
+ *       wide tile is taken when an expert averages 16384 rows or more over the batch
+ *       (n_rows * n_mb / E), where operand re-reads bound the kernel.  Same sums in the same order
+ *       either way: results are identical bit for bit.  Other bits: RELIBRA_EINVAL.
  *   workspace_dev: relibra_workspace_bytes(RELIBRA_WS_WGRAD_BATCHED, ...) bytes
  * Table entries out of range are skipped and flagged RELIBRA_ERR_GROUP_TABLE.
  * Limits: 1 <= n_mb <= RELIBRA_MAX_WGRAD_MB, h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.
  */
 #define RELIBRA_MAX_WGRAD_MB 48
+enum { RELIBRA_WGRAD_ACCUMULATE = 1, RELIBRA_WGRAD_TILE_NARROW = 2, RELIBRA_WGRAD_TILE_WIDE = 4 };
 typedef struct relibra_wgrad_mb {
     const void *dYrows_dev, *Xrows_dev, *A_save_dev;
     const void *bwd_workspace_dev;
@@ -409,7 +415,7 @@ typedef struct relibra_wgrad_mb {
 
 int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs_host, int n_mb, int n_rows,
                                   int G, int inst_cap, int E, int h, int hff,
-                                  float *dWg_dev, float *dWu_dev, float *dWd_dev, int accumulate,
+                                  float *dWg_dev, float *dWu_dev, float *dWd_dev, int flags,
                                   void *workspace_dev, size_t workspace_bytes,
                                   int32_t *err_flag_dev, relibra_stream stream);
 

@@ -21,6 +21,7 @@ ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
 WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD, WS_WGRAD_BATCHED = 0, 1, 2, 3
 BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD, BWD_TRANSPOSED_WEIGHTS = 1, 2, 4, 8, 16
 FWD_TRANSPOSED_WEIGHTS = 1
+WGRAD_ACCUMULATE, WGRAD_TILE_NARROW, WGRAD_TILE_WIDE = 1, 2, 4
 MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
@@ -445,7 +446,7 @@ class WgradMb(C.Structure):
                 ("group_offset_dev", C.c_void_p), ("X_dev", C.c_void_p), ("row_tok_dev", C.c_void_p), ("n_tokens", C.c_int)]
 
 
-def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, workspace=None, err_flag=None):
+def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, workspace=None, err_flag=None, tile=None):
     """mbs: list of dicts(dYrows, Xrows (or X and row_tok: fused gather), A, bwd_workspace, inst_ptr,
     inst_group, group_offset) of device tensors, one per micro-batch whose backward ran with BWD_DEFER_WGRAD.  Writes dWg, dWu [E,h',h],
     dWd [E,h,h'] fp32 in place (sum over all micro-batches and instances)."""
@@ -476,7 +477,8 @@ def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, works
         err_flag = new_err_flag(dev)
     rc = lib().relibra_moe_ffn_wgrad_batched(arr, n_mb, n_rows, G, inst_cap, int(E), h, hff,
                                              _dp(dWg, torch.float32), _dp(dWu, torch.float32), _dp(dWd, torch.float32),
-                                             1 if accumulate else 0, _dp(workspace), C.c_size_t(workspace.numel()),
+                                             (WGRAD_ACCUMULATE if accumulate else 0) | {None: 0, "narrow": WGRAD_TILE_NARROW, "wide": WGRAD_TILE_WIDE}[tile],
+                                             _dp(workspace), C.c_size_t(workspace.numel()),
                                              _dp(err_flag), _stream())
     _check("relibra_moe_ffn_wgrad_batched", rc)
     return err_flag

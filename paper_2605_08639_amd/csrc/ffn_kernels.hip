@@ -530,20 +530,23 @@ template <class KL, int NA, int BA>
 __device__ __forceinline__ void wgrad_epilogue(typename KL::Acc &acc, char *lds, float *out0, float *out1, size_t base,
                                                int m0, int n0, int m_dim, int n_dim, bool add, int wave, int lane)
 {
-    static_assert(KL::TB == 2, "a wave owns 64 columns");
+    static_assert(KL::TB % 2 == 0, "a wave owns a multiple of 64 columns");
     __syncthreads();                                          // every wave is done with the operand slabs
     float *buf = reinterpret_cast<float *>(lds + wave * 8192);
-    const int wm0 = m0 + (wave / (NWAVES / 2)) * (BA / 2), wn0 = n0 + (wave % (NWAVES / 2)) * 64;
-    const int col4 = lane & 15, gcol = wn0 + col4 * 4;
+    const int wm0 = m0 + (wave / (NWAVES / 2)) * (BA / 2);
+    const int col4 = lane & 15;
+#pragma unroll
+    for (int half = 0; half < KL::TB / 2; ++half)             // 64 columns of the wave at a time
 #pragma unroll
     for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int ta = 0; ta < KL::TA; ++ta) {
+            const int wn0 = n0 + (wave % (NWAVES / 2)) * (KL::TB * 32) + half * 64, gcol = wn0 + col4 * 4;
 #pragma unroll
-            for (int tb = 0; tb < KL::TB; ++tb)
+            for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    buf[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 64 + tb * 32 + (lane & 31)] = acc[a][ta][tb][v];
+                    buf[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * 64 + tb * 32 + (lane & 31)] = acc[a][ta][half * 2 + tb][v];
             wave_lds_fence();
             float *out = (a == 0 ? out0 : out1) + base;
             float4 val[8];
@@ -766,16 +769,24 @@ struct WgradPieces {
     }
 };
 
-// NA = 1: dWd.  NA = 2: dWg, dWu.
-template <int NA>
-__global__ void __launch_bounds__(THREADS, WgradCfg<256>::OCC)
+// NA = 1: dWd.  NA = 2: dWg, dWu.  WN: columns of a tile.  128: three slabs, two workgroups per
+// compute unit.  256: a wave holds 128 x 128 of the tile (256 accumulator registers, one wave per
+// SIMD, four slabs): half the LDS fragment reads and two thirds of the operand bytes per flop.
+template <int WN> struct WgradWide {
+    static constexpr int STAGES = WN == 256 ? 4 : WgradCfg<256>::STAGES;
+    static constexpr int OCC = WN == 256 ? 1 : WgradCfg<256>::OCC;
+    static constexpr int SLABS = STAGES * (256 + WN) * BK * 2;
+    static constexpr int LDS = SLABS > NWAVES * 8192 ? SLABS : NWAVES * 8192;
+};
+template <int NA, int WN>
+__global__ void __launch_bounds__(THREADS, WgradWide<WN>::OCC)
 wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int accumulate,
                      float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int WGM = 256, BA = WGM / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES>;
+    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWAVES / 2, 1, true, WgradWide<WN>::STAGES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
+    const int n_nt = (n_dim + WN - 1) / WN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;
     // Tile list: experts in descending order of rows, each expert's tiles in band order, cut into
     // chunks of kWgradChunk tiles (an 8 x 8 patch sharing operand tiles).  The chunks are dealt to
@@ -791,7 +802,7 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int mt, nt;
     band_order((int)(tile % per_expert), n_mt, n_nt, mt, nt);
-    const int m0 = mt * BA, n0 = nt * WGN;
+    const int m0 = mt * BA, n0 = nt * WN;
     typename KL::Acc acc;
     KL::zero(acc);
     const int s0 = w.piece_ptr[e];
@@ -865,8 +876,10 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<128>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<128>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     done = true;
@@ -1033,10 +1046,13 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
 
 extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_mb, int n_rows,
                                              int G, int inst_cap, int E, int h, int hff,
-                                             float *dWg, float *dWu, float *dWd, int accumulate,
+                                             float *dWg, float *dWu, float *dWd, int flags,
                                              void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
+    if (flags & ~(RELIBRA_WGRAD_ACCUMULATE | RELIBRA_WGRAD_TILE_NARROW | RELIBRA_WGRAD_TILE_WIDE)) return RELIBRA_EINVAL;
+    if ((flags & RELIBRA_WGRAD_TILE_NARROW) && (flags & RELIBRA_WGRAD_TILE_WIDE)) return RELIBRA_EINVAL;
+    const int accumulate = (flags & RELIBRA_WGRAD_ACCUMULATE) ? 1 : 0;
     const FfnArgs a{n_rows, G, 0, G, E, h, hff};
     if (int rc = check_ffn_args(a)) return rc;
     if (!mbs || n_mb < 1 || n_mb > kMaxWgradMb || inst_cap < 1 || E > 4096) return RELIBRA_EINVAL;
@@ -1077,13 +1093,33 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
         const long long chunks = ((long long)E * tiles_per_expert + kWgradChunk - 1) / kWgradChunk;
         return (unsigned)(8 * ((chunks + 7) / 8) * kWgradChunk);
     };
-    const unsigned g_down = grid_of((long long)((h + 255) / 256) * ((hff + WGN - 1) / WGN));      // dWd: m in h, n in h'
-    const unsigned g_gu = grid_of((long long)((hff + 127) / 128) * ((h + WGN - 1) / WGN));        // dWg, dWu: m in h', n in h
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1><<<g_down, THREADS, WgradCfg<256>::LDS, stream>>>(
-        tb, E, h, hff, w, accumulate, dWd, nullptr));
+    // Tile width.  The 256-column tile moves two thirds of the operand bytes per flop but runs one
+    // wave per SIMD.  Long contractions (an expert's rows of the whole batch) let the tiles that share
+    // operands drift apart in k until the L2 no longer serves the re-reads; then the kernel is bound by
+    // that traffic and the wide tile wins (config 5, 32 k rows per expert: 71 -> 55 ms and 127 -> 116 ms),
+    // while at 8 k rows per expert and below it loses (config 2: 3.9 -> 4.5 ms and 8.1 -> 8.5 ms).
+    const bool long_k = (long long)n_rows * n_mb >= (long long)16384 * E;
+    const bool forced = (flags & (RELIBRA_WGRAD_TILE_NARROW | RELIBRA_WGRAD_TILE_WIDE)) != 0;
+    const bool want_wide = forced ? (flags & RELIBRA_WGRAD_TILE_WIDE) != 0 : long_k;
+    const bool wide_down = want_wide && (forced || hff >= 256), wide_gu = want_wide && (forced || h >= 256);
+    const int wn_down = wide_down ? 256 : 128, wn_gu = wide_gu ? 256 : 128;
+    const unsigned g_down = grid_of((long long)((h + 255) / 256) * ((hff + wn_down - 1) / wn_down));  // dWd: m in h, n in h'
+    const unsigned g_gu = grid_of((long long)((hff + 127) / 128) * ((h + wn_gu - 1) / wn_gu));        // dWg, dWu: m in h', n in h
+    if (wide_down) {
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1, 256><<<g_down, THREADS, WgradWide<256>::LDS, stream>>>(
+            tb, E, h, hff, w, accumulate, dWd, nullptr));
+    } else {
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1, 128><<<g_down, THREADS, WgradWide<128>::LDS, stream>>>(
+            tb, E, h, hff, w, accumulate, dWd, nullptr));
+    }
     RELIBRA_HIP_TRY(launch_check());
-    RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2><<<g_gu, THREADS, WgradCfg<256>::LDS, stream>>>(
-        tb, E, hff, h, w, accumulate, dWg, dWu));
+    if (wide_gu) {
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2, 256><<<g_gu, THREADS, WgradWide<256>::LDS, stream>>>(
+            tb, E, hff, h, w, accumulate, dWg, dWu));
+    } else {
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2, 128><<<g_gu, THREADS, WgradWide<128>::LDS, stream>>>(
+            tb, E, hff, h, w, accumulate, dWg, dWu));
+    }
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }

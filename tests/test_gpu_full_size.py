@@ -193,5 +193,8 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
     rl.relibra_moe_ffn_wgrad_batched([one_f, one_f], E, *dWf, err_flag=err)
     for a_, b_ in zip(dWf, dWb):
         assert torch.equal(a_, b_)
+    rl.relibra_moe_ffn_wgrad_batched([one_f, one_f], E, *dWf, err_flag=err, tile="wide")     # the 256-column tiles
+    for a_, b_ in zip(dWf, dWb):
+        assert torch.equal(a_, b_)
     assert err.item() == 0
     print(f"[{cfg.name}] fused row gather ok", flush=True)

@@ -548,6 +548,14 @@ def test_batched_weight_gradients_match_oracle_and_per_microbatch_path():
     assert err.item() == 0
     for a_, b_ in zip(dW_f, dW_b):
         assert torch.equal(a_, b_)
+    # both output tile shapes, forced (the default picks by contraction length): same sums, same order
+    for tile in ("narrow", "wide"):
+        for inputs in (kept, fused):
+            dW_t = [torch.full((cfg.E, *s), float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+            rl.relibra_moe_ffn_wgrad_batched(inputs, cfg.E, *dW_t, err_flag=err, tile=tile)
+            assert err.item() == 0
+            for a_, b_ in zip(dW_t, dW_b):
+                assert torch.equal(a_, b_), tile
     once = [w.clone() for w in dW_b]
     rl.relibra_moe_ffn_wgrad_batched(kept, cfg.E, *dW_b, accumulate=True, err_flag=err)
     for got, one in zip(dW_b, once):

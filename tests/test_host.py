@@ -144,6 +144,8 @@ def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
     assert L.relibra_moe_ffn_wgrad_batched(one, rl.MAX_WGRAD_MB + 1, 16, 12, 10, 8, 128, 256, f, f, f, 0, z,
                                            ctypes.c_size_t(0), z, z) == rl.EINVAL
     assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 100, 256, f, f, f, 0, z, ctypes.c_size_t(0), z, z) == rl.EUNSUPPORTED
+    assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 128, 256, f, f, f, 8, z, ctypes.c_size_t(0), z, z) == rl.EINVAL   # unknown flag
+    assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 128, 256, f, f, f, 6, z, ctypes.c_size_t(0), z, z) == rl.EINVAL   # both tiles
     assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 128, 256, f, f, f, 0, z, ctypes.c_size_t(0), z, z) == rl.EINVAL  # null dW
     assert rl.workspace_bytes(rl.WS_WGRAD_BATCHED, 0, 1, 8, 12, 128, 256) > 0
 
