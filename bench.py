@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--wgrad", choices=("batched", "per-mb"), default="batched",
                     help="weight gradients once per batch over all resident micro-batches (default), or "
                          "accumulated into dW micro-batch by micro-batch")
+    ap.add_argument("--wgrad-tile", choices=("auto", "narrow", "wide"), default="auto",
+                    help="output tile of the batched weight gradients (auto: by contraction length)")
     ap.add_argument("--gathered-copy", action="store_true",
                     help="materialise the group-ordered rows in the permutation (default with batched weight gradients: "
                          "the GEMMs gather token rows themselves)")
@@ -156,7 +158,8 @@ def main():
                     inst_ptr=tabs["inst_ptr"][mb], inst_group=tabs["inst_group"][mb], group_offset=tabs["group_offset"][mb],
                     **(dict(X=tok[mb][0], row_tok=row_tok_k[mb]) if fused_gather else dict(Xrows=Xrows_k[mb])))
                for mb in range(n_mb)]
-        rl.relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, workspace=ws_wgrad, err_flag=err)
+        rl.relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, workspace=ws_wgrad, err_flag=err,
+                                         tile=None if args.wgrad_tile == "auto" else args.wgrad_tile)
 
     plan_ms = []
 
