@@ -16,7 +16,7 @@ import argparse
 import json
 import os
 import sys
-import threading
+import concurrent.futures
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -171,6 +171,7 @@ def main():
     # --plan inline: histogram, crossing and plan at the head of the step that uses them.
     counts_pin = torch.empty((n_mb, E), dtype=torch.int32, pin_memory=True)
     ahead = {"thread": None, "plan": None}
+    planner_pool = concurrent.futures.ThreadPoolExecutor(max_workers=1)        # one resident host thread
 
     def plan_from(counts_h):
         tp = time.perf_counter()
@@ -187,14 +188,13 @@ def main():
         def work():
             ev.synchronize()
             ahead["plan"] = plan_from(counts_pin.numpy())
-        ahead["thread"] = threading.Thread(target=work)
-        ahead["thread"].start()
+        ahead["thread"] = planner_pool.submit(work)
 
     def step():
         if args.plan == "ahead":
             if ahead["thread"] is None:                         # very first step: nothing was prepared
                 launch_planning()
-            ahead["thread"].join()
+            ahead["thread"].result()
             plan = ahead["plan"]
             launch_planning()                                   # for the step after this one
         else:
@@ -233,7 +233,7 @@ def main():
     for _ in range(args.steps):
         plan, tabs = step()
     if ahead["thread"] is not None:
-        ahead["thread"].join()          # the plan prepared during the last step belongs to the timed work
+        ahead["thread"].result()        # the plan prepared during the last step belongs to the timed work
     torch.cuda.synchronize()
     t_end = time.perf_counter()
     prof = rl.prof_stop()
