@@ -224,7 +224,9 @@ __device__ __forceinline__ RowTile find_row_tile(const Sched &s, int n_col_tiles
     return t;
 }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
+// 1 / (1 + e^-x) with the hardware reciprocal (1 ulp; the result is rounded to bf16 anyway): a
+// plain division expands to the ten-instruction IEEE sequence, 128 times per lane and tile.
+__device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
 __device__ __forceinline__ uint2 pack4bf(float a, float b, float c, float d)
 {
