@@ -262,29 +262,67 @@ struct WaveStage {
     static __device__ __forceinline__ void put(char *buf, int row, int col, uint2 v) { *reinterpret_cast<uint2 *>(buf + acc_addr(row, col)) = v; }
     static __device__ __forceinline__ uint2 get(const char *buf, int row, int col) { return *reinterpret_cast<const uint2 *>(buf + acc_addr(row, col)); }
 
-    // row-major side: stage -> global, rows grow0.. of a tensor with leading dimension ld
+    // row-major side: stage -> global, rows grow0.. of a tensor with leading dimension ld.
+    // All LDS reads first, then the (predicated) stores: left to itself the compiler moves every
+    // read into the branch of its store, and each store then waits for its own read in turn.
     static __device__ __forceinline__ void flush(const char *buf, bf16_t *out, int ld, int grow0, int row_end,
                                                  int gcol0, int n_dim, int lane)
     {
+        uint4 v[PASSES];
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
-            const uint4 v = *reinterpret_cast<const uint4 *>(buf + r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4));
+            v[p] = *reinterpret_cast<const uint4 *>(buf + r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4));
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)          // the values are needed here: the reads stay above
+            asm volatile("" : "+v"(v[p].x), "+v"(v[p].y), "+v"(v[p].z), "+v"(v[p].w));
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
             if (grow0 + r < row_end && gcol0 + piece * 8 < n_dim)
-                *reinterpret_cast<uint4 *>(out + (size_t)(grow0 + r) * ld + gcol0 + piece * 8) = v;
+                *reinterpret_cast<uint4 *>(out + (size_t)(grow0 + r) * ld + gcol0 + piece * 8) = v[p];
         }
     }
-    // global -> stage
+    // global -> stage.  Rows and columns beyond the tensor are read from clamped (valid) addresses
+    // instead of being skipped: what lands in their places is never stored by flush, and without
+    // the predicates all loads of the fill are in flight together (predicated, every load was
+    // waited for before the next one went out: one memory round trip per pass).
+    // Needs grow0 < row_end and n_dim >= 8.
+    // two tensors of the same shape into two staging areas, all loads in flight together
+    static __device__ __forceinline__ void fill2(char *buf0, char *buf1, const bf16_t *in0, const bf16_t *in1, int ld, int grow0,
+                                                 int row_end, int gcol0, int n_dim, int lane)
+    {
+        uint4 v0[PASSES], v1[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
+            const size_t at = (size_t)min(grow0 + r, row_end - 1) * ld + min(gcol0 + piece * 8, n_dim - 8);
+            v0[p] = *reinterpret_cast<const uint4 *>(in0 + at);
+            v1[p] = *reinterpret_cast<const uint4 *>(in1 + at);
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
+            const int at = r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4);
+            *reinterpret_cast<uint4 *>(buf0 + at) = v0[p];
+            *reinterpret_cast<uint4 *>(buf1 + at) = v1[p];
+        }
+    }
     static __device__ __forceinline__ void fill(char *buf, const bf16_t *in, int ld, int grow0, int row_end,
                                                 int gcol0, int n_dim, int lane)
     {
+        uint4 v[PASSES];
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (grow0 + r < row_end && gcol0 + piece * 8 < n_dim)
-                v = *reinterpret_cast<const uint4 *>(in + (size_t)(grow0 + r) * ld + gcol0 + piece * 8);
-            *reinterpret_cast<uint4 *>(buf + r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4)) = v;
+            const int gr = min(grow0 + r, row_end - 1), gc = min(gcol0 + piece * 8, n_dim - 8);
+            v[p] = *reinterpret_cast<const uint4 *>(in + (size_t)gr * ld + gc);
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int r = p * ROWS_PER_PASS + lane / PIECES, piece = lane % PIECES;
+            *reinterpret_cast<uint4 *>(buf + r * (NCOLS * 2) + (((piece ^ r) & (PIECES - 1)) << 4)) = v[p];
         }
     }
 };
@@ -414,8 +452,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int hcol0 = wcol0 + half * (WCOLS / 2);
-            SH::fill(buf_g, Gt, n_dim, wrow0, row_end, hcol0, n_dim, lane);
-            SH::fill(buf_u, U, n_dim, wrow0, row_end, hcol0, n_dim, lane);
+            SH::fill2(buf_g, buf_u, Gt, U, n_dim, wrow0, row_end, hcol0, n_dim, lane);
             wave_lds_fence();
 #pragma unroll
             for (int tb = 0; tb < KL::TB; ++tb)
