@@ -337,6 +337,10 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The k-loops issue a slab's loads one by one between the MFMAs of a slab period instead of in one
+// burst behind the barrier (gemm_tile.h); needs a ring of at least three slabs to pay.
+constexpr bool kSpreadLoads = true;
+
 // Wave layouts: every wave owns 64 rows; the waves left over split the columns.
 template <int BB> struct Waves { static constexpr int B = BB / 64, A = NWAVES / B; };
 
@@ -348,7 +352,7 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
                                                  int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout, char *lds)
 {
     using WTile = typename std::conditional<WT, KsTile<128>, KcTile<128>>::type;
-    using KL = KLoop<WTile, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false, NSTAGES>;
+    using KL = KLoop<WTile, KcTile<BB>, 2, 1, 128, BB, Waves<BB>::A, Waves<BB>::B, 1, false, NSTAGES, 0, kSpreadLoads>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t wofs = (size_t)t.expert * hff * h;
     const int ldw = WT ? hff : h;                             // (n in h', k in h) at [n*h + k], or at [k*h' + n]
@@ -411,7 +415,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
                                               bf16_t *out0, bf16_t *out1, const bf16_t *Gt, const bf16_t *U, char *lds)
 {
     using WT = typename std::conditional<W_KS, KsTile<256>, KcTile<256>>::type;
-    using KL = KLoop<WT, KcTile<BB>, 1, 1, 256, BB, Waves<BB>::A, Waves<BB>::B, NPH, false, NSTAGES>;
+    using KL = KLoop<WT, KcTile<BB>, 1, 1, 256, BB, Waves<BB>::A, Waves<BB>::B, NPH, false, NSTAGES, 0, kSpreadLoads>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Operand A[NPH][1], B[NPH][1];
     A[0][0] = {W0, ldw, t.col0, n_dim - 1};
@@ -632,7 +636,7 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
              float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int BA = WGM / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES>;
+    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES, 0, (kSpreadLoads && WgradCfg<WGM>::STAGES >= 3)>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
     const int per_group = n_nt * n_mt;
@@ -823,7 +827,7 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
                      float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int WGM = 256, BA = WGM / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWAVES / 2, 1, true, WgradWide<WN>::STAGES>;
+    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWAVES / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WN - 1) / WN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;

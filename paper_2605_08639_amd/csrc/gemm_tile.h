@@ -15,6 +15,7 @@
 // a lane fetches is free, so the swizzle is applied on the global side.
 #pragma once
 #include "common.h"
+#include <type_traits>
 
 namespace relibra {
 
@@ -116,13 +117,19 @@ struct KcTile {
     struct Idx {};                                     // nothing to look up per slab
     template <int NW>
     static __device__ __forceinline__ void fetch(Idx<NW> &, const Lanes<NW> &, int, int, int) {}
+    // load block number i (0 .. BLOCKS/NW - 1) of this wave's share of a slab
     template <int NW>
-    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &, int k0, int /*k_last*/, int wave,
-                                                int /*lane*/)
+    static __device__ __forceinline__ void load_one(char *lds, const Lanes<NW> &ln, const Idx<NW> &, int k0, int /*k_last*/, int wave,
+                                                    int /*lane*/, int i)
+    {
+        load_lds16(ln.p[i] + k0, lds + (wave + i * NW) * 1024);
+    }
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
+                                                int lane)
     {
 #pragma unroll
-        for (int i = 0; i < BLOCKS / NW; ++i)
-            load_lds16(ln.p[i] + k0, lds + (wave + i * NW) * 1024);
+        for (int i = 0; i < BLOCKS / NW; ++i) load_one<NW>(lds, ln, ix, k0, k_last, wave, lane, i);
     }
 
     // fragment of rows r0..r0+31 (r0 % 32 == 0), k = kk*16 + (lane/32)*8 .. +7
@@ -172,31 +179,35 @@ struct KsTile {
             for (int q = 0; q < KPB; ++q) ix.v[i][q] = g[min(k0 + (wave + i * NW) * KPB + q, k_last)];
     }
     template <int NW>
-    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
-                                                int lane)
+    static __device__ __forceinline__ void load_one(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
+                                                    int lane, int i)
     {
         static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
         const Operand &op = ln.op;
+        const int j = wave + i * NW;
+        const int k = j * KPB + lane / SPR;
+        const int s = (lane % SPR) ^ fk(k);
+        int grow = op.row0 + s * 8;
+        if (grow > op.row_last) grow = op.row_last - 7;
+        int mrow;                                   // row of `base` that holds this k-row
+        if (op.gather) {
+            // this lane's k-row picks its lookup by masks (a select over the array would be turned
+            // into a dynamically indexed, hence memory-resident, array)
+            mrow = 0;
 #pragma unroll
-        for (int i = 0; i < BLOCKS / NW; ++i) {
-            const int j = wave + i * NW;
-            const int k = j * KPB + lane / SPR;
-            const int s = (lane % SPR) ^ fk(k);
-            int grow = op.row0 + s * 8;
-            if (grow > op.row_last) grow = op.row_last - 7;
-            int mrow;                                   // row of `base` that holds this k-row
-            if (op.gather) {
-                // this lane's k-row picks its lookup by masks (a select over the array would be turned
-                // into a dynamically indexed, hence memory-resident, array)
-                mrow = 0;
-#pragma unroll
-                for (int q = 0; q < KPB; ++q) mrow |= ix.v[i][q] & -(int)(lane / SPR == q);
-                mrow = min(max(mrow, 0), op.gather_last);
-            } else {
-                mrow = min(k0 + k, k_last);
-            }
-            load_lds16(op.base + (size_t)mrow * op.ld + grow, lds + j * 1024);
+            for (int q = 0; q < KPB; ++q) mrow |= ix.v[i][q] & -(int)(lane / SPR == q);
+            mrow = min(max(mrow, 0), op.gather_last);
+        } else {
+            mrow = min(k0 + k, k_last);
         }
+        load_lds16(op.base + (size_t)mrow * op.ld + grow, lds + j * 1024);
+    }
+    template <int NW>
+    static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
+                                                int lane)
+    {
+#pragma unroll
+        for (int i = 0; i < BLOCKS / NW; ++i) load_one<NW>(lds, ln, ix, k0, k_last, wave, lane, i);
     }
 
     static __device__ __forceinline__ bf16x8_t frag(const char *lds, int r0, int kk, int lane)
@@ -238,7 +249,8 @@ __device__ __forceinline__ bf16x8_t mask_frag(bf16x8_t f, int k_first, int k_val
 //   requests the first fragments of slab t+1 and runs the other half, which covers them.
 // DBG switches parts of the loop off for timing experiments (1: no loads after the prologue,
 // 2: loads only, 3: no loads and no barrier); the library always builds DBG = 0.
-template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0>
+template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0,
+          bool SPREAD = false>
 struct KLoop {
     static constexpr int NW = WA * WB;
     static constexpr int DEPTH = AT::DEPTH;           // k-values per slab
@@ -341,6 +353,37 @@ struct KLoop {
             for (int t = 0; t < TB; ++t) f.b[b][t] = mask_frag(f.b[b][t], k_first, k_valid);
     }
 
+    // Load number j (0 .. LOADS-1) of this wave's share of slab t: A-side operands first.
+    static constexpr int LA = AT::BLOCKS / NW, LB = BT::BLOCKS / NW;
+    static __device__ __forceinline__ void issue_one(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
+                                                     const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane, int j)
+    {
+        const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
+        const int k0 = (t - ph * steps_per_phase) * DEPTH;
+        const int q = (NPH == 1 || ph == 0) ? 0 : NPH - 1;
+        if (j < NA * LA) {
+            const int a = j / LA;
+            AT::template load_one<NW>(stage + a * AT::BYTES, PA[q][a], lk.a[a], k0, k_last, wave, lane, j % LA);
+        } else {
+            const int b = (j - NA * LA) / LB;
+            BT::template load_one<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane,
+                                      (j - NA * LA) % LB);
+        }
+    }
+
+    // Fragment number j (0 .. N_FRAGS-1) of MFMA step kk: A side first.
+    static constexpr int N_FRAGS = NA * TA + NB * TB;
+    static __device__ __forceinline__ void read_frag_one(Frags &f, const char *stage, int kk, int wa, int wb, int lane, int j)
+    {
+        if (j < NA * TA) {
+            const int a = j / TA, t = j % TA;
+            f.a[a][t] = AT::frag(stage + a * AT::BYTES, wa * (BA / WA) + t * 32, kk, lane);
+        } else {
+            const int b = (j - NA * TA) / TB, t = (j - NA * TA) % TB;
+            f.b[b][t] = BT::frag(stage + NA * AT::BYTES + b * BT::BYTES, wb * (BB / WB) + t * 32, kk, lane);
+        }
+    }
+
     // MFMAs number lo .. hi-1 of the NA*NB*TA*TB of one k16 step (all of them: 0 .. N_MFMA)
     static constexpr int N_MFMA = NA * NB * TA * TB;
     template <int LO, int HI>
@@ -361,6 +404,44 @@ struct KLoop {
                     }
     }
     static __device__ __forceinline__ void mfma_all(Acc &acc, const Frags &f) { mfma_range<0, N_MFMA>(acc, f); }
+
+    static __device__ __forceinline__ void mfma_one(Acc &acc, const Frags &f, int idx)
+    {
+        const int tb = idx % TB, ta = (idx / TB) % TA, ab = idx / (TA * TB);
+        acc[ab][ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ab / NB][ta], f.b[ab % NB][tb], acc[ab][ta][tb], 0, 0, 0);
+    }
+
+    // Spread loads (SPREAD): a slab's loads go out one by one between the MFMAs of a slab period
+    // instead of in one burst.  The window of slab t+STAGES's loads runs from the last step of
+    // slab t (its place in the ring is free after that step's barrier) through steps
+    // 0 .. KSTEPS-2 of slab t+1; load j goes after MFMA number (2j+1) * WINDOW / (2 * LOADS).
+    static constexpr int WINDOW = KSTEPS * N_MFMA;
+    static constexpr int load_slot(int j) { return (2 * j + 1) * WINDOW / (2 * LOADS); }
+
+    // One MFMA step in program order: MFMA, then a share of the next step's fragment reads
+    // (all of them within the first three quarters of the step, so that the last have returned
+    // when the step ends), then the loads whose window position falls behind this MFMA.
+    // part = 0 for the last step of a slab, s + 1 for step s < KSTEPS - 1.
+    // ALWAYS: the loads are issued unconditionally (steady state); otherwise if do_load.
+    template <bool ALWAYS, class LoadFn>
+    static __device__ __forceinline__ void step_spread(Acc &acc, const Frags &fc, Frags &fn, const char *rd_stage, int rd_kk, int wa,
+                                                       int wb, int lane, int part, bool do_load, const LoadFn &load_j)
+    {
+        constexpr int SPAN = N_MFMA >= 4 ? N_MFMA - N_MFMA / 4 : N_MFMA;
+#pragma unroll
+        for (int m = 0; m < N_MFMA; ++m) {
+            mfma_one(acc, fc, m);
+#pragma unroll
+            for (int j = 0; j < N_FRAGS; ++j)
+                if (j * SPAN / N_FRAGS == m) read_frag_one(fn, rd_stage, rd_kk, wa, wb, lane, j);
+#pragma unroll
+            for (int j = 0; j < LOADS; ++j)
+                if (load_slot(j) == part * N_MFMA + m) {
+                    if (ALWAYS || do_load) load_j(j);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 
     // Scheduling pattern for a block of "all fragment reads of the next step, all MFMAs of this
     // step" placed in front of it in program order: one MFMA, then a share of the LDS reads, and
@@ -403,6 +484,49 @@ struct KLoop {
         __builtin_amdgcn_sched_barrier(0);
         read_frags(f[0], lds, 0, wa, wb, lane);
         int slot = 0;
+        if (SPREAD) {
+            // Two copies of the slab iteration: the steady state, where both load windows are live
+            // and the loads carry no branch (measured: the branches alone cost 5 %), and the
+            // general one for the first slab and the last STAGES.
+            char *prv = lds;
+            auto slab = [&](auto steady, int t) __attribute__((always_inline)) {
+                constexpr bool SS = decltype(steady)::value;
+                const bool ls = SS || (t >= 1 && t - 1 + STAGES < n), ll = SS || t + STAGES < n;
+                char *cur = lds + slot * STAGE_BYTES;
+                slot = (slot == STAGES - 1) ? 0 : slot + 1;
+                char *nxt = lds + slot * STAGE_BYTES;
+                const bool tail = RAGGED_K && (t + 1) * DEPTH > k_valid;
+                const int kf = t * DEPTH + (lane >> 5) * 8;
+                // steps 0 .. KSTEPS-2: the rest of the loads of slab t-1+STAGES, into slab t-1's place
+                auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one(prv, PA, PB, lk, t - 1 + STAGES, steps_per_phase, k_last, wave, lane, j); };
+#pragma unroll
+                for (int s = 0; s < KSTEPS - 1; ++s) {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): f[s & 1] is there
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (tail) mask_frags(f[s & 1], kf + s * 16, k_valid);
+                    __builtin_amdgcn_sched_barrier(0);
+                    step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur, s + 1, wa, wb, lane, s + 1, ls, load_prev);
+                }
+                wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                // Row lookups of the next window, requested behind the barrier (in front of it its
+                // wait for the LDS reads would wait for them too).  A gathered operand on the B
+                // side has its loads in the later part of the window, a step's MFMAs from here.
+                if (ll) fetch(lk, PA, PB, t + STAGES, steps_per_phase, k_last, wave);
+                // last step: the first loads of slab t+STAGES, into this slab's place
+                auto load_cur = [&](int j) __attribute__((always_inline)) { issue_one(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane, j); };
+                constexpr int L = (KSTEPS - 1) & 1;
+                if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, k_valid);
+                step_spread<SS>(acc, f[L], f[0], nxt, 0, wa, wb, lane, 0, ll, load_cur);
+                prv = cur;
+            };
+            slab(std::false_type{}, 0);
+            int t = 1;
+            for (; t < n - STAGES; ++t) slab(std::true_type{}, t);
+            for (; t < n; ++t) slab(std::false_type{}, t);
+            return;
+        }
         for (int t = 0; t < n; ++t) {
             char *cur = lds + slot * STAGE_BYTES;
             slot = (slot == STAGES - 1) ? 0 : slot + 1;
@@ -474,8 +598,7 @@ struct KLoop {
         int ct = 0, c_valid = i_valid, c_slabs = i_slabs, cp = 0;
         Lookups lk;
         auto fetch_next = [&]() { fetch(lk, PA, PB, it, i_slabs, i_valid - 1, wave); };
-        auto issue_next = [&](char *stage) {
-            issue(stage, PA, PB, lk, it, i_slabs, i_valid - 1, wave, lane);
+        auto advance_loads = [&]() {                        // the load cursor moves on by one slab
             if (++it == i_slabs && ip + 1 < n_pieces) {
                 ++ip;
                 it = 0;
@@ -483,6 +606,10 @@ struct KLoop {
                 prepare(PA, PB, Ai, Bi, wave, lane);
                 i_slabs = (i_valid + DEPTH - 1) / DEPTH;
             }
+        };
+        auto issue_next = [&](char *stage) {
+            issue(stage, PA, PB, lk, it, i_slabs, i_valid - 1, wave, lane);
+            advance_loads();
         };
         Frags f[2];
 #pragma unroll
@@ -496,6 +623,50 @@ struct KLoop {
         __builtin_amdgcn_sched_barrier(0);
         read_frags(f[0], lds, 0, wa, wb, lane);
         int slot = 0;
+        if (SPREAD) {
+            // as in run(): the load cursor stays on slab t+STAGES from the last step of slab t
+            // through the steps of slab t+1 and moves on behind that window's last load
+            char *prv = lds;
+            auto slab = [&](auto steady, int t) __attribute__((always_inline)) {
+                constexpr bool SS = decltype(steady)::value;
+                const bool ls = SS || (t >= 1 && t - 1 + STAGES < n), ll = SS || t + STAGES < n;
+                char *cur = lds + slot * STAGE_BYTES;
+                slot = (slot == STAGES - 1) ? 0 : slot + 1;
+                char *nxt = lds + slot * STAGE_BYTES;
+                const bool tail = (ct + 1) * DEPTH > c_valid;
+                const int kf = ct * DEPTH + (lane >> 5) * 8;
+                auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one(prv, PA, PB, lk, it, i_slabs, i_valid - 1, wave, lane, j); };
+#pragma unroll
+                for (int s = 0; s < KSTEPS - 1; ++s) {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (tail) mask_frags(f[s & 1], kf + s * 16, c_valid);
+                    __builtin_amdgcn_sched_barrier(0);
+                    step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur, s + 1, wa, wb, lane, s + 1, ls, load_prev);
+                }
+                if (ls) advance_loads();
+                wait_younger(n - t - 2);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                if (ll) fetch_next();
+                auto load_cur = [&](int j) __attribute__((always_inline)) { issue_one(cur, PA, PB, lk, it, i_slabs, i_valid - 1, wave, lane, j); };
+                constexpr int L = (KSTEPS - 1) & 1;
+                if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, c_valid);
+                step_spread<SS>(acc, f[L], f[0], nxt, 0, wa, wb, lane, 0, ll, load_cur);
+                prv = cur;
+                if (++ct == c_slabs && cp + 1 < n_pieces) {      // the MFMAs move on to the next piece
+                    ++cp;
+                    ct = 0;
+                    c_valid = src.valid(cp);
+                    c_slabs = (c_valid + DEPTH - 1) / DEPTH;
+                }
+            };
+            slab(std::false_type{}, 0);
+            int t = 1;
+            for (; t < n - STAGES; ++t) slab(std::true_type{}, t);
+            for (; t < n; ++t) slab(std::false_type{}, t);
+            return;
+        }
         for (int t = 0; t < n; ++t) {
             char *cur = lds + slot * STAGE_BYTES;
             slot = (slot == STAGES - 1) ? 0 : slot + 1;
