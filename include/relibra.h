@@ -392,10 +392,11 @@ int relibra_transpose_experts(const void *in_dev, int n_blocks, int rows, int co
  *       inst_ptr [E+1], inst_group [inst_cap], group_offset [G+1] int32: the plan's tables
  *   dWg, dWu [E,hff,h], dWd [E,h,hff] fp32 dev: overwritten, or added to with RELIBRA_WGRAD_ACCUMULATE
  *   flags: RELIBRA_WGRAD_ACCUMULATE, and optionally one of RELIBRA_WGRAD_TILE_NARROW / _WIDE to fix the
- *       output tile (256 x 128, two workgroups per compute unit, or 256 x 256, one): by default the
- *       wide tile is taken when an expert averages 16384 rows or more over the batch
- *       (n_rows * n_mb / E), where operand re-reads bound the kernel.  Same sums in the same order
- *       either way: results are identical bit for bit.  Other bits: RELIBRA_EINVAL.
+ *       output tile (256 x 128 with four waves, two workgroups per compute unit, or 256 x 256 with
+ *       eight waves, one): by default the wide tile wherever the output is at least 256 wide,
+ *       except for dWd when hff < 1024 and an expert averages fewer than 16384 rows over the
+ *       batch (n_rows * n_mb / E).  Same sums in the same order either way: results are identical
+ *       bit for bit.  Other bits: RELIBRA_EINVAL.
  *   workspace_dev: relibra_workspace_bytes(RELIBRA_WS_WGRAD_BATCHED, ...) bytes
  * Table entries out of range are skipped and flagged RELIBRA_ERR_GROUP_TABLE.
  * Limits: 1 <= n_mb <= RELIBRA_MAX_WGRAD_MB, h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.

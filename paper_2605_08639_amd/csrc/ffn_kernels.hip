@@ -569,14 +569,14 @@ transpose_experts_kernel(const bf16_t *__restrict__ in, int rows, int cols, bf16
 // Weight-gradient epilogue.  The accumulators hold, per lane, one column n and 16 rows m of each
 // MFMA tile; each 32 x 64 fp32 block of the wave goes through this wave's 8 KiB of LDS and
 // leaves as 16 bytes per lane along n: 1 KiB per store (or load-add-store) instruction.
-template <class KL, int NA, int BA>
+template <class KL, int NA, int BA, int NWV = NWAVES>
 __device__ __forceinline__ void wgrad_epilogue(typename KL::Acc &acc, char *lds, float *out0, float *out1, size_t base,
                                                int m0, int n0, int m_dim, int n_dim, bool add, int wave, int lane)
 {
     static_assert(KL::TB % 2 == 0, "a wave owns a multiple of 64 columns");
     __syncthreads();                                          // every wave is done with the operand slabs
     float *buf = reinterpret_cast<float *>(lds + wave * 8192);
-    const int wm0 = m0 + (wave / (NWAVES / 2)) * (BA / 2);
+    const int wm0 = m0 + (wave / (NWV / 2)) * (BA / 2);
     const int col4 = lane & 15;
 #pragma unroll
     for (int half = 0; half < KL::TB / 2; ++half)             // 64 columns of the wave at a time
@@ -584,7 +584,7 @@ __device__ __forceinline__ void wgrad_epilogue(typename KL::Acc &acc, char *lds,
     for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int ta = 0; ta < KL::TA; ++ta) {
-            const int wn0 = n0 + (wave % (NWAVES / 2)) * (KL::TB * 32) + half * 64, gcol = wn0 + col4 * 4;
+            const int wn0 = n0 + (wave % (NWV / 2)) * (KL::TB * 32) + half * 64, gcol = wn0 + col4 * 4;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -812,22 +812,24 @@ struct WgradPieces {
     }
 };
 
-// NA = 1: dWd.  NA = 2: dWg, dWu.  WN: columns of a tile.  128: three slabs, two workgroups per
-// compute unit.  256: a wave holds 128 x 128 of the tile (256 accumulator registers, one wave per
-// SIMD, four slabs): half the LDS fragment reads and two thirds of the operand bytes per flop.
+// NA = 1: dWd.  NA = 2: dWg, dWu.  WN: columns of a tile.  128: four waves, three slabs, two
+// workgroups per compute unit.  256: eight waves of 128 x 64 each, one workgroup per compute unit,
+// four slabs: two thirds of the operand bytes (and load instructions) per flop, the same two
+// waves per SIMD.  (Four waves of 128 x 128 on that tile, one per SIMD, were 5-10 % slower.)
+constexpr int kWideWaves = 8;
 template <int WN> struct WgradWide {
     static constexpr int STAGES = WN == 256 ? 4 : WgradCfg<256>::STAGES;
     static constexpr int OCC = WN == 256 ? 1 : WgradCfg<256>::OCC;
     static constexpr int SLABS = STAGES * (256 + WN) * BK * 2;
-    static constexpr int LDS = SLABS > NWAVES * 8192 ? SLABS : NWAVES * 8192;
+    static constexpr int LDS = SLABS > 8 * 8192 ? SLABS : 8 * 8192;
 };
-template <int NA, int WN>
-__global__ void __launch_bounds__(THREADS, WgradWide<WN>::OCC)
+template <int NA, int WN, int NWV = NWAVES>
+__global__ void __launch_bounds__(NWV * 64, WgradWide<WN>::OCC)
 wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int accumulate,
                      float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int WGM = 256, BA = WGM / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWAVES / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads>;
+    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WN - 1) / WN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;
@@ -852,7 +854,7 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
     const WgradPieces<NA> src{tb, (const_i32_ptr)(uintptr_t)(w.piece_mb + s0), (const_i32_ptr)(uintptr_t)(w.piece_row0 + s0),
                               (const_i32_ptr)(uintptr_t)(w.piece_rows + s0), m_dim, n_dim, m0, n0};
     KL::run_pieces(acc, src, w.piece_ptr[e + 1] - s0, w.exp_slabs[e], lds, tid);
-    wgrad_epilogue<KL, NA, BA>(acc, lds, out0, out1, (size_t)e * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
+    wgrad_epilogue<KL, NA, BA, NWV>(acc, lds, out0, out1, (size_t)e * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
 }
 
 // Replica gradients return to the home copy (Section 5.1).  A thread owns element positions
@@ -921,8 +923,8 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<128>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<128>::LDS));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
-    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<1, 256, kWideWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2, 256, kWideWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     done = true;
@@ -1136,29 +1138,29 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
         const long long chunks = ((long long)E * tiles_per_expert + kWgradChunk - 1) / kWgradChunk;
         return (unsigned)(8 * ((chunks + 7) / 8) * kWgradChunk);
     };
-    // Tile width.  The 256-column tile moves two thirds of the operand bytes per flop but runs one
-    // wave per SIMD.  Long contractions (an expert's rows of the whole batch) let the tiles that share
-    // operands drift apart in k until the L2 no longer serves the re-reads; then the kernel is bound by
-    // that traffic and the wide tile wins (config 5, 32 k rows per expert: 71 -> 55 ms and 127 -> 116 ms),
-    // while at 8 k rows per expert and below it loses (config 2: 3.9 -> 4.5 ms and 8.1 -> 8.5 ms).
+    // Tile width.  The 256-column tile moves two thirds of the operand bytes per flop and is the
+    // default wherever the output is at least that wide (measured on every workload shape: 3-10 %
+    // faster), with one exception: dWd with a narrow h' and a short contraction, where its three
+    // tile columns lose to the narrow tile's six (h' = 768, 8 k rows per expert: 3.76 against 3.62 ms).
     const bool long_k = (long long)n_rows * n_mb >= (long long)16384 * E;
     const bool forced = (flags & (RELIBRA_WGRAD_TILE_NARROW | RELIBRA_WGRAD_TILE_WIDE)) != 0;
-    const bool want_wide = forced ? (flags & RELIBRA_WGRAD_TILE_WIDE) != 0 : long_k;
-    const bool wide_down = want_wide && (forced || hff >= 256), wide_gu = want_wide && (forced || h >= 256);
+    const bool want_wide = (flags & RELIBRA_WGRAD_TILE_WIDE) != 0;
+    const bool wide_down = forced ? want_wide : (hff >= 1024 || (long_k && hff >= 256));
+    const bool wide_gu = forced ? want_wide : h >= 256;
     const int wn_down = wide_down ? 256 : 128, wn_gu = wide_gu ? 256 : 128;
     const unsigned g_down = grid_of((long long)((h + 255) / 256) * ((hff + wn_down - 1) / wn_down));  // dWd: m in h, n in h'
     const unsigned g_gu = grid_of((long long)((hff + 127) / 128) * ((h + wn_gu - 1) / wn_gu));        // dWg, dWu: m in h', n in h
     if (wide_down) {
-        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1, 256><<<g_down, THREADS, WgradWide<256>::LDS, stream>>>(
-            tb, E, h, hff, w, accumulate, dWd, nullptr));
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, (wgrad_batched_kernel<1, 256, kWideWaves><<<g_down, kWideWaves * 64, WgradWide<256>::LDS, stream>>>(
+            tb, E, h, hff, w, accumulate, dWd, nullptr)));
     } else {
         RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1, 128><<<g_down, THREADS, WgradWide<128>::LDS, stream>>>(
             tb, E, h, hff, w, accumulate, dWd, nullptr));
     }
     RELIBRA_HIP_TRY(launch_check());
     if (wide_gu) {
-        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2, 256><<<g_gu, THREADS, WgradWide<256>::LDS, stream>>>(
-            tb, E, hff, h, w, accumulate, dWg, dWu));
+        RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, (wgrad_batched_kernel<2, 256, kWideWaves><<<g_gu, kWideWaves * 64, WgradWide<256>::LDS, stream>>>(
+            tb, E, hff, h, w, accumulate, dWg, dWu)));
     } else {
         RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2, 128><<<g_gu, THREADS, WgradWide<128>::LDS, stream>>>(
             tb, E, hff, h, w, accumulate, dWg, dWu));
