@@ -85,6 +85,11 @@ struct KcTile {
     static constexpr int BYTES = ROWS * ROW_BYTES;
     static constexpr int BLOCKS = ROWS / RPB;
     static constexpr int READS = 1;                   // LDS read instructions per fragment
+    // Load blocks per wave and slab.  A tile with fewer blocks than waves has every block loaded
+    // by NW / BLOCKS waves (the same bytes to the same place), so that all waves issue the same
+    // number of loads and count them alike.
+    template <int NW>
+    static constexpr int per_wave() { return BLOCKS >= NW ? BLOCKS / NW : 1; }
 
     static __device__ __forceinline__ int swz(int r)
     {
@@ -95,16 +100,16 @@ struct KcTile {
     // do not change along k, and a gathered row costs its index lookup once per tile.
     template <int NW>
     struct Lanes {
-        const bf16_t *p[BLOCKS / NW];
+        const bf16_t *p[per_wave<NW>()];
     };
     template <int NW>
     static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int wave, int lane)
     {
-        static_assert(BLOCKS % NW == 0, "rows must split evenly over the waves");
+        static_assert(BLOCKS % NW == 0 || NW % BLOCKS == 0, "rows must split evenly over the waves");
         Lanes<NW> ln;
 #pragma unroll
-        for (int i = 0; i < BLOCKS / NW; ++i) {
-            const int j = wave + i * NW;
+        for (int i = 0; i < per_wave<NW>(); ++i) {
+            const int j = (wave + i * NW) % BLOCKS;
             const int r = j * RPB + lane / PIECES;
             const int c = (lane % PIECES) ^ swz(r);
             int grow = min(op.row0 + r, op.row_last);
@@ -122,14 +127,14 @@ struct KcTile {
     static __device__ __forceinline__ void load_one(char *lds, const Lanes<NW> &ln, const Idx<NW> &, int k0, int /*k_last*/, int wave,
                                                     int /*lane*/, int i)
     {
-        load_lds16(ln.p[i] + k0, lds + (wave + i * NW) * 1024);
+        load_lds16(ln.p[i] + k0, lds + ((wave + i * NW) % BLOCKS) * 1024);
     }
     template <int NW>
     static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
                                                 int lane)
     {
 #pragma unroll
-        for (int i = 0; i < BLOCKS / NW; ++i) load_one<NW>(lds, ln, ix, k0, k_last, wave, lane, i);
+        for (int i = 0; i < per_wave<NW>(); ++i) load_one<NW>(lds, ln, ix, k0, k_last, wave, lane, i);
     }
 
     // fragment of rows r0..r0+31 (r0 % 32 == 0), k = kk*16 + (lane/32)*8 .. +7
@@ -152,6 +157,8 @@ struct KsTile {
     static constexpr int BLOCKS = BKT / KPB;
     static constexpr int READS = 2;                   // LDS read instructions per fragment
     static_assert(ROWS >= 64 && ROWS <= 512, "tile height");
+    template <int NW>
+    static constexpr int per_wave() { return BLOCKS / NW; }
 
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
 
@@ -259,7 +266,8 @@ struct KLoop {
     static constexpr int TA = BA / WA / 32, TB = BB / WB / 32;
     static constexpr int STAGE_BYTES = NA * AT::BYTES + NB * BT::BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static constexpr int LOADS = (NA * AT::BLOCKS + NB * BT::BLOCKS) / NW;   // per wave per slab
+    static constexpr int LA = AT::template per_wave<NW>(), LB = BT::template per_wave<NW>();
+    static constexpr int LOADS = NA * LA + NB * LB;   // per wave per slab
     typedef f32x16_t Acc[NA * NB][TA][TB];
 
     struct Frags {
@@ -354,7 +362,6 @@ struct KLoop {
     }
 
     // Load number j (0 .. LOADS-1) of this wave's share of slab t: A-side operands first.
-    static constexpr int LA = AT::BLOCKS / NW, LB = BT::BLOCKS / NW;
     static __device__ __forceinline__ void issue_one(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
                                                      const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane, int j)
     {
