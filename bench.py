@@ -4,8 +4,8 @@
 A step = one pass of the whole hot path over one training batch of the Qwen3-30B-A3B-shaped
 workload (16 micro-batches x 8192 tokens, E=128, top-8, h=2048, h'=768, simulated EP=8, r=2):
 histogram of every micro-batch -> plan (host) -> per micro-batch: permute, expert FFN forward,
-combine, combine backward, expert FFN backward (weight gradients accumulated over the batch),
-gather backward.  Inputs are seeded synthetic and resident in HBM before the timed region.
+combine, combine backward (by default folded into the expert backward: --backward), expert FFN
+backward (weight gradients accumulated over the batch), gather backward.  Inputs are seeded synthetic and resident in HBM before the timed region.
 
 Prints ONE JSON line: metric = expert-layer fwd+bwd TFLOP/s (18*h*h'*N flops per micro-batch
 over the whole step time), plus `roofline` for the dominant kernel (HIP events recorded by the
@@ -50,6 +50,12 @@ def main():
                          "their weight operand is contraction-strided: the forward ones (default; the data gradients "
                          "read the stored layout that way already), the data gradients (both passes then read "
                          "contraction-contiguous weights), or none")
+    ap.add_argument("--backward", choices=("auto", "gate-fused", "plain"), default="auto",
+                    help="gate-fused (needs batched weight gradients and the fused row gather): the combine's backward "
+                         "folded into the expert backward (dOut rows read from the token tensor, the gate applied to dA, dgate "
+                         "reduced in the same epilogue, dWd from dOut rows against gate * A); plain: the combine-backward pass "
+                         "writes gate * dOut rows first.  auto (default): gate-fused when h' < 4096 - the fused form saves a "
+                         "bandwidth pass over N x h and costs the dWd GEMM (N x h x h') about a tenth for its gathered operand")
     ap.add_argument("--plan", choices=("ahead", "inline"), default="ahead",
                     help="histogram and host plan of the next batch overlapped with this step's kernels (default: replayed "
                          "routing is known before a batch trains), or at the head of the step that uses them")
@@ -95,9 +101,13 @@ def main():
     assert not batched or n_mb <= rl.MAX_WGRAD_MB
     n_keep = n_mb if batched else 1          # batched weight gradients keep every micro-batch's rows resident
     fused_gather = batched and not args.gathered_copy
+    gate_fused = fused_gather and (args.backward == "gate-fused" or (args.backward == "auto" and hff < 4096))
     Xrows_k = [bf(N, h) for _ in range(1 if fused_gather else n_keep)]
     row_tok_k = [i32(N) for _ in range(n_keep)] if fused_gather else []
-    dYrows_k = [bf(N, h) for _ in range(n_keep)]
+    dYrows_k = [] if gate_fused else [bf(N, h) for _ in range(n_keep)]   # gate-fused: the upstream rows are never materialised
+    Ag_k = [bf(N, hff) for _ in range(n_keep)] if gate_fused else []
+    row_gate = torch.empty(N, dtype=torch.float32, device=dev)
+    dgate_scratch = torch.empty(max(rl.workspace_bytes(rl.WS_DGATE, N, k, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
     A_k = [bf(N, hff) for _ in range(n_keep)]
     Yrows, dXrows = bf(N, h), bf(N, h)
     Gt, U = bf(N, hff), bf(N, hff)
@@ -110,7 +120,8 @@ def main():
     ws_ffn_k = [torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
                 for _ in range(n_keep)]
     ws_wgrad = torch.empty(rl.workspace_bytes(rl.WS_WGRAD_BATCHED, T, k, E, G, h, hff), dtype=torch.uint8, device=dev)
-    Xrows, dYrows, A, ws_ffn = Xrows_k[0], dYrows_k[0], A_k[0], ws_ffn_k[0]
+    Xrows, A, ws_ffn = Xrows_k[0], A_k[0], ws_ffn_k[0]
+    dYrows = dYrows_k[0] if dYrows_k else None
     transposed = args.weights != "plain"
     fwd_t, bwd_t = args.weights == "fwd-transposed", args.weights == "bwd-transposed"
     WgT = torch.empty((E, h, hff), dtype=torch.bfloat16, device=dev) if transposed else None
@@ -124,7 +135,7 @@ def main():
     def layer(mb, tabs, first):
         X, dOut = tok[mb]
         i = mb if batched else 0
-        dYr, Ar, ws = dYrows_k[i], A_k[i], ws_ffn_k[i]
+        dYr, Ar, ws = (None if gate_fused else dYrows_k[i]), A_k[i], ws_ffn_k[i]
         fw = (WgT, WuT, WdT) if fwd_t else (Wg, Wu, Wd)
         fwd_flags = rl.FWD_TRANSPOSED_WEIGHTS if fwd_t else 0
         if fused_gather:                        # the GEMMs fetch token rows through row_tok: no gathered copy
@@ -133,8 +144,13 @@ def main():
                                tabs["group_offset"][mb], None, E, tabs["group_expert"].shape[1], row_of=row_of, src_of=src_of,
                                workspace=ws_perm, err_flag=err)
             rl.relibra_row_tokens(src_of, k, T, row_tok=row_tok_k[i], err_flag=err)
-            rl.relibra_moe_ffn_fwd_gather(X, row_tok_k[i], tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
-                                          Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
+            if gate_fused:
+                rl.relibra_row_gates(src_of, gates_all[mb], row_gate=row_gate, err_flag=err)
+                rl.relibra_moe_ffn_fwd_gated(X, row_tok_k[i], row_gate, tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
+                                             Gt=Gt, U=U, A=Ar, Ag=Ag_k[i], Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
+            else:
+                rl.relibra_moe_ffn_fwd_gather(X, row_tok_k[i], tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
+                                              Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
         else:
             Xr = Xrows_k[i]
             rl.relibra_permute(ids_all[mb], tabs["inst_ptr"][mb], tabs["inst_rows"][mb], tabs["inst_group"][mb],
@@ -143,19 +159,26 @@ def main():
             rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
                                    Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
         rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
-        rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
-                                     out_rows=dYr, dgate=dgate, err_flag=err)
-        flags = rl.BWD_DEFER_WGRAD if batched else (0 if first else rl.BWD_ACCUMULATE)
         bw = (WgT, WuT, WdT) if bwd_t else (Wg, Wu, Wd)
-        rl.relibra_moe_ffn_bwd(dYr, Xr, Gt, U, Ar, tabs["group_offset"][mb], tabs["group_expert"][mb],
-                               tabs["group_dw_slot"][mb], *bw, dWg, dWu, dWd, E=E,
-                               flags=flags | (rl.BWD_TRANSPOSED_WEIGHTS if bwd_t else 0), dXrows=dXrows,
-                               workspace=ws, err_flag=err)
+        if gate_fused:
+            rl.relibra_moe_ffn_bwd_gated(dOut, row_tok_k[i], row_gate, Gt, U, tabs["group_offset"][mb], tabs["group_expert"][mb],
+                                         tabs["group_dw_slot"][mb], *bw, src_of=src_of, E=E,
+                                         flags=rl.BWD_TRANSPOSED_WEIGHTS if bwd_t else 0, dXrows=dXrows, dgate=dgate,
+                                         workspace=ws, dgate_scratch=dgate_scratch, err_flag=err)
+        else:
+            rl.relibra_unpermute_combine(rl.COMBINE_BWD, Yrows, row_of, T, k, gates=gates_all[mb], tok=dOut,
+                                         out_rows=dYr, dgate=dgate, err_flag=err)
+            flags = rl.BWD_DEFER_WGRAD if batched else (0 if first else rl.BWD_ACCUMULATE)
+            rl.relibra_moe_ffn_bwd(dYr, Xr, Gt, U, Ar, tabs["group_offset"][mb], tabs["group_expert"][mb],
+                                   tabs["group_dw_slot"][mb], *bw, dWg, dWu, dWd, E=E,
+                                   flags=flags | (rl.BWD_TRANSPOSED_WEIGHTS if bwd_t else 0), dXrows=dXrows,
+                                   workspace=ws, err_flag=err)
         rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, out_tok=dX, err_flag=err)
 
     def weight_gradients(tabs):
-        mbs = [dict(dYrows=dYrows_k[mb], A=A_k[mb], bwd_workspace=ws_ffn_k[mb],
+        mbs = [dict(bwd_workspace=ws_ffn_k[mb],
                     inst_ptr=tabs["inst_ptr"][mb], inst_group=tabs["inst_group"][mb], group_offset=tabs["group_offset"][mb],
+                    **(dict(dOut=tok[mb][1], A=Ag_k[mb]) if gate_fused else dict(dYrows=dYrows_k[mb], A=A_k[mb])),
                     **(dict(X=tok[mb][0], row_tok=row_tok_k[mb]) if fused_gather else dict(Xrows=Xrows_k[mb])))
                for mb in range(n_mb)]
         rl.relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, workspace=ws_wgrad, err_flag=err,
@@ -249,8 +272,10 @@ def main():
         w1 = 2.0 * h * hff                       # one bf16 weight matrix
         act_h, act_ff = 2.0 * h * N, 2.0 * hff * N
         act_x = 2.0 * h * T + 4.0 * N if fused_gather else act_h      # the layer's input rows: tokens + row table, or the gathered copy
+        act_dy = 2.0 * h * T + 4.0 * N if gate_fused else act_h       # the upstream rows: dOut tokens + row table, or gate * dOut rows
+        gate_rows = 4.0 * N if gate_fused else 0.0                    # the per-row gates
         if batched and name.startswith("wgrad"):   # one launch per batch: every micro-batch's rows read once, dW written once
-            return n_mb * (act_h + act_ff) + 2 * w1 * E if name == "wgrad_down" else n_mb * (2 * act_ff + act_x) + 4 * w1 * E
+            return n_mb * (act_dy + act_ff) + 2 * w1 * E if name == "wgrad_down" else n_mb * (2 * act_ff + act_x) + 4 * w1 * E
         tot = 0.0
         for mb in range(n_mb):
             rows_g = np.diff(plan["group_offset"][mb])
@@ -258,9 +283,9 @@ def main():
             home_live = int(((rows_g > 0) & (plan["group_dw_slot"][mb] < E)).sum())
             acc_mode = mb > 0
             tot += {
-                "fwd_gate_up": act_x + 2 * w1 * live + 3 * act_ff,
+                "fwd_gate_up": act_x + 2 * w1 * live + (4 if gate_fused else 3) * act_ff + gate_rows,
                 "fwd_down": act_ff + w1 * live + act_h,
-                "bwd_act": act_h + w1 * live + 2 * act_ff + 2 * act_ff,
+                "bwd_act": act_dy + w1 * live + 2 * act_ff + 2 * act_ff + 2 * gate_rows,      # + the row sums of dgate
                 "bwd_dx": 2 * act_ff + 2 * w1 * live + act_h,
                 "wgrad_down": act_h + act_ff + 2 * w1 * live + (2 * w1 * home_live if acc_mode else 0.0),
                 "wgrad_gate_up": 2 * act_ff + act_x + 4 * w1 * live + (4 * w1 * home_live if acc_mode else 0.0),
@@ -551,6 +576,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: E={E} top-{k} h={h} h'={hff} {n_mb}x{T} tokens, simulated EP={EP}, r={r}; "
                                "whole path per step (hist, plan on host, permute, FFN fwd, combine, combine bwd, FFN bwd, gather bwd); "
+                               + ("combine backward folded into the expert backward (gate-fused); " if gate_fused else "")
                                + ("weight gradients once per batch over all resident micro-batches" if batched
                                   else "weight gradients accumulated micro-batch by micro-batch")
                                + ("; row gather fused into the GEMMs" if fused_gather else "")

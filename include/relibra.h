@@ -51,7 +51,8 @@ enum {
 };
 
 /* which = */
-enum { RELIBRA_WS_PERMUTE = 0, RELIBRA_WS_FFN_FWD = 1, RELIBRA_WS_FFN_BWD = 2, RELIBRA_WS_WGRAD_BATCHED = 3 };
+enum { RELIBRA_WS_PERMUTE = 0, RELIBRA_WS_FFN_FWD = 1, RELIBRA_WS_FFN_BWD = 2, RELIBRA_WS_WGRAD_BATCHED = 3,
+       RELIBRA_WS_DGATE = 4 };
 
 /* flags of relibra_moe_ffn_bwd */
 enum {
@@ -330,6 +331,49 @@ int relibra_moe_ffn_fwd_gather(const void *X_dev, int T, const int32_t *row_tok_
                                int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * Gate-side fusion (a restructuring of this build, not of the paper: the combine of Section 2.1,
+ * a gate-weighted sum of the selected experts' outputs, is linear, so its backward can move into
+ * the expert backward).  With row_gate[r] = the gate of the assignment row r serves
+ * (relibra_row_gates: gates_dev [T*k] fp32 indexed by src_of):
+ *   forward (relibra_moe_ffn_fwd_gated): relibra_moe_ffn_fwd_gather that also stores
+ *       Ag_save [n_rows, hff] bf16 = row_gate * A, the right operand of dWd below; all other
+ *       outputs are unchanged (Yrows stays ungated: relibra_unpermute_combine applies the gates);
+ *   backward (relibra_moe_ffn_bwd_gated): takes dOut [T, h] bf16, the gradient of the combined
+ *       output, instead of dYrows = gate * dOut[token] (no combine-backward pass, no dYrows
+ *       buffer).  With dA' = Wd_e^T dOut[tok(r)]:
+ *         dGt = gate * dA' * U * silu'(Gt);  dU = gate * dA' * silu(Gt);  dx as in relibra_moe_ffn_bwd;
+ *         dgate[r] = sum_n dA'[n] * (silu(Gt) * U)[n]   (= <dOut[tok(r)], Yrows[r]> up to rounding)
+ *       dgate_dev fp32: [n_rows] by row, or, with src_of_dev != NULL, written at src_of[r]: the
+ *       gates' own [T*k] layout.  Rows outside the groups' range are left alone.  Always defers
+ *       the weight gradients (dGt, dU stay in workspace_dev for relibra_moe_ffn_wgrad_batched,
+ *       which takes dOut_dev and Ag_save in relibra_wgrad_mb); flags: RELIBRA_BWD_REPLICA_WEIGHTS,
+ *       RELIBRA_BWD_TRANSPOSED_WEIGHTS.  dgate_scratch_dev: relibra_workspace_bytes(RELIBRA_WS_DGATE,
+ *       ...) bytes (partial row sums, added in a fixed order: results are reproducible bit for bit).
+ * Errors as in the ungated calls; a src_of entry outside [0, n_rows) is skipped and flagged
+ * RELIBRA_ERR_PLAN_COVER.
+ */
+int relibra_row_gates(const int32_t *src_of_dev, const float *gates_dev, int N, float *row_gate_dev,
+                      int32_t *err_flag_dev, relibra_stream stream);
+int relibra_moe_ffn_fwd_gated(const void *X_dev, int T, const int32_t *row_tok_dev, const float *row_gate_dev, int n_rows,
+                              const int32_t *group_offset_dev, const int32_t *group_expert_dev,
+                              int G, int g_begin, int g_end, int E,
+                              const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
+                              void *Gt_save_dev, void *U_save_dev, void *A_save_dev, void *Ag_save_dev, void *Yrows_dev,
+                              int flags, void *workspace_dev, size_t workspace_bytes,
+                              int32_t *err_flag_dev, relibra_stream stream);
+int relibra_moe_ffn_bwd_gated(const void *dOut_dev, int T, const int32_t *row_tok_dev, const float *row_gate_dev,
+                              const int32_t *src_of_dev,
+                              const void *Gt_save_dev, const void *U_save_dev, int n_rows,
+                              const int32_t *group_offset_dev, const int32_t *group_expert_dev,
+                              const int32_t *group_dw_slot_dev,
+                              int G, int g_begin, int g_end, int E, int n_dw_slots,
+                              const void *Wg_dev, const void *Wu_dev, const void *Wd_dev, int h, int hff,
+                              void *dXrows_dev, float *dgate_dev, int flags,
+                              void *workspace_dev, size_t workspace_bytes,
+                              void *dgate_scratch_dev, size_t dgate_scratch_bytes,
+                              int32_t *err_flag_dev, relibra_stream stream);
+
+/*
  * Expert FFN backward over groups [g_begin, g_end).  With dy the upstream gradient of a row:
  *   dA = Wd_e^T dy;  dGt = dA * U * silu'(Gt);  dU = dA * silu(Gt);  dx = Wg_e^T dGt + Wu_e^T dU
  *   dWd += dy A^T;   dWg += dGt x^T;   dWu += dU x^T          (contraction over the group's rows)
@@ -412,6 +456,11 @@ typedef struct relibra_wgrad_mb {
     const void *X_dev;
     const int32_t *row_tok_dev;
     int n_tokens;
+    /* gate-fused backward (relibra_moe_ffn_bwd_gated): with dYrows_dev == NULL, the upstream gradient
+       of row r is dOut_dev[row_tok_dev[r]] (dOut_dev [n_tokens, h] bf16) and A_save_dev must hold the
+       gate-scaled activations Ag_save of relibra_moe_ffn_fwd_gated; needs the fused row gather
+       (Xrows_dev == NULL) */
+    const void *dOut_dev;
 } relibra_wgrad_mb;
 
 int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs_host, int n_mb, int n_rows,

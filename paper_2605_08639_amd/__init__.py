@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librelibra.so")
 
 OK, EINVAL, ERANGE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ERR_ID_RANGE, ERR_PLAN_COVER, ERR_GROUP_TABLE = 1, 2, 4
-WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD, WS_WGRAD_BATCHED = 0, 1, 2, 3
+WS_PERMUTE, WS_FFN_FWD, WS_FFN_BWD, WS_WGRAD_BATCHED, WS_DGATE = 0, 1, 2, 3, 4
 BWD_ACCUMULATE, BWD_NO_REPLICA_SUM, BWD_REPLICA_WEIGHTS, BWD_DEFER_WGRAD, BWD_TRANSPOSED_WEIGHTS = 1, 2, 4, 8, 16
 FWD_TRANSPOSED_WEIGHTS = 1
 WGRAD_ACCUMULATE, WGRAD_TILE_NARROW, WGRAD_TILE_WIDE = 1, 2, 4
@@ -27,7 +27,8 @@ COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
            "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src", "relibra_plan_timed",
-           "relibra_permute", "relibra_row_tokens", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd",
+           "relibra_permute", "relibra_row_tokens", "relibra_row_gates", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd_gated",
+           "relibra_moe_ffn_bwd_gated", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push",
            "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
@@ -364,6 +365,83 @@ def relibra_row_tokens(src_of, k, T, row_tok=None, err_flag=None):
     return row_tok
 
 
+def relibra_row_gates(src_of, gates, row_gate=None, err_flag=None):
+    """src_of [N] int32, gates [T,k] fp32 (device) -> row_gate [N] fp32: the gate of the assignment every row serves."""
+    N = src_of.shape[0]
+    assert gates.numel() == N and gates.is_contiguous()
+    if row_gate is None:
+        row_gate = torch.empty(N, dtype=torch.float32, device=src_of.device)
+    if err_flag is None:
+        err_flag = new_err_flag(src_of.device)
+    rc = lib().relibra_row_gates(_dp(src_of, torch.int32), _dp(gates, torch.float32), N, _dp(row_gate, torch.float32),
+                                 _dp(err_flag), _stream())
+    _check("relibra_row_gates", rc)
+    return row_gate
+
+
+def relibra_moe_ffn_fwd_gated(X, row_tok, row_gate, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
+                              Gt=None, U=None, A=None, Ag=None, Yrows=None, workspace=None, err_flag=None, flags=0):
+    """relibra_moe_ffn_fwd_gather that also stores Ag = row_gate * A (the operand of the gate-fused weight gradient)."""
+    T, h = X.shape
+    n_rows = row_tok.shape[0]
+    E, hff = Wg.shape[0], (Wg.shape[2] if flags & FWD_TRANSPOSED_WEIGHTS else Wg.shape[1])
+    G = group_expert.shape[0]
+    g_end = G if g_end is None else g_end
+    dev = X.device
+    mk = lambda cols: torch.empty((n_rows, cols), dtype=torch.bfloat16, device=dev)
+    Gt = mk(hff) if Gt is None else Gt
+    U = mk(hff) if U is None else U
+    A = mk(hff) if A is None else A
+    Ag = mk(hff) if Ag is None else Ag
+    Yrows = mk(h) if Yrows is None else Yrows
+    if workspace is None:
+        workspace = torch.empty(max(workspace_bytes(WS_FFN_FWD, max(n_rows, 1), 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_moe_ffn_fwd_gated(_dp(X, torch.bfloat16), T, _dp(row_tok, torch.int32), _dp(row_gate, torch.float32), n_rows,
+                                         _dp(group_offset, torch.int32), _dp(group_expert, torch.int32), G, g_begin, g_end, E,
+                                         _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16),
+                                         h, hff, _dp(Gt), _dp(U), _dp(A), _dp(Ag), _dp(Yrows), int(flags),
+                                         _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
+    _check("relibra_moe_ffn_fwd_gated", rc)
+    return Gt, U, A, Ag, Yrows
+
+
+def relibra_moe_ffn_bwd_gated(dOut, row_tok, row_gate, Gt, U, group_offset, group_expert, group_dw_slot, Wg, Wu, Wd,
+                              src_of=None, g_begin=0, g_end=None, flags=0, dXrows=None, dgate=None, workspace=None,
+                              dgate_scratch=None, err_flag=None, E=None):
+    """Gate-fused data gradients (weight gradients deferred to relibra_moe_ffn_wgrad_batched): dOut [T,h] bf16 is the
+    gradient of the combined output; -> dXrows [n_rows,h] bf16, dgate fp32 ([n_rows] by row, or with src_of in the
+    gates' [T*k] layout).  The workspace holds dGt, dU for the batched weight gradients."""
+    T, h = dOut.shape
+    n_rows = row_tok.shape[0]
+    hff = Wg.shape[2] if flags & BWD_TRANSPOSED_WEIGHTS else Wg.shape[1]
+    E = Wg.shape[0] if E is None else int(E)
+    G = group_expert.shape[0]
+    g_end = G if g_end is None else g_end
+    dev = dOut.device
+    if dXrows is None:
+        dXrows = torch.empty((n_rows, h), dtype=torch.bfloat16, device=dev)
+    if dgate is None:
+        dgate = torch.zeros(n_rows, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(workspace_bytes(WS_FFN_BWD, max(n_rows, 1), 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
+    if dgate_scratch is None:
+        dgate_scratch = torch.empty(max(workspace_bytes(WS_DGATE, max(n_rows, 1), 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
+    if err_flag is None:
+        err_flag = new_err_flag(dev)
+    rc = lib().relibra_moe_ffn_bwd_gated(_dp(dOut, torch.bfloat16), T, _dp(row_tok, torch.int32), _dp(row_gate, torch.float32),
+                                         _dp(src_of, torch.int32), _dp(Gt, torch.bfloat16), _dp(U, torch.bfloat16), n_rows,
+                                         _dp(group_offset, torch.int32), _dp(group_expert, torch.int32),
+                                         _dp(group_dw_slot, torch.int32), G, g_begin, g_end, E, E,
+                                         _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16), h, hff,
+                                         _dp(dXrows), _dp(dgate, torch.float32), int(flags),
+                                         _dp(workspace), C.c_size_t(workspace.numel()),
+                                         _dp(dgate_scratch), C.c_size_t(dgate_scratch.numel()), _dp(err_flag), _stream())
+    _check("relibra_moe_ffn_bwd_gated", rc)
+    return dXrows, dgate
+
+
 def relibra_moe_ffn_fwd_gather(X, row_tok, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
                                Gt=None, U=None, A=None, Yrows=None, workspace=None, err_flag=None, flags=0):
     """relibra_moe_ffn_fwd with the row gather fused in: X [T,h] token tensor, row_tok [n_rows]."""
@@ -443,7 +521,8 @@ class WgradMb(C.Structure):
     """relibra_wgrad_mb: one micro-batch's device pointers for the batched weight gradients."""
     _fields_ = [("dYrows_dev", C.c_void_p), ("Xrows_dev", C.c_void_p), ("A_save_dev", C.c_void_p),
                 ("bwd_workspace_dev", C.c_void_p), ("inst_ptr_dev", C.c_void_p), ("inst_group_dev", C.c_void_p),
-                ("group_offset_dev", C.c_void_p), ("X_dev", C.c_void_p), ("row_tok_dev", C.c_void_p), ("n_tokens", C.c_int)]
+                ("group_offset_dev", C.c_void_p), ("X_dev", C.c_void_p), ("row_tok_dev", C.c_void_p), ("n_tokens", C.c_int),
+                ("dOut_dev", C.c_void_p)]
 
 
 def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, workspace=None, err_flag=None, tile=None):
@@ -452,14 +531,21 @@ def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, works
     dWd [E,h,h'] fp32 in place (sum over all micro-batches and instances)."""
     n_mb = len(mbs)
     first = mbs[0]
-    n_rows, h = first["dYrows"].shape
-    hff = first["A"].shape[1]
+    n_rows, hff = first["A"].shape
+    # gate-fused form: dOut [T,h] (with X, row_tok) instead of dYrows, and A holding the gate-scaled activations
+    h = (first["dYrows"] if first.get("dYrows") is not None else first["dOut"]).shape[1]
     G = first["group_offset"].shape[0] - 1
     inst_cap = first["inst_group"].shape[0]
     dev = dWg.device
     arr = (WgradMb * n_mb)()
     for i, m in enumerate(mbs):
-        assert m["dYrows"].shape == (n_rows, h) and m["A"].shape == (n_rows, hff)
+        assert m["A"].shape == (n_rows, hff)
+        if m.get("dYrows") is not None:
+            assert m["dYrows"].shape == (n_rows, h)
+            dy, dout = _dp(m["dYrows"], torch.bfloat16), C.c_void_p(0)
+        else:
+            assert m.get("Xrows") is None and m["dOut"].shape == m["X"].shape
+            dy, dout = C.c_void_p(0), _dp(m["dOut"], torch.bfloat16)
         assert m["group_offset"].shape[0] == G + 1 and m["inst_group"].shape[0] == inst_cap and m["inst_ptr"].shape[0] == E + 1
         assert m["bwd_workspace"].numel() >= workspace_bytes(WS_FFN_BWD, max(n_rows, 1), 1, E, G, h, hff)
         if m.get("Xrows") is not None:          # group-ordered rows
@@ -468,9 +554,9 @@ def relibra_moe_ffn_wgrad_batched(mbs, E, dWg, dWu, dWd, accumulate=False, works
         else:                                   # token tensor + row -> token table (fused gather)
             assert m["X"].shape[1] == h and m["row_tok"].shape == (n_rows,)
             x_rows, x_tok, rtok, n_tok = C.c_void_p(0), _dp(m["X"], torch.bfloat16), _dp(m["row_tok"], torch.int32), m["X"].shape[0]
-        arr[i] = WgradMb(_dp(m["dYrows"], torch.bfloat16), x_rows, _dp(m["A"], torch.bfloat16),
+        arr[i] = WgradMb(dy, x_rows, _dp(m["A"], torch.bfloat16),
                          _dp(m["bwd_workspace"]), _dp(m["inst_ptr"], torch.int32), _dp(m["inst_group"], torch.int32),
-                         _dp(m["group_offset"], torch.int32), x_tok, rtok, n_tok)
+                         _dp(m["group_offset"], torch.int32), x_tok, rtok, n_tok, dout)
     if workspace is None:
         workspace = torch.empty(max(workspace_bytes(WS_WGRAD_BATCHED, 0, 1, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
     if err_flag is None:

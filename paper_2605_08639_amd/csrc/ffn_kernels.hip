@@ -59,6 +59,8 @@ constexpr int kLdsBytes = NSTAGES * (256 + BM) * BK * 2;   // NSTAGES slabs of 2
 constexpr int kWideRowWaves = 8;
 constexpr int kLdsBytesWide = 8 * 64 * 128 * 2;            // the epilogue's staging (8 waves x 64 x 128 bf16) exceeds the 3 slabs of 512 + 128 rows
 static_assert(kLdsBytesWide >= NSTAGES * (512 + BM) * BK * 2, "slabs fit");
+constexpr int kDgateParts = 4;                 // partial gate-gradient sums per row and 256-column tile (one per wave column at most)
+inline size_t dgate_scratch_bytes(int n_rows, int hff) { return round256((size_t)kDgateParts * ((hff + 255) / 256) * n_rows * sizeof(float)); }
 inline size_t sched_ints(int n_rows, int Gr) { return 8 + 4 * (size_t)Gr + (Gr + 1) + 4 * (size_t)max_row_tiles(n_rows, Gr) + 2 * (size_t)Gr; }
 inline size_t ffn_ws_bytes(int n_rows, int Gr, int hff, bool bwd)
 {
@@ -357,7 +359,8 @@ template <int BB, int NWV = NWAVES> struct Waves { static constexpr int B = BB /
 template <int BB, bool WT, int AW = 128>
 __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t *X, const int32_t *row_tok, int tok_last,
                                                  const bf16_t *Wg, const bf16_t *Wu,
-                                                 int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout, char *lds)
+                                                 int h, int hff, bf16_t *Gt, bf16_t *U, bf16_t *Aout,
+                                                 const float *row_gate, bf16_t *Agout, char *lds)
 {
     constexpr int NWV = AW == 128 ? NWAVES : kWideRowWaves;
     using WV = Waves<BB, NWV>;
@@ -380,8 +383,13 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     char *buf = lds + wave * ST::BYTES;
     const int wrow0 = t.row0 + (wave % WV::B) * 64, row_end = t.row0 + t.rows;
     const int wcol0 = t.col0 + (wave / WV::B) * WCOLS;
+    // optional fourth tensor: the activations scaled by the gate of the row's assignment
+    float gate[KL::TB];
 #pragma unroll
-    for (int which = 0; which < 3; ++which) {
+    for (int tb = 0; tb < KL::TB; ++tb) gate[tb] = Agout ? row_gate[min(wrow0 + tb * 32 + (lane & 31), row_end - 1)] : 0.0f;
+#pragma unroll
+    for (int which = 0; which < 4; ++which) {
+        if (which == 3 && !Agout) break;
 #pragma unroll
         for (int tb = 0; tb < KL::TB; ++tb)
 #pragma unroll
@@ -392,12 +400,12 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float g = acc[0][ta][tb][q * 4 + e], u = acc[1][ta][tb][q * 4 + e];
-                        v[e] = which == 0 ? g : which == 1 ? u : g * sigmoidf_(g) * u;
+                        v[e] = which == 0 ? g : which == 1 ? u : which == 2 ? g * sigmoidf_(g) * u : gate[tb] * (g * sigmoidf_(g) * u);
                     }
                     ST::put(buf, tb * 32 + (lane & 31), ta * 32 + q * 8 + (lane >> 5) * 4, pack4bf(v[0], v[1], v[2], v[3]));
                 }
         wave_lds_fence();
-        ST::flush(buf, which == 0 ? Gt : which == 1 ? U : Aout, hff, wrow0, row_end, wcol0, hff, lane);
+        ST::flush(buf, which == 0 ? Gt : which == 1 ? U : which == 2 ? Aout : Agout, hff, wrow0, row_end, wcol0, hff, lane);
         wave_lds_fence();
     }
 }
@@ -407,22 +415,38 @@ template <bool WT, int AW = 128>
 __global__ void __launch_bounds__(AW == 128 ? THREADS : kWideRowWaves * 64, AW == 128 ? 2 : 1)
 fwd_gate_up_kernel(Sched s, const bf16_t *__restrict__ X, const int32_t *__restrict__ row_tok, int tok_last,
                    const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu, int h, int hff, int n_col_tiles,
-                   bf16_t *__restrict__ Gt, bf16_t *__restrict__ U, bf16_t *__restrict__ Aout)
+                   bf16_t *__restrict__ Gt, bf16_t *__restrict__ U, bf16_t *__restrict__ Aout,
+                   const float *__restrict__ row_gate, bf16_t *__restrict__ Agout)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, AW);
     if (!t.valid) return;
-    if (t.rows > BM / 2) fwd_gate_up_body<BM, WT, AW>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
-    else fwd_gate_up_body<BM / 2, WT, AW>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, lds);
+    if (t.rows > BM / 2) fwd_gate_up_body<BM, WT, AW>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, row_gate, Agout, lds);
+    else fwd_gate_up_body<BM / 2, WT, AW>(t, X, row_tok, tok_last, Wg, Wu, h, hff, Gt, U, Aout, row_gate, Agout, lds);
 }
 
+// Gate-side fusion of the activation backward (EPI = 2).  With the upstream gradient of row r
+// taken straight from the token tensor, dY'[r] = dOut[tok(r)] (the combine's gate left out), the
+// accumulators hold dA' = dY' Wd, and
+//   dGt = gate * dA' * U * silu'(Gt),  dU = gate * dA' * silu(Gt),  dgate[r] = sum_n dA'[r][n] * A[r][n]
+// with A = silu(Gt) * U recomputed in place: the same values as scaling dOut by the gate first
+// and reducing dOut against the down projection's output, without either pass over the rows.
+struct GateFusion {
+    const int32_t *row_tok = nullptr;   // [n_rows] row -> token (null: P0 holds group-ordered rows)
+    int tok_last = 0;
+    const float *row_gate = nullptr;    // [n_rows]
+    float *dgate_part = nullptr;        // [kDgateParts * column tiles][n_rows] partial row sums, summed later in slot order
+    int n_rows = 0;
+};
+
 // Shared body of the three single-accumulator row-tiled GEMMs.  EPI: 0 = store bf16 (Y, dX);
-// 1 = dA -> dGt, dU (needs Gt, U).  W_KS: weights k-strided (data gradients).  NPH = 2 sums two
-// products (dX = dGt Wg + dU Wu).
+// 1 = dA -> dGt, dU (needs Gt, U); 2 = the same with the gate fused in (GateFusion).
+// W_KS: weights k-strided (data gradients).  NPH = 2 sums two products (dX = dGt Wg + dU Wu).
 template <int BB, bool W_KS, int NPH, int EPI, int AW = 256>
 __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0, const bf16_t *P1, int ldp,
                                               const bf16_t *W0, const bf16_t *W1, int ldw, int n_dim, int k_dim,
-                                              bf16_t *out0, bf16_t *out1, const bf16_t *Gt, const bf16_t *U, char *lds)
+                                              bf16_t *out0, bf16_t *out1, const bf16_t *Gt, const bf16_t *U, char *lds,
+                                              const GateFusion &gf = GateFusion{})
 {
     constexpr int NWV = AW == 256 ? NWAVES : kWideRowWaves;
     using WV = Waves<BB, NWV>;
@@ -432,6 +456,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
     Operand A[NPH][1], B[NPH][1];
     A[0][0] = {W0, ldw, t.col0, n_dim - 1};
     B[0][0] = {P0, ldp, t.row0, t.row0 + t.rows - 1};
+    if (EPI == 2 && gf.row_tok) B[0][0] = {P0, ldp, t.row0, t.row0 + t.rows - 1, gf.row_tok, gf.tok_last};
     if (NPH == 2) {
         A[NPH - 1][0] = {W1, ldw, t.col0, n_dim - 1};
         B[NPH - 1][0] = {P1, ldp, t.row0, t.row0 + t.rows - 1};
@@ -465,11 +490,22 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
         constexpr int TAH = KL::TA / 2;
         static_assert(TAH >= 1, "at least 64 columns per wave");
         char *buf_g = buf, *buf_u = buf + SH::BYTES;
+        float gate[KL::TB], dsum[KL::TB];
+#pragma unroll
+        for (int tb = 0; tb < KL::TB; ++tb) {
+            gate[tb] = EPI == 2 ? gf.row_gate[min(wrow0 + tb * 32 + (lane & 31), row_end - 1)] : 1.0f;
+            dsum[tb] = 0.0f;
+        }
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int hcol0 = wcol0 + half * (WCOLS / 2);
             SH::fill2(buf_g, buf_u, Gt, U, n_dim, wrow0, row_end, hcol0, n_dim, lane);
             wave_lds_fence();
+            // this half's share of the row sums; a half (32 or 64 columns, n_dim % 64 == 0) lies inside
+            // the tensor or outside it as a whole, and outside it holds clamped copies
+            float hsum[KL::TB];
+#pragma unroll
+            for (int tb = 0; tb < KL::TB; ++tb) hsum[tb] = 0.0f;
 #pragma unroll
             for (int tb = 0; tb < KL::TB; ++tb)
 #pragma unroll
@@ -478,23 +514,55 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
                     for (int q = 0; q < 4; ++q) {
                         const int ta = half * TAH + th;
                         const int row = tb * 32 + (lane & 31), col = th * 32 + q * 8 + (lane >> 5) * 4;
-                        float g[4], u[4], dg[4], du[4];
+                        float g[4], u[4], dg[4], du[4], pa[4];
                         unpack4bf(SH::get(buf_g, row, col), g);
                         unpack4bf(SH::get(buf_u, row, col), u);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const float da = acc[0][ta][tb][q * 4 + e];
                             const float sg = sigmoidf_(g[e]);
-                            dg[e] = da * u[e] * (sg * (1.0f + g[e] * (1.0f - sg)));
-                            du[e] = da * (g[e] * sg);
+                            if (EPI == 2) {
+                                pa[e] = da * (g[e] * sg * u[e]);
+                                const float dag = gate[tb] * da;
+                                dg[e] = dag * u[e] * (sg * (1.0f + g[e] * (1.0f - sg)));
+                                du[e] = dag * (g[e] * sg);
+                            } else {
+                                dg[e] = da * u[e] * (sg * (1.0f + g[e] * (1.0f - sg)));
+                                du[e] = da * (g[e] * sg);
+                            }
                         }
                         SH::put(buf_g, row, col, pack4bf(dg[0], dg[1], dg[2], dg[3]));
                         SH::put(buf_u, row, col, pack4bf(du[0], du[1], du[2], du[3]));
+                        // The running sum is needed only after the loop, and the compiler would sink all
+                        // of its arithmetic down there, parking every operand in scratch memory on the
+                        // way; an assembly statement that "uses" the sum keeps each add where it is.
+                        if (EPI == 2) {
+                            hsum[tb] += (pa[0] + pa[1]) + (pa[2] + pa[3]);
+                            asm volatile("" : "+v"(hsum[tb]));
+                        }
                     }
             wave_lds_fence();
             SH::flush(buf_g, out0, n_dim, wrow0, row_end, hcol0, n_dim, lane);
             SH::flush(buf_u, out1, n_dim, wrow0, row_end, hcol0, n_dim, lane);
             wave_lds_fence();
+            if (EPI == 2 && hcol0 < n_dim) {
+#pragma unroll
+                for (int tb = 0; tb < KL::TB; ++tb) dsum[tb] += hsum[tb];
+            }
+        }
+        if (EPI == 2) {
+            // a row's columns lie on lanes l and l + 32; one partial sum per row, wave column and column tile
+            const int slot0 = (t.col0 / 256) * kDgateParts, wa = wave / WV::B;
+#pragma unroll
+            for (int tb = 0; tb < KL::TB; ++tb) {
+                const float total = dsum[tb] + __shfl_xor(dsum[tb], 32);
+                const int r = wrow0 + tb * 32 + (lane & 31);
+                if (lane < 32 && r < row_end) {
+                    gf.dgate_part[(size_t)(slot0 + wa) * gf.n_rows + r] = total;
+                    // the slots of wave columns this tile shape does not have
+                    if (WV::A < kDgateParts) gf.dgate_part[(size_t)(slot0 + WV::A + wa) * gf.n_rows + r] = 0.0f;
+                }
+            }
         }
     }
 }
@@ -519,19 +587,44 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
 // WT = false: Wd as the forward pass holds it, [h][h'], contraction index strided (transposing
 // LDS reads, full-line loads: the faster operand path).  WT = true: a transposed copy [h'][h],
 // contraction index contiguous.
-template <bool WT>
+template <bool WT, bool GATED = false>
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
                const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles,
-               int w_from_slot)
+               int w_from_slot, GateFusion gf)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const RowTile t = find_row_tile(s, n_col_tiles, 256, w_from_slot != 0);
     if (!t.valid) return;
     const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n], or at [n*h + k]
     const int ldw = WT ? h : hff;
-    if (t.rows > BM / 2) row_gemm_body<BM, !WT, 1, 1>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds);
-    else row_gemm_body<BM / 2, !WT, 1, 1>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds);
+    constexpr int EPI = GATED ? 2 : 1;
+    if (t.rows > BM / 2) row_gemm_body<BM, !WT, 1, EPI>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds, gf);
+    else row_gemm_body<BM / 2, !WT, 1, EPI>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds, gf);
+}
+
+// dgate of the gate-fused backward: the partial row sums of the activation backward added up in
+// slot order (fixed order: bit-reproducible), written per row or, with src_of, at the assignment
+// the row serves (the [T,k] layout of the gates).  Rows outside [group_offset[g_begin],
+// group_offset[g_end]) were not computed and are left alone.
+__global__ void __launch_bounds__(256)
+dgate_reduce_kernel(const float *__restrict__ part, int n_slots, int n_rows, const int32_t *__restrict__ group_offset,
+                    int g_begin, int g_end, const int32_t *__restrict__ src_of, float *__restrict__ dgate,
+                    int32_t *__restrict__ err_flag)
+{
+    const int lo = max(0, min(group_offset[g_begin], n_rows)), hi = max(lo, min(group_offset[g_end], n_rows));
+    bool bad = false;
+    for (int r = lo + blockIdx.x * 256 + threadIdx.x; r < hi; r += gridDim.x * 256) {
+        float sum = 0.0f;
+        for (int p = 0; p < n_slots; ++p) sum += part[(size_t)p * n_rows + r];
+        int at = r;
+        if (src_of) {
+            at = src_of[r];
+            if (at < 0 || at >= n_rows) { bad = true; continue; }
+        }
+        dgate[at] = sum;
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_PLAN_COVER);
 }
 
 // dX = dGt Wg + dU Wu (one accumulator, the contraction runs over both products).
@@ -687,6 +780,7 @@ struct MbTable {
     const int32_t *iptr[kMaxWgradMb], *igrp[kMaxWgradMb], *goff[kMaxWgradMb];
     const int32_t *rtok[kMaxWgradMb];      // null: X holds group-ordered rows; else X holds tokens and row r is X[rtok[r]]
     int tok_last[kMaxWgradMb];
+    unsigned long long dy_tokens;          // bit mb set: dY[mb] is the token tensor dOut and row r is dOut[rtok[r]]
 };
 
 // Instance range of expert e in micro-batch mb, sanitised: [p0, p1) inside the instance table.
@@ -812,8 +906,9 @@ struct WgradPieces {
     {
         const int b = mb[i], r0 = row0[i];
         k_valid = rows[i];
-        if (NA == 1) {      // dWd: L = dY, R = A
-            A[0][0] = {tb.dY[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
+        if (NA == 1) {      // dWd: L = dY (or token rows of dOut against gate-scaled A), R = A
+            if ((tb.dy_tokens >> b) & 1) A[0][0] = {tb.dY[b], m_dim, m0, m_dim - 1, tb.rtok[b] + r0, tb.tok_last[b]};
+            else A[0][0] = {tb.dY[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
             B[0][0] = {tb.A[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
         } else {            // dWg, dWu: L = dGt, dU; R = X
             A[0][0] = {tb.dGt[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
@@ -841,7 +936,8 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
                      float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int WGM = 256, BA = WGM / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads>;
+    // NA = 1: the A side (dY) may be gathered; its loads go last in the window (see KLoop)
+    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads, NA == 1>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WN - 1) / WN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;
@@ -913,6 +1009,7 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     case RELIBRA_WS_FFN_FWD: return ffn_ws_bytes(N, G, hff, false);
     case RELIBRA_WS_FFN_BWD: return ffn_ws_bytes(N, G, hff, true);
     case RELIBRA_WS_WGRAD_BATCHED: return round256(wgrad_plan_ints(E, G) * sizeof(int32_t));
+    case RELIBRA_WS_DGATE: return dgate_scratch_bytes(N, hff);
     default: return 0;
     }
     (void)h;
@@ -929,6 +1026,8 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel<false, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesWide));
@@ -975,10 +1074,12 @@ static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_
                                    int G, int g_begin, int g_end, int E,
                                    const void *Wg, const void *Wu, const void *Wd, int h, int hff,
                                    void *Gt_save, void *U_save, void *A_save, void *Yrows, int flags,
-                                   void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+                                   void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_,
+                                   const float *row_gate = nullptr, void *Ag_save = nullptr)
 {
     hipStream_t stream = (hipStream_t)stream_;
     if (flags & ~RELIBRA_FWD_TRANSPOSED_WEIGHTS) return RELIBRA_EINVAL;
+    if ((row_gate == nullptr) != (Ag_save == nullptr) || !aligned16(Ag_save)) return RELIBRA_EINVAL;
     const bool wt = (flags & RELIBRA_FWD_TRANSPOSED_WEIGHTS) != 0;
     const FfnArgs a{n_rows, G, g_begin, g_end, E, h, hff};
     if (int rc = check_ffn_args(a)) return rc;
@@ -1001,7 +1102,7 @@ static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_
     const int ct1 = wide1 ? hff / 256 : (hff + 127) / 128, ct2 = wide2 ? h / 512 : (h + 255) / 256;
     RELIBRA_ROW_LAUNCH(RELIBRA_K_FWD_GATE_UP, fwd_gate_up_kernel, wt, wide1, 128, 256, R * ct1,
                        s, (const bf16_t *)Xrows, row_tok, T - 1, (const bf16_t *)Wg, (const bf16_t *)Wu, h, hff, ct1,
-                       (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save);
+                       (bf16_t *)Gt_save, (bf16_t *)U_save, (bf16_t *)A_save, row_gate, (bf16_t *)Ag_save);
     RELIBRA_HIP_TRY(launch_check());
     RELIBRA_ROW_LAUNCH(RELIBRA_K_FWD_DOWN, fwd_down_kernel, wt, wide2, 256, 512, R * ct2,
                        s, (const bf16_t *)A_save, (const bf16_t *)Wd, h, hff, ct2, (bf16_t *)Yrows);
@@ -1032,19 +1133,51 @@ extern "C" int relibra_moe_ffn_fwd_gather(const void *X, int T, const int32_t *r
                         Gt_save, U_save, A_save, Yrows, flags, ws, ws_bytes, err_flag, stream_);
 }
 
-extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
+extern "C" int relibra_moe_ffn_fwd_gated(const void *X, int T, const int32_t *row_tok, const float *row_gate, int n_rows,
+                                         const int32_t *group_offset, const int32_t *group_expert,
+                                         int G, int g_begin, int g_end, int E,
+                                         const void *Wg, const void *Wu, const void *Wd, int h, int hff,
+                                         void *Gt_save, void *U_save, void *A_save, void *Ag_save, void *Yrows, int flags,
+                                         void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+{
+    if (T < 1 || !row_tok || !row_gate || !Ag_save) return RELIBRA_EINVAL;
+    return ffn_fwd_impl(X, row_tok, T, n_rows, group_offset, group_expert, G, g_begin, g_end, E, Wg, Wu, Wd, h, hff,
+                        Gt_save, U_save, A_save, Yrows, flags, ws, ws_bytes, err_flag, stream_, row_gate, Ag_save);
+}
+
+// Gate-fused form of the backward call: the upstream gradient comes from the token tensor.
+struct GatedBwd {
+    const void *dOut;
+    int T;
+    const int32_t *row_tok;
+    const float *row_gate;
+    const int32_t *src_of;   // optional
+    float *dgate;
+    void *scratch;
+    size_t scratch_bytes;
+};
+
+static int ffn_bwd_impl(const void *dYrows, const void *Xrows,
                                    const void *Gt_save, const void *U_save, const void *A_save, int n_rows,
                                    const int32_t *group_offset, const int32_t *group_expert,
                                    const int32_t *group_dw_slot,
                                    int G, int g_begin, int g_end, int E, int n_dw_slots,
                                    const void *Wg, const void *Wu, const void *Wd, int h, int hff,
                                    void *dXrows, float *dWg, float *dWu, float *dWd, int flags,
-                                   void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+                                   void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_,
+                                   const GatedBwd *gb)
 {
     hipStream_t stream = (hipStream_t)stream_;
     const FfnArgs a{n_rows, G, g_begin, g_end, E, h, hff};
     if (int rc = check_ffn_args(a)) return rc;
     if (n_dw_slots < E) return RELIBRA_EINVAL;
+    if (gb) {
+        if (!(flags & RELIBRA_BWD_DEFER_WGRAD) || gb->T < 1 || !gb->dOut || !gb->row_tok || !gb->row_gate || !gb->dgate ||
+            !gb->scratch || !aligned16(gb->dOut) || !aligned16(gb->scratch))
+            return RELIBRA_EINVAL;
+        if (gb->scratch_bytes < dgate_scratch_bytes(n_rows, hff)) return RELIBRA_EWORKSPACE;
+        dYrows = gb->dOut;                       // the argument checks below see the tensor the kernels read
+    }
     const int Gr = g_end - g_begin;
     if (Gr == 0) return RELIBRA_OK;
     const bool defer = (flags & RELIBRA_BWD_DEFER_WGRAD) != 0;    // then dW is not touched and may be null
@@ -1072,20 +1205,32 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     if (n_rows > 0) {
         const bf16_t *wd = (const bf16_t *)Wd, *wg = (const bf16_t *)Wg, *wu = (const bf16_t *)Wu;
         const bf16_t *dy = (const bf16_t *)dYrows, *gt = (const bf16_t *)Gt_save, *us = (const bf16_t *)U_save;
-        if (flags & RELIBRA_BWD_TRANSPOSED_WEIGHTS) {
-            RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<true><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
-                s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot));
-            RELIBRA_HIP_TRY(launch_check());
-            RELIBRA_ROW_LAUNCH(RELIBRA_K_BWD_DX, bwd_dx_kernel, true, wide_h, 256, 512, R * ct_h,
-                               s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows);
-        } else {
-            RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, bwd_act_kernel<false><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(
-                s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot));
-            RELIBRA_HIP_TRY(launch_check());
-            RELIBRA_ROW_LAUNCH(RELIBRA_K_BWD_DX, bwd_dx_kernel, false, wide_h, 256, 512, R * ct_h,
-                               s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows);
+        const bool wt = (flags & RELIBRA_BWD_TRANSPOSED_WEIGHTS) != 0;
+        GateFusion gf;
+        gf.n_rows = n_rows;
+        if (gb) {
+            gf.row_tok = gb->row_tok;
+            gf.tok_last = gb->T - 1;
+            gf.row_gate = gb->row_gate;
+            gf.dgate_part = (float *)gb->scratch;
         }
+#define RELIBRA_BWD_ACT(WT_, GATED_)                                                                                            \
+    RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, (bwd_act_kernel<WT_, GATED_><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(   \
+        s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot, gf)))
+        if (wt) { if (gb) RELIBRA_BWD_ACT(true, true); else RELIBRA_BWD_ACT(true, false); }
+        else { if (gb) RELIBRA_BWD_ACT(false, true); else RELIBRA_BWD_ACT(false, false); }
+#undef RELIBRA_BWD_ACT
         RELIBRA_HIP_TRY(launch_check());
+        if (wt) RELIBRA_ROW_LAUNCH(RELIBRA_K_BWD_DX, bwd_dx_kernel, true, wide_h, 256, 512, R * ct_h,
+                                   s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows);
+        else RELIBRA_ROW_LAUNCH(RELIBRA_K_BWD_DX, bwd_dx_kernel, false, wide_h, 256, 512, R * ct_h,
+                                s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows);
+        RELIBRA_HIP_TRY(launch_check());
+        if (gb) {
+            RELIBRA_LAUNCH(RELIBRA_K_COMBINE_BWD, stream, dgate_reduce_kernel<<<std::min(1024, (n_rows + 255) / 256), 256, 0, stream>>>(
+                (const float *)gb->scratch, kDgateParts * ct_ff, n_rows, group_offset, g_begin, g_end, gb->src_of, gb->dgate, err_flag));
+            RELIBRA_HIP_TRY(launch_check());
+        }
     }
     if (defer) return RELIBRA_OK;                                  // dGt, dU stay in the workspace
     // short groups (few rows per group on average): the small, high-occupancy geometry
@@ -1118,6 +1263,39 @@ extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
     return RELIBRA_OK;
 }
 
+extern "C" int relibra_moe_ffn_bwd(const void *dYrows, const void *Xrows,
+                                   const void *Gt_save, const void *U_save, const void *A_save, int n_rows,
+                                   const int32_t *group_offset, const int32_t *group_expert,
+                                   const int32_t *group_dw_slot,
+                                   int G, int g_begin, int g_end, int E, int n_dw_slots,
+                                   const void *Wg, const void *Wu, const void *Wd, int h, int hff,
+                                   void *dXrows, float *dWg, float *dWu, float *dWd, int flags,
+                                   void *ws, size_t ws_bytes, int32_t *err_flag, relibra_stream stream_)
+{
+    return ffn_bwd_impl(dYrows, Xrows, Gt_save, U_save, A_save, n_rows, group_offset, group_expert, group_dw_slot, G, g_begin,
+                        g_end, E, n_dw_slots, Wg, Wu, Wd, h, hff, dXrows, dWg, dWu, dWd, flags, ws, ws_bytes, err_flag, stream_,
+                        nullptr);
+}
+
+extern "C" int relibra_moe_ffn_bwd_gated(const void *dOut, int T, const int32_t *row_tok, const float *row_gate,
+                                         const int32_t *src_of,
+                                         const void *Gt_save, const void *U_save, int n_rows,
+                                         const int32_t *group_offset, const int32_t *group_expert,
+                                         const int32_t *group_dw_slot,
+                                         int G, int g_begin, int g_end, int E, int n_dw_slots,
+                                         const void *Wg, const void *Wu, const void *Wd, int h, int hff,
+                                         void *dXrows, float *dgate, int flags,
+                                         void *ws, size_t ws_bytes, void *dgate_scratch, size_t dgate_scratch_bytes_,
+                                         int32_t *err_flag, relibra_stream stream_)
+{
+    if (flags & ~(RELIBRA_BWD_REPLICA_WEIGHTS | RELIBRA_BWD_TRANSPOSED_WEIGHTS | RELIBRA_BWD_DEFER_WGRAD)) return RELIBRA_EINVAL;
+    const GatedBwd gb{dOut, T, row_tok, row_gate, src_of, dgate, dgate_scratch, dgate_scratch_bytes_};
+    // the saved activations are an operand of the weight gradients only: Gt stands in for the pointer check
+    return ffn_bwd_impl(nullptr, nullptr, Gt_save, U_save, Gt_save, n_rows, group_offset, group_expert, group_dw_slot, G, g_begin,
+                        g_end, E, n_dw_slots, Wg, Wu, Wd, h, hff, dXrows, nullptr, nullptr, nullptr,
+                        flags | RELIBRA_BWD_DEFER_WGRAD, ws, ws_bytes, err_flag, stream_, &gb);
+}
+
 extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_mb, int n_rows,
                                              int G, int inst_cap, int E, int h, int hff,
                                              float *dWg, float *dWu, float *dWd, int flags,
@@ -1134,11 +1312,13 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
         return RELIBRA_EINVAL;
     if (ws_bytes < relibra_workspace_bytes(RELIBRA_WS_WGRAD_BATCHED, 0, 1, E, G, h, hff)) return RELIBRA_EWORKSPACE;
     MbTable tb;
+    tb.dy_tokens = 0;
     for (int mb = 0; mb < kMaxWgradMb; ++mb) {
         const relibra_wgrad_mb &m = mbs[mb < n_mb ? mb : 0];
         if (mb < n_mb) {
             const bool gathered = m.Xrows_dev == nullptr;
-            if (!m.dYrows_dev || !m.A_save_dev || !m.bwd_workspace_dev || !m.inst_ptr_dev || !m.inst_group_dev ||
+            if (!m.dYrows_dev && (!m.dOut_dev || !gathered || !aligned16(m.dOut_dev))) return RELIBRA_EINVAL;
+            if (!m.A_save_dev || !m.bwd_workspace_dev || !m.inst_ptr_dev || !m.inst_group_dev ||
                 !m.group_offset_dev || (gathered && (!m.X_dev || !m.row_tok_dev || m.n_tokens < 1)))
                 return RELIBRA_EINVAL;
             if (!aligned16(m.dYrows_dev) || !aligned16(gathered ? m.X_dev : m.Xrows_dev) || !aligned16(m.A_save_dev) ||
@@ -1146,7 +1326,8 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
                 return RELIBRA_EINVAL;
         }
         const Sched s = carve(const_cast<void *>(m.bwd_workspace_dev), n_rows, G, hff, true);
-        tb.dY[mb] = (const bf16_t *)m.dYrows_dev;
+        tb.dY[mb] = (const bf16_t *)(m.dYrows_dev ? m.dYrows_dev : m.dOut_dev);
+        if (!m.dYrows_dev) tb.dy_tokens |= 1ull << mb;
         tb.X[mb] = (const bf16_t *)(m.Xrows_dev ? m.Xrows_dev : m.X_dev);
         tb.rtok[mb] = m.Xrows_dev ? nullptr : m.row_tok_dev;
         tb.tok_last[mb] = m.Xrows_dev ? 0 : m.n_tokens - 1;

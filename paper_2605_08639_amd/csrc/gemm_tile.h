@@ -185,6 +185,10 @@ struct KsTile {
 #pragma unroll
             for (int q = 0; q < KPB; ++q) ix.v[i][q] = g[min(k0 + (wave + i * NW) * KPB + q, k_last)];
     }
+    // The memory row of a k-row is the same for every lane that loads a piece of it, and a wave's
+    // load block holds KPB k-rows: the rows (clamped, or looked up when the operand is gathered) and
+    // their offsets are worked out with scalar instructions, one select per further k-row picks a
+    // lane's own, and gathered and plain operands run the same branch-free sequence.
     template <int NW>
     static __device__ __forceinline__ void load_one(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
                                                     int lane, int i)
@@ -192,22 +196,20 @@ struct KsTile {
         static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
         const Operand &op = ln.op;
         const int j = wave + i * NW;
-        const int k = j * KPB + lane / SPR;
-        const int s = (lane % SPR) ^ fk(k);
+        const int kq = lane / SPR;                  // which of the block's k-rows this lane loads from
+        const int s = (lane % SPR) ^ fk(j * KPB + kq);
         int grow = op.row0 + s * 8;
         if (grow > op.row_last) grow = op.row_last - 7;
-        int mrow;                                   // row of `base` that holds this k-row
-        if (op.gather) {
-            // this lane's k-row picks its lookup by masks (a select over the array would be turned
-            // into a dynamically indexed, hence memory-resident, array)
-            mrow = 0;
+        const bool gathered = op.gather != nullptr;
+        long long off = 0;
 #pragma unroll
-            for (int q = 0; q < KPB; ++q) mrow |= ix.v[i][q] & -(int)(lane / SPR == q);
-            mrow = min(max(mrow, 0), op.gather_last);
-        } else {
-            mrow = min(k0 + k, k_last);
+        for (int q = 0; q < KPB; ++q) {
+            const int plain = min(k0 + j * KPB + q, k_last);
+            const int looked = min(max(gathered ? ix.v[i][q] : 0, 0), op.gather_last);
+            const long long row_off = (long long)(gathered ? looked : plain) * op.ld;       // scalar
+            off = (q == 0 || kq == q) ? row_off : off;
         }
-        load_lds16(op.base + (size_t)mrow * op.ld + grow, lds + j * 1024);
+        load_lds16(op.base + off + grow, lds + j * 1024);
     }
     template <int NW>
     static __device__ __forceinline__ void load(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
@@ -257,7 +259,7 @@ __device__ __forceinline__ bf16x8_t mask_frag(bf16x8_t f, int k_first, int k_val
 // DBG switches parts of the loop off for timing experiments (1: no loads after the prologue,
 // 2: loads only, 3: no loads and no barrier); the library always builds DBG = 0.
 template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0,
-          bool SPREAD = false>
+          bool SPREAD = false, bool B_FIRST = false>
 struct KLoop {
     static constexpr int NW = WA * WB;
     static constexpr int DEPTH = AT::DEPTH;           // k-values per slab
@@ -361,20 +363,22 @@ struct KLoop {
             for (int t = 0; t < TB; ++t) f.b[b][t] = mask_frag(f.b[b][t], k_first, k_valid);
     }
 
-    // Load number j (0 .. LOADS-1) of this wave's share of slab t: A-side operands first.
+    // Load number j (0 .. LOADS-1) of this wave's share of slab t: A-side operands first, or, with
+    // B_FIRST, last (an operand gathered through per-slab row lookups belongs in the later part of
+    // the window, where its lookups have had time to arrive).
     static __device__ __forceinline__ void issue_one(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
                                                      const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane, int j)
     {
         const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
         const int k0 = (t - ph * steps_per_phase) * DEPTH;
         const int q = (NPH == 1 || ph == 0) ? 0 : NPH - 1;
-        if (j < NA * LA) {
-            const int a = j / LA;
-            AT::template load_one<NW>(stage + a * AT::BYTES, PA[q][a], lk.a[a], k0, k_last, wave, lane, j % LA);
+        const bool a_side = B_FIRST ? j >= NB * LB : j < NA * LA;
+        if (a_side) {
+            const int ja = B_FIRST ? j - NB * LB : j, a = ja / LA;
+            AT::template load_one<NW>(stage + a * AT::BYTES, PA[q][a], lk.a[a], k0, k_last, wave, lane, ja % LA);
         } else {
-            const int b = (j - NA * LA) / LB;
-            BT::template load_one<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane,
-                                      (j - NA * LA) % LB);
+            const int jb = B_FIRST ? j : j - NA * LA, b = jb / LB;
+            BT::template load_one<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane, jb % LB);
         }
     }
 

@@ -345,6 +345,21 @@ row_tokens_kernel(const int32_t *__restrict__ src_of, int N, int k, int T, int32
     if (bad) atomicOr(err_flag, RELIBRA_ERR_PLAN_COVER);
 }
 
+// row -> gate of the assignment the row serves: row_gate[row] = gates[src_of[row]] (gates flat [T*k]).
+__global__ void __launch_bounds__(256)
+row_gates_kernel(const int32_t *__restrict__ src_of, const float *__restrict__ gates, int N, float *__restrict__ row_gate,
+                 int32_t *__restrict__ err_flag)
+{
+    bool bad = false;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < N; i += gridDim.x * 256) {
+        const int a = src_of[i];
+        float g = 0.0f;
+        if (a < 0 || a >= N) bad = true; else g = gates[a];
+        row_gate[i] = g;
+    }
+    if (bad) atomicOr(err_flag, RELIBRA_ERR_PLAN_COVER);
+}
+
 inline int grid_for(size_t work_items, int per_block, int cap)
 {
     size_t b = (work_items + per_block - 1) / per_block;
@@ -496,6 +511,19 @@ extern "C" int relibra_row_tokens(const int32_t *src_of_dev, int N, int k, int T
     if (!src_of_dev || !row_tok_dev || !err_flag_dev) return RELIBRA_EINVAL;
     RELIBRA_LAUNCH(RELIBRA_K_ROW_TOKENS, stream, row_tokens_kernel<<<grid_for((size_t)N, 256, 1024), 256, 0, stream>>>(
         src_of_dev, N, k, T, row_tok_dev, err_flag_dev));
+    RELIBRA_HIP_TRY(launch_check());
+    return RELIBRA_OK;
+}
+
+extern "C" int relibra_row_gates(const int32_t *src_of_dev, const float *gates_dev, int N, float *row_gate_dev,
+                                 int32_t *err_flag_dev, relibra_stream stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    if (N < 0) return RELIBRA_EINVAL;
+    if (N == 0) return RELIBRA_OK;
+    if (!src_of_dev || !gates_dev || !row_gate_dev || !err_flag_dev) return RELIBRA_EINVAL;
+    RELIBRA_LAUNCH(RELIBRA_K_ROW_TOKENS, stream, row_gates_kernel<<<grid_for((size_t)N, 256, 1024), 256, 0, stream>>>(
+        src_of_dev, gates_dev, N, row_gate_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }

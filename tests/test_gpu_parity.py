@@ -666,3 +666,98 @@ def test_forward_with_fused_row_gather_is_bit_identical():
     err = rl.new_err_flag()
     rt = rl.relibra_row_tokens(bad, cfg.k, cfg.T, err_flag=err)
     assert err.item() == rl.ERR_PLAN_COVER and rt[3].item() == 0
+
+
+# ------------------------------------------------------------------ gate-side fusion of the backward
+@pytest.mark.parametrize("weights_t", [False, True], ids=["stored-layout", "transposed-copies"])
+def test_gate_fused_backward_matches_the_unfused_definition(weights_t):
+    """The combine (Section 2.1: gate-weighted sum of the selected experts' outputs) is linear, so its
+    backward may move into the expert backward: dOut rows read straight from the token tensor, the gate
+    applied to dA, dgate as a row reduction of dA' against A, dWd from dOut rows against gate * A.  The
+    oracle computes the unfused definition (combine backward, then expert backward); the fused path must
+    agree within the floating-point tolerance on dX, dgate and all three weight gradients, its forward
+    outputs must equal the unfused forward's bit for bit, and two runs must agree bit for bit."""
+    cfg = wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=2, h=512, hff=320)
+    ids, gates = routing(cfg)
+    counts = oracle.route_hist(ids, cfg.E)[0]
+    p = plan_both(cfg, counts)
+    Wg, Wu, Wd = wl.make_weights(cfg)
+    W_d = [W.to(DEV) for W in (Wg, Wu, Wd)]
+    W_f = [rl.relibra_transpose_experts(W) for W in W_d] if weights_t else W_d       # forward operands
+    f_flags = rl.FWD_TRANSPOSED_WEIGHTS if weights_t else 0
+    shapes = [(cfg.hff, cfg.h), (cfg.hff, cfg.h), (cfg.h, cfg.hff)]
+    dW_ref = [np.zeros((cfg.E, *s)) for s in shapes]
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    err = rl.new_err_flag()
+    kept = []
+    for mb in range(cfg.n_mb):
+        X, dOut = wl.make_tokens(cfg, mb)
+        Xd, dOut_d, gates_d = X.to(DEV), dOut.to(DEV), t(gates[mb])
+        tabs = {key: dev_i32(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset",
+                                                     "group_expert", "group_dw_slot")}
+        row_of, src_of, _ = rl.relibra_permute(t(ids[mb]), tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                               tabs["group_offset"], Xd, cfg.E, cfg.G, err_flag=err)
+        row_tok = rl.relibra_row_tokens(src_of, cfg.k, cfg.T, err_flag=err)
+        row_gate = rl.relibra_row_gates(src_of, gates_d, err_flag=err)
+        row_of_o, src_o = oracle.permute(ids[mb], cfg.E, p["inst_ptr"][mb], p["inst_rows"][mb], p["inst_group"][mb],
+                                         p["group_offset"][mb])
+        assert np.array_equal(row_gate.cpu().numpy(), gates[mb].reshape(-1)[src_o])
+        # forward: everything the ungated call writes, bit for bit, plus Ag = gate * A
+        plain = rl.relibra_moe_ffn_fwd_gather(Xd, row_tok, tabs["group_offset"], tabs["group_expert"], *W_f, err_flag=err, flags=f_flags)
+        Gt, U, A, Ag, Y = rl.relibra_moe_ffn_fwd_gated(Xd, row_tok, row_gate, tabs["group_offset"], tabs["group_expert"], *W_f,
+                                                       err_flag=err, flags=f_flags)
+        for a_, b_ in zip(plain, (Gt, U, A, Y)):
+            assert torch.equal(a_, b_)
+        Xrows_o = oracle.gather_rows(X, src_o, cfg.k)
+        go, ge = p["group_offset"][mb], p["group_expert"][mb]
+        _, _, A_o, Y_o = oracle.ffn_fwd(Xrows_o, go, ge, Wg, Wu, Wd)
+        assert rel_l2(Ag, gates[mb].reshape(-1)[src_o][:, None].astype(np.float64) * A_o) <= TOL
+        # backward
+        ws = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, cfg.N, 1, cfg.E, cfg.G, cfg.h, cfg.hff), dtype=torch.uint8, device=DEV)
+        b_flags = rl.BWD_TRANSPOSED_WEIGHTS if weights_t else 0
+        W_b = W_f if weights_t else W_d
+        dgate = torch.full((cfg.T, cfg.k), float("nan"), dtype=torch.float32, device=DEV)
+        dXrows, _ = rl.relibra_moe_ffn_bwd_gated(dOut_d, row_tok, row_gate, Gt, U, tabs["group_offset"], tabs["group_expert"],
+                                                 tabs["group_dw_slot"], *W_b, src_of=src_of, flags=b_flags, dgate=dgate,
+                                                 workspace=ws, err_flag=err, E=cfg.E)
+        dXrows2, dgate_rows = rl.relibra_moe_ffn_bwd_gated(dOut_d, row_tok, row_gate, Gt, U, tabs["group_offset"],
+                                                           tabs["group_expert"], tabs["group_dw_slot"], *W_b, flags=b_flags,
+                                                           err_flag=err, E=cfg.E)
+        assert torch.equal(dXrows, dXrows2)                                       # reproducible
+        assert torch.equal(dgate.reshape(-1)[src_of.long()], dgate_rows)          # the two dgate layouts
+        dX = rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, cfg.T, cfg.k, err_flag=err)
+        # oracle: the unfused definition
+        dY_o, dgate_o = oracle.combine_bwd(dOut.double().numpy(), Y_o, gates[mb], row_of_o, cfg.T, cfg.k)
+        dY16 = torch.from_numpy(dY_o).to(torch.bfloat16)
+        dXrows_o, dWg_o, dWu_o, dWd_o = oracle.ffn_bwd(Xrows_o, dY16, go, ge, Wg, Wu, Wd)
+        dX_o = oracle.combine_fwd(dXrows_o, None, row_of_o, cfg.T, cfg.k)
+        assert rel_l2(dX, dX_o) <= TOL
+        assert rel_l2(dgate, dgate_o) <= TOL
+        for acc, o in zip(dW_ref, (dWg_o, dWu_o, dWd_o)):
+            acc += o
+        kept.append(dict(dOut=dOut_d, X=Xd, row_tok=row_tok, A=Ag, bwd_workspace=ws, inst_ptr=tabs["inst_ptr"],
+                         inst_group=tabs["inst_group"], group_offset=tabs["group_offset"]))
+    assert err.item() == 0
+    for tile in (None, "narrow", "wide"):
+        dW = [torch.full((cfg.E, *s), float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+        rl.relibra_moe_ffn_wgrad_batched(kept, cfg.E, *dW, err_flag=err, tile=tile)
+        assert err.item() == 0
+        for got, want in zip(dW, dW_ref):
+            assert rel_l2(got, want) <= TOL, tile
+        if tile is None:
+            first = dW
+        else:
+            for a_, b_ in zip(dW, first):
+                assert torch.equal(a_, b_), tile
+    # argument checks: the fused backward needs its scratch, and a bad src_of entry is flagged, not followed
+    with pytest.raises(rl.RelibraError):
+        rl.relibra_moe_ffn_bwd_gated(dOut_d, row_tok, row_gate, Gt, U, tabs["group_offset"], tabs["group_expert"],
+                                     tabs["group_dw_slot"], *W_b, flags=b_flags, E=cfg.E,
+                                     dgate_scratch=torch.empty(256, dtype=torch.uint8, device=DEV))
+    bad = src_of.clone()
+    bad[5] = cfg.N + 3
+    err2 = rl.new_err_flag()
+    rl.relibra_moe_ffn_bwd_gated(dOut_d, row_tok, row_gate, Gt, U, tabs["group_offset"], tabs["group_expert"],
+                                 tabs["group_dw_slot"], *W_b, src_of=bad, flags=b_flags, err_flag=err2, E=cfg.E,
+                                 dgate=torch.zeros(cfg.N, dtype=torch.float32, device=DEV))
+    assert err2.item() == rl.ERR_PLAN_COVER
