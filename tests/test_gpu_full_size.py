@@ -198,3 +198,44 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
         assert torch.equal(a_, b_)
     assert err.item() == 0
     print(f"[{cfg.name}] fused row gather ok", flush=True)
+
+    # ---- the gate-fused backward (what bench.py runs where h' < 4096): forward outputs unchanged bit for bit,
+    # dX rows and dgate on the sampled tokens against the oracle's unfused definition, and all of it against
+    # the plain path (checked above) within the tolerance; weight gradients of the doubled micro-batch likewise
+    row_gate = rl.relibra_row_gates(src_of, gates_d, err_flag=err)
+    assert np.array_equal(row_gate.cpu().numpy(), gates.reshape(-1)[src_o])
+    Gt2, U2, A2, Ag, Y2 = rl.relibra_moe_ffn_fwd_gated(X_d, row_tok, row_gate, tabs["group_offset"], tabs["group_expert"],
+                                                       Wg_d, Wu_d, Wd_d, err_flag=err)
+    for a_, b_ in zip((Gt2, U2, A2, Y2), (Gt, U, A, Y)):
+        assert torch.equal(a_, b_)
+    del Gt2, U2, A2, Y2
+    for r0 in range(0, N, 16384):                          # gate * A, two bf16 roundings apart at most
+        want = row_gate[r0:r0 + 16384, None] * A[r0:r0 + 16384].float()
+        assert torch.allclose(Ag[r0:r0 + 16384].float(), want, rtol=2.0 ** -7, atol=1e-30)
+    dgate_g = torch.full((T, k), float("nan"), dtype=torch.float32, device=DEV)
+    ws_g = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, N, 1, E, G, h, hff), dtype=torch.uint8, device=DEV)
+    dXrows_g, _ = rl.relibra_moe_ffn_bwd_gated(dOut_d, row_tok, row_gate, Gt, U, tabs["group_offset"], tabs["group_expert"],
+                                               tabs["group_dw_slot"], Wg_d, Wu_d, Wd_d, src_of=src_of, dgate=dgate_g,
+                                               workspace=ws_g, err_flag=err, E=E)
+    assert rel_l2(dgate_g[tk].double().cpu().numpy(), dgate_o) <= TOL
+    assert rel_l2(dXrows_g[sr].double().cpu().numpy(), dXr_o) <= TOL
+    assert not torch.isnan(dgate_g).any()
+    assert (torch.linalg.vector_norm((dgate_g - dgate).double()) <= TOL * torch.linalg.vector_norm(dgate.double())).item()
+    num = den = 0.0
+    for r0 in range(0, N, 16384):
+        a_, b_ = dXrows_g[r0:r0 + 16384].double(), dXrows[r0:r0 + 16384].double()
+        num += torch.linalg.vector_norm(a_ - b_).item() ** 2
+        den += torch.linalg.vector_norm(b_).item() ** 2
+    assert num ** 0.5 <= TOL * den ** 0.5
+    one_g = dict(dOut=dOut_d, X=X_d, row_tok=row_tok, A=Ag, bwd_workspace=ws_g, inst_ptr=tabs["inst_ptr"],
+                 inst_group=tabs["inst_group"], group_offset=tabs["group_offset"])
+    rl.relibra_moe_ffn_wgrad_batched([one_g, one_g], E, *dWf, err_flag=err)
+    for name, got, full in zip(("dWg", "dWu", "dWd"), dWf, (dWg, dWu, dWd)):
+        num = den = 0.0
+        for e0 in range(0, E, 16):
+            w2 = 2.0 * full[:E][e0:e0 + 16].double()
+            num += torch.linalg.vector_norm(got[e0:e0 + 16].double() - w2).item() ** 2
+            den += torch.linalg.vector_norm(w2).item() ** 2
+        assert num ** 0.5 <= TOL * den ** 0.5, (name, (num / max(den, 1e-300)) ** 0.5)
+    assert err.item() == 0
+    print(f"[{cfg.name}] gate-fused backward ok", flush=True)

@@ -148,6 +148,21 @@ def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
     assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 128, 256, f, f, f, 6, z, ctypes.c_size_t(0), z, z) == rl.EINVAL   # both tiles
     assert L.relibra_moe_ffn_wgrad_batched(one, 1, 16, 12, 10, 8, 128, 256, f, f, f, 0, z, ctypes.c_size_t(0), z, z) == rl.EINVAL  # null dW
     assert rl.workspace_bytes(rl.WS_WGRAD_BATCHED, 0, 1, 8, 12, 128, 256) > 0
+    # gate-fused forward / backward
+    assert L.relibra_row_gates(z, z, -1, z, z, z) == rl.EINVAL
+    assert L.relibra_row_gates(z, z, 0, z, z, z) == rl.OK
+    assert L.relibra_row_gates(z, z, 8, z, z, z) == rl.EINVAL                               # null tensors
+    assert L.relibra_moe_ffn_fwd_gated(z, 4, z, z, 16, z, z, 12, 0, 12, 8, z, z, z, 128, 256, z, z, z, z, z, 0, z,
+                                       ctypes.c_size_t(0), z, z) == rl.EINVAL               # no row table, no gates
+    sz = ctypes.c_size_t(0)
+    assert L.relibra_moe_ffn_bwd_gated(z, 4, z, z, z, z, z, 16, z, z, z, 12, 0, 12, 8, 8, z, z, z, 128, 256, z, f, 1, z, sz, z, sz,
+                                       z, z) == rl.EINVAL                                   # a flag of the ungated call only
+    assert L.relibra_moe_ffn_bwd_gated(z, 4, z, z, z, z, z, 16, z, z, z, 12, 0, 12, 8, 8, z, z, z, 100, 256, z, f, 0, z, sz, z, sz,
+                                       z, z) == rl.EUNSUPPORTED                             # h % 64
+    assert L.relibra_moe_ffn_bwd_gated(z, 4, z, z, z, z, z, 16, z, z, z, 12, 0, 12, 8, 8, z, z, z, 128, 256, z, f, 0, z, sz, z, sz,
+                                       z, z) == rl.EINVAL                                   # null tensors
+    # partial row sums of dgate: four per row and 256-column tile of h'
+    assert rl.workspace_bytes(rl.WS_DGATE, 512, 2, 8, 12, 128, 768) >= 4 * 3 * 1024 * 4
 
 
 # ------------------------------------------------------------------ communication-aware model, Algorithm 1
