@@ -105,10 +105,10 @@ def main():
     Xrows_k = [bf(N, h) for _ in range(1 if fused_gather else n_keep)]
     row_tok_k = [i32(N) for _ in range(n_keep)] if fused_gather else []
     dYrows_k = [] if gate_fused else [bf(N, h) for _ in range(n_keep)]   # gate-fused: the upstream rows are never materialised
-    Ag_k = [bf(N, hff) for _ in range(n_keep)] if gate_fused else []
     row_gate = torch.empty(N, dtype=torch.float32, device=dev)
     dgate_scratch = torch.empty(max(rl.workspace_bytes(rl.WS_DGATE, N, k, E, G, h, hff), 1), dtype=torch.uint8, device=dev)
-    A_k = [bf(N, hff) for _ in range(n_keep)]
+    A_k = [bf(N, hff) for _ in range(n_keep)]            # gate-fused: holds gate * A (see layer())
+    Ag_k = A_k if gate_fused else []
     Yrows, dXrows = bf(N, h), bf(N, h)
     Gt, U = bf(N, hff), bf(N, hff)
     Out, dX = bf(T, h), bf(T, h)
@@ -146,8 +146,9 @@ def main():
             rl.relibra_row_tokens(src_of, k, T, row_tok=row_tok_k[i], err_flag=err)
             if gate_fused:
                 rl.relibra_row_gates(src_of, gates_all[mb], row_gate=row_gate, err_flag=err)
+                # gated in place: A = gate * A, the rows come out gate-scaled and the combine below is a plain sum
                 rl.relibra_moe_ffn_fwd_gated(X, row_tok_k[i], row_gate, tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
-                                             Gt=Gt, U=U, A=Ar, Ag=Ag_k[i], Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
+                                             Gt=Gt, U=U, A=Ag_k[i], Ag=Ag_k[i], Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
             else:
                 rl.relibra_moe_ffn_fwd_gather(X, row_tok_k[i], tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
                                               Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
@@ -158,7 +159,10 @@ def main():
                                Xrows=Xr, workspace=ws_perm, err_flag=err)
             rl.relibra_moe_ffn_fwd(Xr, tabs["group_offset"][mb], tabs["group_expert"][mb], *fw,
                                    Gt=Gt, U=U, A=Ar, Yrows=Yrows, workspace=ws, err_flag=err, flags=fwd_flags)
-        rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
+        if gate_fused:
+            rl.relibra_unpermute_combine(rl.COMBINE_SUM, Yrows, row_of, T, k, out_tok=Out, err_flag=err)
+        else:
+            rl.relibra_unpermute_combine(rl.COMBINE_FWD, Yrows, row_of, T, k, gates=gates_all[mb], out_tok=Out, err_flag=err)
         bw = (WgT, WuT, WdT) if bwd_t else (Wg, Wu, Wd)
         if gate_fused:
             rl.relibra_moe_ffn_bwd_gated(dOut, row_tok_k[i], row_gate, Gt, U, tabs["group_offset"][mb], tabs["group_expert"][mb],
@@ -283,7 +287,7 @@ def main():
             home_live = int(((rows_g > 0) & (plan["group_dw_slot"][mb] < E)).sum())
             acc_mode = mb > 0
             tot += {
-                "fwd_gate_up": act_x + 2 * w1 * live + (4 if gate_fused else 3) * act_ff + gate_rows,
+                "fwd_gate_up": act_x + 2 * w1 * live + 3 * act_ff + gate_rows,
                 "fwd_down": act_ff + w1 * live + act_h,
                 "bwd_act": act_dy + w1 * live + 2 * act_ff + 2 * act_ff + 2 * gate_rows,      # + the row sums of dgate
                 "bwd_dx": 2 * act_ff + 2 * w1 * live + act_h,

@@ -337,7 +337,10 @@ int relibra_moe_ffn_fwd_gather(const void *X_dev, int T, const int32_t *row_tok_
  * (relibra_row_gates: gates_dev [T*k] fp32 indexed by src_of):
  *   forward (relibra_moe_ffn_fwd_gated): relibra_moe_ffn_fwd_gather that also stores
  *       Ag_save [n_rows, hff] bf16 = row_gate * A, the right operand of dWd below; all other
- *       outputs are unchanged (Yrows stays ungated: relibra_unpermute_combine applies the gates);
+ *       outputs are unchanged (Yrows stays ungated: relibra_unpermute_combine applies the gates).
+ *       With Ag_save_dev == A_save_dev the gated activations take the plain ones' place (one tensor
+ *       less to write): the down projection then yields gate-scaled rows, and the combine is
+ *       RELIBRA_COMBINE_SUM (rounding differs from gating afterwards; within the tolerance);
  *   backward (relibra_moe_ffn_bwd_gated): takes dOut [T, h] bf16, the gradient of the combined
  *       output, instead of dYrows = gate * dOut[token] (no combine-backward pass, no dYrows
  *       buffer).  With dA' = Wd_e^T dOut[tok(r)]:

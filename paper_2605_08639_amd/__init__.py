@@ -381,7 +381,8 @@ def relibra_row_gates(src_of, gates, row_gate=None, err_flag=None):
 
 def relibra_moe_ffn_fwd_gated(X, row_tok, row_gate, group_offset, group_expert, Wg, Wu, Wd, g_begin=0, g_end=None,
                               Gt=None, U=None, A=None, Ag=None, Yrows=None, workspace=None, err_flag=None, flags=0):
-    """relibra_moe_ffn_fwd_gather that also stores Ag = row_gate * A (the operand of the gate-fused weight gradient)."""
+    """relibra_moe_ffn_fwd_gather that also stores Ag = row_gate * A (the operand of the gate-fused weight gradient).
+    Passing the same tensor as A and Ag gates in place: Yrows then come out gate-scaled (combine with COMBINE_SUM)."""
     T, h = X.shape
     n_rows = row_tok.shape[0]
     E, hff = Wg.shape[0], (Wg.shape[2] if flags & FWD_TRANSPOSED_WEIGHTS else Wg.shape[1])

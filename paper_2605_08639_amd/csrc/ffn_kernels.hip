@@ -383,13 +383,17 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     char *buf = lds + wave * ST::BYTES;
     const int wrow0 = t.row0 + (wave % WV::B) * 64, row_end = t.row0 + t.rows;
     const int wcol0 = t.col0 + (wave / WV::B) * WCOLS;
-    // optional fourth tensor: the activations scaled by the gate of the row's assignment
+    // With row gates: the activations scaled by the gate of the row's assignment, as a fourth tensor
+    // (Agout) or, with Agout == Aout, in place of the plain ones (the down projection then yields
+    // gated rows and the combine is a plain sum).
+    const bool gated = row_gate != nullptr, in_place = gated && Agout == Aout;
     float gate[KL::TB];
 #pragma unroll
-    for (int tb = 0; tb < KL::TB; ++tb) gate[tb] = Agout ? row_gate[min(wrow0 + tb * 32 + (lane & 31), row_end - 1)] : 0.0f;
+    for (int tb = 0; tb < KL::TB; ++tb) gate[tb] = gated ? row_gate[min(wrow0 + tb * 32 + (lane & 31), row_end - 1)] : 0.0f;
 #pragma unroll
     for (int which = 0; which < 4; ++which) {
-        if (which == 3 && !Agout) break;
+        if (which == 3 && !gated) break;
+        if (which == 2 && in_place) continue;                 // the fourth pass writes A's place
 #pragma unroll
         for (int tb = 0; tb < KL::TB; ++tb)
 #pragma unroll
@@ -1079,7 +1083,7 @@ static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_
 {
     hipStream_t stream = (hipStream_t)stream_;
     if (flags & ~RELIBRA_FWD_TRANSPOSED_WEIGHTS) return RELIBRA_EINVAL;
-    if ((row_gate == nullptr) != (Ag_save == nullptr) || !aligned16(Ag_save)) return RELIBRA_EINVAL;
+    if ((row_gate == nullptr) != (Ag_save == nullptr) || !aligned16(Ag_save)) return RELIBRA_EINVAL;   // Ag_save == A_save: gated in place
     const bool wt = (flags & RELIBRA_FWD_TRANSPOSED_WEIGHTS) != 0;
     const FfnArgs a{n_rows, G, g_begin, g_end, E, h, hff};
     if (int rc = check_ffn_args(a)) return rc;

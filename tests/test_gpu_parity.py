@@ -712,6 +712,13 @@ def test_gate_fused_backward_matches_the_unfused_definition(weights_t):
         go, ge = p["group_offset"][mb], p["group_expert"][mb]
         _, _, A_o, Y_o = oracle.ffn_fwd(Xrows_o, go, ge, Wg, Wu, Wd)
         assert rel_l2(Ag, gates[mb].reshape(-1)[src_o][:, None].astype(np.float64) * A_o) <= TOL
+        # gated in place (A and Ag the same tensor): same Gt, U and Ag; rows come out gate-scaled, the combine is a sum
+        A_ip = torch.empty_like(A)
+        Gt_p, U_p, _, Ag_p, Y_p = rl.relibra_moe_ffn_fwd_gated(Xd, row_tok, row_gate, tabs["group_offset"], tabs["group_expert"],
+                                                               *W_f, A=A_ip, Ag=A_ip, err_flag=err, flags=f_flags)
+        assert torch.equal(Gt_p, Gt) and torch.equal(U_p, U) and torch.equal(Ag_p, Ag)
+        Out_p = rl.relibra_unpermute_combine(rl.COMBINE_SUM, Y_p, row_of, cfg.T, cfg.k, err_flag=err)
+        assert rel_l2(Out_p, oracle.combine_fwd(Y_o, gates[mb], row_of_o, cfg.T, cfg.k)) <= TOL
         # backward
         ws = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, cfg.N, 1, cfg.E, cfg.G, cfg.h, cfg.hff), dtype=torch.uint8, device=DEV)
         b_flags = rl.BWD_TRANSPOSED_WEIGHTS if weights_t else 0
