@@ -555,16 +555,20 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
             }
         }
         if (EPI == 2) {
-            // a row's columns lie on lanes l and l + 32; one partial sum per row, wave column and column tile
-            const int slot0 = (t.col0 / 256) * kDgateParts, wa = wave / WV::B;
+            // a row's columns lie on lanes l and l + 32; one partial sum per row and wave column, in the
+            // slot of its 256 columns (kDgateParts slots each; a wave column is 64 or 128 wide)
+            constexpr int PER = 256 / WCOLS;
+            static_assert(PER >= 1 && PER <= kDgateParts, "wave columns per 256 columns");
+            const int slot = (wcol0 / 256) * kDgateParts + (wcol0 % 256) / WCOLS;
 #pragma unroll
             for (int tb = 0; tb < KL::TB; ++tb) {
                 const float total = dsum[tb] + __shfl_xor(dsum[tb], 32);
                 const int r = wrow0 + tb * 32 + (lane & 31);
                 if (lane < 32 && r < row_end) {
-                    gf.dgate_part[(size_t)(slot0 + wa) * gf.n_rows + r] = total;
-                    // the slots of wave columns this tile shape does not have
-                    if (WV::A < kDgateParts) gf.dgate_part[(size_t)(slot0 + WV::A + wa) * gf.n_rows + r] = 0.0f;
+                    gf.dgate_part[(size_t)slot * gf.n_rows + r] = total;
+#pragma unroll
+                    for (int extra = PER; extra < kDgateParts; extra += PER)      // the slots this tile shape does not fill
+                        gf.dgate_part[(size_t)(slot + extra) * gf.n_rows + r] = 0.0f;
                 }
             }
         }
@@ -591,20 +595,20 @@ fwd_down_kernel(Sched s, const bf16_t *__restrict__ Ain, const bf16_t *__restric
 // WT = false: Wd as the forward pass holds it, [h][h'], contraction index strided (transposing
 // LDS reads, full-line loads: the faster operand path).  WT = true: a transposed copy [h'][h],
 // contraction index contiguous.
-template <bool WT, bool GATED = false>
-__global__ void __launch_bounds__(THREADS, 2)
+template <bool WT, bool GATED = false, int AW = 256>
+__global__ void __launch_bounds__(AW == 256 ? THREADS : kWideRowWaves * 64, AW == 256 ? 2 : 1)
 bwd_act_kernel(Sched s, const bf16_t *__restrict__ dY, const bf16_t *__restrict__ Wd,
                const bf16_t *__restrict__ Gt, const bf16_t *__restrict__ U, int h, int hff, int n_col_tiles,
                int w_from_slot, GateFusion gf)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const RowTile t = find_row_tile(s, n_col_tiles, 256, w_from_slot != 0);
+    const RowTile t = find_row_tile(s, n_col_tiles, AW, w_from_slot != 0);
     if (!t.valid) return;
     const bf16_t *W = Wd + (size_t)t.expert * h * hff;      // (n in h', k in h) at [k*h' + n], or at [n*h + k]
     const int ldw = WT ? h : hff;
     constexpr int EPI = GATED ? 2 : 1;
-    if (t.rows > BM / 2) row_gemm_body<BM, !WT, 1, EPI>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds, gf);
-    else row_gemm_body<BM / 2, !WT, 1, EPI>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds, gf);
+    if (t.rows > BM / 2) row_gemm_body<BM, !WT, 1, EPI, AW>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds, gf);
+    else row_gemm_body<BM / 2, !WT, 1, EPI, AW>(t, dY, nullptr, h, W, nullptr, ldw, hff, h, s.dGt, s.dU, Gt, U, lds, gf);
 }
 
 // dgate of the gate-fused backward: the partial row sums of the activation backward added up in
@@ -1032,6 +1036,10 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false, false, 512>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesWide));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true, false, 512>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesWide));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<false, true, 512>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesWide));
+    RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_act_kernel<true, true, 512>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesWide));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)bwd_dx_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel<false, 256>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesWide));
@@ -1203,7 +1211,8 @@ static int ffn_bwd_impl(const void *dYrows, const void *Xrows,
     RELIBRA_HIP_TRY(launch_check());
     const long long R = max_row_tiles(n_rows, Gr);
     const bool wide_h = row_tiles_wide(h, 512);
-    const int ct_ff = (hff + 255) / 256, ct_h = wide_h ? h / 512 : (h + 255) / 256;
+    const bool wide_ff = row_tiles_wide(hff, 512);
+    const int ct_ff = wide_ff ? hff / 512 : (hff + 255) / 256, ct_h = wide_h ? h / 512 : (h + 255) / 256;
     const int accumulate = (flags & RELIBRA_BWD_ACCUMULATE) ? 1 : 0;
     const int w_from_slot = (flags & RELIBRA_BWD_REPLICA_WEIGHTS) ? 1 : 0;
     if (n_rows > 0) {
@@ -1218,9 +1227,13 @@ static int ffn_bwd_impl(const void *dYrows, const void *Xrows,
             gf.row_gate = gb->row_gate;
             gf.dgate_part = (float *)gb->scratch;
         }
-#define RELIBRA_BWD_ACT(WT_, GATED_)                                                                                            \
-    RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, (bwd_act_kernel<WT_, GATED_><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(   \
-        s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot, gf)))
+#define RELIBRA_BWD_ACT(WT_, GATED_)                                                                                              \
+    do {                                                                                                                          \
+        if (wide_ff) RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, (bwd_act_kernel<WT_, GATED_, 512><<<grid8(R * ct_ff), kWideRowWaves * 64, kLdsBytesWide, stream>>>( \
+            s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot, gf)));                                                                 \
+        else RELIBRA_LAUNCH(RELIBRA_K_BWD_ACT, stream, (bwd_act_kernel<WT_, GATED_, 256><<<grid8(R * ct_ff), THREADS, kLdsBytes, stream>>>(         \
+            s, dy, wd, gt, us, h, hff, ct_ff, w_from_slot, gf)));                                                                 \
+    } while (0)
         if (wt) { if (gb) RELIBRA_BWD_ACT(true, true); else RELIBRA_BWD_ACT(true, false); }
         else { if (gb) RELIBRA_BWD_ACT(false, true); else RELIBRA_BWD_ACT(false, false); }
 #undef RELIBRA_BWD_ACT
@@ -1232,7 +1245,7 @@ static int ffn_bwd_impl(const void *dYrows, const void *Xrows,
         RELIBRA_HIP_TRY(launch_check());
         if (gb) {
             RELIBRA_LAUNCH(RELIBRA_K_COMBINE_BWD, stream, dgate_reduce_kernel<<<std::min(1024, (n_rows + 255) / 256), 256, 0, stream>>>(
-                (const float *)gb->scratch, kDgateParts * ct_ff, n_rows, group_offset, g_begin, g_end, gb->src_of, gb->dgate, err_flag));
+                (const float *)gb->scratch, kDgateParts * ((hff + 255) / 256), n_rows, group_offset, g_begin, g_end, gb->src_of, gb->dgate, err_flag));
             RELIBRA_HIP_TRY(launch_check());
         }
     }

@@ -242,6 +242,9 @@ FFN_CASES = [
     dict(seed=4, E=2, h=320, hff=448, rows=(200, 0, 131), experts=(0, 1, 0)),
     # long groups: the large weight-gradient tile geometry (512 or more rows per group on average)
     dict(seed=7, E=2, h=128, hff=256, rows=(1100, 700), experts=(1, 0)),
+    # widths that take the 512-column (eight-wave) tiles in every row-tiled kernel, ragged rows and a replica
+    dict(seed=8, E=3, h=512, hff=512, rows=(1, 64, 65, 200, 0, 129), experts=(2, 0, 1, 0, -1, 2)),
+    dict(seed=9, E=2, h=1024, hff=1536, rows=(300, 77), experts=(1, 0)),
 ]
 
 
@@ -669,15 +672,16 @@ def test_forward_with_fused_row_gather_is_bit_identical():
 
 
 # ------------------------------------------------------------------ gate-side fusion of the backward
+@pytest.mark.parametrize("hff", [320, 512], ids=["narrow-dA-tiles", "wide-dA-tiles"])
 @pytest.mark.parametrize("weights_t", [False, True], ids=["stored-layout", "transposed-copies"])
-def test_gate_fused_backward_matches_the_unfused_definition(weights_t):
+def test_gate_fused_backward_matches_the_unfused_definition(weights_t, hff):
     """The combine (Section 2.1: gate-weighted sum of the selected experts' outputs) is linear, so its
     backward may move into the expert backward: dOut rows read straight from the token tensor, the gate
     applied to dA, dgate as a row reduction of dA' against A, dWd from dOut rows against gate * A.  The
     oracle computes the unfused definition (combine backward, then expert backward); the fused path must
     agree within the floating-point tolerance on dX, dgate and all three weight gradients, its forward
     outputs must equal the unfused forward's bit for bit, and two runs must agree bit for bit."""
-    cfg = wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=2, h=512, hff=320)
+    cfg = wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=2, h=512, hff=hff)
     ids, gates = routing(cfg)
     counts = oracle.route_hist(ids, cfg.E)[0]
     p = plan_both(cfg, counts)
