@@ -945,7 +945,8 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
 {
     constexpr int WGM = 256, BA = WGM / NA;
     // NA = 1: the A side (dY) may be gathered; its loads go last in the window (see KLoop)
-    using KL = KLoop<KsTile<BA>, KsTile<WN>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads, NA == 1>;
+    // the operand that may come through a row table: dY of dWd (A side), X of dWg, dWu (B side)
+    using KL = KLoop<KsTile<BA, BK, NA == 1>, KsTile<WN, BK, NA == 2>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads, NA == 1>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WN - 1) / WN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;

@@ -148,7 +148,10 @@ struct KcTile {
 
 // k-strided operand: LDS [k][ROWS] as in memory; 16-byte pieces of a k-row XOR-ed with fk(k) so
 // that the 8-byte transposing reads of 4 k-rows x 16 (or 32) rows hit distinct banks.
-template <int ROWS, int BKT = BK>
+// MAY_GATHER: the operand may carry a row table (Operand::gather); without it the lookup code is
+// not compiled in (even unused it cost the weight-gradient kernels 4-5 %: selects and scalar
+// registers in every load).
+template <int ROWS, int BKT = BK, bool MAY_GATHER = false>
 struct KsTile {
     static constexpr int DEPTH = BKT;
     static constexpr int BYTES = ROWS * BKT * 2;
@@ -178,7 +181,7 @@ struct KsTile {
     template <int NW>
     static __device__ __forceinline__ void fetch(Idx<NW> &ix, const Lanes<NW> &ln, int k0, int k_last, int wave)
     {
-        if (!ln.op.gather) return;
+        if (!MAY_GATHER || !ln.op.gather) return;
         const_i32_ptr g = (const_i32_ptr)(uintptr_t)ln.op.gather;
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i)
@@ -200,7 +203,7 @@ struct KsTile {
         const int s = (lane % SPR) ^ fk(j * KPB + kq);
         int grow = op.row0 + s * 8;
         if (grow > op.row_last) grow = op.row_last - 7;
-        const bool gathered = op.gather != nullptr;
+        const bool gathered = MAY_GATHER && op.gather != nullptr;
         long long off = 0;
 #pragma unroll
         for (int q = 0; q < KPB; ++q) {
