@@ -29,6 +29,12 @@ constexpr int BK = 32;                      // default contraction slab per pipe
 // Uniform loads through this type are scalar loads (tracked by lgkmcnt, not by the vmcnt the
 // pipeline counts by hand); the memory must not change while the kernel runs.
 typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+// C consecutive table entries as one scalar load (the table is only 4-byte aligned)
+template <int C> struct ScalarRun {
+    typedef int32_t vec __attribute__((ext_vector_type(C)));
+    typedef vec unaligned __attribute__((aligned(4)));
+    typedef const __attribute__((address_space(4))) unaligned *ptr;
+};
 
 #define RELIBRA_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define RELIBRA_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -162,6 +168,17 @@ struct KsTile {
     static_assert(ROWS >= 64 && ROWS <= 512, "tile height");
     template <int NW>
     static constexpr int per_wave() { return BLOCKS / NW; }
+    // i-th load block of a wave.  An operand that may be gathered gives a wave consecutive blocks,
+    // so that the rows it looks up per slab are consecutive table entries (one wide scalar load).
+    template <int NW>
+    static __device__ __forceinline__ int block_of(int wave, int i)
+    {
+#ifdef RELIBRA_PROBE_STRIDED_BLOCKS
+        return wave + i * NW;
+#else
+        return MAY_GATHER ? wave * (BLOCKS / NW) + i : wave + i * NW;
+#endif
+    }
 
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
 
@@ -183,10 +200,22 @@ struct KsTile {
     {
         if (!MAY_GATHER || !ln.op.gather) return;
         const_i32_ptr g = (const_i32_ptr)(uintptr_t)ln.op.gather;
+#ifndef RELIBRA_PROBE_STRIDED_BLOCKS
+        constexpr int C = (BLOCKS / NW) * KPB;              // this wave's k-rows of the slab: consecutive
+        const int first = k0 + block_of<NW>(wave, 0) * KPB;
+        if (first + C - 1 <= k_last) {                      // all but a piece's last slab: no clamping
+            const typename ScalarRun<C>::vec run = *(typename ScalarRun<C>::ptr)(g + first);
+#pragma unroll
+            for (int i = 0; i < BLOCKS / NW; ++i)
+#pragma unroll
+                for (int q = 0; q < KPB; ++q) ix.v[i][q] = run[i * KPB + q];
+            return;
+        }
+#endif
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i)
 #pragma unroll
-            for (int q = 0; q < KPB; ++q) ix.v[i][q] = g[min(k0 + (wave + i * NW) * KPB + q, k_last)];
+            for (int q = 0; q < KPB; ++q) ix.v[i][q] = g[min(k0 + block_of<NW>(wave, i) * KPB + q, k_last)];
     }
     // The memory row of a k-row is the same for every lane that loads a piece of it, and a wave's
     // load block holds KPB k-rows: the rows (clamped, or looked up when the operand is gathered) and
@@ -198,7 +227,7 @@ struct KsTile {
     {
         static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
         const Operand &op = ln.op;
-        const int j = wave + i * NW;
+        const int j = block_of<NW>(wave, i);
         const int kq = lane / SPR;                  // which of the block's k-rows this lane loads from
         const int s = (lane % SPR) ^ fk(j * KPB + kq);
         int grow = op.row0 + s * 8;
