@@ -173,11 +173,7 @@ struct KsTile {
     template <int NW>
     static __device__ __forceinline__ int block_of(int wave, int i)
     {
-#ifdef RELIBRA_PROBE_STRIDED_BLOCKS
-        return wave + i * NW;
-#else
         return MAY_GATHER ? wave * (BLOCKS / NW) + i : wave + i * NW;
-#endif
     }
 
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
@@ -190,7 +186,9 @@ struct KsTile {
     static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int /*wave*/, int /*lane*/) { return Lanes<NW>{op}; }
 
     // A gathered operand (contraction index -> row of `base`) needs, per slab, the rows of the KPB
-    // k-rows of each of this wave's load blocks: fetched as scalars (fetch) ahead of the loads.
+    // k-rows of each of this wave's load blocks: fetched as scalars (fetch) ahead of the loads, in
+    // one wide scalar load (one scalar load per k-row cost the weight gradients 1.5 % each: eight
+    // per wave and slab 12 %; every lgkmcnt(0) of the loop waits for scalar loads too).
     template <int NW>
     struct Idx {
         int v[BLOCKS / NW][KPB];
@@ -200,7 +198,6 @@ struct KsTile {
     {
         if (!MAY_GATHER || !ln.op.gather) return;
         const_i32_ptr g = (const_i32_ptr)(uintptr_t)ln.op.gather;
-#ifndef RELIBRA_PROBE_STRIDED_BLOCKS
         constexpr int C = (BLOCKS / NW) * KPB;              // this wave's k-rows of the slab: consecutive
         const int first = k0 + block_of<NW>(wave, 0) * KPB;
         if (first + C - 1 <= k_last) {                      // all but a piece's last slab: no clamping
@@ -211,7 +208,6 @@ struct KsTile {
                 for (int q = 0; q < KPB; ++q) ix.v[i][q] = run[i * KPB + q];
             return;
         }
-#endif
 #pragma unroll
         for (int i = 0; i < BLOCKS / NW; ++i)
 #pragma unroll
