@@ -780,7 +780,8 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
 // ---------------------------------------------------------------- batched weight gradients
 // One pass over every micro-batch of a training batch: the tile of expert e contracts over all
 // rows e received, instance by instance, micro-batch by micro-batch, in registers, and writes
-// dW once.  Per-micro-batch device pointers travel as a kernel argument.
+// dW once.  Per-micro-batch device pointers travel as a kernel argument of the ordering kernel,
+// which turns them into one record per piece for the GEMM kernels.
 constexpr int kMaxWgradMb = RELIBRA_MAX_WGRAD_MB;
 constexpr int kWgradChunk = 64;
 struct MbTable {
@@ -819,8 +820,20 @@ struct WgradPlan {
     int32_t *exp_order;    // [E] experts in descending order of rows (ties: lower id)
     int32_t *piece_ptr;    // [E+1] CSR over experts into the piece arrays
     int32_t *piece_mb, *piece_row0, *piece_rows;   // [S] micro-batch, first row, rows (> 0) of a piece
+    // [S] what a tile's k-loop needs of a piece, as one record each (one wide scalar load per switch
+    // of piece instead of a chain of single ones): operand addresses at the piece's first row, the
+    // row table (0: none), rows, last token.  64-byte aligned.
+    int32_t *rec_down, *rec_gu;
 };
-inline size_t wgrad_plan_ints(int E, int G) { return 4 * (size_t)E + 1 + 3 * (size_t)kMaxWgradMb * ((size_t)E + G); }
+constexpr int kRecDownInts = 8, kRecGuInts = 16;
+struct PieceRecDown { unsigned long long L, R, gather; int32_t rows, tok_last; };
+struct PieceRecGu { unsigned long long L0, L1, R, gather; int32_t rows, tok_last; int32_t pad[6]; };
+static_assert(sizeof(PieceRecDown) == kRecDownInts * 4 && sizeof(PieceRecGu) == kRecGuInts * 4, "record sizes");
+inline size_t wgrad_plan_ints(int E, int G)
+{
+    const size_t S = (size_t)kMaxWgradMb * ((size_t)E + G);
+    return 4 * (size_t)E + 1 + 3 * S + 16 + (kRecDownInts + kRecGuInts) * S;
+}
 inline WgradPlan carve_wgrad(void *ws, int E, int G)
 {
     WgradPlan w;
@@ -832,7 +845,10 @@ inline WgradPlan carve_wgrad(void *ws, int E, int G)
     w.piece_ptr = p; p += E + 1;
     w.piece_mb = p; p += S;
     w.piece_row0 = p; p += S;
-    w.piece_rows = p;
+    w.piece_rows = p; p += S;
+    p += (16 - ((p - (int32_t *)ws) & 15)) & 15;             // records: 64-byte aligned (the workspace is 256-byte aligned)
+    w.rec_down = p; p += kRecDownInts * S;
+    w.rec_gu = p;
     return w;
 }
 
@@ -840,7 +856,7 @@ inline WgradPlan carve_wgrad(void *ws, int E, int G)
 // batch by micro-batch in the order of the plan's instance table (entries out of range are left
 // out and flagged), and ranks the experts by rows so that the tiles run heaviest first.
 __global__ void __launch_bounds__(256)
-wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E, WgradPlan w, int32_t *err_flag)
+wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E, int h, int hff, WgradPlan w, int32_t *err_flag)
 {
     extern __shared__ int32_t rows_of[];       // [E]
     __shared__ int32_t scan[256];
@@ -884,7 +900,28 @@ wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
                 for (int p = p0; p < p1; ++p) {
                     int row0, rows;
                     inst_rows(tb, mb, p, G, n_rows, row0, rows);
-                    if (rows > 0) { w.piece_mb[at] = mb; w.piece_row0[at] = row0; w.piece_rows[at] = rows; ++at; }
+                    if (rows > 0) {
+                        w.piece_mb[at] = mb; w.piece_row0[at] = row0; w.piece_rows[at] = rows;
+                        const bool dy_tok = (tb.dy_tokens >> mb) & 1, x_tok = tb.rtok[mb] != nullptr;
+                        const unsigned long long table = (unsigned long long)(uintptr_t)(tb.rtok[mb] + row0);
+                        PieceRecDown d;     // dWd: L = dY rows (or dOut tokens through the table), R = A rows
+                        d.L = (unsigned long long)(uintptr_t)(dy_tok ? tb.dY[mb] : tb.dY[mb] + (size_t)row0 * h);
+                        d.R = (unsigned long long)(uintptr_t)(tb.A[mb] + (size_t)row0 * hff);
+                        d.gather = dy_tok ? table : 0ull;
+                        d.rows = rows;
+                        d.tok_last = tb.tok_last[mb];
+                        ((PieceRecDown *)w.rec_down)[at] = d;
+                        PieceRecGu u;       // dWg, dWu: L = dGt, dU rows; R = X rows (or tokens through the table)
+                        u.L0 = (unsigned long long)(uintptr_t)(tb.dGt[mb] + (size_t)row0 * hff);
+                        u.L1 = (unsigned long long)(uintptr_t)(tb.dU[mb] + (size_t)row0 * hff);
+                        u.R = (unsigned long long)(uintptr_t)(x_tok ? tb.X[mb] : tb.X[mb] + (size_t)row0 * h);
+                        u.gather = x_tok ? table : 0ull;
+                        u.rows = rows;
+                        u.tok_last = tb.tok_last[mb];
+                        for (int z = 0; z < 6; ++z) u.pad[z] = 0;
+                        ((PieceRecGu *)w.rec_gu)[at] = u;
+                        ++at;
+                    }
                 }
             }
         }
@@ -902,27 +939,32 @@ wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
     }
 }
 
-// The pieces of one expert's contraction as the k-loop sees them.
+// The pieces of one expert's contraction as the k-loop sees them: one record per piece, written
+// by the ordering kernel (an earlier launch, the same for every lane: read as scalars).
 template <int NA>
 struct WgradPieces {
-    const MbTable &tb;
-    const_i32_ptr mb, row0, rows;          // this expert's slice of the piece arrays (read as scalars: they
-                                           // were written by an earlier launch and are the same for every lane)
+    const_i32_ptr rows;                    // this expert's slice of the piece rows
+    const_i32_ptr recs;                    // and of the records
     int m_dim, n_dim, m0, n0;
     __device__ __forceinline__ int valid(int i) const { return rows[i]; }
     __device__ __forceinline__ void piece(int i, Operand (&A)[1][NA], Operand (&B)[1][1], int &k_valid) const
     {
-        const int b = mb[i], r0 = row0[i];
-        k_valid = rows[i];
-        if (NA == 1) {      // dWd: L = dY (or token rows of dOut against gate-scaled A), R = A
-            if ((tb.dy_tokens >> b) & 1) A[0][0] = {tb.dY[b], m_dim, m0, m_dim - 1, tb.rtok[b] + r0, tb.tok_last[b]};
-            else A[0][0] = {tb.dY[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
-            B[0][0] = {tb.A[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
-        } else {            // dWg, dWu: L = dGt, dU; R = X
-            A[0][0] = {tb.dGt[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
-            A[0][NA - 1] = {tb.dU[b] + (size_t)r0 * m_dim, m_dim, m0, m_dim - 1};
-            if (tb.rtok[b]) B[0][0] = {tb.X[b], n_dim, n0, n_dim - 1, tb.rtok[b] + r0, tb.tok_last[b]};
-            else B[0][0] = {tb.X[b] + (size_t)r0 * n_dim, n_dim, n0, n_dim - 1};
+        constexpr int RI = NA == 1 ? kRecDownInts : kRecGuInts;
+        typedef int32_t rec_vec __attribute__((ext_vector_type(RI)));
+        typedef const __attribute__((address_space(4))) rec_vec *rec_ptr;
+        const rec_vec r = *(rec_ptr)(recs + (size_t)i * RI);
+        auto ptr = [&](int at) { return (const bf16_t *)(uintptr_t)(((unsigned long long)(uint32_t)r[at + 1] << 32) | (uint32_t)r[at]); };
+        if (NA == 1) {
+            const int32_t *table = (const int32_t *)ptr(4);
+            k_valid = r[6];
+            A[0][0] = {ptr(0), m_dim, m0, m_dim - 1, table, r[7]};
+            B[0][0] = {ptr(2), n_dim, n0, n_dim - 1};
+        } else {
+            const int32_t *table = (const int32_t *)ptr(6);
+            k_valid = r[8];
+            A[0][0] = {ptr(0), m_dim, m0, m_dim - 1};
+            A[0][NA - 1] = {ptr(2), m_dim, m0, m_dim - 1};
+            B[0][0] = {ptr(4), n_dim, n0, n_dim - 1, table, r[9]};
         }
     }
 };
@@ -940,7 +982,7 @@ template <int WN> struct WgradWide {
 };
 template <int NA, int WN, int NWV = NWAVES>
 __global__ void __launch_bounds__(NWV * 64, WgradWide<WN>::OCC)
-wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int accumulate,
+wgrad_batched_kernel(int E, int m_dim, int n_dim, WgradPlan w, int accumulate,
                      float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int WGM = 256, BA = WGM / NA;
@@ -968,8 +1010,9 @@ wgrad_batched_kernel(MbTable tb, int E, int m_dim, int n_dim, WgradPlan w, int a
     typename KL::Acc acc;
     KL::zero(acc);
     const int s0 = w.piece_ptr[e];
-    const WgradPieces<NA> src{tb, (const_i32_ptr)(uintptr_t)(w.piece_mb + s0), (const_i32_ptr)(uintptr_t)(w.piece_row0 + s0),
-                              (const_i32_ptr)(uintptr_t)(w.piece_rows + s0), m_dim, n_dim, m0, n0};
+    const WgradPieces<NA> src{(const_i32_ptr)(uintptr_t)(w.piece_rows + s0),
+                              (const_i32_ptr)(uintptr_t)((NA == 1 ? w.rec_down + (size_t)s0 * kRecDownInts : w.rec_gu + (size_t)s0 * kRecGuInts)),
+                              m_dim, n_dim, m0, n0};
     KL::run_pieces(acc, src, w.piece_ptr[e + 1] - s0, w.exp_slabs[e], lds, tid);
     wgrad_epilogue<KL, NA, BA, NWV>(acc, lds, out0, out1, (size_t)e * m_dim * n_dim, m0, n0, m_dim, n_dim, add, wave, lane);
 }
@@ -1360,7 +1403,7 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
     if (inst_cap > E + G) return RELIBRA_EINVAL;               // an instance is a group: at most G of them
     const WgradPlan w = carve_wgrad(ws, E, G);
     RELIBRA_LAUNCH(RELIBRA_K_WGRAD_ORDER, stream, wgrad_order_kernel<<<1, 256, E * sizeof(int32_t), stream>>>(
-        tb, n_mb, G, inst_cap, n_rows, E, w, err_flag));
+        tb, n_mb, G, inst_cap, n_rows, E, h, hff, w, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     auto grid_of = [&](long long tiles_per_expert) {          // blocks: 8 XCDs x chunks per XCD x tiles per chunk
         const long long chunks = ((long long)E * tiles_per_expert + kWgradChunk - 1) / kWgradChunk;
@@ -1380,18 +1423,18 @@ extern "C" int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs, int n_
     const unsigned g_gu = grid_of((long long)((hff + 127) / 128) * ((h + wn_gu - 1) / wn_gu));        // dWg, dWu: m in h', n in h
     if (wide_down) {
         RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, (wgrad_batched_kernel<1, 256, kWideWaves><<<g_down, kWideWaves * 64, WgradWide<256>::LDS, stream>>>(
-            tb, E, h, hff, w, accumulate, dWd, nullptr)));
+            E, h, hff, w, accumulate, dWd, nullptr)));
     } else {
         RELIBRA_LAUNCH(RELIBRA_K_WGRAD_DOWN, stream, wgrad_batched_kernel<1, 128><<<g_down, THREADS, WgradWide<128>::LDS, stream>>>(
-            tb, E, h, hff, w, accumulate, dWd, nullptr));
+            E, h, hff, w, accumulate, dWd, nullptr));
     }
     RELIBRA_HIP_TRY(launch_check());
     if (wide_gu) {
         RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, (wgrad_batched_kernel<2, 256, kWideWaves><<<g_gu, kWideWaves * 64, WgradWide<256>::LDS, stream>>>(
-            tb, E, hff, h, w, accumulate, dWg, dWu)));
+            E, hff, h, w, accumulate, dWg, dWu)));
     } else {
         RELIBRA_LAUNCH(RELIBRA_K_WGRAD_GATE_UP, stream, wgrad_batched_kernel<2, 128><<<g_gu, THREADS, WgradWide<128>::LDS, stream>>>(
-            tb, E, hff, h, w, accumulate, dWg, dWu));
+            E, hff, h, w, accumulate, dWg, dWu));
     }
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
