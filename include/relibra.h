@@ -299,7 +299,8 @@ int relibra_permute_src(const int32_t *ids_dev, const int32_t *inst_ptr_dev,
  * identical bit for bit.  The weight operand is then read along full cache lines through the
  * transposing LDS reads, which measures a few percent faster; the copies cost one pass over the
  * weights per optimizer step.  Other flag bits: RELIBRA_EINVAL.
- * Limits: h % 64 == 0, hff % 64 == 0, 16-byte aligned tensors.
+ * Limits: h % 64 == 0, hff % 64 == 0, g_end - g_begin <= 8192 (RELIBRA_EUNSUPPORTED beyond), 16-byte
+ *   aligned tensors.
  */
 #define RELIBRA_FWD_TRANSPOSED_WEIGHTS 1
 int relibra_moe_ffn_fwd(const void *Xrows_dev, int n_rows,

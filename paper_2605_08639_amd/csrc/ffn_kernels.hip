@@ -101,6 +101,7 @@ inline Sched carve(void *ws, int n_rows, int Gr, int hff, bool bwd)
 // dX kernels (measured, bands of 8) and about 1 % off their time: the L2 misses are not what
 // bounds them.
 constexpr int kBand = 8;
+constexpr int kMaxSchedGroups = 8192;          // groups of one call (g_end - g_begin)
 
 // One block.  Validates the group tables of [g_begin, g_end) (bad groups become empty and raise
 // the flag), lists the row tiles group by group, and lists the live replica slots.
@@ -109,10 +110,11 @@ sched_kernel(const int32_t *__restrict__ group_offset, const int32_t *__restrict
              const int32_t *__restrict__ group_dw_slot, int g_begin, int Gr, int n_rows, int E, int n_dw_slots,
              Sched s, int32_t *err_flag)
 {
+    extern __shared__ int32_t prefix[];        // [Gr + 1] tile_prefix, kept in LDS for the searches below
     __shared__ int32_t scan[256];
     __shared__ int32_t carry;
     const int tid = threadIdx.x;
-    if (tid == 0) { carry = 0; s.tile_prefix[0] = 0; }
+    if (tid == 0) { carry = 0; s.tile_prefix[0] = 0; prefix[0] = 0; }
     __syncthreads();
     bool bad_any = false;
     for (int base = 0; base < Gr; base += 256) {
@@ -140,7 +142,7 @@ sched_kernel(const int32_t *__restrict__ group_offset, const int32_t *__restrict
             scan[tid] += v;
             __syncthreads();
         }
-        if (i < Gr) s.tile_prefix[i + 1] = carry + scan[tid];
+        if (i < Gr) s.tile_prefix[i + 1] = prefix[i + 1] = carry + scan[tid];
         __syncthreads();
         if (tid == 255) carry += scan[255];
         __syncthreads();
@@ -154,14 +156,14 @@ sched_kernel(const int32_t *__restrict__ group_offset, const int32_t *__restrict
         int lo = 0, hi = Gr;                 // last group whose prefix <= t
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (s.tile_prefix[mid] <= t) lo = mid; else hi = mid;
+            if (prefix[mid] <= t) lo = mid; else hi = mid;
         }
-        const int j = t - s.tile_prefix[lo];
+        const int j = t - prefix[lo];
         s.tile_group[t] = lo;
         s.tile_row0[t] = s.grp_row0[lo] + j * BM;
         s.tile_rows[t] = min(BM, s.grp_rows[lo] - j * BM);
-        const int m = s.tile_prefix[lo + 1] - s.tile_prefix[lo], b0 = j / kBand * kBand;
-        s.tile_band[t] = (s.tile_prefix[lo] + b0) | (min(kBand, m - b0) << 24);
+        const int m = prefix[lo + 1] - prefix[lo], b0 = j / kBand * kBand;
+        s.tile_band[t] = (prefix[lo] + b0) | (min(kBand, m - b0) << 24);
     }
     // live replica slots, in group order (256 groups at a time; a running count in LDS)
     if (tid == 0) carry = 0;
@@ -1043,6 +1045,7 @@ struct FfnArgs {
 inline int check_ffn_args(const FfnArgs &a)
 {
     if (a.n_rows < 0 || a.G < 1 || a.g_begin < 0 || a.g_end > a.G || a.g_begin > a.g_end || a.E < 1) return RELIBRA_EINVAL;
+    if (a.g_end - a.g_begin > kMaxSchedGroups) return RELIBRA_EUNSUPPORTED;   // the schedule kernel keeps a prefix per group in LDS
     if (a.h < 64 || a.hff < 64 || a.h % 64 || a.hff % 64) return RELIBRA_EUNSUPPORTED;
     if ((size_t)a.n_rows * (size_t)(a.h > a.hff ? a.h : a.hff) > ((size_t)1 << 40)) return RELIBRA_EUNSUPPORTED;
     return RELIBRA_OK;
@@ -1150,7 +1153,7 @@ static int ffn_fwd_impl(const void *Xrows, const int32_t *row_tok, int T, int n_
     if (ws_bytes < ffn_ws_bytes(n_rows, Gr, hff, false)) return RELIBRA_EWORKSPACE;
     if (int rc = ensure_lds_limits()) return rc;
     Sched s = carve(ws, n_rows, Gr, hff, false);
-    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, nullptr, g_begin, Gr, n_rows, E, 0, s, err_flag));
+    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, (size_t)(Gr + 1) * sizeof(int32_t), stream>>>(group_offset, group_expert, nullptr, g_begin, Gr, n_rows, E, 0, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     const long long R = max_row_tiles(n_rows, Gr);
     // column tiles: the wide ones where they divide the output
@@ -1250,7 +1253,7 @@ static int ffn_bwd_impl(const void *dYrows, const void *Xrows,
     Sched s = carve(ws, n_rows, Gr, hff, true);
     // the slot table matters only to kernels that write dW or read replica parameters
     const int32_t *slot_table = (defer && !(flags & RELIBRA_BWD_REPLICA_WEIGHTS)) ? nullptr : group_dw_slot;
-    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, 0, stream>>>(group_offset, group_expert, slot_table, g_begin, Gr, n_rows, E,
+    RELIBRA_LAUNCH(RELIBRA_K_SCHED, stream, sched_kernel<<<1, 256, (size_t)(Gr + 1) * sizeof(int32_t), stream>>>(group_offset, group_expert, slot_table, g_begin, Gr, n_rows, E,
                                         n_dw_slots, s, err_flag));
     RELIBRA_HIP_TRY(launch_check());
     const long long R = max_row_tiles(n_rows, Gr);
