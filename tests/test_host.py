@@ -129,6 +129,8 @@ def test_device_entry_points_reject_bad_sizes_before_touching_the_gpu():
                                  ctypes.c_size_t(0), z, z) == rl.EUNSUPPORTED  # h % 64
     assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 5, 3, 8, z, z, z, 128, 256, z, z, z, z, 0, z,
                                  ctypes.c_size_t(0), z, z) == rl.EINVAL        # g_begin > g_end
+    assert L.relibra_moe_ffn_fwd(z, 16, z, z, 9000, 0, 9000, 8, z, z, z, 128, 256, z, z, z, z, 0, z,
+                                 ctypes.c_size_t(0), z, z) == rl.EUNSUPPORTED  # more than 8192 groups in one call
     assert L.relibra_moe_ffn_fwd(z, 16, z, z, 12, 0, 12, 8, z, z, z, 128, 256, z, z, z, z, 2, z,
                                  ctypes.c_size_t(0), z, z) == rl.EINVAL        # unknown flag bit
     assert L.relibra_unpermute_combine(7, z, z, z, z, 4, 2, 128, z, z, z, z, z) == rl.EINVAL
