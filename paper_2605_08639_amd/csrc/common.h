@@ -5,6 +5,9 @@
 
 #include "../../include/relibra.h"
 
+// Assignments per unit of the permutation kernels (one wave each); sizes their count matrix.
+#define RELIBRA_PERM_UNIT 128
+
 #define RELIBRA_HIP_TRY(expr)                      \
     do {                                           \
         hipError_t e_ = (expr);                    \

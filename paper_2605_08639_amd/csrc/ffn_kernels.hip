@@ -1060,7 +1060,7 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     if (T < 0 || k < 1 || E < 1 || G < 1 || (size_t)T * k > 0x7fffffffull) return 0;
     const int N = T * k;
     switch (which) {
-    case RELIBRA_WS_PERMUTE: return round256((size_t)((N + 511) / 512 + 4) * E * sizeof(int32_t));
+    case RELIBRA_WS_PERMUTE: return round256((size_t)((N + RELIBRA_PERM_UNIT - 1) / RELIBRA_PERM_UNIT + 4) * E * sizeof(int32_t));
     case RELIBRA_WS_FFN_FWD: return ffn_ws_bytes(N, G, hff, false);
     case RELIBRA_WS_FFN_BWD: return ffn_ws_bytes(N, G, hff, true);
     case RELIBRA_WS_WGRAD_BATCHED: return round256(wgrad_plan_ints(E, G) * sizeof(int32_t));

@@ -9,7 +9,8 @@ namespace relibra {
 constexpr int kMaxExperts = 4096;
 constexpr int kHistThreads = 256;
 constexpr int kHistChunk = 8192;     // assignments per histogram block
-constexpr int kUnit = 512;           // assignments per permutation unit (one wave)
+constexpr int kUnit = RELIBRA_PERM_UNIT;   // assignments per permutation unit (one wave): short units, many waves -
+                                         // the rank kernel is a chain of dependent table reads per round of 64
 constexpr int kPermThreads = 256;    // 4 waves = 4 units per block
 
 // ---------------------------------------------------------------- fill
@@ -65,7 +66,7 @@ hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int blocks_per_m
 
 // ---------------------------------------------------------------- permutation indices
 // The stable partition is a counting sort over experts in three passes:
-//   1. every wave counts its 512-assignment unit per expert        -> unit_cnt[unit][e]
+//   1. every wave counts its unit of assignments per expert        -> unit_cnt[unit][e]
 //   2. an exclusive scan over units, per expert                    -> unit_cnt[unit][e] = base
 //   3. every wave walks its unit in order, 64 assignments at a time; a ballot-built mask of
 //      the lanes holding the same expert gives each lane its ordinal inside the step, an LDS
