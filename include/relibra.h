@@ -157,6 +157,14 @@ typedef struct relibra_cost_model {
 } relibra_cost_model;
 
 /*
+ * Fill the model from the quantities of Eq. 4-5: h, hff = h', F = effective FLOP/s of the expert
+ * GEMMs, B_intra / B_inter = bytes per second of the intra-node link and of RDMA, bytes_per_value
+ * = 2 for bf16 activations.  RELIBRA_EINVAL on a non-positive argument or EP % ranks_per_node != 0.
+ */
+int relibra_cost_model_init(relibra_cost_model *model_host, int EP, int ranks_per_node, int h, int hff,
+                            double F, double B_intra, double B_inter, int bytes_per_value);
+
+/*
  * Evaluate the model for one placement (Eq. 1-6).  All pointers HOST.
  *   x_host      [EP, E] int64 in   tokens on source rank j routed to expert e (token t of a
  *                                  micro-batch sits on rank t / (T/EP): relibra_route_hist on
@@ -186,6 +194,22 @@ int relibra_moe_time(const int64_t *x_host, int E, const relibra_cost_model *mod
 int relibra_reorder_sa(const int64_t *x_host, int E, const relibra_cost_model *model,
                        double beta, double gamma, double eps, int n_seeds, uint64_t seed,
                        int32_t *expert_rank_out, double *stats5);
+
+/*
+ * One seed's run of Algorithm 1 (generator started at `seed`: what relibra_reorder_sa runs for seed
+ * index 0) with its trajectory written out, for checking the acceptance rule, the cooling and the
+ * order of the random draws step by step.  All pointers HOST.
+ *   moves_out [trace_cap, 3] int32: e_a, e_b, accepted (0/1) of the first trace_cap iterations
+ *   vals_out  [trace_cap, 3] double: u, the smoothed objective T' of the swapped state, theta
+ *   start_rank_out [E]: the greedy-LPT start; expert_rank_out [E]: the run's best placement
+ *   stats2 [2]: the start's exact T_MoE (every time is divided by it before smoothing), its
+ *   smoothed objective (= the first theta)
+ * Returns the number of iterations (>= 0) or a negative status.
+ */
+long long relibra_reorder_sa_trace(const int64_t *x_host, int E, const relibra_cost_model *model,
+                                   double beta, double gamma, double eps, uint64_t seed,
+                                   int trace_cap, int32_t *moves_out, double *vals_out,
+                                   int32_t *start_rank_out, int32_t *expert_rank_out, double *stats2);
 
 /*
  * Token permutation of one micro-batch (Section 5.2, token splitting; the local half of the

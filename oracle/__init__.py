@@ -284,6 +284,33 @@ def permute_src(ids, E, EP, inst_ptr, inst_group, group_offset, y):
     return row_of, src_of
 
 
+def splitmix64(seed, n):
+    """First n outputs of the annealing's generator started at state `seed` (uint64)."""
+    out = np.empty(n, np.uint64)
+    lib().oracle_splitmix64(C.c_uint64(seed), int(n), _p(out))
+    return out
+
+
+def reorder_sa_trace(x, rpn, model, beta=20.0, gamma=0.999, eps=1e-3, seed=0, cap=64):
+    """One seed of Algorithm 1 with its trajectory: dict(start, rank, t_ref, smooth_start, iterations,
+    moves [n,3] = (e_a, e_b, accepted), vals [n,3] = (u, T', theta)) for the first n = min(cap, iterations) steps."""
+    x = _i64(x)
+    EP, E = x.shape
+    model = np.ascontiguousarray(model, dtype=np.float64)
+    moves = np.zeros((cap, 3), np.int32)
+    vals = np.zeros((cap, 3), np.float64)
+    start, rank = np.empty(E, np.int32), np.empty(E, np.int32)
+    st = np.empty(2, np.float64)
+    fn = lib().oracle_reorder_sa_trace
+    fn.restype = C.c_longlong
+    it = fn(_p(x), E, EP, int(rpn), _p(model), C.c_double(beta), C.c_double(gamma), C.c_double(eps), C.c_uint64(seed),
+            int(cap), _p(moves), _p(vals), _p(start), _p(rank), _p(st))
+    if it < 0:
+        raise ValueError("oracle_reorder_sa_trace: bad arguments")
+    n = min(int(it), cap)
+    return dict(start=start, rank=rank, t_ref=st[0], smooth_start=st[1], iterations=int(it), moves=moves[:n], vals=vals[:n])
+
+
 def reorder_sa(x, rpn, model, beta=20.0, gamma=0.999, eps=1e-3, n_seeds=8, seed=0):
     """Algorithm 1 -> (rank_of [E], dict(T_start, T, smooth_start, smooth, iterations))."""
     x = _i64(x)

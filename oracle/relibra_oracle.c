@@ -7,11 +7,12 @@
  * everything that is floating point (inputs are bf16 bit patterns, widened exactly).
  * Each function names the passage of the paper it follows.
  *
- * Parity pins live in tests/test_oracle_*.py.  Pinned: everything except
- * oracle_reorder_sa, the randomized annealing of Algorithm 1: PARITY UNPINNED for its
- * trajectory (cooling rate, threshold, seed set and random generator are not published);
- * its cost model, its smoothed objective and its invariants (never worse than its start
- * in the smoothed objective, capacity kept) are pinned.
+ * Parity pins live in tests/test_oracle_*.py; every function is pinned.  The randomized
+ * annealing of Algorithm 1 (oracle_reorder_sa) depends on constants the paper does not
+ * publish (cooling rate, threshold, seed set, random generator): they are arguments, the
+ * generator is splitmix64 (pinned against its published outputs), and the acceptance
+ * rule, cooling and draw order are pinned by a hand-worked three-step run; its cost
+ * model, smoothed objective and invariants are pinned separately.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -302,6 +303,58 @@ static uint64_t sm64_next(uint64_t *state)
 /* iteration in the order e_a, e_b, u; seed s starts its generator at           */
 /* seed + s * 0xD1342543DE82EF95.  stats[0] = exact T of the start, [1] = exact */
 /* T of the result, [2] = smoothed start, [3] = smoothed result, [4] = iterations per seed. */
+/* first n outputs of the generator started at state `seed` (for the pin against the    */
+/* published test vectors)                                                             */
+void oracle_splitmix64(uint64_t seed, int n, uint64_t *out)
+{
+    for (int i = 0; i < n; ++i) out[i] = sm64_next(&seed);
+}
+
+/* One seed of Algorithm 1 from `start` (generator state rng).  best receives the seed's */
+/* best placement, *T_best_out its smoothed objective; returns the iterations.  With    */
+/* trace_cap > 0 the first trace_cap iterations are recorded: moves[i] = {e_a, e_b,      */
+/* accepted (0/1)}, vals[i] = {u, T' (smoothed objective of the swapped state), theta}. */
+static i64 sa_one_seed(const i64 *x, int E, int EP, int rpn, const double *model, double beta,
+                       double t_ref, double gamma, double eps, uint64_t rng,
+                       const int32_t *start, double smooth0, int32_t *cur, int32_t *best,
+                       int trace_cap, int32_t *moves, double *vals)
+{
+    double o[4];
+    memcpy(cur, start, sizeof(int32_t) * E);
+    memcpy(best, start, sizeof(int32_t) * E);
+    double T = smooth0, T_best = smooth0, theta = smooth0;
+    i64 iters = 0;
+    while (theta > eps) {
+        int ea = (int)(sm64_next(&rng) % (uint64_t)E);
+        int eb = (int)(sm64_next(&rng) % (uint64_t)E);
+        double u = (double)(sm64_next(&rng) >> 11) * (1.0 / 9007199254740992.0);
+        int32_t ra = cur[ea], rb = cur[eb];
+        cur[ea] = rb;
+        cur[eb] = ra;
+        oracle_moe_time(x, E, EP, rpn, cur, model, beta, t_ref, o);
+        double Tn = o[3];
+        int accepted = 0;
+        if (Tn < T || u < exp(-(Tn - T) / theta)) {
+            T = Tn;
+            accepted = 1;
+        } else {
+            cur[ea] = ra;
+            cur[eb] = rb;
+        }
+        if (T < T_best) {
+            T_best = T;
+            memcpy(best, cur, sizeof(int32_t) * E);
+        }
+        if (iters < trace_cap) {
+            moves[3 * iters] = ea; moves[3 * iters + 1] = eb; moves[3 * iters + 2] = accepted;
+            vals[3 * iters] = u; vals[3 * iters + 1] = Tn; vals[3 * iters + 2] = theta;
+        }
+        theta *= gamma;
+        ++iters;
+    }
+    return iters;
+}
+
 int oracle_reorder_sa(const i64 *x, int E, int EP, int rpn, const double *model,
                       double beta, double gamma, double eps, int n_seeds, uint64_t seed,
                       int32_t *rank_out, double *stats)
@@ -322,33 +375,8 @@ int oracle_reorder_sa(const i64 *x, int E, int EP, int rpn, const double *model,
     double best_exact = 0.0, best_smooth = 0.0;
     i64 iters = 0;
     for (int s = 0; s < n_seeds; ++s) {
-        uint64_t rng = seed + (uint64_t)s * 0xD1342543DE82EF95ull;
-        memcpy(cur, start, sizeof(int32_t) * E);
-        memcpy(best, start, sizeof(int32_t) * E);
-        double T = smooth0, T_best = smooth0, theta = smooth0;
-        iters = 0;
-        while (theta > eps) {
-            int ea = (int)(sm64_next(&rng) % (uint64_t)E);
-            int eb = (int)(sm64_next(&rng) % (uint64_t)E);
-            double u = (double)(sm64_next(&rng) >> 11) * (1.0 / 9007199254740992.0);
-            int32_t ra = cur[ea], rb = cur[eb];
-            cur[ea] = rb;
-            cur[eb] = ra;
-            oracle_moe_time(x, E, EP, rpn, cur, model, beta, t_ref, o);
-            double Tn = o[3];
-            if (Tn < T || u < exp(-(Tn - T) / theta)) {
-                T = Tn;
-            } else {
-                cur[ea] = ra;
-                cur[eb] = rb;
-            }
-            if (T < T_best) {
-                T_best = T;
-                memcpy(best, cur, sizeof(int32_t) * E);
-            }
-            theta *= gamma;
-            ++iters;
-        }
+        iters = sa_one_seed(x, E, EP, rpn, model, beta, t_ref, gamma, eps, seed + (uint64_t)s * 0xD1342543DE82EF95ull,
+                            start, smooth0, cur, best, 0, NULL, NULL);
         oracle_moe_time(x, E, EP, rpn, best, model, beta, t_ref, o);
         if (s == 0 || o[0] < best_exact) {
             best_exact = o[0];
@@ -366,6 +394,34 @@ int oracle_reorder_sa(const i64 *x, int E, int EP, int rpn, const double *model,
     free(cur);
     free(best);
     return 0;
+}
+
+/* The first seed's run of oracle_reorder_sa with its trajectory written out (see    */
+/* sa_one_seed); rank_out = that seed's best placement, start_out = the LPT start,   */
+/* stats[0] = t_ref (the start's exact T_MoE), stats[1] = smoothed start.  Returns   */
+/* the iterations, or -1.                                                           */
+long long oracle_reorder_sa_trace(const i64 *x, int E, int EP, int rpn, const double *model,
+                                  double beta, double gamma, double eps, uint64_t seed,
+                                  int trace_cap, int32_t *moves, double *vals,
+                                  int32_t *start_out, int32_t *rank_out, double *stats)
+{
+    if (E % EP || !(gamma > 0.0 && gamma < 1.0) || !(eps > 0.0)) return -1;
+    i64 *l = (i64 *)calloc(E, sizeof(i64));
+    for (int j = 0; j < EP; ++j)
+        for (int e = 0; e < E; ++e) l[e] += x[(size_t)j * E + e];
+    int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * E);
+    oracle_lpt(l, E, EP, start_out);
+    double o[4];
+    oracle_moe_time(x, E, EP, rpn, start_out, model, beta, 1.0, o);
+    const double t_ref = o[0] > 0.0 ? o[0] : 1.0;
+    oracle_moe_time(x, E, EP, rpn, start_out, model, beta, t_ref, o);
+    stats[0] = t_ref;
+    stats[1] = o[3];
+    i64 iters = sa_one_seed(x, E, EP, rpn, model, beta, t_ref, gamma, eps, seed, start_out, o[3], cur, rank_out,
+                            trace_cap, moves, vals);
+    free(l);
+    free(cur);
+    return iters;
 }
 
 /* ------------------------------------------------------------------------- */

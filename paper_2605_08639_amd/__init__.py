@@ -26,6 +26,7 @@ MAX_WGRAD_MB = 48
 COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
+           "relibra_cost_model_init", "relibra_reorder_sa_trace",
            "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src", "relibra_plan_timed",
            "relibra_permute", "relibra_row_tokens", "relibra_row_gates", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd_gated",
            "relibra_moe_ffn_bwd_gated", "relibra_moe_ffn_fwd",
@@ -197,8 +198,11 @@ class CostModel(C.Structure):
 
 
 def cost_model(EP, ranks_per_node, h, hff, F, B_intra, B_inter, bytes_per_value=2):
-    return CostModel(int(EP), int(ranks_per_node), 6.0 * h * hff / F, bytes_per_value * h / B_intra,
-                     bytes_per_value * h / B_inter)
+    m = CostModel()
+    rc = lib().relibra_cost_model_init(C.byref(m), int(EP), int(ranks_per_node), int(h), int(hff), C.c_double(F),
+                                       C.c_double(B_intra), C.c_double(B_inter), int(bytes_per_value))
+    _check("relibra_cost_model_init", rc)
+    return m
 
 
 def relibra_route_hist_src(ids, E, EP, err_flag=None):
@@ -238,6 +242,24 @@ def relibra_reorder_sa(x_host, model, beta=20.0, gamma=0.9995, eps=1e-4, n_seeds
                                   int(n_seeds), C.c_uint64(seed), _hp(rank), _hp(st))
     _check("relibra_reorder_sa", rc)
     return rank, dict(T_start=st[0], T=st[1], smooth_start=st[2], smooth=st[3], iterations=int(st[4]))
+
+
+def relibra_reorder_sa_trace(x_host, model, beta=20.0, gamma=0.9995, eps=1e-4, seed=0, cap=64):
+    """One seed of Algorithm 1 with its trajectory -> dict(start, rank, t_ref, smooth_start, iterations,
+    moves [n,3] = (e_a, e_b, accepted), vals [n,3] = (u, T', theta))."""
+    x_host = np.ascontiguousarray(x_host, dtype=np.int64)
+    EP, E = x_host.shape
+    assert EP == model.EP
+    moves, vals = np.zeros((cap, 3), np.int32), np.zeros((cap, 3), np.float64)
+    start, rank, st = np.empty(E, np.int32), np.empty(E, np.int32), np.empty(2, np.float64)
+    fn = lib().relibra_reorder_sa_trace
+    fn.restype = C.c_longlong
+    it = fn(_hp(x_host), E, C.byref(model), C.c_double(beta), C.c_double(gamma), C.c_double(eps), C.c_uint64(seed),
+            int(cap), _hp(moves), _hp(vals), _hp(start), _hp(rank), _hp(st))
+    if it < 0:
+        raise RelibraError("relibra_reorder_sa_trace", int(it))
+    n = min(int(it), cap)
+    return dict(start=start, rank=rank, t_ref=st[0], smooth_start=st[1], iterations=int(it), moves=moves[:n], vals=vals[:n])
 
 
 def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,
@@ -434,7 +456,8 @@ def relibra_moe_ffn_bwd_gated(dOut, row_tok, row_gate, Gt, U, group_offset, grou
     rc = lib().relibra_moe_ffn_bwd_gated(_dp(dOut, torch.bfloat16), T, _dp(row_tok, torch.int32), _dp(row_gate, torch.float32),
                                          _dp(src_of, torch.int32), _dp(Gt, torch.bfloat16), _dp(U, torch.bfloat16), n_rows,
                                          _dp(group_offset, torch.int32), _dp(group_expert, torch.int32),
-                                         _dp(group_dw_slot, torch.int32), G, g_begin, g_end, E, E,
+                                         _dp(group_dw_slot, torch.int32), G, g_begin, g_end, E,
+                                         Wg.shape[0] if flags & BWD_REPLICA_WEIGHTS else E,   # parameter blocks addressable by slot
                                          _dp(Wg, torch.bfloat16), _dp(Wu, torch.bfloat16), _dp(Wd, torch.bfloat16), h, hff,
                                          _dp(dXrows), _dp(dgate, torch.float32), int(flags),
                                          _dp(workspace), C.c_size_t(workspace.numel()),
@@ -491,7 +514,8 @@ def relibra_moe_ffn_bwd(dYrows, Xrows, Gt, U, A, group_offset, group_expert, gro
     if err_flag is None:
         err_flag = new_err_flag(dev)
     if flags & BWD_DEFER_WGRAD:
-        n_slots = E if dWg is None else dWg.shape[0]
+        # no dW is written: the slot table only selects parameter blocks (replica slots included)
+        n_slots = dWg.shape[0] if dWg is not None else (Wg.shape[0] if flags & BWD_REPLICA_WEIGHTS else E)
     else:
         n_slots = dWg.shape[0]
         assert dWu.shape[0] == n_slots and dWd.shape[0] == n_slots

@@ -867,24 +867,25 @@ wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
     bool bad = false;
     if (tid == 0) { carry = 0; w.piece_ptr[0] = 0; }
     __syncthreads();
+    // The piece arrays hold S entries: enough for every instance of every micro-batch of a well-formed
+    // (monotone) instance table.  A corrupted table whose ranges overlap could list more; pieces
+    // beyond S are left out (and flagged), so that nothing is written past the arrays.
+    const int S = kMaxWgradMb * (E + G);
     for (int base = 0; base < E; base += 256) {
         const int e = base + tid;
         int pieces = 0;
         if (e < E) {
-            long long total = 0, slabs = 0;
             for (int mb = 0; mb < n_mb; ++mb) {
                 int p0, p1;
                 if (!inst_range(tb, mb, e, inst_cap, p0, p1)) bad = true;
                 for (int p = p0; p < p1; ++p) {
                     int row0, rows;
                     if (!inst_rows(tb, mb, p, G, n_rows, row0, rows)) bad = true;
-                    if (rows > 0) { ++pieces; total += rows; slabs += (rows + BK - 1) / BK; }
+                    if (rows > 0) ++pieces;
                 }
             }
-            rows_of[e] = (int32_t)(total > 0x7fffffffLL ? 0x7fffffffLL : total);
-            w.exp_rows[e] = rows_of[e];
-            w.exp_slabs[e] = (int32_t)(slabs > 0x7fffffffLL ? 0x7fffffffLL : slabs);
         }
+        pieces = min(pieces, S + 1);                 // saturate: the sums below stay inside an int
         scan[tid] = pieces;
         __syncthreads();
         for (int off = 1; off < 256; off <<= 1) {
@@ -894,15 +895,20 @@ wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
             __syncthreads();
         }
         if (e < E) {
-            int at = carry + scan[tid] - pieces;
-            w.piece_ptr[e + 1] = carry + scan[tid];
-            for (int mb = 0; mb < n_mb; ++mb) {
+            int at = min(carry + scan[tid] - pieces, S);
+            const int end = min(carry + scan[tid], S);
+            if (carry + scan[tid] > S) bad = true;
+            w.piece_ptr[e + 1] = end;
+            long long total = 0, slabs = 0;
+            for (int mb = 0; mb < n_mb && at < end; ++mb) {
                 int p0, p1;
                 inst_range(tb, mb, e, inst_cap, p0, p1);
-                for (int p = p0; p < p1; ++p) {
+                for (int p = p0; p < p1 && at < end; ++p) {
                     int row0, rows;
                     inst_rows(tb, mb, p, G, n_rows, row0, rows);
                     if (rows > 0) {
+                        total += rows;
+                        slabs += (rows + BK - 1) / BK;
                         w.piece_mb[at] = mb; w.piece_row0[at] = row0; w.piece_rows[at] = rows;
                         const bool dy_tok = (tb.dy_tokens >> mb) & 1, x_tok = tb.rtok[mb] != nullptr;
                         const unsigned long long table = (unsigned long long)(uintptr_t)(tb.rtok[mb] + row0);
@@ -926,9 +932,12 @@ wgrad_order_kernel(MbTable tb, int n_mb, int G, int inst_cap, int n_rows, int E,
                     }
                 }
             }
+            rows_of[e] = (int32_t)(total > 0x7fffffffLL ? 0x7fffffffLL : total);
+            w.exp_rows[e] = rows_of[e];
+            w.exp_slabs[e] = (int32_t)(slabs > 0x7fffffffLL ? 0x7fffffffLL : slabs);
         }
         __syncthreads();
-        if (tid == 255) carry += scan[255];
+        if (tid == 255) carry = min(carry + scan[255], S + 1);
         __syncthreads();
     }
     if (bad) atomicOr(err_flag, RELIBRA_ERR_GROUP_TABLE);

@@ -145,8 +145,15 @@ struct SeedResult {
     i64 iterations = 0;
 };
 
+// trace (optional): the first trace_cap iterations as moves[i] = {e_a, e_b, accepted}, vals[i] = {u, T', theta}
+struct Trace {
+    int cap = 0;
+    int32_t *moves = nullptr;
+    double *vals = nullptr;
+};
+
 SeedResult anneal(const Problem &P, const std::vector<int> &start, double smooth_start, double gamma, double eps,
-                  uint64_t rng_state)
+                  uint64_t rng_state, const Trace &trace = Trace{})
 {
     SplitMix64 rng{rng_state};
     std::vector<int> cur = start;
@@ -166,7 +173,14 @@ SeedResult anneal(const Problem &P, const std::vector<int> &start, double smooth
             P.place(L, eb, rb, -1); P.place(L, eb, ra, +1);
             Tn = P.smooth(L, zc, zm);
         }
-        if (Tn < T || u < std::exp(-(Tn - T) / theta)) {
+        const bool accept = Tn < T || u < std::exp(-(Tn - T) / theta);
+        if (res.iterations < trace.cap) {
+            int32_t *mv = trace.moves + 3 * res.iterations;
+            double *vl = trace.vals + 3 * res.iterations;
+            mv[0] = ea; mv[1] = eb; mv[2] = accept ? 1 : 0;
+            vl[0] = u; vl[1] = Tn; vl[2] = theta;
+        }
+        if (accept) {
             T = Tn;
             cur[ea] = rb;
             cur[eb] = ra;
@@ -230,6 +244,67 @@ extern "C" int relibra_moe_time(const int64_t *x_host, int E, const relibra_cost
     return RELIBRA_OK;
 }
 
+extern "C" int relibra_cost_model_init(relibra_cost_model *model, int EP, int ranks_per_node, int h, int hff,
+                                       double F, double B_intra, double B_inter, int bytes_per_value)
+{
+    if (!model || EP < 1 || ranks_per_node < 1 || EP % ranks_per_node || h < 1 || hff < 1 || bytes_per_value < 1 ||
+        !(F > 0.0) || !(B_intra > 0.0) || !(B_inter > 0.0))
+        return RELIBRA_EINVAL;
+    model->EP = EP;
+    model->ranks_per_node = ranks_per_node;
+    model->sec_per_token_comp = 6.0 * (double)h * (double)hff / F;                 // three GEMMs of 2 h h' flops (Eq. 4)
+    model->sec_per_token_intra = (double)bytes_per_value * (double)h / B_intra;    // one token's hidden vector (Eq. 5)
+    model->sec_per_token_inter = (double)bytes_per_value * (double)h / B_inter;
+    return RELIBRA_OK;
+}
+
+namespace {
+
+// Greedy-LPT start of Algorithm 1 and the normalisation it fixes: P.t_ref = the start's exact T_MoE.
+struct SaStart {
+    std::vector<int> rank_of;
+    double exact_T, smooth_T;
+};
+SaStart sa_start(Problem &P)
+{
+    std::vector<i64> load(P.E, 0);
+    for (int j = 0; j < P.EP; ++j)
+        for (int e = 0; e < P.E; ++e) load[e] += P.x[(size_t)j * P.E + e];
+    SaStart st{lpt(load, P.EP), 0.0, 0.0};
+    P.t_ref = 1.0;
+    const Loads L0 = P.loads_of(st.rank_of);
+    double ex0[3];
+    P.exact(L0, ex0);
+    st.exact_T = ex0[0];
+    P.t_ref = ex0[0] > 0.0 ? ex0[0] : 1.0;
+    std::vector<double> zc(P.EP), zm(P.EP);
+    st.smooth_T = P.smooth(L0, zc, zm);
+    return st;
+}
+
+}  // namespace
+
+extern "C" long long relibra_reorder_sa_trace(const int64_t *x_host, int E, const relibra_cost_model *model,
+                                              double beta, double gamma, double eps, uint64_t seed,
+                                              int trace_cap, int32_t *moves_out, double *vals_out,
+                                              int32_t *start_rank_out, int32_t *expert_rank_out, double *stats2)
+{
+    if (int rc = check_model(x_host, E, model)) return rc;
+    if (!expert_rank_out || !start_rank_out || !stats2 || !(beta > 0.0) || !(gamma > 0.0 && gamma < 1.0) || !(eps > 0.0) ||
+        trace_cap < 0 || (trace_cap > 0 && (!moves_out || !vals_out)))
+        return RELIBRA_EINVAL;
+    Problem P = make_problem(x_host, E, model, beta, 1.0);
+    const SaStart st = sa_start(P);
+    const SeedResult res = anneal(P, st.rank_of, st.smooth_T, gamma, eps, seed, Trace{trace_cap, moves_out, vals_out});
+    for (int e = 0; e < E; ++e) {
+        start_rank_out[e] = st.rank_of[e];
+        expert_rank_out[e] = res.rank_of[e];
+    }
+    stats2[0] = P.t_ref;
+    stats2[1] = st.smooth_T;
+    return res.iterations;
+}
+
 extern "C" int relibra_reorder_sa(const int64_t *x_host, int E, const relibra_cost_model *model,
                                   double beta, double gamma, double eps, int n_seeds, uint64_t seed,
                                   int32_t *expert_rank_out, double *stats5)
@@ -239,18 +314,12 @@ extern "C" int relibra_reorder_sa(const int64_t *x_host, int E, const relibra_co
         n_seeds < 1 || n_seeds > 4096)
         return RELIBRA_EINVAL;
     const int EP = model->EP;
-    std::vector<i64> load(E, 0);
-    for (int j = 0; j < EP; ++j)
-        for (int e = 0; e < E; ++e) load[e] += x_host[(size_t)j * E + e];
-    const std::vector<int> start = lpt(load, EP);
-
     Problem P = make_problem(x_host, E, model, beta, 1.0);
-    const Loads L0 = P.loads_of(start);
-    double ex0[3];
-    P.exact(L0, ex0);
-    P.t_ref = ex0[0] > 0.0 ? ex0[0] : 1.0;
-    std::vector<double> zc(EP), zm(EP);
-    const double smooth0 = P.smooth(L0, zc, zm);
+    const SaStart st0 = sa_start(P);
+    const std::vector<int> &start = st0.rank_of;
+    const double ex0[1] = {st0.exact_T};
+    const double smooth0 = st0.smooth_T;
+    (void)EP;
 
     std::vector<SeedResult> results(n_seeds);
     unsigned hw = std::thread::hardware_concurrency();

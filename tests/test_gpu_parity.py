@@ -154,7 +154,13 @@ def test_source_aware_permute_bit_exact(kw):
     row_of, _, _ = rl.relibra_permute_src(
         torch.from_numpy(ids[-1]).to(DEV), dev_i32(ptr), dev_i32(grp), dev_i32(off), cfg.EP,
         dev_i32(tabs["src_first"]), dev_i32(bad), dev_i32(tabs["inst_src_base"]), None, cfg.E, cfg.G, err_flag=err)
-    assert (row_of >= 0).all().item() or err.item() & rl.ERR_PLAN_COVER
+    # one token of source j fewer than routed: exactly the source's last assignment of that expert has no row
+    e_bad = int(np.searchsorted(np.asarray(ptr), i, side="right") - 1)
+    tps = cfg.T // cfg.EP
+    flat = ids[-1].reshape(-1)
+    a_of = np.flatnonzero((flat == e_bad) & (np.arange(flat.size) // cfg.k // tps == j))
+    assert err.item() == rl.ERR_PLAN_COVER
+    assert np.array_equal(np.flatnonzero(row_of.cpu().numpy() < 0), a_of[-1:])
 
 
 def test_source_aware_permute_one_token_per_source():
@@ -480,6 +486,26 @@ def test_replica_push_fills_slots_and_ffn_reads_them():
             outs.append((Y, dXrows, dW[0][:cfg.E], dW[1][:cfg.E], dW[2][:cfg.E]))
         for a, b in zip(*outs):
             assert torch.equal(a, b)
+        # the same through the deferred and the gate-fused backward (no dW array: the slot table only
+        # selects parameter blocks, and the wrapper must size it by the parameter arrays)
+        row_tok = rl.relibra_row_tokens(src_of, cfg.k, cfg.T)
+        row_gate = rl.relibra_row_gates(src_of, t(gates[mb]))
+        Gt, U, A, Y = rl.relibra_moe_ffn_fwd(Xrows, tabs["group_offset"], tabs["group_expert"], *home_d)
+        dY = torch.randn(Y.shape, generator=torch.Generator().manual_seed(100 + mb)).to(torch.bfloat16).to(DEV)
+        got = []
+        for use_slots in (False, True):
+            err = rl.new_err_flag()
+            W3 = big_d if use_slots else home_d
+            fl = rl.BWD_REPLICA_WEIGHTS if use_slots else 0
+            dXd = rl.relibra_moe_ffn_bwd(dY, None, Gt, U, A, tabs["group_offset"], tabs["group_expert"], tabs["group_dw_slot"],
+                                         *W3, None, None, None, err_flag=err, E=cfg.E, flags=fl | rl.BWD_DEFER_WGRAD)
+            dXg, dgate = rl.relibra_moe_ffn_bwd_gated(dOut.to(DEV), row_tok, row_gate, Gt, U, tabs["group_offset"],
+                                                     tabs["group_expert"], tabs["group_dw_slot"], *W3, src_of=src_of,
+                                                     err_flag=err, E=cfg.E, flags=fl)
+            assert err.item() == 0
+            got.append((dXd, dXg, dgate))
+        for a, b in zip(*got):
+            assert torch.equal(a, b)
 
 
 def test_replica_push_flags_bad_table_and_leaves_empty_slots():
@@ -569,6 +595,14 @@ def test_batched_weight_gradients_match_oracle_and_per_microbatch_path():
     bad["inst_group"][0] = cfg.G + 5
     err2 = rl.relibra_moe_ffn_wgrad_batched([kept[0], bad, kept[2]], cfg.E, *dW_b)
     assert err2.item() == rl.ERR_GROUP_TABLE
+    # an instance table that is not monotone (ranges of different experts overlap) lists more pieces than
+    # a well-formed one can: the surplus is dropped and flagged, nothing is written past the piece arrays
+    cap = kept[0]["inst_group"].shape[0]
+    zig = dict(kept[0])
+    zig["inst_ptr"] = dev_i32([0 if e % 2 == 0 else cap for e in range(cfg.E + 1)])
+    err3 = rl.relibra_moe_ffn_wgrad_batched([zig] * rl.MAX_WGRAD_MB, cfg.E, *dW_b)
+    torch.cuda.synchronize()
+    assert err3.item() == rl.ERR_GROUP_TABLE
 
 
 # ------------------------------------------------------------------ transposed weights for the data gradients

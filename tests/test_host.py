@@ -198,26 +198,59 @@ def test_moe_time_equals_oracle(EP, rpn, E):
             assert got[key] == pytest.approx(want[key], rel=1e-12), key
 
 
-def test_reorder_sa_matches_oracle_in_quality():
+def test_reorder_sa_hand_worked_trajectory():
+    """The library's Algorithm 1 on the hand-worked instance of tests/test_oracle_comm.py: draws,
+    accept/reject sequence, objective values, cooling and final placement."""
+    from test_oracle_comm import SA_HAND as hw, check_sa_hand_trace
+    m = rl.CostModel(2, 2, 1.0, 1.0, 1.0)
+    tr = rl.relibra_reorder_sa_trace(np.array(hw["x"]), m, gamma=hw["gamma"], eps=hw["eps"], seed=hw["seed"], cap=8)
+    check_sa_hand_trace(tr)
+    rank, st = rl.relibra_reorder_sa(np.array(hw["x"]), m, gamma=hw["gamma"], eps=hw["eps"], n_seeds=1, seed=hw["seed"])
+    assert rank.tolist() == hw["final"] and st["iterations"] == 3 and st["T_start"] == 22.0 and st["T"] == 18.0
+
+
+def test_reorder_sa_equals_oracle():
     """Algorithm 1 in the library (incremental O(|G|) state update, one thread per seed) against the
-    oracle (objective recomputed from the definition at every step).  The trajectory depends on
-    unpublished constants, so the bar is quality: same start, capacity kept, never worse than the
-    start in the smoothed objective, final exact T_MoE within 2 % of the oracle's.  (With the
-    same generator and arithmetic the two usually agree exactly; that is not required.)"""
+    oracle (objective recomputed from the definition at every step): same generator, same rule,
+    so the same trajectory (every move and accept/reject decision of the first seed; objective
+    values to rounding) and the same final placement."""
     for seed, (E, EP, rpn) in enumerate([(32, 8, 4), (16, 4, 2), (64, 8, 8)]):
         x = _skewed_sources(seed, E, EP)
         m_or = oracle.cost_model(2048, 768, 5e14, 1.0e12, 5e10)
         m_lib = rl.cost_model(EP, rpn, 2048, 768, 5e14, 1.0e12, 5e10)
+        assert [m_lib.sec_per_token_comp, m_lib.sec_per_token_intra, m_lib.sec_per_token_inter] == pytest.approx(m_or.tolist(), rel=1e-15)
+        t_or = oracle.reorder_sa_trace(x, rpn, m_or, gamma=0.999, eps=1e-3, seed=11, cap=4096)
+        t_lib = rl.relibra_reorder_sa_trace(x, m_lib, gamma=0.999, eps=1e-3, seed=11, cap=4096)
+        assert t_lib["iterations"] == t_or["iterations"] and len(t_or["moves"]) == 4096
+        assert np.array_equal(t_lib["moves"], t_or["moves"])
+        assert np.array_equal(t_lib["vals"][:, 0], t_or["vals"][:, 0])
+        assert np.allclose(t_lib["vals"], t_or["vals"], rtol=1e-10, atol=0)
+        assert np.array_equal(t_lib["start"], t_or["start"]) and np.array_equal(t_lib["rank"], t_or["rank"])
+        assert 0 < t_or["moves"][:, 2].sum() < 4096            # both outcomes occur
         r_or, s_or = oracle.reorder_sa(x, rpn, m_or, gamma=0.999, eps=1e-3, n_seeds=4, seed=11)
         r_lib, s_lib = rl.relibra_reorder_sa(x, m_lib, gamma=0.999, eps=1e-3, n_seeds=4, seed=11)
+        assert np.array_equal(r_lib, r_or)
         assert sorted(np.bincount(r_lib, minlength=EP).tolist()) == [E // EP] * EP
         assert s_lib["T_start"] == pytest.approx(s_or["T_start"], rel=1e-12)
         assert s_lib["smooth"] <= s_lib["smooth_start"]
         assert s_lib["iterations"] == s_or["iterations"]
-        assert s_lib["T"] == pytest.approx(oracle.moe_time(x, r_lib, rpn, m_or)["T"], rel=1e-12)
-        assert abs(s_lib["T"] - s_or["T"]) <= 0.02 * s_or["T"]
+        assert s_lib["T"] == pytest.approx(s_or["T"], rel=1e-12)
         again, s2 = rl.relibra_reorder_sa(x, m_lib, gamma=0.999, eps=1e-3, n_seeds=4, seed=11)
         assert np.array_equal(again, r_lib) and s2 == s_lib
+
+
+def test_cost_model_init_follows_eq4_eq5():
+    """6hh'/F seconds of computation per token (three GEMMs of 2hh' flops, Eq. 4) and one hidden vector of
+    bf16 values over each link (Eq. 5), on numbers that divide evenly."""
+    m = rl.cost_model(8, 4, 1024, 512, 2.0 ** 40, 2.0 ** 30, 2.0 ** 20)
+    assert (m.EP, m.ranks_per_node) == (8, 4)
+    assert m.sec_per_token_comp == 6 * 2.0 ** 19 / 2.0 ** 40
+    assert m.sec_per_token_intra == 2048 / 2.0 ** 30 and m.sec_per_token_inter == 2048 / 2.0 ** 20
+    for bad in (dict(EP=8, ranks_per_node=3), dict(F=0.0), dict(h=0)):
+        kw = dict(EP=8, ranks_per_node=4, h=64, hff=64, F=1e12, B_intra=1e11, B_inter=1e10)
+        kw.update(bad)
+        with pytest.raises(rl.RelibraError):
+            rl.cost_model(**kw)
 
 
 def test_plan_placed_equals_oracle_under_the_annealed_placement():

@@ -1,8 +1,9 @@
 """Pins of the oracle's communication-aware cost model (Section 4.1, Eq. 1-6), its smoothed
 objective and Algorithm 1 (Section 4.2) against things other than itself: the definitions
 applied token by token, scipy's logsumexp, closed forms, brute force over all placements.
-The annealing's trajectory is parity-unpinned (cooling rate, threshold, seeds and generator are
-not published); what is pinned are its cost model and its invariants."""
+The annealing's constants (cooling rate, threshold, seeds, generator) are not published and are
+arguments; its generator is pinned against published outputs and its acceptance rule, cooling and
+draw order by a hand-worked three-step run (end of this file)."""
 import itertools
 
 import numpy as np
@@ -155,3 +156,85 @@ def test_sa_near_bruteforce_optimum_on_tiny_instances():
         _, st = oracle.reorder_sa(x, rpn, m, gamma=0.995, eps=1e-3, n_seeds=4, seed=seed)
         worst = max(worst, st["T"] / best)
     assert worst <= 1.10
+
+
+# ------------------------------------------------------------------ Algorithm 1, step by step
+def test_splitmix64_published_vectors():
+    """The generator of the annealing's draws against its published outputs: state 0 (the
+    reference implementation's first values) and state 1234567 (the widely reproduced test vector)."""
+    assert oracle.splitmix64(0, 5).tolist() == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F,
+                                                0xF88BB8A8724C81EC, 0x1B39896A51A8749B]
+    assert oracle.splitmix64(1234567, 5).tolist() == [6457827717110365317, 3203168211198807973, 9817491932198370423,
+                                                      4593380528125082431, 16408922859458223821]
+
+
+# A hand-worked run of Algorithm 1: 4 experts, 2 ranks in one node (every remote token crosses the
+# intra-node link), one second per token of computation and per token over the link, beta = 20,
+# gamma = 1/2, eps = 0.2 -> theta = T0, T0/2, T0/4 (> 0.2) and T0/8 (< 0.2): three iterations.
+#   x[j][e]:  source 0 -> 8 1 1 6     loads l = 9 8 6 7
+#             source 1 -> 1 7 5 1
+# Greedy LPT: e0 (9) -> rank 0, e1 (8) -> rank 1, e3 (7) -> rank 1 (8 < 9; rank 1 is full), e2 -> rank 0.
+# States met, as (computation load per rank | link send per rank | link receive per rank):
+#   A = [0,1,0,1] start:      15 15 | 7 6 | 6 7     exact T = 15 + 7 = 22 = t_ref
+#   B = [1,1,0,0] swap(0,3):  13 17 | 9 6 | 6 9
+#   C = [0,1,1,0] swap(2,0):  16 14 | 2 2 | 2 2
+#   D = [0,0,1,1] swap(1,3):  17 13 | 7 8 | 8 7
+# Draws from splitmix64 started at 49 (e_a = o1 % 4, e_b = o2 % 4, u = (o3 >> 11) / 2^53, ...).
+SA_HAND = dict(
+    x=[[8, 1, 1, 6], [1, 7, 5, 1]], seed=49, gamma=0.5, eps=0.2, t_ref=22.0,
+    start=[0, 1, 0, 1],
+    draws=[(0, 3, 0.8379287921965335), (2, 0, 0.906503715108172), (1, 3, 0.4090126122385679)],
+    loads={"A": ([15, 15], [7, 6], [6, 7]), "B": ([13, 17], [9, 6], [6, 9]),
+           "C": ([16, 14], [2, 2], [2, 2]), "D": ([17, 13], [7, 8], [8, 7])},
+    visited=["B", "C", "D"],            # the swapped state of each iteration
+    accepted=[1, 1, 0],                 # B is worse but u < exp(-(T_B - T_A)/theta0); C improves; D is rejected
+    final=[0, 1, 1, 0])
+
+
+def sa_hand_smooth(name):
+    """Smoothed objective of a hand-worked state from its loads (scipy's logsumexp, beta = 20, times / 22)."""
+    from scipy.special import logsumexp
+    comp, tx, rx = (np.array(v, np.float64) / SA_HAND["t_ref"] for v in SA_HAND["loads"][name])
+    link = [logsumexp(20.0 * np.array([tx[g], rx[g], 0.0, 0.0])) / 20.0 for g in range(2)]   # no RDMA in one node
+    return logsumexp(20.0 * comp) / 20.0 + logsumexp(20.0 * np.array(link)) / 20.0
+
+
+def check_sa_hand_trace(tr):
+    hw = SA_HAND
+    assert tr["start"].tolist() == hw["start"] and tr["t_ref"] == hw["t_ref"] and tr["iterations"] == 3
+    T = sa_hand_smooth("A")
+    assert tr["smooth_start"] == pytest.approx(T, rel=1e-12)
+    theta = T
+    for i, ((ea, eb, u), name, acc) in enumerate(zip(hw["draws"], hw["visited"], hw["accepted"])):
+        Tn = sa_hand_smooth(name)
+        # the rule itself, on the hand-worked numbers: better, or u below the Metropolis threshold
+        assert acc == int(Tn < T or u < np.exp(-(Tn - T) / theta))
+        assert tr["moves"][i].tolist() == [ea, eb, acc]
+        assert tr["vals"][i][0] == u
+        assert tr["vals"][i][1] == pytest.approx(Tn, rel=1e-12)
+        assert tr["vals"][i][2] == pytest.approx(theta, rel=1e-12)
+        if acc:
+            T = Tn
+        theta *= hw["gamma"]
+    assert tr["rank"].tolist() == hw["final"]
+
+
+def test_sa_hand_worked_trajectory():
+    hw = SA_HAND
+    # the draws written above are what the pinned generator yields
+    o = oracle.splitmix64(hw["seed"], 9)
+    for i, (ea, eb, u) in enumerate(hw["draws"]):
+        assert (int(o[3 * i]) % 4, int(o[3 * i + 1]) % 4) == (ea, eb)
+        assert (int(o[3 * i + 2]) >> 11) / 2.0 ** 53 == u
+    # the thresholds are not close calls made by rounding: 0.838 < 0.883 (accept), 0.409 > 0.348 (reject)
+    TA, TB, TC, TD = (sa_hand_smooth(n) for n in "ABCD")
+    assert TB > TA > TC and TD > TC
+    assert np.exp(-(TB - TA) / TA) == pytest.approx(0.8834, abs=5e-4)
+    assert np.exp(-(TD - TC) / (TA / 4)) == pytest.approx(0.3479, abs=5e-4)
+    tr = oracle.reorder_sa_trace(np.array(hw["x"]), 2, np.array([1.0, 1.0, 1.0]), beta=20.0, gamma=hw["gamma"],
+                                 eps=hw["eps"], seed=hw["seed"], cap=8)
+    check_sa_hand_trace(tr)
+    # and the multi-seed call's first seed is that run
+    rank, st = oracle.reorder_sa(np.array(hw["x"]), 2, np.array([1.0, 1.0, 1.0]), gamma=hw["gamma"], eps=hw["eps"],
+                                 n_seeds=1, seed=hw["seed"])
+    assert rank.tolist() == hw["final"] and st["iterations"] == 3 and st["T_start"] == 22.0 and st["T"] == 18.0
