@@ -9,7 +9,9 @@
  *
  * Conventions
  *  - Every pointer is marked "dev" (device memory, the caller's allocation) or "host".
- *    The library allocates no device memory and keeps no state between calls.
+ *    The library allocates no device memory and keeps no state between calls that affects
+ *    results (process-wide and set once, thread-safely: the kernels' LDS size attributes; the
+ *    optional launch timing of relibra_prof_* is process-global and not thread-safe).
  *  - Device work is enqueued on `stream` (a hipStream_t) and not waited for.  Only
  *    relibra_plan is synchronous: it is host code with host inputs and outputs.
  *  - bf16 tensors are passed as `void*` to 2-byte elements, row-major, last index contiguous.
@@ -77,6 +79,9 @@ enum { RELIBRA_COMBINE_FWD = 0, RELIBRA_COMBINE_BWD = 1, RELIBRA_COMBINE_SUM = 2
  *   counts_dev [n_mb, E]    int32, dev, out  overwritten
  *   err_flag_dev            int32, dev, in/out  RELIBRA_ERR_ID_RANGE on an id outside [0,E);
  *                                              such ids are not counted
+ * One workgroup per micro-batch counts in LDS and stores the finished histogram (no zero-fill pass,
+ * no global atomics); the launch is bandwidth-bound when it covers many micro-batches, e.g. the
+ * replayed routing of every layer, ids [layers * n_mb, T, k], in one call.
  * Limits: 1 <= E <= 4096, 1 <= k <= E.  Empty input (n_mb*T == 0) is a no-op on counts of size 0,
  * or zeroes counts when only T == 0.
  */
@@ -508,11 +513,28 @@ int relibra_moe_ffn_wgrad_batched(const relibra_wgrad_mb *mbs_host, int n_mb, in
  * and the call copies block e to block E + s for every live slot.  n_workgroups (>= 1) bounds
  * the compute units the copy may occupy, so that it can run beside other kernels on a second
  * stream (the paper overlaps it with attention and gives it few SMs).  Values >= E in the
- * table are skipped and flagged RELIBRA_ERR_ID_RANGE.  The reverse direction (replica
- * gradients back to the home block) is part of relibra_moe_ffn_bwd.
+ * table are skipped and flagged RELIBRA_ERR_ID_RANGE.
  * Limits: h*hff % 8 == 0, 16-byte aligned tensors.
  */
 int relibra_replica_push(void *Wg_dev, void *Wu_dev, void *Wd_dev,
+                         const int32_t *replica_expert_dev, int E, int EP, int r, int h, int hff,
+                         int n_workgroups, int32_t *err_flag_dev, relibra_stream stream);
+
+/*
+ * Layer-shared replica buffer, gradient return (Section 5.1: in the backward pass the gradients
+ * produced by the replicas of a micro-batch are pushed back and accumulated on the source GPUs;
+ * the gradient buffer has the replica buffer's size and is reused the same way).  The reverse of
+ * relibra_replica_push on the gradient arrays
+ *   dWg, dWu [E + EP*r, hff, h], dWd [E + EP*r, h, hff] fp32, dev, in/out:
+ * for every live slot s (replica_expert[s] = e >= 0), in ascending slot order, block E + s is
+ * added into block e.  relibra_moe_ffn_bwd does the same sum in line unless it is given
+ * RELIBRA_BWD_NO_REPLICA_SUM; this call makes it a kernel of its own with a caller-bounded number
+ * of workgroups (n_workgroups >= 1), to run on a second stream beside other work.  The order of
+ * every element's additions is the in-line sum's: results are identical bit for bit.  The slots
+ * keep their contents (the next backward call overwrites them).  Entries >= E: skipped, flagged
+ * RELIBRA_ERR_ID_RANGE.  Limits: h*hff % 4 == 0, 16-byte aligned tensors.
+ */
+int relibra_replica_pull(float *dWg_dev, float *dWu_dev, float *dWd_dev,
                          const int32_t *replica_expert_dev, int E, int EP, int r, int h, int hff,
                          int n_workgroups, int32_t *err_flag_dev, relibra_stream stream);
 
@@ -546,11 +568,12 @@ int relibra_unpermute_combine(int mode, const void *rows_dev, const void *tok_de
  * RELIBRA_K_COUNT entries.  Process-global, not thread-safe.
  */
 enum {
-    RELIBRA_K_FILL = 0, RELIBRA_K_HIST, RELIBRA_K_PERM_COUNT, RELIBRA_K_PERM_SCAN, RELIBRA_K_PERM_RANK,
+    RELIBRA_K_HIST = 0, RELIBRA_K_PERM_COUNT, RELIBRA_K_PERM_SCAN, RELIBRA_K_PERM_RANK,
     RELIBRA_K_GATHER, RELIBRA_K_COMBINE_FWD, RELIBRA_K_COMBINE_BWD, RELIBRA_K_COMBINE_SUM, RELIBRA_K_SCHED,
     RELIBRA_K_FWD_GATE_UP, RELIBRA_K_FWD_DOWN, RELIBRA_K_BWD_ACT, RELIBRA_K_BWD_DX,
     RELIBRA_K_WGRAD_DOWN, RELIBRA_K_WGRAD_GATE_UP, RELIBRA_K_REPLICA_SUM, RELIBRA_K_REPLICA_PUSH,
-    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_TRANSPOSE, RELIBRA_K_ROW_TOKENS, RELIBRA_K_COUNT
+    RELIBRA_K_WGRAD_ORDER, RELIBRA_K_TRANSPOSE, RELIBRA_K_ROW_TOKENS, RELIBRA_K_ROW_GATES, RELIBRA_K_DGATE_REDUCE,
+    RELIBRA_K_REPLICA_PULL, RELIBRA_K_COUNT
 };
 int relibra_prof_start(int level, int max_records);
 int relibra_prof_stop(double *ms_by_kernel_host, int64_t *launches_by_kernel_host);

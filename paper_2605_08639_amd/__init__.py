@@ -30,13 +30,14 @@ EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra
            "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src", "relibra_plan_timed",
            "relibra_permute", "relibra_row_tokens", "relibra_row_gates", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd_gated",
            "relibra_moe_ffn_bwd_gated", "relibra_moe_ffn_fwd",
-           "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push",
+           "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push", "relibra_replica_pull",
            "relibra_workspace_bytes",
            "relibra_status_string", "relibra_prof_start", "relibra_prof_stop")
 
-KERNELS = ("fill", "hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
+KERNELS = ("hist", "perm_count", "perm_scan", "perm_rank", "gather", "combine_fwd", "combine_bwd",
            "combine_sum", "sched", "fwd_gate_up", "fwd_down", "bwd_act", "bwd_dx", "wgrad_down",
-           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order", "transpose", "row_tokens")
+           "wgrad_gate_up", "replica_sum", "replica_push", "wgrad_order", "transpose", "row_tokens", "row_gates",
+           "dgate_reduce", "replica_pull")
 
 _lib = None
 
@@ -606,6 +607,20 @@ def relibra_replica_push(Wg, Wu, Wd, replica_expert, E, EP, r, n_workgroups=16, 
                                     _dp(replica_expert, torch.int32), int(E), int(EP), int(r), h, hff,
                                     int(n_workgroups), _dp(err_flag), _stream())
     _check("relibra_replica_push", rc)
+    return err_flag
+
+
+def relibra_replica_pull(dWg, dWu, dWd, replica_expert, E, EP, r, n_workgroups=16, err_flag=None):
+    """Add the EP*r replica-slot gradients behind the E home blocks of dWg, dWu, dWd into their home blocks (in place)."""
+    assert dWg.shape[0] >= E + EP * r and dWu.shape[0] >= E + EP * r and dWd.shape[0] >= E + EP * r
+    assert replica_expert.numel() == EP * r
+    hff, h = dWg.shape[1], dWg.shape[2]
+    if err_flag is None:
+        err_flag = new_err_flag(dWg.device)
+    rc = lib().relibra_replica_pull(_dp(dWg, torch.float32), _dp(dWu, torch.float32), _dp(dWd, torch.float32),
+                                    _dp(replica_expert, torch.int32), int(E), int(EP), int(r), h, hff,
+                                    int(n_workgroups), _dp(err_flag), _stream())
+    _check("relibra_replica_pull", rc)
     return err_flag
 
 

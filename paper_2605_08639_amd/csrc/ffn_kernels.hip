@@ -1,28 +1,31 @@
 // Expert FFN forward / backward as grouped bf16 MFMA GEMMs (gfx950, v_mfma_f32_32x32x16_bf16).
 //
-// One workgroup of 4 wavefronts owns a 128-row x 256-column output tile (64 x 256 for a group's
-// tail of at most 64 rows); a wavefront owns 64 rows x 128 columns of it as 4 x 2 MFMA tiles
-// with fp32 accumulators.  Operand slabs of 32 k-values go global -> LDS directly
-// (global_load_lds, 16 bytes per lane) through a three-deep ring; see gemm_tile.h for the tile
-// layouts and the pipeline.  72 KiB of LDS and ~200 VGPRs per workgroup let two workgroups
-// share a compute unit, so that one group's prologue, barrier waits and epilogue overlap the
-// other's MFMAs.  (A 256-row, 8-wave, one-workgroup-per-CU geometry measured slower on every
-// workload shape tried, long groups included, and is not built.)
+// A wavefront always owns 64 rows x 128 columns of the output as 2 x 4 MFMA tiles with fp32
+// accumulators, two wavefronts per SIMD.  Row-tiled kernels (forward, data gradients) come in two
+// workgroup shapes: narrow, 4 waves = 128 rows x 256 columns, 72 KiB of LDS, two workgroups per
+// compute unit; wide, 8 waves = 128 rows x 512 columns (gate/up: 2 x 256), one workgroup per
+// compute unit, used where the wide tile divides the output width (the rows' slab is loaded once
+// for twice the columns).  A group's tail of at most 64 rows runs as a 64-row tile.  Operand slabs
+// of 32 k-values go global -> LDS directly (global_load_lds, 16 bytes per lane) through a ring of
+// three slabs (four in the wide weight-gradient tile); see gemm_tile.h for the tile layouts and
+// the pipeline.
 //
 // MFMA operand roles: the lanes carry the index that is contiguous in the output's memory
 // only for the fp32 weight gradients (128-byte runs per store); for the bf16 row tensors the
-// lanes carry the row index and each lane holds 4 consecutive columns (8-byte accesses).
+// lanes carry the row index and each lane holds 4 consecutive columns, re-laid through per-wave
+// LDS staging so that global accesses are 16 bytes per lane along rows.
 // The ragged dimension is always clamped (reads) and masked (writes); a ragged contraction
 // (weight gradients) is masked to zero in the fragments.
 //
-// Block index -> tile: consecutive tiles (same rows, next column block) are given to the same
-// XCD (blockIdx % 8), so that operand tiles shared by neighbouring tiles are served by one L2.
+// Block index -> tile: XCD x (blockIdx % 8) takes the x-th eighth of the ordered tile list, so
+// that operand tiles shared by neighbouring tiles are served by one L2.
 //
 // Weight gradients exist in two forms: per micro-batch (read-add-write of fp32 dW, replica slots
 // summed into the home slot) and once per batch over every resident micro-batch, contracted in
 // registers (wgrad_batched_kernel), which avoids the dW traffic that dominates short groups.
 #include "gemm_tile.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace relibra {
@@ -367,7 +370,7 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     constexpr int NWV = AW == 128 ? NWAVES : kWideRowWaves;
     using WV = Waves<BB, NWV>;
     using WTile = typename std::conditional<WT, KsTile<AW>, KcTile<AW>>::type;
-    using KL = KLoop<WTile, KcTile<BB>, 2, 1, AW, BB, WV::A, WV::B, 1, false, NSTAGES, 0, kSpreadLoads>;
+    using KL = KLoop<WTile, KcTile<BB>, 2, 1, AW, BB, WV::A, WV::B, 1, false, NSTAGES, kSpreadLoads>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t wofs = (size_t)t.expert * hff * h;
     const int ldw = WT ? hff : h;                             // (n in h', k in h) at [n*h + k], or at [k*h' + n]
@@ -457,7 +460,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
     constexpr int NWV = AW == 256 ? NWAVES : kWideRowWaves;
     using WV = Waves<BB, NWV>;
     using WT = typename std::conditional<W_KS, KsTile<AW>, KcTile<AW>>::type;
-    using KL = KLoop<WT, KcTile<BB>, 1, 1, AW, BB, WV::A, WV::B, NPH, false, NSTAGES, 0, kSpreadLoads>;
+    using KL = KLoop<WT, KcTile<BB>, 1, 1, AW, BB, WV::A, WV::B, NPH, false, NSTAGES, kSpreadLoads>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Operand A[NPH][1], B[NPH][1];
     A[0][0] = {W0, ldw, t.col0, n_dim - 1};
@@ -751,7 +754,7 @@ wgrad_kernel(Sched s, const bf16_t *__restrict__ L0, const bf16_t *__restrict__ 
              float *__restrict__ out0, float *__restrict__ out1)
 {
     constexpr int BA = WGM / NA;
-    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES, 0, (kSpreadLoads && WgradCfg<WGM>::STAGES >= 3)>;
+    using KL = KLoop<KsTile<BA>, KsTile<WGN>, NA, 1, BA, WGN, 2, NWAVES / 2, 1, true, WgradCfg<WGM>::STAGES, (kSpreadLoads && WgradCfg<WGM>::STAGES >= 3)>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WGN - 1) / WGN, n_mt = (m_dim + BA - 1) / BA;
     const int per_group = n_nt * n_mt;
@@ -999,7 +1002,7 @@ wgrad_batched_kernel(int E, int m_dim, int n_dim, WgradPlan w, int accumulate,
     constexpr int WGM = 256, BA = WGM / NA;
     // NA = 1: the A side (dY) may be gathered; its loads go last in the window (see KLoop)
     // the operand that may come through a row table: dY of dWd (A side), X of dWg, dWu (B side)
-    using KL = KLoop<KsTile<BA, BK, NA == 1>, KsTile<WN, BK, NA == 2>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, 0, kSpreadLoads, NA == 1>;
+    using KL = KLoop<KsTile<BA, BK, NA == 1>, KsTile<WN, BK, NA == 2>, NA, 1, BA, WN, 2, NWV / 2, 1, true, WgradWide<WN>::STAGES, kSpreadLoads, NA == 1>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int n_nt = (n_dim + WN - 1) / WN, n_mt = (m_dim + BA - 1) / BA;
     const int per_expert = n_nt * n_mt;
@@ -1079,11 +1082,10 @@ extern "C" size_t relibra_workspace_bytes(int which, int T, int k, int E, int G,
     (void)h;
 }
 
-// Kernels use more than 64 KiB of dynamic LDS: raise the per-kernel limit once.
-static int ensure_lds_limits()
+// Kernels use more than 64 KiB of dynamic LDS: raise the per-kernel limit (an attribute of the
+// loaded kernel, not of a call) once per process, whichever thread calls first.
+static int set_lds_limits()
 {
-    static bool done = false;
-    if (done) return RELIBRA_OK;
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_gate_up_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)fwd_down_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
@@ -1112,8 +1114,14 @@ static int ensure_lds_limits()
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_batched_kernel<2, 256, kWideWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradWide<256>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<1, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
     RELIBRA_HIP_TRY(hipFuncSetAttribute((const void *)wgrad_kernel<2, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, WgradCfg<128>::LDS));
-    done = true;
     return RELIBRA_OK;
+}
+static int ensure_lds_limits()
+{
+    static std::once_flag once;
+    static int status = RELIBRA_OK;
+    std::call_once(once, [] { status = set_lds_limits(); });
+    return status;
 }
 
 static inline unsigned grid8(long long tiles) { return (unsigned)((tiles + 7) / 8 * 8); }
@@ -1300,7 +1308,7 @@ static int ffn_bwd_impl(const void *dYrows, const void *Xrows,
                                 s, wg, wu, h, hff, ct_h, w_from_slot, (bf16_t *)dXrows);
         RELIBRA_HIP_TRY(launch_check());
         if (gb) {
-            RELIBRA_LAUNCH(RELIBRA_K_COMBINE_BWD, stream, dgate_reduce_kernel<<<std::min(1024, (n_rows + 255) / 256), 256, 0, stream>>>(
+            RELIBRA_LAUNCH(RELIBRA_K_DGATE_REDUCE, stream, dgate_reduce_kernel<<<std::min(1024, (n_rows + 255) / 256), 256, 0, stream>>>(
                 (const float *)gb->scratch, kDgateParts * ((hff + 255) / 256), n_rows, group_offset, g_begin, g_end, gb->src_of, gb->dgate, err_flag));
             RELIBRA_HIP_TRY(launch_check());
         }

@@ -284,9 +284,7 @@ __device__ __forceinline__ bf16x8_t mask_frag(bf16x8_t f, int k_first, int k_val
 //   meets the other waves: slab t+1 is complete and nobody reads slab t any more,
 //   so it issues the loads of slab t+STAGES into slab t's place, runs half of the step's MFMAs,
 //   requests the first fragments of slab t+1 and runs the other half, which covers them.
-// DBG switches parts of the loop off for timing experiments (1: no loads after the prologue,
-// 2: loads only, 3: no loads and no barrier); the library always builds DBG = 0.
-template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4, int DBG = 0,
+template <class AT, class BT, int NA, int NB, int BA, int BB, int WA, int WB, int NPH, bool RAGGED_K, int STAGES = 4,
           bool SPREAD = false, bool B_FIRST = false>
 struct KLoop {
     static constexpr int NW = WA * WB;
@@ -574,41 +572,37 @@ struct KLoop {
             const int kf = t * DEPTH + (lane >> 5) * 8;
 #pragma unroll
             for (int s = 0; s < KSTEPS - 1; ++s) {
-                if (DBG != 2) {
-                    // f[s & 1] was requested before the previous MFMA block: it is there by now.
-                    // Waiting for it here, before the next requests go out, lets the MFMAs below
-                    // start at once instead of waiting for the requests issued just above them.
-                    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (tail) mask_frags(f[s & 1], kf + s * 16, k_valid);
-                    __builtin_amdgcn_sched_barrier(0);
-                    read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
-                    mfma_all(acc, f[s & 1]);
-                    interleave_reads_with_mfmas();
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                // f[s & 1] was requested before the previous MFMA block: it is there by now.
+                // Waiting for it here, before the next requests go out, lets the MFMAs below
+                // start at once instead of waiting for the requests issued just above them.
+                __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+                __builtin_amdgcn_sched_barrier(0);
+                if (tail) mask_frags(f[s & 1], kf + s * 16, k_valid);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
+                mfma_all(acc, f[s & 1]);
+                interleave_reads_with_mfmas();
+                __builtin_amdgcn_sched_barrier(0);
             }
             wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
-            if (DBG != 3) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (t + STAGES < n && DBG != 1 && DBG != 3) {
+            if (t + STAGES < n) {
                 fetch(lk, PA, PB, t + STAGES, steps_per_phase, k_last, wave);
                 issue(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane);
             }
-            if (DBG != 2) {
-                // First half of the last step's MFMAs, then the requests for the next slab's first
-                // fragments (always issued: after the last slab they fetch stale LDS that nobody
-                // uses, and a request that is not conditional lets the wait in front of these
-                // MFMAs count only the older requests), then the second half, which covers them.
-                constexpr int L = (KSTEPS - 1) & 1;
-                if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, k_valid);
-                mfma_range<0, N_MFMA / 2>(acc, f[L]);
-                __builtin_amdgcn_sched_barrier(0);
-                read_frags(f[0], nxt, 0, wa, wb, lane);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_range<N_MFMA / 2, N_MFMA>(acc, f[L]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            // First half of the last step's MFMAs, then the requests for the next slab's first
+            // fragments (always issued: after the last slab they fetch stale LDS that nobody
+            // uses, and a request that is not conditional lets the wait in front of these
+            // MFMAs count only the older requests), then the second half, which covers them.
+            constexpr int L = (KSTEPS - 1) & 1;
+            if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, k_valid);
+            mfma_range<0, N_MFMA / 2>(acc, f[L]);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(f[0], nxt, 0, wa, wb, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_range<N_MFMA / 2, N_MFMA>(acc, f[L]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 

@@ -7,60 +7,71 @@
 namespace relibra {
 
 constexpr int kMaxExperts = 4096;
-constexpr int kHistThreads = 256;
-constexpr int kHistChunk = 8192;     // assignments per histogram block
+constexpr int kHistThreads = 1024;   // one block per micro-batch
+constexpr int kHistLdsBytes = 64 * 1024;
 constexpr int kUnit = RELIBRA_PERM_UNIT;   // assignments per permutation unit (one wave): short units, many waves -
                                          // the rank kernel is a chain of dependent table reads per round of 64
 constexpr int kPermThreads = 256;    // 4 waves = 4 units per block
 
-// ---------------------------------------------------------------- fill
-__global__ void fill_i32_kernel(int32_t *p, size_t n, int32_t v)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
 // ---------------------------------------------------------------- histogram (Eq. 1)
-// grid = n_mb * blocks_per_mb.  A block owns a contiguous chunk of one micro-batch's ids,
-// counts them in an LDS-private histogram (LDS atomics absorb the hot-expert conflicts) and
-// adds its non-zero bins to the micro-batch's global histogram with integer atomics, so the
-// result does not depend on the order in which blocks finish.
+// One block per micro-batch: it counts the micro-batch's ids in LDS and STORES the finished
+// histogram, so there is no zero-fill launch in front, no global atomics, and the result does
+// not depend on any execution order.  Hot experts (a Zipf router sends a fifth of the assignments
+// to one expert) would serialise LDS atomics on one address; every bin is therefore kept in C
+// copies, lane l adding to copy l % C, laid out so that the copies of a bin sit in different banks.
+// A single micro-batch (<= 512 KiB of ids) is latency-sized whatever the kernel does; the
+// bandwidth-bound use is many micro-batches at once (every layer's replayed routing, Section 3),
+// where the grid is thousands of blocks.
 __global__ void __launch_bounds__(kHistThreads)
-hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int blocks_per_mb, int vec_ok,
+hist_kernel(const int32_t *__restrict__ ids, int per_mb, int E, int copies_log2, int vec_ok,
             int32_t *__restrict__ counts, int32_t *err_flag)
 {
-    extern __shared__ int32_t bins[];
-    const int mb = blockIdx.x / blocks_per_mb;
-    const int chunk = blockIdx.x % blocks_per_mb;
-    for (int e = threadIdx.x; e < E; e += kHistThreads) bins[e] = 0;
+    extern __shared__ int32_t bins[];          // [E << copies_log2]
+    const int mb = blockIdx.x;
+    const int n_bins = E << copies_log2;
+    for (int i = threadIdx.x; i < n_bins; i += kHistThreads) bins[i] = 0;
     __syncthreads();
     const int32_t *src = ids + (size_t)mb * per_mb;
-    const int lo = chunk * kHistChunk;
-    const int hi = min(per_mb, lo + kHistChunk);
+    const int copy = threadIdx.x & ((1 << copies_log2) - 1);
     bool bad = false;
     if (vec_ok) {                      // 16-byte aligned rows of the id tensor
         const int4 *v = reinterpret_cast<const int4 *>(src);
-        for (int i = lo / 4 + threadIdx.x; i < hi / 4; i += kHistThreads) {
+        const int n4 = per_mb / 4;
+        int i = threadIdx.x;
+        for (; i + 3 * kHistThreads < n4; i += 4 * kHistThreads) {       // four loads in flight per lane
+            const int4 q[4] = {v[i], v[i + kHistThreads], v[i + 2 * kHistThreads], v[i + 3 * kHistThreads]};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e4[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if ((unsigned)e4[j] < (unsigned)E) atomicAdd(&bins[(e4[j] << copies_log2) + copy], 1);
+                    else bad = true;
+                }
+            }
+        }
+        for (; i < n4; i += kHistThreads) {
             const int4 q = v[i];
             const int e4[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if ((unsigned)e4[j] < (unsigned)E) atomicAdd(&bins[e4[j]], 1);
+                if ((unsigned)e4[j] < (unsigned)E) atomicAdd(&bins[(e4[j] << copies_log2) + copy], 1);
                 else bad = true;
             }
         }
     } else {
-        for (int i = lo + threadIdx.x; i < hi; i += kHistThreads) {
+        for (int i = threadIdx.x; i < per_mb; i += kHistThreads) {
             const int e = src[i];
-            if ((unsigned)e < (unsigned)E) atomicAdd(&bins[e], 1);
+            if ((unsigned)e < (unsigned)E) atomicAdd(&bins[(e << copies_log2) + copy], 1);
             else bad = true;
         }
     }
     if (bad) atomicOr(err_flag, RELIBRA_ERR_ID_RANGE);
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += kHistThreads) {
-        const int c = bins[e];
-        if (c) atomicAdd(&counts[(size_t)mb * E + e], c);
+        int c = 0;
+        for (int j = 0; j < (1 << copies_log2); ++j) c += bins[(e << copies_log2) + ((j + e) & ((1 << copies_log2) - 1))];
+        counts[(size_t)mb * E + e] = c;
     }
 }
 
@@ -381,15 +392,12 @@ extern "C" int relibra_route_hist(const int32_t *ids_dev, int n_mb, int T, int k
     if ((size_t)T * k > 0x7fffffffull) return RELIBRA_EINVAL;
     if (n_mb == 0) return RELIBRA_OK;
     if (!counts_dev || !err_flag_dev) return RELIBRA_EINVAL;
-    const size_t n_counts = (size_t)n_mb * E;
-    RELIBRA_LAUNCH(RELIBRA_K_FILL, stream, fill_i32_kernel<<<(unsigned)((n_counts + 255) / 256), 256, 0, stream>>>(counts_dev, n_counts, 0));
-    RELIBRA_HIP_TRY(launch_check());
     const int per_mb = T * k;
-    if (per_mb == 0) return RELIBRA_OK;
-    if (!ids_dev) return RELIBRA_EINVAL;
-    const int blocks_per_mb = (per_mb + kHistChunk - 1) / kHistChunk;
-    RELIBRA_LAUNCH(RELIBRA_K_HIST, stream, hist_kernel<<<(unsigned)(n_mb * blocks_per_mb), kHistThreads, E * sizeof(int32_t), stream>>>(
-        ids_dev, per_mb, E, blocks_per_mb, ((per_mb & 3) == 0 && aligned16(ids_dev)) ? 1 : 0, counts_dev, err_flag_dev));
+    if (per_mb > 0 && !ids_dev) return RELIBRA_EINVAL;
+    int copies_log2 = 4;                     // up to 16 copies of every bin, as many as fit the LDS budget
+    while (copies_log2 > 0 && ((size_t)E << copies_log2) * sizeof(int32_t) > (size_t)kHistLdsBytes) --copies_log2;
+    RELIBRA_LAUNCH(RELIBRA_K_HIST, stream, hist_kernel<<<(unsigned)n_mb, kHistThreads, ((size_t)E << copies_log2) * sizeof(int32_t), stream>>>(
+        ids_dev, per_mb, E, copies_log2, ((per_mb & 3) == 0 && aligned16(ids_dev)) ? 1 : 0, counts_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;
 }
@@ -523,7 +531,7 @@ extern "C" int relibra_row_gates(const int32_t *src_of_dev, const float *gates_d
     if (N < 0) return RELIBRA_EINVAL;
     if (N == 0) return RELIBRA_OK;
     if (!src_of_dev || !gates_dev || !row_gate_dev || !err_flag_dev) return RELIBRA_EINVAL;
-    RELIBRA_LAUNCH(RELIBRA_K_ROW_TOKENS, stream, row_gates_kernel<<<grid_for((size_t)N, 256, 1024), 256, 0, stream>>>(
+    RELIBRA_LAUNCH(RELIBRA_K_ROW_GATES, stream, row_gates_kernel<<<grid_for((size_t)N, 256, 1024), 256, 0, stream>>>(
         src_of_dev, gates_dev, N, row_gate_dev, err_flag_dev));
     RELIBRA_HIP_TRY(launch_check());
     return RELIBRA_OK;

@@ -239,3 +239,178 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
         assert num ** 0.5 <= TOL * den ** 0.5, (name, (num / max(den, 1e-300)) ** 0.5)
     assert err.item() == 0
     print(f"[{cfg.name}] gate-fused backward ok", flush=True)
+
+
+def _tile_rows(lo, hi, tile=128):
+    """Rows of the first, a middle and the tail row tile of a group [lo, hi)."""
+    n_tiles = (hi - lo + tile - 1) // tile
+    picks = sorted({0, n_tiles // 2, n_tiles - 1})
+    return np.concatenate([np.arange(lo + t * tile, min(lo + (t + 1) * tile, hi)) for t in picks]).astype(np.int64)
+
+
+def _per_row_rel(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    return np.linalg.norm(got - want, axis=1) / np.maximum(np.linalg.norm(want, axis=1), 1e-30)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_full_size_bench_path_matches_oracle_on_whole_tiles(idx):
+    """The exact form bench.py times, at full size, against the oracle: forward GEMMs on transposed weight
+    copies with the row gather fused in; where h' < 4096 the activations gated in place, the combine a plain sum
+    and the combine's backward folded into the expert backward (else the plain combine and backward); data
+    gradients with the weight gradients deferred; then ONE batched weight-gradient pass over three DISTINCT
+    micro-batches, each with its own plan tables.  Checked: whole row tiles (first, middle, tail) of the largest
+    and of the smallest live group of micro-batch 0 for the expert output rows, the data-gradient rows and dgate
+    (tensor and worst row); whole tokens for Out, dX; 8-column slices of dW for a replicated, the smallest and a
+    median expert against the oracle's sum over the three micro-batches."""
+    cfg = wl.CONFIGS[idx]
+    E, k, h, hff, T, N, G = cfg.E, cfg.k, cfg.h, cfg.hff, cfg.T, cfg.N, cfg.G
+    n_mb = min(cfg.n_mb, N_MB)
+    gate_fused = hff < 4096
+    rng = np.random.default_rng(200 + idx)
+    routed = [wl.make_routing(cfg, mb) for mb in range(n_mb)]
+    ids = np.stack([r[0] for r in routed])
+    gates = np.stack([r[1] for r in routed])
+    counts_o, _ = oracle.route_hist(ids, E)
+    po = oracle.plan(counts_o, cfg.EP, cfg.rpn, cfg.r)
+    perm_o = [oracle.permute(ids[mb], E, po["inst_ptr"][mb], po["inst_rows"][mb], po["inst_group"][mb], po["group_offset"][mb])
+              for mb in range(n_mb)]
+
+    err = rl.new_err_flag()
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    ids_d, gates_d = t(ids), t(gates)
+    p = rl.relibra_plan(rl.relibra_route_hist(ids_d, E, err_flag=err).cpu().numpy(), k, cfg.EP, cfg.rpn, cfg.r)
+    W = wl.make_weights(cfg, DEV)
+    W_t = [rl.relibra_transpose_experts(w) for w in W]
+    toks = [wl.make_tokens_device(cfg, mb, DEV) for mb in range(n_mb)]
+    kept, first = [], None
+    for mb in range(n_mb):
+        X_d, dOut_d = toks[mb]
+        tabs = {key: t(p[key][mb]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset", "group_expert", "group_dw_slot")}
+        row_of, src_of, _ = rl.relibra_permute(ids_d[mb], tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                               tabs["group_offset"], None, E, G, err_flag=err)
+        assert np.array_equal(row_of.cpu().numpy(), perm_o[mb][0])
+        row_tok = rl.relibra_row_tokens(src_of, k, T, err_flag=err)
+        ws = torch.empty(rl.workspace_bytes(rl.WS_FFN_BWD, N, 1, E, G, h, hff), dtype=torch.uint8, device=DEV)
+        if gate_fused:
+            row_gate = rl.relibra_row_gates(src_of, gates_d[mb], err_flag=err)
+            A = torch.empty((N, hff), dtype=torch.bfloat16, device=DEV)
+            Gt, U, _, _, Y = rl.relibra_moe_ffn_fwd_gated(X_d, row_tok, row_gate, tabs["group_offset"], tabs["group_expert"], *W_t,
+                                                          A=A, Ag=A, err_flag=err, flags=rl.FWD_TRANSPOSED_WEIGHTS)
+            Out = rl.relibra_unpermute_combine(rl.COMBINE_SUM, Y, row_of, T, k, err_flag=err)
+            dgate = torch.full((T, k), float("nan"), dtype=torch.float32, device=DEV)
+            dXrows, _ = rl.relibra_moe_ffn_bwd_gated(dOut_d, row_tok, row_gate, Gt, U, tabs["group_offset"], tabs["group_expert"],
+                                                     tabs["group_dw_slot"], *W, src_of=src_of, dgate=dgate, workspace=ws,
+                                                     err_flag=err, E=E)
+            kept.append(dict(dOut=dOut_d, X=X_d, row_tok=row_tok, A=A, bwd_workspace=ws, inst_ptr=tabs["inst_ptr"],
+                             inst_group=tabs["inst_group"], group_offset=tabs["group_offset"]))
+        else:
+            Gt, U, A, Y = rl.relibra_moe_ffn_fwd_gather(X_d, row_tok, tabs["group_offset"], tabs["group_expert"], *W_t,
+                                                        err_flag=err, flags=rl.FWD_TRANSPOSED_WEIGHTS)
+            Out = rl.relibra_unpermute_combine(rl.COMBINE_FWD, Y, row_of, T, k, gates=gates_d[mb], err_flag=err)
+            dY, dgate = rl.relibra_unpermute_combine(rl.COMBINE_BWD, Y, row_of, T, k, gates=gates_d[mb], tok=dOut_d, err_flag=err)
+            dXrows = rl.relibra_moe_ffn_bwd(dY, None, Gt, U, A, tabs["group_offset"], tabs["group_expert"], tabs["group_dw_slot"],
+                                            *W, None, None, None, flags=rl.BWD_DEFER_WGRAD, workspace=ws, err_flag=err, E=E)
+            kept.append(dict(dYrows=dY, X=X_d, row_tok=row_tok, A=A, bwd_workspace=ws, inst_ptr=tabs["inst_ptr"],
+                             inst_group=tabs["inst_group"], group_offset=tabs["group_offset"]))
+        dX = rl.relibra_unpermute_combine(rl.COMBINE_SUM, dXrows, row_of, T, k, err_flag=err)
+        if mb == 0:
+            first = dict(Y=Y, Out=Out, dgate=dgate, dXrows=dXrows, dX=dX)
+        del Gt, U
+    dWb = [torch.empty(s, dtype=torch.float32, device=DEV) for s in ((E, hff, h), (E, hff, h), (E, h, hff))]
+    rl.relibra_moe_ffn_wgrad_batched(kept, E, *dWb, err_flag=err)
+    torch.cuda.synchronize()
+    assert err.item() == 0
+
+    # ---- whole row tiles of micro-batch 0
+    mb = 0
+    row_o, src_o = perm_o[mb]
+    go, ge = po["group_offset"][mb], po["group_expert"][mb]
+    rows_per_group = np.diff(go)
+    live = np.nonzero(rows_per_group > 0)[0]
+    big, small = live[np.argmax(rows_per_group[live])], live[np.argmin(rows_per_group[live])]
+    X_h, dOut_h = toks[mb][0].cpu(), toks[mb][1].cpu()
+    g_flat = gates[mb].reshape(-1)
+    worst = {}
+    for g in dict.fromkeys([int(big), int(small)]):
+        rows = _tile_rows(int(go[g]), int(go[g + 1]))
+        a_idx = src_o[rows].astype(np.int64)
+        tok_idx = torch.from_numpy(a_idx // k)
+        w_sub = [w[int(ge[g])][None].cpu() for w in W]
+        sgo, sge = np.array([0, len(rows)], np.int32), np.zeros(1, np.int32)
+        Xs = X_h[tok_idx]
+        _, _, _, Y_o = oracle.ffn_fwd(Xs, sgo, sge, *w_sub)
+        gate_r = g_flat[a_idx].astype(np.float64)
+        dY_o = gate_r[:, None] * dOut_h[tok_idx].double().numpy()            # the combine's backward, row by row
+        dgate_o = (dOut_h[tok_idx].double().numpy() * Y_o).sum(1)
+        dXr_o, _, _, _ = oracle.ffn_bwd(Xs, bf16_round(dY_o), sgo, sge, *w_sub)
+        rd = torch.from_numpy(rows).to(DEV)
+        Y_want = gate_r[:, None] * Y_o if gate_fused else Y_o                # gated in place: the rows come out gate-scaled
+        got_Y = first["Y"][rd].double().cpu().numpy()
+        got_dX = first["dXrows"][rd].double().cpu().numpy()
+        got_dgate = first["dgate"].reshape(-1)[torch.from_numpy(a_idx).to(DEV)].double().cpu().numpy()
+        assert rel_l2(got_Y, Y_want) <= TOL and rel_l2(got_dX, dXr_o) <= TOL and rel_l2(got_dgate, dgate_o) <= TOL
+        worst[g] = (float(_per_row_rel(got_Y, Y_want).max()), float(_per_row_rel(got_dX, dXr_o).max()))
+        assert worst[g][0] <= TOL and worst[g][1] <= TOL, worst
+    print(f"[{cfg.name}] whole tiles ok, worst rows {worst}", flush=True)
+
+    # ---- whole tokens: Out and dX through all k rows of a few tokens
+    grp_of_row = np.searchsorted(go, np.arange(N), side="right") - 1
+    tk_list = sorted(set([int(src_o[go[big]]) // k, int(src_o[go[small]]) // k] + rng.integers(0, T, size=4).tolist()))
+    s_rows = np.array([row_o[tk * k + s] for tk in tk_list for s in range(k)], np.int64)
+    s_exp = ge[grp_of_row[s_rows]]
+    experts = sorted(set(s_exp.tolist()))
+    remap = {e: i for i, e in enumerate(experts)}
+    idx_e = torch.tensor(experts, device=DEV)
+    w_sub = [w[idx_e].cpu() for w in W]
+    sub_go = np.arange(len(s_rows) + 1, dtype=np.int32)
+    sub_ge = np.array([remap[e] for e in s_exp], np.int32)
+    Xs = X_h[torch.from_numpy(src_o[s_rows].astype(np.int64) // k)]
+    _, _, _, Y_o = oracle.ffn_fwd(Xs, sub_go, sub_ge, *w_sub)
+    ident = np.arange(len(s_rows), dtype=np.int32)
+    Out_o = oracle.combine_fwd(Y_o, gates[mb][tk_list], ident, len(tk_list), k)
+    dY_o, dgate_o = oracle.combine_bwd(dOut_h[tk_list].double().numpy(), Y_o, gates[mb][tk_list], ident, len(tk_list), k)
+    dXr_o, _, _, _ = oracle.ffn_bwd(Xs, bf16_round(dY_o), sub_go, sub_ge, *w_sub)
+    dX_o = oracle.combine_fwd(dXr_o, None, ident, len(tk_list), k)
+    tkd = torch.tensor(tk_list, device=DEV)
+    assert rel_l2(first["Out"][tkd].double().cpu().numpy(), Out_o) <= TOL
+    assert rel_l2(first["dX"][tkd].double().cpu().numpy(), dX_o) <= TOL
+    assert rel_l2(first["dgate"][tkd].double().cpu().numpy(), dgate_o) <= TOL
+    assert not torch.isnan(first["dgate"]).any()
+
+    # ---- batched weight gradients over the three distinct micro-batches: slices of whole experts
+    total = counts_o[:n_mb].sum(0)
+    inst_n = np.stack([np.diff(po["inst_ptr"][m]) for m in range(n_mb)])
+    cand = []
+    repl = np.nonzero((inst_n > 1).any(0))[0]
+    if len(repl):
+        cand.append(int(repl[np.argmin(total[repl])]))                        # cheapest expert replicated in some micro-batch
+    nz = np.nonzero(total > 0)[0]
+    cand.append(int(nz[np.argmin(total[nz])]))
+    cand.append(int(nz[np.argsort(total[nz])[len(nz) // 2]]))
+    J = np.sort(rng.choice(hff, size=8, replace=False))
+    Jt = torch.from_numpy(J).to(DEV)
+    for e in dict.fromkeys(cand):
+        want = [0.0, 0.0, 0.0]
+        n_rows_e = n_inst_e = 0
+        for m in range(n_mb):
+            go_m, ge_m, src_m = po["group_offset"][m], po["group_expert"][m], perm_o[m][1]
+            groups = [g for g in range(G) if ge_m[g] == e and go_m[g + 1] > go_m[g]]
+            if not groups:
+                continue
+            rws = np.concatenate([np.arange(go_m[g], go_m[g + 1]) for g in groups]).astype(np.int64)
+            a_idx = src_m[rws].astype(np.int64)
+            Xm, dOm = toks[m][0].cpu(), toks[m][1].cpu()
+            tok_idx = torch.from_numpy(a_idx // k)
+            dYe = bf16_round(gates[m].reshape(-1)[a_idx][:, None].astype(np.float64) * dOm[tok_idx].double().numpy())
+            sgo = np.array([0, len(rws)], np.int32)
+            _, dWg_o, dWu_o, dWd_o = oracle.ffn_bwd(Xm[tok_idx], dYe, sgo, np.zeros(1, np.int32), W[0][e][Jt].cpu()[None],
+                                                    W[1][e][Jt].cpu()[None], W[2][e][:, Jt].cpu().contiguous()[None])
+            want = [want[0] + dWg_o[0], want[1] + dWu_o[0], want[2] + dWd_o[0]]
+            n_rows_e, n_inst_e = n_rows_e + len(rws), n_inst_e + len(groups)
+        assert rel_l2(dWb[0][e][Jt].double().cpu().numpy(), want[0]) <= TOL, ("dWg", e)
+        assert rel_l2(dWb[1][e][Jt].double().cpu().numpy(), want[1]) <= TOL, ("dWu", e)
+        assert rel_l2(dWb[2][e][:, Jt].double().cpu().numpy(), want[2]) <= TOL, ("dWd", e)
+        print(f"[{cfg.name}] batched dW slices of expert {e} ({n_rows_e} rows in {n_inst_e} pieces) ok", flush=True)
+    for e in np.nonzero(total == 0)[0][:2].tolist():                          # experts nobody routed to: exact zeros
+        assert (dWb[0][e] == 0).all() and (dWb[1][e] == 0).all() and (dWb[2][e] == 0).all()

@@ -508,6 +508,76 @@ def test_replica_push_fills_slots_and_ffn_reads_them():
             assert torch.equal(a, b)
 
 
+def test_replica_pull_equals_the_inline_sum_and_two_layers_share_one_slot_buffer():
+    """Section 5.1: one buffer of r slots per rank serves every layer in turn (parameters pushed
+    before a layer's expert computation, gradients pulled back after its backward).  Two layers with
+    their own weights and routing run through ONE shared slot buffer (parameters and gradients),
+    the slots overwritten between layers; every result must equal, bit for bit, the run in which
+    each layer has private slots and the backward call sums the replica gradients in line."""
+    L = 2
+    cfgs = [wl.small_config(E=16, k=4, EP=4, r=2, T=777, n_mb=1, h=256, hff=192, index=70 + l) for l in range(L)]
+    E, EP, r, h, hff = cfgs[0].E, cfgs[0].EP, cfgs[0].r, cfgs[0].h, cfgs[0].hff
+    n_rep = EP * r
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    layers = []
+    for cfg in cfgs:
+        ids, gates = routing(cfg)
+        p = plan_both(cfg, oracle.route_hist(ids, cfg.E)[0])
+        assert (p["replica_expert"] >= 0).any()
+        X, dOut = wl.make_tokens(cfg, 0)
+        tabs = {key: dev_i32(p[key][0]) for key in ("inst_ptr", "inst_rows", "inst_group", "group_offset",
+                                                    "group_expert", "group_dw_slot")}
+        row_of, src_of, Xrows = rl.relibra_permute(t(ids[0]), tabs["inst_ptr"], tabs["inst_rows"], tabs["inst_group"],
+                                                   tabs["group_offset"], X.to(DEV), E, cfg.G)
+        dY = torch.randn((cfg.N, h), generator=torch.Generator().manual_seed(cfg.index)).to(torch.bfloat16).to(DEV)
+        layers.append(dict(p=p, tabs=tabs, Xrows=Xrows, dY=dY, W=[W.to(DEV) for W in wl.make_weights(cfg)],
+                           rep=dev_i32(p["replica_expert"][0].reshape(-1))))
+
+    def run_layer(ly, Wp, dWp, n_blocks, slot_table, pull):
+        """forward + backward of one layer on parameter arrays Wp / gradient arrays dWp of n_blocks blocks whose
+        first E are the layer's home blocks and whose last n_rep are the replica slots."""
+        err = rl.new_err_flag()
+        rl.relibra_replica_push(*Wp, ly["rep"], n_blocks - n_rep, EP, r, n_workgroups=5, err_flag=err)
+        Gt, U, A, Y = rl.relibra_moe_ffn_fwd(ly["Xrows"], ly["tabs"]["group_offset"], slot_table, *Wp, err_flag=err)
+        flags = rl.BWD_REPLICA_WEIGHTS | (rl.BWD_NO_REPLICA_SUM if pull else 0)
+        dXrows = rl.relibra_moe_ffn_bwd(ly["dY"], ly["Xrows"], Gt, U, A, ly["tabs"]["group_offset"], ly["tabs"]["group_expert"],
+                                        slot_table, *Wp, *dWp, err_flag=err, E=n_blocks - n_rep, flags=flags)
+        if pull:
+            rl.relibra_replica_pull(*dWp, ly["rep"], n_blocks - n_rep, EP, r, n_workgroups=3, err_flag=err)
+        assert err.item() == 0
+        return Y, dXrows
+
+    shapes = [(hff, h), (hff, h), (h, hff)]
+    # reference: private slots per layer, replica gradients summed inside the backward call
+    want = []
+    for ly in layers:
+        Wp = [torch.cat([W, torch.zeros((n_rep, *W.shape[1:]), dtype=W.dtype, device=DEV)]) for W in ly["W"]]
+        dWp = [torch.zeros((E + n_rep, *s), dtype=torch.float32, device=DEV) for s in shapes]
+        Y, dXrows = run_layer(ly, Wp, dWp, E + n_rep, ly["tabs"]["group_dw_slot"], pull=False)
+        want.append((Y, dXrows, *[d[:E].clone() for d in dWp]))
+    # shared: [layer 0 home | layer 1 home | slots]; layer l sees the tail that starts at its home blocks, so a
+    # replica slot's block index is (L - l) * E + s in its view
+    W_all = [torch.cat([ly["W"][i] for ly in layers] + [torch.full((n_rep, *shapes[i]), 7.0, dtype=torch.bfloat16, device=DEV)])
+             for i in range(3)]
+    dW_all = [torch.full((L * E + n_rep, *s), float("nan"), dtype=torch.float32, device=DEV) for s in shapes]
+    got = [None] * L
+    for l in (0, 1, 1, 0):                                   # forward order, then backward order: slots refilled each time
+        ly = layers[l]
+        slot = ly["p"]["group_dw_slot"][0].copy()
+        slot[slot >= E] += (L - l - 1) * E
+        view_W = [W[l * E:] for W in W_all]
+        view_dW = [d[l * E:] for d in dW_all]
+        Y, dXrows = run_layer(ly, view_W, view_dW, (L - l) * E + n_rep, dev_i32(slot), pull=True)
+        got[l] = (Y, dXrows, *[d[l * E:(l + 1) * E].clone() for d in dW_all])
+    for l in range(L):
+        for a, b in zip(got[l], want[l]):
+            assert torch.equal(a, b), l
+    # the home parameters were never written
+    for i in range(3):
+        for l, ly in enumerate(layers):
+            assert torch.equal(W_all[i][l * E:(l + 1) * E], ly["W"][i])
+
+
 def test_replica_push_flags_bad_table_and_leaves_empty_slots():
     E, EP, r, h, hff = 4, 2, 2, 64, 64
     W = [torch.arange((E + EP * r) * h * hff, dtype=torch.float32).reshape(E + EP * r, hff, h).to(torch.bfloat16).to(DEV)
