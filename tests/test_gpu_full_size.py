@@ -132,9 +132,11 @@ def test_full_size_layer_matches_oracle_on_samples(idx):
     cand.append(int(nz[np.argmin(counts_o[mb][nz])]))
     cand.append(int(nz[np.argsort(counts_o[mb][nz])[len(nz) // 2]]))
     zero = np.nonzero(counts_o[mb] == 0)[0]
-    J = np.sort(rng.choice(hff, size=8, replace=False))
-    Jt = torch.from_numpy(J).to(DEV)
     for e in dict.fromkeys(cand):
+        # 8 columns of h' where the expert has many rows, all columns where it has a handful (there a norm over
+        # 8 columns is a dozen single roundings, not the tensor-level figure the bar is stated for)
+        J = np.sort(rng.choice(hff, size=8, replace=False)) if counts_o[mb][e] >= 64 else np.arange(hff)
+        Jt = torch.from_numpy(J).to(DEV)
         groups = [g for g in range(G) if ge[g] == e and rows_per_group[g] > 0]
         rws = np.concatenate([np.arange(go[g], go[g + 1]) for g in groups]).astype(np.int64)
         sgo = np.concatenate([[0], np.cumsum([rows_per_group[g] for g in groups])]).astype(np.int32)
@@ -388,9 +390,12 @@ def test_full_size_bench_path_matches_oracle_on_whole_tiles(idx):
     nz = np.nonzero(total > 0)[0]
     cand.append(int(nz[np.argmin(total[nz])]))
     cand.append(int(nz[np.argsort(total[nz])[len(nz) // 2]]))
-    J = np.sort(rng.choice(hff, size=8, replace=False))
-    Jt = torch.from_numpy(J).to(DEV)
     for e in dict.fromkeys(cand):
+        # 8 columns of h' for experts with many rows; an expert with a handful of rows is compared on ALL its
+        # columns (cheap for the oracle), since a norm over 8 columns x 2 rows is a dozen single roundings, not
+        # the tensor-level figure the 5e-3 bar is stated for
+        J = np.sort(rng.choice(hff, size=8, replace=False)) if total[e] >= 64 else np.arange(hff)
+        Jt = torch.from_numpy(J).to(DEV)
         want = [0.0, 0.0, 0.0]
         n_rows_e = n_inst_e = 0
         for m in range(n_mb):
