@@ -239,6 +239,24 @@ int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const i
                     int32_t *err_flag_dev, relibra_stream stream);
 
 /*
+ * relibra_permute for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels with
+ * their scratch (the per-unit count matrix, relibra_workspace_bytes(RELIBRA_WS_PERMUTE, ...) bytes)
+ * in a static device array of RELIBRA_PERMUTE_STATIC_BYTES that each GPU the library runs on holds
+ * until the process ends.  Sizes that need more return RELIBRA_EWORKSPACE; a failed lookup of the
+ * array's device address returns RELIBRA_EHIP.  The call allocates and frees nothing.  Every call on
+ * a GPU uses that GPU's one array: calls that overlap on one GPU (different streams) race and must
+ * be ordered by the caller; calls in sequence need no clearing in between.  All other arguments,
+ * results and error flags as relibra_permute.
+ */
+#define RELIBRA_PERMUTE_STATIC_BYTES (4u << 20)
+int relibra_permute_static(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
+                           const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                           const void *X_dev, int T, int k, int E, int G, int h,
+                           int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                           int32_t *err_flag_dev, relibra_stream stream);
+
+/*
  * Source-aware token split (Section 5.2: y_{j,e,g}, the share of source rank j's tokens of
  * expert e served by rank g; Section 4.1 for the link types).  The plan fixes how many tokens
  * every instance of an expert serves; which sources fill an instance decides the traffic.  Per

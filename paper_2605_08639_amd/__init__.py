@@ -28,7 +28,7 @@ COMBINE_FWD, COMBINE_BWD, COMBINE_SUM = 0, 1, 2
 EXPORTS = ("relibra_route_hist", "relibra_plan", "relibra_plan_placed", "relibra_moe_time", "relibra_reorder_sa", "relibra_load_stats",
            "relibra_cost_model_init", "relibra_reorder_sa_trace",
            "relibra_assign_sources", "relibra_moe_time_split", "relibra_permute_src", "relibra_plan_timed",
-           "relibra_permute", "relibra_row_tokens", "relibra_row_gates", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd_gated",
+           "relibra_permute", "relibra_permute_static", "relibra_row_tokens", "relibra_row_gates", "relibra_moe_ffn_fwd_gather", "relibra_moe_ffn_fwd_gated",
            "relibra_moe_ffn_bwd_gated", "relibra_moe_ffn_fwd",
            "relibra_moe_ffn_bwd", "relibra_moe_ffn_wgrad_batched", "relibra_transpose_experts", "relibra_unpermute_combine", "relibra_replica_push", "relibra_replica_pull",
            "relibra_workspace_bytes",
@@ -286,6 +286,23 @@ def relibra_permute(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G,
                                _dp(X), T, k, E, G, h, _dp(row_of), _dp(src_of), _dp(Xrows),
                                _dp(workspace), C.c_size_t(workspace.numel()), _dp(err_flag), _stream())
     _check("relibra_permute", rc)
+    return row_of, src_of, Xrows
+
+
+PERMUTE_STATIC_BYTES = 4 << 20
+
+
+def relibra_permute_static(ids, inst_ptr, inst_rows, inst_group, group_offset, X, E, G, row_of, src_of, Xrows=None, err_flag=None):
+    """relibra_permute with the library's static device scratch instead of a workspace: nothing is allocated, so
+    every output (row_of, src_of [N] int32, Xrows [N,h] bf16 when X is given, err_flag) is the caller's."""
+    T, k = ids.shape
+    h = 0 if X is None else X.shape[1]
+    assert row_of.shape == (T * k,) and src_of.shape == (T * k,) and err_flag is not None
+    rc = lib().relibra_permute_static(_dp(ids, torch.int32), _dp(inst_ptr, torch.int32), _dp(inst_rows, torch.int32),
+                                      _dp(inst_group, torch.int32), _dp(group_offset, torch.int32),
+                                      _dp(X), T, k, E, G, h, _dp(row_of, torch.int32), _dp(src_of, torch.int32), _dp(Xrows),
+                                      _dp(err_flag, torch.int32), _stream())
+    _check("relibra_permute_static", rc)
     return row_of, src_of, Xrows
 
 

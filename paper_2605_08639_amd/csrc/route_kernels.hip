@@ -4,6 +4,8 @@
 // wave-level ballots and LDS-private counters.
 #include "common.h"
 
+#include <mutex>
+
 namespace relibra {
 
 constexpr int kMaxExperts = 4096;
@@ -455,6 +457,52 @@ extern "C" int relibra_permute(const int32_t *ids_dev, const int32_t *inst_ptr_d
     if (T > 0 && !inst_rows_dev) return RELIBRA_EINVAL;
     return permute_impl(ids_dev, inst_ptr_dev, inst_rows_dev, inst_group_dev, group_offset_dev, SrcSplit{},
                         X_dev, T, k, E, G, h, row_of_dev, src_of_dev, Xrows_dev, workspace_dev, workspace_bytes,
+                        err_flag_dev, stream_);
+}
+
+// The permutation for callers that cannot allocate: its unit-count matrix lives in a static device
+// array instead of a caller's workspace.  Every GPU holds its own copy of the array at its own
+// address; host code never uses the array's name as an address, only what hipGetSymbolAddress
+// returned for the device that is current.
+static __device__ __align__(256) int32_t scratch[RELIBRA_PERMUTE_STATIC_BYTES / sizeof(int32_t)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t *g_scratch_ptr[kMaxDevices] = {};     // per device: the device address of `scratch`
+}  // namespace
+
+// Device address of this device's copy of `scratch` (looked up once per device); null on failure.
+static int32_t *scratch_for_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = (int32_t *)ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+extern "C" int relibra_permute_static(const int32_t *ids_dev, const int32_t *inst_ptr_dev, const int32_t *inst_rows_dev,
+                                      const int32_t *inst_group_dev, const int32_t *group_offset_dev,
+                                      const void *X_dev, int T, int k, int E, int G, int h,
+                                      int32_t *row_of_dev, int32_t *src_of_dev, void *Xrows_dev,
+                                      int32_t *err_flag_dev, relibra_stream stream_)
+{
+    if (T > 0 && !inst_rows_dev) return RELIBRA_EINVAL;
+    if (T < 0 || k < 1 || E < 1 || G < 1) return RELIBRA_EINVAL;
+    const size_t need = relibra_workspace_bytes(RELIBRA_WS_PERMUTE, T, k, E, G, h, 0);
+    if (need == 0 && (size_t)T * k > 0) return RELIBRA_EINVAL;
+    if (need > (size_t)RELIBRA_PERMUTE_STATIC_BYTES) return RELIBRA_EWORKSPACE;     // beyond the static array
+    int32_t *ws = scratch_for_current_device();
+    if (!ws) return RELIBRA_EHIP;
+    // Nothing in the array has to start at zero: the counting kernel overwrites every entry the other
+    // two kernels read.
+    return permute_impl(ids_dev, inst_ptr_dev, inst_rows_dev, inst_group_dev, group_offset_dev, SrcSplit{},
+                        X_dev, T, k, E, G, h, row_of_dev, src_of_dev, Xrows_dev, ws, (size_t)RELIBRA_PERMUTE_STATIC_BYTES,
                         err_flag_dev, stream_);
 }
 
