@@ -350,6 +350,24 @@ def run_config(args, config_index, steps, warmup, extras_level, cpu_seconds):
                                   "GBps": b / (avg * 1e-3) / 1e9, "frac_of_8TBps": b / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS}
         del ids_layers, counts_layers
         extras["hbm_kernels"] = hbm
+        # what this machine's memory system sustains for plain streams (torch's own copy and fill kernels, calibration
+        # only): a 1 GiB copy (read + write) and a 2 GiB fill (write only); the read-only stream is hist_all_layers
+        src_c = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst_c = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        best = {"copy": 1e9, "fill": 1e9}
+        for _ in range(5):
+            e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            dst_c[:1 << 30].copy_(src_c)
+            e1.record()
+            dst_c.zero_()
+            e2.record()
+            e2.synchronize()
+            best["copy"], best["fill"] = min(best["copy"], e0.elapsed_time(e1)), min(best["fill"], e1.elapsed_time(e2))
+        extras["measured_stream_GBps"] = {"copy_read_plus_write": 2.0 * (1 << 30) / (best["copy"] * 1e-3) / 1e9,
+                                          "fill_write_only": 2.0 * (1 << 30) / (best["fill"] * 1e-3) / 1e9,
+                                          "read_only": hbm["hist_all_layers"]["GBps"]}
+        del src_c, dst_c
         extras["index_kernels_ms"] = {nm: p2[nm][0] / p2[nm][1] for nm in ("sched", "wgrad_order", "replica_sum") if nm in p2}
         assert err.item() == 0
 

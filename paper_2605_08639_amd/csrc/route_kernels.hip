@@ -231,20 +231,39 @@ perm_rank_kernel(const int32_t *__restrict__ ids, int N, int E, int G, int ebits
     if (flags) atomicOr(err_flag, flags);
 }
 
-// Row gather: Xrows[row] = X[src_of[row] / k], 16 bytes per thread, consecutive threads on
-// consecutive 16-byte pieces of a row.
-__global__ void __launch_bounds__(256)
-gather_rows_kernel(const uint4 *__restrict__ X, const int32_t *__restrict__ src_of, int N, int T, int k,
-                   int vec_per_row, uint4 *__restrict__ Xrows)
+// Thread mapping of the row-streaming kernels: a row of vec_per_row 16-byte pieces is walked by
+// LPR = 2^lpr_log2 consecutive threads, each taking every LPR-th piece (LPR = the smallest power
+// of two that leaves a thread at most `pieces` pieces, at most the block), so a block of 256
+// threads serves 256 / LPR rows at a time and no index needs a division.
+constexpr int kRowThreads = 256;
+inline int lanes_per_row_log2(int vec_per_row, int pieces)
 {
-    const size_t total = (size_t)N * vec_per_row;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const int row = (int)(i / vec_per_row), c = (int)(i % vec_per_row);
+    int l = 0;
+    while ((1 << l) * pieces < vec_per_row && (1 << l) < kRowThreads) ++l;
+    return l;
+}
+
+// Row gather: Xrows[row] = X[src_of[row] / k], 16 bytes per piece, four pieces of a row in flight
+// per thread.
+__global__ void __launch_bounds__(kRowThreads)
+gather_rows_kernel(const uint4 *__restrict__ X, const int32_t *__restrict__ src_of, int N, int T, int k,
+                   int vec_per_row, int lpr_log2, uint4 *__restrict__ Xrows)
+{
+    const int lpr = 1 << lpr_log2, rows_per_block = kRowThreads >> lpr_log2;
+    const int r_local = threadIdx.x >> lpr_log2, c0 = threadIdx.x & (lpr - 1);
+    for (int row = blockIdx.x * rows_per_block + r_local; row < N; row += gridDim.x * rows_per_block) {
         const int a = src_of[row];
         if (a < 0) continue;
         const int t = a / k;
         if (t >= T) continue;
-        Xrows[i] = X[(size_t)t * vec_per_row + c];
+        const uint4 *__restrict__ src = X + (size_t)t * vec_per_row;
+        uint4 *__restrict__ dst = Xrows + (size_t)row * vec_per_row;
+        int c = c0;
+        for (; c + 3 * lpr < vec_per_row; c += 4 * lpr) {
+            const uint4 v0 = src[c], v1 = src[c + lpr], v2 = src[c + 2 * lpr], v3 = src[c + 3 * lpr];
+            dst[c] = v0; dst[c + lpr] = v1; dst[c + 2 * lpr] = v2; dst[c + 3 * lpr] = v3;
+        }
+        for (; c < vec_per_row; c += lpr) dst[c] = src[c];
     }
 }
 
@@ -438,10 +457,10 @@ static int permute_impl(const int32_t *ids_dev, const int32_t *inst_ptr_dev, con
                                                             row_of_dev, src_of_dev, err_flag_dev, split));
     RELIBRA_HIP_TRY(launch_check());
     if (with_rows) {
-        const int vpr = h / 8;
-        const int grid = grid_for((size_t)N * vpr, 256 * 4, 256 * 64);
-        RELIBRA_LAUNCH(RELIBRA_K_GATHER, stream, gather_rows_kernel<<<grid, 256, 0, stream>>>((const uint4 *)X_dev, src_of_dev, N, T, k, vpr,
-                                                     (uint4 *)Xrows_dev));
+        const int vpr = h / 8, lpr_log2 = lanes_per_row_log2(vpr, 4);
+        const int grid = grid_for((size_t)N, kRowThreads >> lpr_log2, 256 * 32);
+        RELIBRA_LAUNCH(RELIBRA_K_GATHER, stream, gather_rows_kernel<<<grid, kRowThreads, 0, stream>>>((const uint4 *)X_dev, src_of_dev, N, T, k, vpr,
+                                                     lpr_log2, (uint4 *)Xrows_dev));
         RELIBRA_HIP_TRY(launch_check());
     }
     return RELIBRA_OK;
