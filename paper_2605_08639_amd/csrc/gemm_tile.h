@@ -61,6 +61,14 @@ __device__ __forceinline__ void load_lds16(const bf16_t *g, char *block)
     const uint32_t m = (uint32_t)(uintptr_t)RELIBRA_LDS(block);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(m) : "memory", "m0");
 }
+// The same load with the address split into a wave-uniform base (scalar register pair) and a
+// 32-bit per-lane byte offset: when only the uniform part changes from slab to slab, the k-loop
+// spends no vector instruction on addresses.
+__device__ __forceinline__ void load_lds16_sv(const bf16_t *uniform_base, uint32_t lane_byte_off, char *block)
+{
+    const uint32_t m = (uint32_t)(uintptr_t)RELIBRA_LDS(block);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_byte_off), "s"(uniform_base), "s"(m) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 
 struct Operand {
@@ -128,8 +136,8 @@ struct KcTile {
     struct Idx {};                                     // nothing to look up per slab
     template <int NW>
     static __device__ __forceinline__ void fetch(Idx<NW> &, const Lanes<NW> &, int, int, int) {}
-    // load block number i (0 .. BLOCKS/NW - 1) of this wave's share of a slab
-    template <int NW>
+    // load block number i (0 .. BLOCKS/NW - 1) of this wave's share of a slab (the same in the steady state)
+    template <int NW, bool STEADY = false>
     static __device__ __forceinline__ void load_one(char *lds, const Lanes<NW> &ln, const Idx<NW> &, int k0, int /*k_last*/, int wave,
                                                     int /*lane*/, int i)
     {
@@ -178,12 +186,26 @@ struct KsTile {
 
     static __device__ __forceinline__ int fk(int k) { return (((k & 1) * 10) ^ (((k >> 1) & 1) * 4)) & (SPR - 1); }
 
+    // The piece of a k-row a lane loads is XOR-ed with fk(k), which depends on k mod 4 only; with
+    // the blocks dealt to the waves round robin and a number of waves divisible by four, k mod 4 of
+    // a lane's k-row is the same in every block the wave loads, so the lane-dependent part of the
+    // address is ONE constant: lane_off, in bytes from the first element of the block's first k-row.
+    template <int NW>
+    static constexpr bool steady_ok() { return !MAY_GATHER && NW % 4 == 0 && (KPB == 1 || KPB == 2 || KPB % 4 == 0); }
     template <int NW>
     struct Lanes {
         Operand op;
+        uint32_t lane_off;
     };
     template <int NW>
-    static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int /*wave*/, int /*lane*/) { return Lanes<NW>{op}; }
+    static __device__ __forceinline__ Lanes<NW> prepare(const Operand &op, int wave, int lane)
+    {
+        const int kq = lane / SPR;
+        const int s = (lane % SPR) ^ fk(block_of<NW>(wave, 0) * KPB + kq);
+        int grow = op.row0 + s * 8;
+        if (grow > op.row_last) grow = op.row_last - 7;
+        return Lanes<NW>{op, (uint32_t)(((long long)kq * op.ld + grow) * 2)};
+    }
 
     // A gathered operand (contraction index -> row of `base`) needs, per slab, the rows of the KPB
     // k-rows of each of this wave's load blocks: fetched as scalars (fetch) ahead of the loads, in
@@ -217,13 +239,19 @@ struct KsTile {
     // load block holds KPB k-rows: the rows (clamped, or looked up when the operand is gathered) and
     // their offsets are worked out with scalar instructions, one select per further k-row picks a
     // lane's own, and gathered and plain operands run the same branch-free sequence.
-    template <int NW>
+    // STEADY: the caller guarantees that every k-row of the slab exists (k0 + DEPTH - 1 <= k_last) and
+    // that the operand has no row table; the address is then a uniform base plus the lane's constant.
+    template <int NW, bool STEADY = false>
     static __device__ __forceinline__ void load_one(char *lds, const Lanes<NW> &ln, const Idx<NW> &ix, int k0, int k_last, int wave,
                                                     int lane, int i)
     {
         static_assert(BLOCKS % NW == 0, "k-rows must split evenly over the waves");
         const Operand &op = ln.op;
         const int j = block_of<NW>(wave, i);
+        if (STEADY && steady_ok<NW>()) {
+            load_lds16_sv(op.base + (long long)(k0 + j * KPB) * op.ld, ln.lane_off, lds + j * 1024);
+            return;
+        }
         const int kq = lane / SPR;                  // which of the block's k-rows this lane loads from
         const int s = (lane % SPR) ^ fk(j * KPB + kq);
         int grow = op.row0 + s * 8;
@@ -392,6 +420,7 @@ struct KLoop {
     // Load number j (0 .. LOADS-1) of this wave's share of slab t: A-side operands first, or, with
     // B_FIRST, last (an operand gathered through per-slab row lookups belongs in the later part of
     // the window, where its lookups have had time to arrive).
+    template <bool STEADY = false>
     static __device__ __forceinline__ void issue_one(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
                                                      const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane, int j)
     {
@@ -401,10 +430,10 @@ struct KLoop {
         const bool a_side = B_FIRST ? j >= NB * LB : j < NA * LA;
         if (a_side) {
             const int ja = B_FIRST ? j - NB * LB : j, a = ja / LA;
-            AT::template load_one<NW>(stage + a * AT::BYTES, PA[q][a], lk.a[a], k0, k_last, wave, lane, ja % LA);
+            AT::template load_one<NW, STEADY>(stage + a * AT::BYTES, PA[q][a], lk.a[a], k0, k_last, wave, lane, ja % LA);
         } else {
             const int jb = B_FIRST ? j : j - NA * LA, b = jb / LB;
-            BT::template load_one<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane, jb % LB);
+            BT::template load_one<NW, STEADY>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane, jb % LB);
         }
     }
 
@@ -495,6 +524,16 @@ struct KLoop {
         }
     }
 
+    // One trip of the steady state: slabs t .. t+STAGES-1 in ring slots 1, 2, .., 0 (t % STAGES == 1).
+    template <class Slab, int U>
+    static __device__ __forceinline__ void steady_trip(const Slab &slab, int t, std::integral_constant<int, U>)
+    {
+        if constexpr (U < STAGES) {
+            slab(std::true_type{}, std::integral_constant<int, (1 + U) % STAGES>{}, t + U);
+            steady_trip(slab, t, std::integral_constant<int, U + 1>{});
+        }
+    }
+
     // k extent per phase = steps_per_phase * DEPTH; k_valid (<= that) is the ragged contraction length.
     static __device__ __forceinline__ void run(Acc &acc, const Operand (&A)[NPH][NA], const Operand (&B)[NPH][NB],
                                                int steps_per_phase, int k_valid, char *lds, int tid)
@@ -522,20 +561,32 @@ struct KLoop {
         read_frags(f[0], lds, 0, wa, wb, lane);
         int slot = 0;
         if (SPREAD) {
-            // Two copies of the slab iteration: the steady state, where both load windows are live
-            // and the loads carry no branch (measured: the branches alone cost 5 %), and the
-            // general one for the first slab and the last STAGES.
+            // Copies of the slab iteration: the steady state, where both load windows are live, the
+            // loads carry no branch (measured: the branches alone cost 5 %), no k-row needs clamping
+            // and the ring slot is a compile-time constant (LDS addresses become immediates, operand
+            // addresses a uniform base plus a per-lane constant: the steady state spends no vector
+            // instruction on addresses) - one copy per ring slot, run STAGES slabs per trip - and the
+            // general one (ring slot in a register) for the first slab and the last few.
             char *prv = lds;
-            auto slab = [&](auto steady, int t) __attribute__((always_inline)) {
+            auto slab = [&](auto steady, auto slot_c, int t) __attribute__((always_inline)) {
                 constexpr bool SS = decltype(steady)::value;
+                constexpr int SLOT = decltype(slot_c)::value;          // -1: the ring slot is the variable `slot`
                 const bool ls = SS || (t >= 1 && t - 1 + STAGES < n), ll = SS || t + STAGES < n;
-                char *cur = lds + slot * STAGE_BYTES;
-                slot = (slot == STAGES - 1) ? 0 : slot + 1;
-                char *nxt = lds + slot * STAGE_BYTES;
-                const bool tail = RAGGED_K && (t + 1) * DEPTH > k_valid;
+                char *cur, *nxt, *before;
+                if (SLOT >= 0) {
+                    cur = lds + SLOT * STAGE_BYTES;
+                    nxt = lds + ((SLOT + 1) % STAGES) * STAGE_BYTES;
+                    before = lds + ((SLOT + STAGES - 1) % STAGES) * STAGE_BYTES;
+                } else {
+                    cur = lds + slot * STAGE_BYTES;
+                    slot = (slot == STAGES - 1) ? 0 : slot + 1;
+                    nxt = lds + slot * STAGE_BYTES;
+                    before = prv;
+                }
+                const bool tail = !SS && RAGGED_K && (t + 1) * DEPTH > k_valid;
                 const int kf = t * DEPTH + (lane >> 5) * 8;
                 // steps 0 .. KSTEPS-2: the rest of the loads of slab t-1+STAGES, into slab t-1's place
-                auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one(prv, PA, PB, lk, t - 1 + STAGES, steps_per_phase, k_last, wave, lane, j); };
+                auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one<SS>(before, PA, PB, lk, t - 1 + STAGES, steps_per_phase, k_last, wave, lane, j); };
 #pragma unroll
                 for (int s = 0; s < KSTEPS - 1; ++s) {
                     __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): f[s & 1] is there
@@ -544,7 +595,8 @@ struct KLoop {
                     __builtin_amdgcn_sched_barrier(0);
                     step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur, s + 1, wa, wb, lane, s + 1, ls, load_prev);
                 }
-                wait_younger(n - t - 2);       // slab t+1 has landed; later slabs may still be in flight
+                if (SS) wait_younger(STAGES);  // slab t+1 has landed; later slabs may still be in flight
+                else wait_younger(n - t - 2);
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
                 // Row lookups of the next window, requested behind the barrier (in front of it its
@@ -552,16 +604,22 @@ struct KLoop {
                 // side has its loads in the later part of the window, a step's MFMAs from here.
                 if (ll) fetch(lk, PA, PB, t + STAGES, steps_per_phase, k_last, wave);
                 // last step: the first loads of slab t+STAGES, into this slab's place
-                auto load_cur = [&](int j) __attribute__((always_inline)) { issue_one(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane, j); };
+                auto load_cur = [&](int j) __attribute__((always_inline)) { issue_one<SS>(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane, j); };
                 constexpr int L = (KSTEPS - 1) & 1;
                 if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, k_valid);
                 step_spread<SS>(acc, f[L], f[0], nxt, 0, wa, wb, lane, 0, ll, load_cur);
-                prv = cur;
+                if (SLOT < 0) prv = cur;
             };
-            slab(std::false_type{}, 0);
+            constexpr auto dyn = std::integral_constant<int, -1>{};
+            slab(std::false_type{}, dyn, 0);
             int t = 1;
-            for (; t < n - STAGES; ++t) slab(std::true_type{}, t);
-            for (; t < n; ++t) slab(std::false_type{}, t);
+            // Steady trips: slab t sits in ring slot t % STAGES (t = 1 in slot 1); a trip leaves `slot`
+            // and `prv` as they are.  The loads a steady slab issues are those of slabs t-1+STAGES and
+            // t+STAGES, which must be whole (no clamped k-rows): the last slab of a ragged contraction
+            // is left to the general copy.
+            const int steady_end = n - STAGES - (RAGGED_K ? 1 : 0);
+            for (; t + STAGES <= steady_end; t += STAGES) steady_trip(slab, t, std::integral_constant<int, 0>{});
+            for (; t < n; ++t) slab(std::false_type{}, dyn, t);
             return;
         }
         for (int t = 0; t < n; ++t) {
