@@ -11,6 +11,9 @@ SOURCES = ["route_kernels.hip", "ffn_kernels.hip", "replica_kernels.hip", "prof.
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # loop heads on 32-byte boundaries: the batched weight-gradient k-loop measured 6 % slower when a
+         # change elsewhere in the file moved it to an unaligned address
+         "-falign-loops=32",
          "-Wall", "-Wno-unused-function"]
 
 

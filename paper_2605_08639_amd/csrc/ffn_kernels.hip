@@ -60,8 +60,17 @@ constexpr int kLdsBytes = NSTAGES * (256 + BM) * BK * 2;   // NSTAGES slabs of 2
 // wave and slab instead of six, one of them instead of two on the half-line k-contiguous rows);
 // measured on dense problems of these shapes: 17-20 % faster.
 constexpr int kWideRowWaves = 8;
-constexpr int kLdsBytesWide = 8 * 64 * 128 * 2;            // the epilogue's staging (8 waves x 64 x 128 bf16) exceeds the 3 slabs of 512 + 128 rows
-static_assert(kLdsBytesWide >= NSTAGES * (512 + BM) * BK * 2, "slabs fit");
+// In the wide tiles the rows (the k-contiguous operand) are staged 64 k-values deep, in full 128-byte
+// lines, through a ring of their own (KLoop, deep B side): three slabs of 512 weight rows plus three
+// 64-deep tiles of 128 rows.
+#ifndef RELIBRA_DEEP_ROWS
+#define RELIBRA_DEEP_ROWS 1
+#endif
+constexpr bool kDeepRows = RELIBRA_DEEP_ROWS != 0;
+constexpr int kRowDepthWide = kDeepRows ? 2 * BK : BK;
+constexpr int kLdsBytesWide = kDeepRows ? NSTAGES * 512 * BK * 2 + ((NSTAGES + 3) / 2) * BM * 2 * BK * 2 : 8 * 64 * 128 * 2;
+static_assert(kLdsBytesWide >= NSTAGES * (512 + BM) * BK * 2 && kLdsBytesWide >= 8 * 64 * 128 * 2 && kLdsBytesWide <= 160 * 1024,
+              "slabs and the epilogue's staging (8 waves x 64 x 128 bf16) fit");
 constexpr int kDgateParts = 4;                 // partial gate-gradient sums per row and 256-column tile (one per wave column at most)
 inline size_t dgate_scratch_bytes(int n_rows, int hff) { return round256((size_t)kDgateParts * ((hff + 255) / 256) * n_rows * sizeof(float)); }
 inline size_t sched_ints(int n_rows, int Gr) { return 8 + 4 * (size_t)Gr + (Gr + 1) + 4 * (size_t)max_row_tiles(n_rows, Gr) + 2 * (size_t)Gr; }
@@ -370,7 +379,7 @@ __device__ __forceinline__ void fwd_gate_up_body(const RowTile &t, const bf16_t 
     constexpr int NWV = AW == 128 ? NWAVES : kWideRowWaves;
     using WV = Waves<BB, NWV>;
     using WTile = typename std::conditional<WT, KsTile<AW>, KcTile<AW>>::type;
-    using KL = KLoop<WTile, KcTile<BB>, 2, 1, AW, BB, WV::A, WV::B, 1, false, NSTAGES, kSpreadLoads>;
+    using KL = KLoop<WTile, KcTile<BB, (AW == 128 ? BK : kRowDepthWide)>, 2, 1, AW, BB, WV::A, WV::B, 1, false, NSTAGES, kSpreadLoads>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t wofs = (size_t)t.expert * hff * h;
     const int ldw = WT ? hff : h;                             // (n in h', k in h) at [n*h + k], or at [k*h' + n]
@@ -460,7 +469,7 @@ __device__ __forceinline__ void row_gemm_body(const RowTile &t, const bf16_t *P0
     constexpr int NWV = AW == 256 ? NWAVES : kWideRowWaves;
     using WV = Waves<BB, NWV>;
     using WT = typename std::conditional<W_KS, KsTile<AW>, KcTile<AW>>::type;
-    using KL = KLoop<WT, KcTile<BB>, 1, 1, AW, BB, WV::A, WV::B, NPH, false, NSTAGES, kSpreadLoads>;
+    using KL = KLoop<WT, KcTile<BB, (AW == 256 ? BK : kRowDepthWide)>, 1, 1, AW, BB, WV::A, WV::B, NPH, false, NSTAGES, kSpreadLoads>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Operand A[NPH][1], B[NPH][1];
     A[0][0] = {W0, ldw, t.col0, n_dim - 1};

@@ -158,6 +158,47 @@ struct KcTile {
         const int c = (kk * 2 + (lane >> 5)) ^ swz(lane & 31);
         return *reinterpret_cast<const bf16x8_t *>(lds + r * ROW_BYTES + c * 16);
     }
+
+    // Loading the tile in two halves (the load blocks of rows 0 .. ROWS/2-1, then the rest), for a
+    // k-loop whose slabs are half as deep as this tile (KLoop, "deep B side"): one half per slab
+    // period keeps the number of loads per wave and period constant while every request is a full
+    // 128-byte line (BKT = 64).
+    template <int NW>
+    static constexpr int per_wave_half() { return BLOCKS / 2 >= NW ? BLOCKS / 2 / NW : 1; }
+    template <int NW>
+    struct LanesHalf {
+        const bf16_t *p[2][per_wave_half<NW>()];
+    };
+    template <int NW>
+    static __device__ __forceinline__ LanesHalf<NW> prepare_half(const Operand &op, int wave, int lane)
+    {
+        static_assert(BLOCKS % 2 == 0 && ((BLOCKS / 2) % NW == 0 || NW % (BLOCKS / 2) == 0), "rows must split evenly over the waves");
+        LanesHalf<NW> ln;
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int i = 0; i < per_wave_half<NW>(); ++i) {
+                const int j = half * (BLOCKS / 2) + (wave + i * NW) % (BLOCKS / 2);
+                const int r = j * RPB + lane / PIECES;
+                const int c = (lane % PIECES) ^ swz(r);
+                int grow = min(op.row0 + r, op.row_last);
+                if (op.gather) grow = min(max(op.gather[grow], 0), op.gather_last);
+                ln.p[half][i] = op.base + (size_t)grow * op.ld + c * 8;
+            }
+        return ln;
+    }
+    // load block number i of this wave's share of half `half` (uniform) of the tile whose first k is k0
+    template <int NW>
+    static __device__ __forceinline__ void load_half_one(char *lds, const LanesHalf<NW> &ln, int k0, int wave, int half, int i)
+    {
+        // both pointers are read with constant indices and blended by a mask: a select between the two
+        // array elements would be turned into a dynamically indexed load, i.e. the array into scratch
+        // memory, whose loads would also disturb the k-loop's hand-counted vmcnt
+        const uintptr_t a0 = (uintptr_t)ln.p[0][i], a1 = (uintptr_t)ln.p[1][i];
+        const uintptr_t m = (uintptr_t)0 - (uintptr_t)(half & 1);
+        const bf16_t *src = (const bf16_t *)((a0 & ~m) | (a1 & m));
+        load_lds16(src + k0, lds + (half * (BLOCKS / 2) + (wave + i * NW) % (BLOCKS / 2)) * 1024);
+    }
 };
 
 // k-strided operand: LDS [k][ROWS] as in memory; 16-byte pieces of a k-row XOR-ed with fk(k) so
@@ -318,11 +359,25 @@ struct KLoop {
     static constexpr int NW = WA * WB;
     static constexpr int DEPTH = AT::DEPTH;           // k-values per slab
     static constexpr int KSTEPS = DEPTH / 16;          // MFMA steps per slab
-    static_assert(AT::DEPTH == BT::DEPTH && KSTEPS >= 2 && KSTEPS % 2 == 0, "slab depth");
+    // Deep B side (BD): the B tiles are twice as deep as a slab (a k-contiguous operand with 64
+    // k-values per row is fetched in full 128-byte lines; with 32 every request is half a line and
+    // costs the address unit a whole one).  B tile U serves slabs 2U and 2U+1 from a ring of its
+    // own behind the A ring; it is loaded in two halves (KcTile::load_half_one), one per slab
+    // period, so that a wave issues the same number of loads in every period: the period that
+    // fills the A slab of slab w also fetches half (w+1) % 2 of B tile (w+1) / 2.  Row kernels only:
+    // no ragged contraction, an even number of slabs per phase, spread loads.
+    static constexpr bool BD = BT::DEPTH == 2 * AT::DEPTH;
+    static_assert((AT::DEPTH == BT::DEPTH || BD) && KSTEPS >= 2 && KSTEPS % 2 == 0, "slab depth");
+    static_assert(!BD || (!RAGGED_K && SPREAD && STAGES >= 3), "deep B side: row kernels");
     static constexpr int TA = BA / WA / 32, TB = BB / WB / 32;
-    static constexpr int STAGE_BYTES = NA * AT::BYTES + NB * BT::BYTES;
-    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static constexpr int LA = AT::template per_wave<NW>(), LB = BT::template per_wave<NW>();
+    static constexpr int A_STAGE = NA * AT::BYTES, B_STAGE = NB * BT::BYTES;
+    static constexpr int STAGE_BYTES = BD ? A_STAGE : A_STAGE + B_STAGE;      // stride of the (A) ring
+    static constexpr int SB = (STAGES + 3) / 2;        // B ring depth (BD): tile U - SB is dead when tile U's first half is issued
+    static constexpr int B_RING = STAGES * A_STAGE;    // offset of the B ring (BD)
+    static constexpr int LDS_BYTES = BD ? STAGES * A_STAGE + SB * B_STAGE : STAGES * STAGE_BYTES;
+    template <class T, bool DEEP> struct PerWaveB { static constexpr int N = T::template per_wave<NW>(); };
+    template <class T> struct PerWaveB<T, true> { static constexpr int N = T::template per_wave_half<NW>(); };
+    static constexpr int LA = AT::template per_wave<NW>(), LB = PerWaveB<BT, BD>::N;
     static constexpr int LOADS = NA * LA + NB * LB;   // per wave per slab
     typedef f32x16_t Acc[NA * NB][TA][TB];
 
@@ -330,10 +385,38 @@ struct KLoop {
         bf16x8_t a[NA][TA], b[NB][TB];
     };
 
+    template <class T, bool DEEP> struct LanesOfB { typedef typename T::template Lanes<NW> type; };
+    template <class T> struct LanesOfB<T, true> { typedef typename T::template LanesHalf<NW> type; };
     typedef typename AT::template Lanes<NW> LanesA;
-    typedef typename BT::template Lanes<NW> LanesB;
+    typedef typename LanesOfB<BT, BD>::type LanesB;
     typedef typename AT::template Idx<NW> IdxA;
     typedef typename BT::template Idx<NW> IdxB;
+
+    // Where slab t's operands sit in LDS: the A tiles, the B tiles, and the MFMA step of the B
+    // tile that is the slab's first (BD: the second slab of a B tile starts at step KSTEPS).
+    struct Where {
+        char *a, *b;
+        int kb;
+    };
+    static __device__ __forceinline__ Where where(char *lds, int slot, int t)
+    {
+        if (BD) return Where{lds + slot * A_STAGE, lds + B_RING + ((t >> 1) % SB) * B_STAGE, (t & 1) * KSTEPS};
+        return Where{lds + slot * STAGE_BYTES, lds + slot * STAGE_BYTES + A_STAGE, 0};
+    }
+    // BD: the B loads of the period that fills slab w's A tiles: half (w+1) % 2 of B tile (w+1) / 2; past the last
+    // tile the last tile's first half again (same bytes to the same place), so that every period has LOADS loads.
+    struct BWindow {
+        char *tile;
+        int k0, half, q;
+    };
+    static __device__ __forceinline__ BWindow b_window(char *lds, int w, int steps_per_phase, int n)
+    {
+        const int tiles = n >> 1;
+        const int u = min((w + 1) >> 1, tiles - 1);
+        const int ph = (NPH == 1) ? 0 : (2 * u >= steps_per_phase ? 1 : 0);
+        return BWindow{lds + B_RING + (u % SB) * B_STAGE, (u - ph * (steps_per_phase >> 1)) * BT::DEPTH, (w + 1) & 1,
+                       (NPH == 1 || ph == 0) ? 0 : NPH - 1};
+    }
     struct Lookups {                                    // per-slab row lookups of gathered k-strided operands
         IdxA a[NA];
         IdxB b[NB];
@@ -347,7 +430,10 @@ struct KLoop {
 #pragma unroll
             for (int a = 0; a < NA; ++a) PA[ph][a] = AT::template prepare<NW>(A[ph][a], wave, lane);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) PB[ph][b] = BT::template prepare<NW>(B[ph][b], wave, lane);
+            for (int b = 0; b < NB; ++b) {
+                if constexpr (BD) PB[ph][b] = BT::template prepare_half<NW>(B[ph][b], wave, lane);
+                else PB[ph][b] = BT::template prepare<NW>(B[ph][b], wave, lane);
+            }
         }
     }
 
@@ -361,48 +447,55 @@ struct KLoop {
         if (NPH == 1 || ph == 0) {
 #pragma unroll
             for (int a = 0; a < NA; ++a) AT::template fetch<NW>(lk.a[a], PA[0][a], k0, k_last, wave);
+            if constexpr (!BD) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) BT::template fetch<NW>(lk.b[b], PB[0][b], k0, k_last, wave);
+                for (int b = 0; b < NB; ++b) BT::template fetch<NW>(lk.b[b], PB[0][b], k0, k_last, wave);
+            }
         } else {
 #pragma unroll
             for (int a = 0; a < NA; ++a) AT::template fetch<NW>(lk.a[a], PA[NPH - 1][a], k0, k_last, wave);
+            if constexpr (!BD) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) BT::template fetch<NW>(lk.b[b], PB[NPH - 1][b], k0, k_last, wave);
+                for (int b = 0; b < NB; ++b) BT::template fetch<NW>(lk.b[b], PB[NPH - 1][b], k0, k_last, wave);
+            }
         }
     }
 
+    // All loads of the period that fills slab t's A tiles (ring slot at `stage`), in one burst.
     static __device__ __forceinline__ void issue(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
                                                  const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane)
     {
         const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
         const int k0 = (t - ph * steps_per_phase) * DEPTH;
-        if (NPH == 1 || ph == 0) {
+        if constexpr (!BD) {
+            if (NPH == 1 || ph == 0) {
 #pragma unroll
-            for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[0][a], lk.a[a], k0, k_last, wave, lane);
+                for (int a = 0; a < NA; ++a) AT::template load<NW>(stage + a * AT::BYTES, PA[0][a], lk.a[a], k0, k_last, wave, lane);
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[0][b], lk.b[b], k0, k_last, wave, lane);
-        } else {
+                for (int b = 0; b < NB; ++b)
+                    BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[0][b], lk.b[b], k0, k_last, wave, lane);
+            } else {
 #pragma unroll
-            for (int a = 0; a < NA; ++a)
-                AT::template load<NW>(stage + a * AT::BYTES, PA[NPH - 1][a], lk.a[a], k0, k_last, wave, lane);
+                for (int a = 0; a < NA; ++a)
+                    AT::template load<NW>(stage + a * AT::BYTES, PA[NPH - 1][a], lk.a[a], k0, k_last, wave, lane);
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[NPH - 1][b], lk.b[b], k0, k_last, wave, lane);
+                for (int b = 0; b < NB; ++b)
+                    BT::template load<NW>(stage + NA * AT::BYTES + b * BT::BYTES, PB[NPH - 1][b], lk.b[b], k0, k_last, wave, lane);
+            }
         }
     }
 
-    static __device__ __forceinline__ void read_frags(Frags &f, const char *stage, int kk, int wa, int wb, int lane)
+    static __device__ __forceinline__ void read_frags(Frags &f, const Where &at, int kk, int wa, int wb, int lane)
     {
 #pragma unroll
         for (int a = 0; a < NA; ++a)
 #pragma unroll
-            for (int t = 0; t < TA; ++t) f.a[a][t] = AT::frag(stage + a * AT::BYTES, wa * (BA / WA) + t * 32, kk, lane);
+            for (int t = 0; t < TA; ++t) f.a[a][t] = AT::frag(at.a + a * AT::BYTES, wa * (BA / WA) + t * 32, kk, lane);
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int t = 0; t < TB; ++t)
-                f.b[b][t] = BT::frag(stage + NA * AT::BYTES + b * BT::BYTES, wb * (BB / WB) + t * 32, kk, lane);
+                f.b[b][t] = BT::frag(at.b + b * BT::BYTES, wb * (BB / WB) + t * 32, at.kb + kk, lane);
     }
 
     static __device__ __forceinline__ void mask_frags(Frags &f, int k_first, int k_valid)
@@ -420,9 +513,11 @@ struct KLoop {
     // Load number j (0 .. LOADS-1) of this wave's share of slab t: A-side operands first, or, with
     // B_FIRST, last (an operand gathered through per-slab row lookups belongs in the later part of
     // the window, where its lookups have had time to arrive).
+    // stage: the ring slot of slab t's A tiles; lds: the ring's base; n: slabs of the whole loop (BD only).
     template <bool STEADY = false>
     static __device__ __forceinline__ void issue_one(char *stage, const LanesA (&PA)[NPH][NA], const LanesB (&PB)[NPH][NB],
-                                                     const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane, int j)
+                                                     const Lookups &lk, int t, int steps_per_phase, int k_last, int wave, int lane, int j,
+                                                     char *lds = nullptr, int n = 0)
     {
         const int ph = (NPH == 1) ? 0 : (t >= steps_per_phase ? 1 : 0);
         const int k0 = (t - ph * steps_per_phase) * DEPTH;
@@ -433,20 +528,25 @@ struct KLoop {
             AT::template load_one<NW, STEADY>(stage + a * AT::BYTES, PA[q][a], lk.a[a], k0, k_last, wave, lane, ja % LA);
         } else {
             const int jb = B_FIRST ? j : j - NA * LA, b = jb / LB;
-            BT::template load_one<NW, STEADY>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane, jb % LB);
+            if constexpr (BD) {
+                const BWindow bw = b_window(lds, t, steps_per_phase, n);
+                BT::template load_half_one<NW>(bw.tile + b * BT::BYTES, PB[bw.q][b], bw.k0, wave, bw.half, jb % LB);
+            } else {
+                BT::template load_one<NW, STEADY>(stage + NA * AT::BYTES + b * BT::BYTES, PB[q][b], lk.b[b], k0, k_last, wave, lane, jb % LB);
+            }
         }
     }
 
     // Fragment number j (0 .. N_FRAGS-1) of MFMA step kk: A side first.
     static constexpr int N_FRAGS = NA * TA + NB * TB;
-    static __device__ __forceinline__ void read_frag_one(Frags &f, const char *stage, int kk, int wa, int wb, int lane, int j)
+    static __device__ __forceinline__ void read_frag_one(Frags &f, const Where &at, int kk, int wa, int wb, int lane, int j)
     {
         if (j < NA * TA) {
             const int a = j / TA, t = j % TA;
-            f.a[a][t] = AT::frag(stage + a * AT::BYTES, wa * (BA / WA) + t * 32, kk, lane);
+            f.a[a][t] = AT::frag(at.a + a * AT::BYTES, wa * (BA / WA) + t * 32, kk, lane);
         } else {
             const int b = (j - NA * TA) / TB, t = (j - NA * TA) % TB;
-            f.b[b][t] = BT::frag(stage + NA * AT::BYTES + b * BT::BYTES, wb * (BB / WB) + t * 32, kk, lane);
+            f.b[b][t] = BT::frag(at.b + b * BT::BYTES, wb * (BB / WB) + t * 32, at.kb + kk, lane);
         }
     }
 
@@ -490,7 +590,7 @@ struct KLoop {
     // part = 0 for the last step of a slab, s + 1 for step s < KSTEPS - 1.
     // ALWAYS: the loads are issued unconditionally (steady state); otherwise if do_load.
     template <bool ALWAYS, class LoadFn>
-    static __device__ __forceinline__ void step_spread(Acc &acc, const Frags &fc, Frags &fn, const char *rd_stage, int rd_kk, int wa,
+    static __device__ __forceinline__ void step_spread(Acc &acc, const Frags &fc, Frags &fn, const Where &rd_stage, int rd_kk, int wa,
                                                        int wb, int lane, int part, bool do_load, const LoadFn &load_j)
     {
         constexpr int SPAN = N_MFMA >= 4 ? N_MFMA - N_MFMA / 4 : N_MFMA;
@@ -549,18 +649,31 @@ struct KLoop {
         prepare(PA, PB, A, B, wave, lane);
         Lookups lk;
         Frags f[2];
+        if constexpr (BD) {
+            // the first half of B tile 0 belongs to no period of the loop: it goes first
 #pragma unroll
-        for (int i = 0; i < STAGES; ++i)
-            if (i < n) {
-                fetch(lk, PA, PB, i, steps_per_phase, k_last, wave);
-                issue(lds + i * STAGE_BYTES, PA, PB, lk, i, steps_per_phase, k_last, wave, lane);
-            }
+            for (int j = 0; j < LOADS; ++j)
+                if ((B_FIRST ? j < NB * LB : j >= NA * LA)) issue_one(lds, PA, PB, lk, -1, steps_per_phase, k_last, wave, lane, j, lds, n);
+#pragma unroll
+            for (int i = 0; i < STAGES; ++i)
+                if (i < n) {
+#pragma unroll
+                    for (int j = 0; j < LOADS; ++j) issue_one(lds + i * STAGE_BYTES, PA, PB, lk, i, steps_per_phase, k_last, wave, lane, j, lds, n);
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < STAGES; ++i)
+                if (i < n) {
+                    fetch(lk, PA, PB, i, steps_per_phase, k_last, wave);
+                    issue(lds + i * STAGE_BYTES, PA, PB, lk, i, steps_per_phase, k_last, wave, lane);
+                }
+        }
         wait_younger(n - 1);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(f[0], lds, 0, wa, wb, lane);
+        read_frags(f[0], where(lds, 0, 0), 0, wa, wb, lane);
         int slot = 0;
-        if (SPREAD) {
+        if constexpr (SPREAD) {
             // Copies of the slab iteration: the steady state, where both load windows are live, the
             // loads carry no branch (measured: the branches alone cost 5 %), no k-row needs clamping
             // and the ring slot is a compile-time constant (LDS addresses become immediates, operand
@@ -572,28 +685,31 @@ struct KLoop {
                 constexpr bool SS = decltype(steady)::value;
                 constexpr int SLOT = decltype(slot_c)::value;          // -1: the ring slot is the variable `slot`
                 const bool ls = SS || (t >= 1 && t - 1 + STAGES < n), ll = SS || t + STAGES < n;
-                char *cur, *nxt, *before;
+                char *cur, *before;
+                Where cur_at, nxt_at;
                 if (SLOT >= 0) {
                     cur = lds + SLOT * STAGE_BYTES;
-                    nxt = lds + ((SLOT + 1) % STAGES) * STAGE_BYTES;
+                    cur_at = where(lds, SLOT, t);
+                    nxt_at = where(lds, (SLOT + 1) % STAGES, t + 1);
                     before = lds + ((SLOT + STAGES - 1) % STAGES) * STAGE_BYTES;
                 } else {
                     cur = lds + slot * STAGE_BYTES;
+                    cur_at = where(lds, slot, t);
                     slot = (slot == STAGES - 1) ? 0 : slot + 1;
-                    nxt = lds + slot * STAGE_BYTES;
+                    nxt_at = where(lds, slot, t + 1);
                     before = prv;
                 }
                 const bool tail = !SS && RAGGED_K && (t + 1) * DEPTH > k_valid;
                 const int kf = t * DEPTH + (lane >> 5) * 8;
                 // steps 0 .. KSTEPS-2: the rest of the loads of slab t-1+STAGES, into slab t-1's place
-                auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one<SS>(before, PA, PB, lk, t - 1 + STAGES, steps_per_phase, k_last, wave, lane, j); };
+                auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one<SS>(before, PA, PB, lk, t - 1 + STAGES, steps_per_phase, k_last, wave, lane, j, lds, n); };
 #pragma unroll
                 for (int s = 0; s < KSTEPS - 1; ++s) {
                     __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): f[s & 1] is there
                     __builtin_amdgcn_sched_barrier(0);
                     if (tail) mask_frags(f[s & 1], kf + s * 16, k_valid);
                     __builtin_amdgcn_sched_barrier(0);
-                    step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur, s + 1, wa, wb, lane, s + 1, ls, load_prev);
+                    step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur_at, s + 1, wa, wb, lane, s + 1, ls, load_prev);
                 }
                 if (SS) wait_younger(STAGES);  // slab t+1 has landed; later slabs may still be in flight
                 else wait_younger(n - t - 2);
@@ -604,10 +720,10 @@ struct KLoop {
                 // side has its loads in the later part of the window, a step's MFMAs from here.
                 if (ll) fetch(lk, PA, PB, t + STAGES, steps_per_phase, k_last, wave);
                 // last step: the first loads of slab t+STAGES, into this slab's place
-                auto load_cur = [&](int j) __attribute__((always_inline)) { issue_one<SS>(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane, j); };
+                auto load_cur = [&](int j) __attribute__((always_inline)) { issue_one<SS>(cur, PA, PB, lk, t + STAGES, steps_per_phase, k_last, wave, lane, j, lds, n); };
                 constexpr int L = (KSTEPS - 1) & 1;
                 if (tail) mask_frags(f[L], kf + (KSTEPS - 1) * 16, k_valid);
-                step_spread<SS>(acc, f[L], f[0], nxt, 0, wa, wb, lane, 0, ll, load_cur);
+                step_spread<SS>(acc, f[L], f[0], nxt_at, 0, wa, wb, lane, 0, ll, load_cur);
                 if (SLOT < 0) prv = cur;
             };
             constexpr auto dyn = std::integral_constant<int, -1>{};
@@ -620,12 +736,12 @@ struct KLoop {
             const int steady_end = n - STAGES - (RAGGED_K ? 1 : 0);
             for (; t + STAGES <= steady_end; t += STAGES) steady_trip(slab, t, std::integral_constant<int, 0>{});
             for (; t < n; ++t) slab(std::false_type{}, dyn, t);
-            return;
-        }
+        } else {
         for (int t = 0; t < n; ++t) {
             char *cur = lds + slot * STAGE_BYTES;
+            const Where cur_at = where(lds, slot, t);
             slot = (slot == STAGES - 1) ? 0 : slot + 1;
-            char *nxt = lds + slot * STAGE_BYTES;
+            const Where nxt = where(lds, slot, t + 1);
             const bool tail = RAGGED_K && (t + 1) * DEPTH > k_valid;
             const int kf = t * DEPTH + (lane >> 5) * 8;
 #pragma unroll
@@ -637,7 +753,7 @@ struct KLoop {
                 __builtin_amdgcn_sched_barrier(0);
                 if (tail) mask_frags(f[s & 1], kf + s * 16, k_valid);
                 __builtin_amdgcn_sched_barrier(0);
-                read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
+                read_frags(f[(s + 1) & 1], cur_at, s + 1, wa, wb, lane);
                 mfma_all(acc, f[s & 1]);
                 interleave_reads_with_mfmas();
                 __builtin_amdgcn_sched_barrier(0);
@@ -662,6 +778,7 @@ struct KLoop {
             mfma_range<N_MFMA / 2, N_MFMA>(acc, f[L]);
             __builtin_amdgcn_sched_barrier(0);
         }
+        }
     }
 
     // The same loop over a list of pieces of the contraction (single phase, ragged pieces): piece i
@@ -672,7 +789,7 @@ struct KLoop {
     template <class Src>
     static __device__ __forceinline__ void run_pieces(Acc &acc, const Src &src, int n_pieces, int total_slabs, char *lds, int tid)
     {
-        static_assert(NPH == 1 && RAGGED_K, "pieces: one phase, ragged contraction");
+        static_assert(NPH == 1 && RAGGED_K && !BD, "pieces: one phase, ragged contraction");
         const int lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int wa = wave / WB, wb = wave % WB;
@@ -712,7 +829,7 @@ struct KLoop {
         wait_younger(n - 1);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(f[0], lds, 0, wa, wb, lane);
+        read_frags(f[0], where(lds, 0, 0), 0, wa, wb, lane);
         int slot = 0;
         if (SPREAD) {
             // as in run(): the load cursor stays on slab t+STAGES from the last step of slab t
@@ -722,8 +839,9 @@ struct KLoop {
                 constexpr bool SS = decltype(steady)::value;
                 const bool ls = SS || (t >= 1 && t - 1 + STAGES < n), ll = SS || t + STAGES < n;
                 char *cur = lds + slot * STAGE_BYTES;
+                const Where cur_at = where(lds, slot, 0);
                 slot = (slot == STAGES - 1) ? 0 : slot + 1;
-                char *nxt = lds + slot * STAGE_BYTES;
+                const Where nxt = where(lds, slot, 0);
                 const bool tail = (ct + 1) * DEPTH > c_valid;
                 const int kf = ct * DEPTH + (lane >> 5) * 8;
                 auto load_prev = [&](int j) __attribute__((always_inline)) { issue_one(prv, PA, PB, lk, it, i_slabs, i_valid - 1, wave, lane, j); };
@@ -733,7 +851,7 @@ struct KLoop {
                     __builtin_amdgcn_sched_barrier(0);
                     if (tail) mask_frags(f[s & 1], kf + s * 16, c_valid);
                     __builtin_amdgcn_sched_barrier(0);
-                    step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur, s + 1, wa, wb, lane, s + 1, ls, load_prev);
+                    step_spread<SS>(acc, f[s & 1], f[(s + 1) & 1], cur_at, s + 1, wa, wb, lane, s + 1, ls, load_prev);
                 }
                 if (ls) advance_loads();
                 wait_younger(n - t - 2);
@@ -760,8 +878,9 @@ struct KLoop {
         }
         for (int t = 0; t < n; ++t) {
             char *cur = lds + slot * STAGE_BYTES;
+            const Where cur_at = where(lds, slot, 0);
             slot = (slot == STAGES - 1) ? 0 : slot + 1;
-            char *nxt = lds + slot * STAGE_BYTES;
+            const Where nxt = where(lds, slot, 0);
             const bool tail = (ct + 1) * DEPTH > c_valid;
             const int kf = ct * DEPTH + (lane >> 5) * 8;
 #pragma unroll
@@ -772,7 +891,7 @@ struct KLoop {
                 if (s == 0 && t + STAGES < n) fetch_next();
                 if (tail) mask_frags(f[s & 1], kf + s * 16, c_valid);
                 __builtin_amdgcn_sched_barrier(0);
-                read_frags(f[(s + 1) & 1], cur, s + 1, wa, wb, lane);
+                read_frags(f[(s + 1) & 1], cur_at, s + 1, wa, wb, lane);
                 mfma_all(acc, f[s & 1]);
                 interleave_reads_with_mfmas();
                 __builtin_amdgcn_sched_barrier(0);
