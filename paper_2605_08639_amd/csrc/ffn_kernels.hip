@@ -7,8 +7,9 @@
 // compute unit, used where the wide tile divides the output width (the rows' slab is loaded once
 // for twice the columns).  A group's tail of at most 64 rows runs as a 64-row tile.  Operand slabs
 // of 32 k-values go global -> LDS directly (global_load_lds, 16 bytes per lane) through a ring of
-// three slabs (four in the wide weight-gradient tile); see gemm_tile.h for the tile layouts and
-// the pipeline.
+// three slabs (four in the wide weight-gradient tile); the wide row tiles stage their rows 64
+// k-values deep (full 128-byte lines) in a ring of their own, 144 KiB of LDS in all; see gemm_tile.h
+// for the tile layouts and the pipeline.
 //
 // MFMA operand roles: the lanes carry the index that is contiguous in the output's memory
 // only for the fp32 weight gradients (128-byte runs per store); for the bf16 row tensors the
