@@ -64,12 +64,8 @@ constexpr int kWideRowWaves = 8;
 // In the wide tiles the rows (the k-contiguous operand) are staged 64 k-values deep, in full 128-byte
 // lines, through a ring of their own (KLoop, deep B side): three slabs of 512 weight rows plus three
 // 64-deep tiles of 128 rows.
-#ifndef RELIBRA_DEEP_ROWS
-#define RELIBRA_DEEP_ROWS 1
-#endif
-constexpr bool kDeepRows = RELIBRA_DEEP_ROWS != 0;
-constexpr int kRowDepthWide = kDeepRows ? 2 * BK : BK;
-constexpr int kLdsBytesWide = kDeepRows ? NSTAGES * 512 * BK * 2 + ((NSTAGES + 3) / 2) * BM * 2 * BK * 2 : 8 * 64 * 128 * 2;
+constexpr int kRowDepthWide = 2 * BK;
+constexpr int kLdsBytesWide = NSTAGES * 512 * BK * 2 + ((NSTAGES + 3) / 2) * BM * kRowDepthWide * 2;
 static_assert(kLdsBytesWide >= NSTAGES * (512 + BM) * BK * 2 && kLdsBytesWide >= 8 * 64 * 128 * 2 && kLdsBytesWide <= 160 * 1024,
               "slabs and the epilogue's staging (8 waves x 64 x 128 bf16) fit");
 constexpr int kDgateParts = 4;                 // partial gate-gradient sums per row and 256-column tile (one per wave column at most)
