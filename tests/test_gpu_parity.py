@@ -251,6 +251,10 @@ FFN_CASES = [
     # widths that take the 512-column (eight-wave) tiles in every row-tiled kernel, ragged rows and a replica
     dict(seed=8, E=3, h=512, hff=512, rows=(1, 64, 65, 200, 0, 129), experts=(2, 0, 1, 0, -1, 2)),
     dict(seed=9, E=2, h=1024, hff=1536, rows=(300, 77), experts=(1, 0)),
+    # the shortest contractions the wide tiles can meet (two slabs: fewer than the ring holds): gate/up and dA
+    # over h = 64 with 512-wide outputs, then down over h' = 64 and dX over two phases of two slabs
+    dict(seed=10, E=2, h=64, hff=512, rows=(130, 64), experts=(1, 0)),
+    dict(seed=11, E=2, h=512, hff=64, rows=(129, 3), experts=(0, 1)),
 ]
 
 
